@@ -1,0 +1,149 @@
+/*
+ * blasx.h -- C ABI of the single-GPU tile level-3 BLAS for MI355X (gfx950).
+ *
+ * The routines compute on HOST-resident matrices: the output is cut into T x T tile tasks
+ * (paper Section IV.A), operand tiles stream over the host link into a tile cache in HBM
+ * (Section IV.B, Alg. 2), every tile step runs as a hand-written MFMA kernel, and finished
+ * tiles are written back to the host matrix (Section IV.D).  A call returns after the last
+ * tile has landed in host memory, as a CPU BLAS would (Section I: legacy-BLAS compatible).
+ *
+ * Conventions
+ *   - All matrix pointers are HOST pointers owned by the caller.  They may be pageable, but
+ *     only page-locked memory (blasx_host_alloc, hipHostMalloc, torch pin_memory) gives
+ *     asynchronous DMA; the paper likewise page-locks its matrices (Section V.A).
+ *   - Enum values are those of the C BLAS interface:
+ *       Order 101 row-major / 102 column-major;  Trans 111 none / 112 transpose / 113 conjugate
+ *       transpose (= transpose for real data);  Uplo 121 upper / 122 lower;
+ *       Diag 131 non-unit / 132 unit;  Side 141 left / 142 right.
+ *   - Leading dimensions are in elements.  Dimensions are int; all offsets are computed in
+ *     size_t, so matrices beyond 2^31 elements are fine.
+ *   - Input matrices are only read.  Outputs must not overlap inputs.
+ *   - Return value: 0 on success; -k if the k-th argument is invalid (1-based, as counted in
+ *     the prototype); a positive BLASX_ERR_* code for run-time failures.  Nothing is written
+ *     to the output when an argument error is returned.
+ *   - The library is not re-entrant: one call at a time per process.
+ */
+#ifndef BLASX_H
+#define BLASX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    BLASX_ROW_MAJOR = 101, BLASX_COL_MAJOR = 102,
+    BLASX_NO_TRANS = 111, BLASX_TRANS = 112, BLASX_CONJ_TRANS = 113,
+    BLASX_UPPER = 121, BLASX_LOWER = 122,
+    BLASX_NON_UNIT = 131, BLASX_UNIT = 132,
+    BLASX_LEFT = 141, BLASX_RIGHT = 142
+};
+
+enum {
+    BLASX_OK = 0,
+    BLASX_ERR_NOT_INITIALIZED = 1,  /* blasx_init has not been called (or shutdown was) */
+    BLASX_ERR_ARENA_TOO_SMALL = 2,  /* the tile cache cannot hold the minimum working set */
+    BLASX_ERR_DEVICE = 3,           /* a HIP call failed; see blasx_last_error() */
+    BLASX_ERR_CONFIG = 4,           /* invalid tile size / stream count / option value */
+    BLASX_ERR_NO_MEMORY = 5,        /* host allocation failed */
+    BLASX_ERR_UNSUPPORTED = 6       /* valid BLAS arguments that this build does not cover */
+};
+
+/* ------------------------------------------------------------------ level-3 routines -- */
+
+/* C <- alpha * op(A) * op(B) + beta * C                (paper Eq. 1a, task per C tile)
+ * op(A) is M x K, op(B) is K x N, C is M x N.  beta == 0: C is not read.
+ * alpha == 0: A and B are not read.  Arguments 1..14 in prototype order. */
+int blasx_dgemm(int Order, int TransA, int TransB, int M, int N, int K, double alpha,
+                const double* A, int lda, const double* B, int ldb, double beta, double* C, int ldc);
+int blasx_sgemm(int Order, int TransA, int TransB, int M, int N, int K, float alpha,
+                const float* A, int lda, const float* B, int ldb, float beta, float* C, int ldc);
+
+/* C <- alpha * A * A^T + beta * C (Trans = none, A is N x K) or
+ * C <- alpha * A^T * A + beta * C (Trans = transpose, A is K x N)      (paper Eq. 1b)
+ * Only the Uplo triangle of C (with its diagonal) is read or written; the other triangle of
+ * the host matrix is left bit-identical. */
+int blasx_dsyrk(int Order, int Uplo, int Trans, int N, int K, double alpha,
+                const double* A, int lda, double beta, double* C, int ldc);
+
+/* Solve op(A) * X = alpha * B (Side = left, A is M x M) or X * op(A) = alpha * B (right,
+ * A is N x N); X overwrites B (M x N).                                  (paper Eq. 1c, with
+ * alpha placed as in the BLAS standard).  Only the Uplo triangle of A is read; with
+ * Diag = unit the diagonal is not read either. */
+int blasx_dtrsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha,
+                const double* A, int lda, double* B, int ldb);
+
+/* B <- alpha * op(A) * B (left) or alpha * B * op(A) (right)            (paper Eq. 1d, alpha on
+ * every term).  Same triangle rules as blasx_dtrsm. */
+int blasx_dtrmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha,
+                const double* A, int lda, double* B, int ldb);
+
+/* ------------------------------------------------------------------ run-time control -- */
+
+/* Hand the library its device resources (paper Section IV.E: one pre-allocated chunk, no
+ * per-tile device malloc).
+ *   arena        DEVICE pointer to arena_bytes of HBM that stays valid until blasx_shutdown
+ *                (e.g. a torch uint8 tensor).  NULL: the library allocates arena_bytes itself.
+ *   hip_streams  HOST array of nstreams hipStream_t handles (e.g. torch streams), used in
+ *                this order: compute, host-to-device, device-to-host, second host-to-device.
+ *                NULL: the library creates nstreams streams.  All at default priority.
+ *   nstreams     2..4.  With 2, both copy directions share one stream; with 3 each direction
+ *                has its own; with 4 inbound copies alternate between two streams.
+ * Must be called with the target device current.  Calling it again re-initialises. */
+int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int nstreams);
+int blasx_shutdown(void);
+
+/* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192. */
+int blasx_set_tile(int T);
+/* Cap on the bytes of the arena that the tile cache may use (0 = all of it); lowers the
+ * number of tile slots so that eviction (Alg. 2, Dequeue) can be exercised. */
+int blasx_set_cache_bytes(size_t cap);
+/* Scheduling knobs.  name is one of
+ *   "group"    tile tasks that run together and advance k-step by k-step (>= 1)
+ *   "kchain"   consecutive k-steps of a task fused into one launch (1..4; 1 = the paper's
+ *              one kernel per (i,j,k))
+ *   "depth"    launches the host may run ahead of the device (>= 1)
+ *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)
+ *   "sb_rows", "sb_cols"  super-block shape used to order the task queue
+ *   "profile"  1: time every launch with events (adds two event records per launch)
+ * Returns BLASX_ERR_CONFIG for an unknown name or an out-of-range value. */
+int blasx_set_option(const char* name, long value);
+long blasx_get_option(const char* name);   /* -1 for an unknown name */
+
+/* Page-locked host memory for matrices (hipHostMalloc).  Returns NULL on failure. */
+void* blasx_host_alloc(size_t bytes);
+int   blasx_host_free(void* p);
+
+typedef struct blasx_stats {
+    uint64_t calls;          /* level-3 calls since the last reset */
+    uint64_t tasks;          /* C tiles solved */
+    uint64_t tile_steps;     /* (i, j, k) steps executed */
+    uint64_t launches;       /* kernel launches */
+    uint64_t hits;           /* tile-cache hits (operand tiles) */
+    uint64_t misses;         /* tile-cache misses (each one is an inbound tile copy) */
+    uint64_t evictions;      /* blocks discarded to make room */
+    uint64_t refetches;      /* misses on a tile that had been evicted before */
+    uint64_t copies_h2d, copies_d2h;
+    uint64_t bytes_h2d, bytes_d2h;
+    uint64_t slot_waits;     /* times the host had to wait for a slot to become free */
+    uint64_t peak_slots;     /* most tile slots in use at once */
+    uint64_t profiled_launches;
+    double   flops;          /* floating-point operations of the executed tile steps */
+    double   t_total_s;      /* wall time inside level-3 calls */
+    double   t_issue_s;      /* of which: host scheduling/issue time (not waiting) */
+    double   t_kernel_s;     /* sum of event-timed launch durations ("profile" = 1) */
+} blasx_stats;
+
+int blasx_get_stats(blasx_stats* out);
+int blasx_reset_stats(void);
+
+const char* blasx_strerror(int rc);
+/* Text of the most recent device error ("" if none). */
+const char* blasx_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLASX_H */

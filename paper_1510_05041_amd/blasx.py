@@ -1,0 +1,210 @@
+"""Thin Python binding of the C ABI in include/blasx.h (argument marshalling only).
+
+Every step of the path -- task-ization, tile cache, scheduling, copies, kernels -- runs
+inside ``libblasx.so``.  PyTorch is used for two things only: owning the HBM arena and the
+HIP streams handed to ``blasx_init``, and allocating page-locked host matrices.
+
+Matrix arguments may be numpy arrays, CPU torch tensors or raw integer addresses; they are
+passed as host pointers, untouched.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import _build
+
+RowMajor, ColMajor = 101, 102
+NoTrans, Trans, ConjTrans = 111, 112, 113
+Upper, Lower = 121, 122
+NonUnit, Unit = 131, 132
+Left, Right = 141, 142
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint64) for n in (
+        "calls", "tasks", "tile_steps", "launches", "hits", "misses", "evictions", "refetches",
+        "copies_h2d", "copies_d2h", "bytes_h2d", "bytes_d2h", "slot_waits", "peak_slots",
+        "profiled_launches")] + [(n, ctypes.c_double) for n in ("flops", "t_total_s", "t_issue_s", "t_kernel_s")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class BlasxError(RuntimeError):
+    def __init__(self, name, rc, text):
+        super().__init__("%s failed: rc=%d (%s)" % (name, rc, text))
+        self.rc = rc
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    if hasattr(x, "data_ptr"):          # torch tensor
+        if getattr(x, "is_cuda", False):
+            raise TypeError("matrices must be host memory")
+        return x.data_ptr()
+    raise TypeError("unsupported matrix argument: %r" % type(x))
+
+
+class Library:
+    """One loaded copy of the C library (the product ``libblasx.so`` unless a path is given)."""
+
+    def __init__(self, path=None):
+        path = path or _build.LIB_PATH
+        if not os.path.exists(path):
+            raise OSError("%s is not built: run __graft_entry__.build() (hipcc, gfx950) first" % path)
+        self.path = path
+        self._lib = lib = ctypes.CDLL(path)
+        ci, cd, cf, vp, sz = ctypes.c_int, ctypes.c_double, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+        lib.blasx_dgemm.argtypes = [ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci, cd, vp, ci]
+        lib.blasx_sgemm.argtypes = [ci, ci, ci, ci, ci, ci, cf, vp, ci, vp, ci, cf, vp, ci]
+        lib.blasx_dsyrk.argtypes = [ci, ci, ci, ci, ci, cd, vp, ci, cd, vp, ci]
+        lib.blasx_dtrsm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci]
+        lib.blasx_dtrmm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci]
+        lib.blasx_init.argtypes = [vp, sz, ctypes.POINTER(vp), ci]
+        lib.blasx_set_tile.argtypes = [ci]
+        lib.blasx_set_cache_bytes.argtypes = [sz]
+        lib.blasx_set_option.argtypes = [ctypes.c_char_p, ctypes.c_long]
+        lib.blasx_get_option.argtypes = [ctypes.c_char_p]
+        lib.blasx_get_option.restype = ctypes.c_long
+        lib.blasx_host_alloc.argtypes = [sz]
+        lib.blasx_host_alloc.restype = vp
+        lib.blasx_host_free.argtypes = [vp]
+        lib.blasx_get_stats.argtypes = [ctypes.POINTER(Stats)]
+        lib.blasx_strerror.argtypes = [ci]
+        lib.blasx_strerror.restype = ctypes.c_char_p
+        lib.blasx_last_error.restype = ctypes.c_char_p
+        self._keep = None
+
+    # -- error handling ---------------------------------------------------------------
+    def _check(self, name, rc):
+        if rc != 0:
+            text = self._lib.blasx_strerror(rc).decode()
+            extra = self._lib.blasx_last_error().decode()
+            raise BlasxError(name, rc, text + (": " + extra if extra and rc > 0 else ""))
+
+    # -- run-time control ------------------------------------------------------------
+    def init(self, arena_bytes, nstreams=4, arena_ptr=None, stream_ptrs=None):
+        """blasx_init.  Without explicit pointers the arena is a torch uint8 CUDA tensor and the
+        streams are torch.cuda.Stream objects (default priority); both are kept alive here."""
+        keep = []
+        if arena_ptr is None or stream_ptrs is None:
+            import torch
+            if not torch.cuda.is_available():
+                raise RuntimeError("no GPU visible: the HIP library cannot run")
+            if arena_ptr is None:
+                arena = torch.empty(int(arena_bytes), dtype=torch.uint8, device="cuda")
+                keep.append(arena)
+                arena_ptr = arena.data_ptr()
+            if stream_ptrs is None:
+                streams = [torch.cuda.Stream() for _ in range(nstreams)]
+                keep.append(streams)
+                stream_ptrs = [s.cuda_stream for s in streams]
+        arr = (ctypes.c_void_p * nstreams)(*stream_ptrs)
+        self._check("blasx_init", self._lib.blasx_init(arena_ptr, int(arena_bytes), arr, nstreams))
+        self._keep = keep
+
+    def init_raw(self, arena_bytes, nstreams=4):
+        """blasx_init with NULL arena and streams: the library allocates its own."""
+        self._check("blasx_init", self._lib.blasx_init(None, int(arena_bytes), None, nstreams))
+        self._keep = None
+
+    def shutdown(self):
+        self._check("blasx_shutdown", self._lib.blasx_shutdown())
+        self._keep = None
+
+    def set_tile(self, T):
+        self._check("blasx_set_tile", self._lib.blasx_set_tile(T))
+
+    def set_cache_bytes(self, cap):
+        self._check("blasx_set_cache_bytes", self._lib.blasx_set_cache_bytes(int(cap)))
+
+    def set_option(self, name, value):
+        self._check("blasx_set_option(%s)" % name, self._lib.blasx_set_option(name.encode(), int(value)))
+
+    def get_option(self, name):
+        return self._lib.blasx_get_option(name.encode())
+
+    def host_alloc(self, nbytes):
+        p = self._lib.blasx_host_alloc(int(nbytes))
+        if not p:
+            raise MemoryError("blasx_host_alloc(%d) failed" % nbytes)
+        return p
+
+    def host_free(self, ptr):
+        self._check("blasx_host_free", self._lib.blasx_host_free(ptr))
+
+    def get_stats(self):
+        s = Stats()
+        self._check("blasx_get_stats", self._lib.blasx_get_stats(ctypes.byref(s)))
+        return s.as_dict()
+
+    def reset_stats(self):
+        self._check("blasx_reset_stats", self._lib.blasx_reset_stats())
+
+    def strerror(self, rc):
+        return self._lib.blasx_strerror(rc).decode()
+
+    def last_error(self):
+        return self._lib.blasx_last_error().decode()
+
+    # -- level-3 routines: same argument lists as the C prototypes --------------------
+    def dgemm(self, Order, TransA, TransB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, check=True):
+        rc = self._lib.blasx_dgemm(Order, TransA, TransB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc)
+        if check:
+            self._check("blasx_dgemm", rc)
+        return rc
+
+    def sgemm(self, Order, TransA, TransB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, check=True):
+        rc = self._lib.blasx_sgemm(Order, TransA, TransB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc)
+        if check:
+            self._check("blasx_sgemm", rc)
+        return rc
+
+    def dsyrk(self, Order, Uplo, Trans_, N, K, alpha, A, lda, beta, C, ldc, check=True):
+        rc = self._lib.blasx_dsyrk(Order, Uplo, Trans_, N, K, alpha, _ptr(A), lda, beta, _ptr(C), ldc)
+        if check:
+            self._check("blasx_dsyrk", rc)
+        return rc
+
+    def dtrsm(self, Order, Side, Uplo, TransA, Diag, M, N, alpha, A, lda, B, ldb, check=True):
+        rc = self._lib.blasx_dtrsm(Order, Side, Uplo, TransA, Diag, M, N, alpha, _ptr(A), lda, _ptr(B), ldb)
+        if check:
+            self._check("blasx_dtrsm", rc)
+        return rc
+
+    def dtrmm(self, Order, Side, Uplo, TransA, Diag, M, N, alpha, A, lda, B, ldb, check=True):
+        rc = self._lib.blasx_dtrmm(Order, Side, Uplo, TransA, Diag, M, N, alpha, _ptr(A), lda, _ptr(B), ldb)
+        if check:
+            self._check("blasx_dtrmm", rc)
+        return rc
+
+
+def pinned_matrix(rows, cols, dtype=np.float64, ld=None):
+    """Column-major rows x cols numpy view (leading dimension ld) of a page-locked torch buffer.
+
+    Returns (view, owner); keep ``owner`` alive as long as the view is used.
+    """
+    import torch
+    ld = max(rows, 1) if ld is None else ld
+    tdt = {np.dtype(np.float64): torch.float64, np.dtype(np.float32): torch.float32}[np.dtype(dtype)]
+    owner = torch.empty(int(ld) * int(max(cols, 1)), dtype=tdt, pin_memory=True)
+    flat = owner.numpy()
+    view = flat.reshape((max(cols, 1), ld)).T[:rows, :cols]
+    return view, owner
+
+
+_default = None
+
+
+def default():
+    """The product library, loaded on first use; raises if it has not been built."""
+    global _default
+    if _default is None:
+        _default = Library()
+    return _default

@@ -1,0 +1,279 @@
+// C ABI of the tile level-3 BLAS: argument checking, BLAS quick returns, row-major to
+// column-major rewriting, then task-ization and the scheduler run.  See include/blasx.h.
+#include "../../include/blasx.h"
+
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <string>
+
+#include "backend.h"
+#include "scheduler.h"
+#include "tasks.h"
+
+using namespace blasx;
+
+namespace {
+
+struct Library {
+    std::unique_ptr<Backend> be;
+    int T = 1024;
+    size_t cache_cap = 0;
+    SchedConfig cfg;
+    OrderOpts order;
+    Stats stats;
+    std::string last_error;
+};
+
+Library& lib() {
+    static Library L;
+    return L;
+}
+
+bool is_trans(int t) { return t == BLASX_TRANS || t == BLASX_CONJ_TRANS; }
+bool ok_trans(int t) { return t == BLASX_NO_TRANS || is_trans(t); }
+
+int run_problem(Problem& p) {
+    Library& L = lib();
+    const size_t tile_bytes = (size_t)L.T * (size_t)L.T * p.esize;
+    const size_t slot_bytes = (tile_bytes + 255) / 256 * 256;
+    size_t usable = L.be->arena_bytes();
+    if (L.cache_cap && L.cache_cap < usable) usable = L.cache_cap;
+    const size_t nslots = usable / slot_bytes;
+    if (nslots < 4) {
+        L.last_error = "tile cache holds fewer than 4 tiles of the configured size";
+        return BLASX_ERR_ARENA_TOO_SMALL;
+    }
+    SchedConfig cfg = L.cfg;
+    // the running set and its operands must fit: each running task owns an accumulator slot
+    cfg.group = (int)std::max<size_t>(1, std::min<size_t>((size_t)cfg.group, nslots / 4));
+    ++L.stats.calls;
+    Scheduler sched(*L.be, (int)std::min<size_t>(nslots, 1u << 30), slot_bytes, cfg, L.stats);
+    const int rc = sched.run(p);
+    if (rc == BLASX_ERR_DEVICE) L.last_error = L.be->last_error();
+    if (rc == BLASX_ERR_ARENA_TOO_SMALL) L.last_error = "tile cache too small for the working set of this call";
+    return rc;
+}
+
+template <typename T>
+int gemm_impl(int dtype, int Order, int TransA, int TransB, int M, int N, int K, double alpha, const T* A, int lda,
+              const T* B, int ldb, double beta, T* C, int ldc) {
+    if (Order != BLASX_ROW_MAJOR && Order != BLASX_COL_MAJOR) return -1;
+    if (!ok_trans(TransA)) return -2;
+    if (!ok_trans(TransB)) return -3;
+    if (M < 0) return -4;
+    if (N < 0) return -5;
+    if (K < 0) return -6;
+    // stored extents in the order's own terms: rows of A as stored (column-major) / columns (row-major)
+    const bool col = Order == BLASX_COL_MAJOR;
+    const int a_lead = col ? (is_trans(TransA) ? K : M) : (is_trans(TransA) ? M : K);
+    const int b_lead = col ? (is_trans(TransB) ? N : K) : (is_trans(TransB) ? K : N);
+    const int c_lead = col ? M : N;
+    if (lda < std::max(1, a_lead)) return -9;
+    if (ldb < std::max(1, b_lead)) return -11;
+    if (ldc < std::max(1, c_lead)) return -14;
+    if (M == 0 || N == 0) return 0;
+    if ((alpha == 0.0 || K == 0) && beta == 1.0) return 0;
+    if (!lib().be) return BLASX_ERR_NOT_INITIALIZED;
+    if ((!A || !B) && alpha != 0.0 && K > 0) return A ? -10 : -8;
+    if (!C) return -13;
+    Problem p;
+    if (col)
+        build_gemm(p, dtype, lib().T, is_trans(TransA), is_trans(TransB), M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+    else   // C^T = op(B)^T op(A)^T: the row-major arrays are the column-major transposes
+        build_gemm(p, dtype, lib().T, is_trans(TransB), is_trans(TransA), N, M, K, alpha, B, ldb, A, lda, beta, C, ldc, lib().order);
+    return run_problem(p);
+}
+
+int tri_check(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, const void* A, int lda, const void* B,
+              int ldb) {
+    if (Order != BLASX_ROW_MAJOR && Order != BLASX_COL_MAJOR) return -1;
+    if (Side != BLASX_LEFT && Side != BLASX_RIGHT) return -2;
+    if (Uplo != BLASX_UPPER && Uplo != BLASX_LOWER) return -3;
+    if (!ok_trans(TransA)) return -4;
+    if (Diag != BLASX_NON_UNIT && Diag != BLASX_UNIT) return -5;
+    if (M < 0) return -6;
+    if (N < 0) return -7;
+    const int na = Side == BLASX_LEFT ? M : N;
+    if (lda < std::max(1, na)) return -10;
+    if (ldb < std::max(1, Order == BLASX_COL_MAJOR ? M : N)) return -12;
+    if (M > 0 && N > 0) {
+        if (!A) return -9;
+        if (!B) return -11;
+    }
+    return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int blasx_dgemm(int Order, int TransA, int TransB, int M, int N, int K, double alpha, const double* A, int lda,
+                const double* B, int ldb, double beta, double* C, int ldc) {
+    return gemm_impl<double>(0, Order, TransA, TransB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+int blasx_sgemm(int Order, int TransA, int TransB, int M, int N, int K, float alpha, const float* A, int lda,
+                const float* B, int ldb, float beta, float* C, int ldc) {
+    return gemm_impl<float>(1, Order, TransA, TransB, M, N, K, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc);
+}
+
+int blasx_dsyrk(int Order, int Uplo, int Trans, int N, int K, double alpha, const double* A, int lda, double beta,
+                double* C, int ldc) {
+    if (Order != BLASX_ROW_MAJOR && Order != BLASX_COL_MAJOR) return -1;
+    if (Uplo != BLASX_UPPER && Uplo != BLASX_LOWER) return -2;
+    if (!ok_trans(Trans)) return -3;
+    if (N < 0) return -4;
+    if (K < 0) return -5;
+    const bool col = Order == BLASX_COL_MAJOR;
+    const int a_lead = col ? (is_trans(Trans) ? K : N) : (is_trans(Trans) ? N : K);
+    if (lda < std::max(1, a_lead)) return -8;
+    if (ldc < std::max(1, N)) return -11;
+    if (N == 0) return 0;
+    if ((alpha == 0.0 || K == 0) && beta == 1.0) return 0;
+    if (!lib().be) return BLASX_ERR_NOT_INITIALIZED;
+    if (!A && alpha != 0.0 && K > 0) return -7;
+    if (!C) return -10;
+    Problem p;
+    // row-major: the arrays are the column-major transposes, so the triangle and the
+    // transposition flag both flip
+    const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
+    const bool trans = col ? is_trans(Trans) : !is_trans(Trans);
+    build_syrk(p, 0, lib().T, lower, trans, N, K, alpha, A, lda, beta, C, ldc, lib().order);
+    return run_problem(p);
+}
+
+int blasx_dtrmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const double* A, int lda,
+                double* B, int ldb) {
+    const int chk = tri_check(Order, Side, Uplo, TransA, Diag, M, N, A, lda, B, ldb);
+    if (chk) return chk;
+    if (M == 0 || N == 0) return 0;
+    if (!lib().be) return BLASX_ERR_NOT_INITIALIZED;
+    const bool col = Order == BLASX_COL_MAJOR;
+    // row-major: B^T = alpha (op(A) B)^T = alpha B^T op(A)^T: side and triangle flip, M and N swap
+    const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
+    const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
+    Problem p;
+    build_trmm(p, 0, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+               ldb, lib().order);
+    return run_problem(p);
+}
+
+int blasx_dtrsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const double* A, int lda,
+                double* B, int ldb) {
+    const int chk = tri_check(Order, Side, Uplo, TransA, Diag, M, N, A, lda, B, ldb);
+    if (chk) return chk;
+    if (M == 0 || N == 0) return 0;
+    if (!lib().be) return BLASX_ERR_NOT_INITIALIZED;
+    const bool col = Order == BLASX_COL_MAJOR;
+    const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
+    const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
+    Problem p;
+    if (alpha == 0.0) {
+        // X = 0 and A is not read: a TRMM with no steps writes zero tiles
+        build_trmm(p, 0, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, 0.0, A, lda, B,
+                   ldb, lib().order);
+    } else {
+        build_trsm(p, 0, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+                   ldb, lib().order);
+    }
+    return run_problem(p);
+}
+
+int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int nstreams) {
+    Library& L = lib();
+    L.be.reset();
+    if (nstreams < 2 || nstreams > 4 || arena_bytes == 0) return BLASX_ERR_CONFIG;
+    std::string err;
+    Backend* b = make_backend(arena, arena_bytes, hip_streams, nstreams, &err);
+    if (!b) {
+        L.last_error = err;
+        return BLASX_ERR_DEVICE;
+    }
+    L.be.reset(b);
+    return 0;
+}
+
+int blasx_shutdown(void) {
+    lib().be.reset();
+    return 0;
+}
+
+int blasx_set_tile(int T) {
+    if (T < 16 || T > 8192 || T % 16) return BLASX_ERR_CONFIG;
+    lib().T = T;
+    return 0;
+}
+
+int blasx_set_cache_bytes(size_t cap) {
+    lib().cache_cap = cap;
+    return 0;
+}
+
+int blasx_set_option(const char* name, long value) {
+    if (!name) return BLASX_ERR_CONFIG;
+    Library& L = lib();
+    const std::string n(name);
+    if (n == "group") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.group = (int)value; }
+    else if (n == "kchain") { if (value < 1 || value > kMaxChain) return BLASX_ERR_CONFIG; L.cfg.kchain = (int)value; }
+    else if (n == "depth") { if (value < 1 || value > 1024) return BLASX_ERR_CONFIG; L.cfg.depth = (int)value; }
+    else if (n == "rs") { if (value < 1 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.rs = (int)value; }
+    else if (n == "sb_rows") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_rows = (int)value; }
+    else if (n == "sb_cols") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_cols = (int)value; }
+    else if (n == "profile") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.profile = value != 0; }
+    else return BLASX_ERR_CONFIG;
+    return 0;
+}
+
+long blasx_get_option(const char* name) {
+    if (!name) return -1;
+    Library& L = lib();
+    const std::string n(name);
+    if (n == "group") return L.cfg.group;
+    if (n == "kchain") return L.cfg.kchain;
+    if (n == "depth") return L.cfg.depth;
+    if (n == "rs") return L.cfg.rs;
+    if (n == "sb_rows") return L.order.sb_rows;
+    if (n == "sb_cols") return L.order.sb_cols;
+    if (n == "profile") return L.cfg.profile ? 1 : 0;
+    if (n == "tile") return L.T;
+    return -1;
+}
+
+void* blasx_host_alloc(size_t bytes) { return backend_host_alloc(bytes); }
+int blasx_host_free(void* p) { return backend_host_free(p) ? BLASX_ERR_DEVICE : 0; }
+
+int blasx_get_stats(blasx_stats* out) {
+    if (!out) return BLASX_ERR_CONFIG;
+    const Stats& s = lib().stats;
+    std::memset(out, 0, sizeof(*out));
+    out->calls = s.calls; out->tasks = s.tasks; out->tile_steps = s.tile_steps; out->launches = s.launches;
+    out->hits = s.hits; out->misses = s.misses; out->evictions = s.evictions; out->refetches = s.refetches;
+    out->copies_h2d = s.copies_h2d; out->copies_d2h = s.copies_d2h; out->bytes_h2d = s.bytes_h2d; out->bytes_d2h = s.bytes_d2h;
+    out->slot_waits = s.slot_waits; out->peak_slots = s.peak_slots; out->profiled_launches = s.profiled_launches;
+    out->flops = s.flops; out->t_total_s = s.t_total_s; out->t_issue_s = s.t_issue_s; out->t_kernel_s = s.t_kernel_s;
+    return 0;
+}
+
+int blasx_reset_stats(void) {
+    lib().stats = Stats();
+    return 0;
+}
+
+const char* blasx_strerror(int rc) {
+    if (rc < 0) return "invalid argument (its 1-based position is the negated code)";
+    switch (rc) {
+        case BLASX_OK: return "success";
+        case BLASX_ERR_NOT_INITIALIZED: return "blasx_init has not been called";
+        case BLASX_ERR_ARENA_TOO_SMALL: return "tile cache too small";
+        case BLASX_ERR_DEVICE: return "device error";
+        case BLASX_ERR_CONFIG: return "invalid configuration value";
+        case BLASX_ERR_NO_MEMORY: return "out of host memory";
+        case BLASX_ERR_UNSUPPORTED: return "not supported";
+        default: return "unknown error";
+    }
+}
+
+const char* blasx_last_error(void) { return lib().last_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,211 @@
+// HIP implementation of the scheduler's device interface: streams by role, SDMA tile copies
+// (hipMemcpy2DAsync on page-locked memory), grouped tile-step launches, events.
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "backend.h"
+
+namespace blasx {
+
+hipError_t launch_tile_steps(int dtype, bool ta, bool tb, bool general, const LaunchPack& pack, hipStream_t stream);
+
+// Inverse of the nb x nb diagonal blocks of a triangular tile (the base case of the TRSM
+// diagonal step; paper Eq. 1c needs A_ii^{-1}).  One wave per block, thread c solves for
+// column c of the inverse by substitution.  Only the triangle is written.
+template <typename T>
+__global__ void trtri_blocks_kernel(const T* __restrict__ tri, int ld_tri, T* __restrict__ inv, int ld_inv, int n,
+                                    int nb, int lower, int unit) {
+    __shared__ double L[32][33];
+    __shared__ double X[32][33];
+    const int o = blockIdx.x * nb;
+    const int bs = min(nb, n - o);
+    const int c = threadIdx.x;
+    for (int idx = threadIdx.x; idx < bs * bs; idx += blockDim.x) {
+        const int r = idx % bs, q = idx / bs;
+        double v = 0.0;
+        if (r == q) v = unit ? 1.0 : (double)tri[(size_t)(o + r) + (size_t)(o + q) * ld_tri];
+        else if (lower ? (r > q) : (r < q)) v = (double)tri[(size_t)(o + r) + (size_t)(o + q) * ld_tri];
+        L[r][q] = v;
+    }
+    __syncthreads();
+    if (c < bs) {
+        X[c][c] = 1.0 / L[c][c];
+        if (lower) {
+            for (int r = c + 1; r < bs; ++r) {
+                double s = 0.0;
+                for (int q = c; q < r; ++q) s += L[r][q] * X[q][c];
+                X[r][c] = -s / L[r][r];
+            }
+            for (int r = c; r < bs; ++r) inv[(size_t)(o + r) + (size_t)(o + c) * ld_inv] = (T)X[r][c];
+        } else {
+            for (int r = c - 1; r >= 0; --r) {
+                double s = 0.0;
+                for (int q = r + 1; q <= c; ++q) s += L[r][q] * X[q][c];
+                X[r][c] = -s / L[r][r];
+            }
+            for (int r = 0; r <= c; ++r) inv[(size_t)(o + r) + (size_t)(o + c) * ld_inv] = (T)X[r][c];
+        }
+    }
+}
+
+#define HB_CHECK(call)                                   \
+    do {                                                 \
+        hipError_t e_ = (call);                          \
+        if (e_ != hipSuccess) {                          \
+            err_ = std::string(#call) + ": " + hipGetErrorString(e_); \
+            return 1;                                    \
+        }                                                \
+    } while (0)
+
+class HipBackend : public Backend {
+public:
+    HipBackend() {}
+    ~HipBackend() override {
+        for (hipEvent_t e : events_) (void)hipEventDestroy(e);
+        for (size_t s = 0; s < streams_.size(); ++s)
+            if (own_stream_[s]) (void)hipStreamDestroy(streams_[s]);
+        if (own_arena_ && arena_) (void)hipFree(arena_);
+    }
+
+    int init(void* arena, size_t bytes, void* const* streams, int nstreams) {
+        if (nstreams < 2 || nstreams > 4) {
+            err_ = "nstreams must be 2..4";
+            return 1;
+        }
+        if (arena) {
+            arena_ = static_cast<char*>(arena);
+            own_arena_ = false;
+        } else {
+            HB_CHECK(hipMalloc(reinterpret_cast<void**>(&arena_), bytes));
+            own_arena_ = true;
+        }
+        bytes_ = bytes;
+        for (int s = 0; s < nstreams; ++s) {
+            hipStream_t st = nullptr;
+            bool own = false;
+            if (streams && streams[s]) {
+                st = static_cast<hipStream_t>(streams[s]);
+            } else {
+                HB_CHECK(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+                own = true;
+            }
+            streams_.push_back(st);
+            own_stream_.push_back(own);
+        }
+        return 0;
+    }
+
+    char* arena() override { return arena_; }
+    size_t arena_bytes() override { return bytes_; }
+    int num_streams() override { return (int)streams_.size(); }
+
+    hipStream_t stream(int role) {
+        const int n = (int)streams_.size();
+        if (role < n) return streams_[role];
+        return streams_[STREAM_H2D];           // fewer streams: copy roles share one
+    }
+
+    int copy_h2d(void* dst, size_t dpitch, const void* src, size_t spitch, size_t width, size_t height, int s) override {
+        HB_CHECK(hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, hipMemcpyHostToDevice, stream(s)));
+        return 0;
+    }
+    int copy_d2h(void* dst, size_t dpitch, const void* src, size_t spitch, size_t width, size_t height, int s) override {
+        HB_CHECK(hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, hipMemcpyDeviceToHost, stream(s)));
+        return 0;
+    }
+    int launch(int dtype, bool ta, bool tb, bool general, const LaunchPack& pack, int s) override {
+        HB_CHECK(launch_tile_steps(dtype, ta, tb, general, pack, stream(s)));
+        return 0;
+    }
+    int launch_trtri_blocks(int dtype, const void* tri, int ld_tri, void* inv, int ld_inv, int n, int nb, uint32_t flags,
+                            int s) override {
+        if (n <= 0) return 0;
+        if (nb > 32) {
+            err_ = "trtri block order above 32";
+            return 1;
+        }
+        const int grid = (n + nb - 1) / nb;
+        const int lower = (flags & TS_TRI_LOWER) ? 1 : 0, unit = (flags & TS_TRI_UNIT) ? 1 : 0;
+        if (dtype == 0)
+            hipLaunchKernelGGL(trtri_blocks_kernel<double>, dim3(grid), dim3(64), 0, stream(s), static_cast<const double*>(tri),
+                               ld_tri, static_cast<double*>(inv), ld_inv, n, nb, lower, unit);
+        else
+            hipLaunchKernelGGL(trtri_blocks_kernel<float>, dim3(grid), dim3(64), 0, stream(s), static_cast<const float*>(tri),
+                               ld_tri, static_cast<float*>(inv), ld_inv, n, nb, lower, unit);
+        HB_CHECK(hipGetLastError());
+        return 0;
+    }
+
+    int event_create() override {
+        if (!free_.empty()) {
+            const int ev = free_.back();
+            free_.pop_back();
+            return ev;
+        }
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) {
+            err_ = "hipEventCreate failed";
+            return -1;
+        }
+        events_.push_back(e);
+        return (int)events_.size() - 1;
+    }
+    void event_destroy(int ev) override {
+        if (ev >= 0) free_.push_back(ev);
+    }
+    int event_record(int ev, int s) override {
+        HB_CHECK(hipEventRecord(events_[ev], stream(s)));
+        return 0;
+    }
+    int stream_wait_event(int s, int ev) override {
+        HB_CHECK(hipStreamWaitEvent(stream(s), events_[ev], 0));
+        return 0;
+    }
+    bool event_done(int ev) override { return hipEventQuery(events_[ev]) == hipSuccess; }
+    int event_sync(int ev) override {
+        HB_CHECK(hipEventSynchronize(events_[ev]));
+        return 0;
+    }
+    double event_elapsed_s(int a, int b) override {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, events_[a], events_[b]) != hipSuccess) return 0.0;
+        return (double)ms * 1e-3;
+    }
+    int sync_all() override {
+        for (hipStream_t s : streams_) HB_CHECK(hipStreamSynchronize(s));
+        return 0;
+    }
+    const char* last_error() override { return err_.c_str(); }
+
+private:
+    char* arena_ = nullptr;
+    size_t bytes_ = 0;
+    bool own_arena_ = false;
+    std::vector<hipStream_t> streams_;
+    std::vector<bool> own_stream_;
+    std::vector<hipEvent_t> events_;
+    std::vector<int> free_;
+    std::string err_;
+};
+
+Backend* make_backend(void* arena, size_t bytes, void* const* streams, int nstreams, std::string* err) {
+    HipBackend* b = new HipBackend();
+    if (b->init(arena, bytes, streams, nstreams)) {
+        if (err) *err = b->last_error();
+        delete b;
+        return nullptr;
+    }
+    return b;
+}
+
+void* backend_host_alloc(size_t bytes) {
+    void* p = nullptr;
+    if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess) return nullptr;
+    return p;
+}
+
+int backend_host_free(void* p) { return hipHostFree(p) == hipSuccess ? 0 : 1; }
+
+}  // namespace blasx

@@ -1,0 +1,722 @@
+#include "scheduler.h"
+
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+
+#include "../../include/blasx.h"
+
+namespace blasx {
+
+namespace {
+double now_s() {
+    return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+constexpr int kTrtriBlock = 32;   // order of the diagonal blocks inverted directly
+}  // namespace
+
+#define BX_TRY(expr)                      \
+    do {                                  \
+        const int rc_ = (expr);           \
+        if (rc_ != 0) return rc_;         \
+    } while (0)
+
+Scheduler::Scheduler(Backend& be, int nslots, size_t slot_bytes, const SchedConfig& cfg, Stats& stats)
+    : be_(be), cache_(nslots), arena_(be.arena()), slot_bytes_(slot_bytes), cfg_(cfg), stats_(stats) {
+    fill_ev_.assign(nslots, -1);
+    fill_seq_.assign(nslots, 0);
+    fill_stream_.assign(nslots, STREAM_H2D);
+    cfg_.kchain = std::max(1, std::min(cfg_.kchain, kMaxChain));
+    cfg_.group = std::max(1, cfg_.group);
+    cfg_.depth = std::max(1, cfg_.depth);
+    cfg_.rs = std::max(cfg_.rs, cfg_.group);
+    fast_.general = false;
+    gen_.general = true;
+}
+
+Scheduler::~Scheduler() {
+    for (int ev : fill_ev_)
+        if (ev >= 0) be_.event_destroy(ev);
+    for (int ev : free_events_) be_.event_destroy(ev);
+}
+
+TileKey Scheduler::key_of(const TileRef& t, int tag) const {
+    TileKey k;
+    k.host = t.host;
+    k.ld = t.ld;
+    k.rows = t.rows;
+    k.cols = t.cols;
+    k.esize = (int32_t)p_->esize;
+    k.tag = tag;
+    return k;
+}
+
+int Scheduler::new_event() {
+    if (!free_events_.empty()) {
+        const int ev = free_events_.back();
+        free_events_.pop_back();
+        return ev;
+    }
+    return be_.event_create();
+}
+
+// ---------------------------------------------------------------- completion tracking ----
+
+// Alg. 1 "ReaderUpdate": drop the readers of every launch the device has finished.  The
+// paper does this after a full StreamsSynch; here one event per launch tells the same thing
+// without draining the streams.
+bool Scheduler::retire(bool block_on_oldest) {
+    bool any = false;
+    while (!inflight_.empty()) {
+        InFlight& f = inflight_.front();
+        if (!be_.event_done(f.done_ev)) {
+            if (!block_on_oldest) break;
+            be_.event_sync(f.done_ev);
+        }
+        block_on_oldest = false;
+        if (f.start_ev >= 0) {
+            stats_.t_kernel_s += be_.event_elapsed_s(f.start_ev, f.done_ev);
+            ++stats_.profiled_launches;
+            put_event(f.start_ev);
+        }
+        for (Block* b : f.blocks) cache_.release(b);
+        for (int s : f.free_slots) cache_.give_slot(s);
+        put_event(f.done_ev);
+        inflight_.pop_front();
+        any = true;
+    }
+    return any;
+}
+
+// Result tiles whose outbound copy has landed: their slot is free again (or, for TRSM, the
+// adopted cache block loses the reader that protected it during the copy).
+void Scheduler::poll_writebacks(bool block) {
+    while (!writebacks_.empty()) {
+        WriteBack& w = writebacks_.front();
+        if (!be_.event_done(w.ev)) {
+            if (!block) break;
+            be_.event_sync(w.ev);
+        }
+        if (w.block) {
+            cache_.release(w.block);
+            auto it = pending_wb_.find(w.key);
+            if (it != pending_wb_.end() && it->second == w.ev) pending_wb_.erase(it);
+        } else {
+            cache_.give_slot(w.slot);
+        }
+        put_event(w.ev);
+        writebacks_.pop_front();
+    }
+}
+
+int Scheduler::take_slot_blocking(int* slot) {
+    for (;;) {
+        const int s = cache_.take_slot();
+        if (s >= 0) {
+            // fill_seq_/fill_ev_ of the slot are kept: an inbound copy issued for its previous
+            // owner may still be in flight, and whoever writes the slot next must be ordered after it
+            *slot = s;
+            return 0;
+        }
+        ++stats_.slot_waits;
+        BX_TRY(flush_all());
+        if (!inflight_.empty()) {
+            retire(true);
+        } else if (!writebacks_.empty()) {
+            poll_writebacks(true);
+        } else {
+            return BLASX_ERR_ARENA_TOO_SMALL;
+        }
+        poll_writebacks(false);
+    }
+}
+
+// ---------------------------------------------------------------- tile movement ----------
+
+int Scheduler::issue_h2d(const TileRef& t, int slot) {
+    int stream = STREAM_H2D;
+    if (be_.num_streams() >= 4) {
+        stream = (h2d_rr_++ & 1) ? STREAM_H2D_B : STREAM_H2D;
+    }
+    const size_t es = p_->esize;
+    // A slot can change owner while a copy for its previous owner is still queued on the other
+    // inbound stream (a block that was evicted before any launch read it): order the two copies.
+    if (fill_seq_[slot] != 0 && fill_stream_[slot] != stream) {
+        if (be_.stream_wait_event(stream, fill_ev_[slot])) return BLASX_ERR_DEVICE;
+    }
+    if (be_.copy_h2d(slot_ptr(slot), (size_t)T_ * es, t.host, (size_t)t.ld * es, (size_t)t.rows * es, (size_t)t.cols, stream))
+        return BLASX_ERR_DEVICE;
+    if (fill_ev_[slot] < 0) fill_ev_[slot] = be_.event_create();
+    if (be_.event_record(fill_ev_[slot], stream)) return BLASX_ERR_DEVICE;
+    fill_seq_[slot] = ++h2d_issued_[stream];
+    fill_stream_[slot] = stream;
+    ++stats_.copies_h2d;
+    stats_.bytes_h2d += (uint64_t)t.rows * t.cols * es;
+    return 0;
+}
+
+// Alg. 1 lines 22-23 (tile = CCP(&tile)): translate a host tile to its device copy, starting
+// the inbound copy when it is not cached.  -1: no slot could be found right now.
+int Scheduler::fetch(const TileRef& t, Block** out) {
+    const TileKey key = key_of(t);
+    bool hit = false;
+    Block* b = cache_.translate(key, &hit);
+    if (!b) return -1;
+    if (!hit) {
+        auto it = pending_wb_.find(key);
+        if (it != pending_wb_.end()) {
+            // the host copy of this tile is still being written by an outbound copy
+            be_.stream_wait_event(STREAM_H2D, it->second);
+            if (be_.num_streams() >= 4) be_.stream_wait_event(STREAM_H2D_B, it->second);
+        }
+        const int rc = issue_h2d(t, b->slot);
+        if (rc) return rc;
+    }
+    *out = b;
+    return 0;
+}
+
+// TRMM: fetch and pin the original tiles of a panel before its first task starts.
+int Scheduler::ensure_panel(int panel) {
+    PanelState& ps = panels_[panel];
+    if (ps.loaded) return 0;
+    const Panel& pn = p_->panels[panel];
+    for (const TileRef& t : pn.tiles) {
+        Block* b = nullptr;
+        for (;;) {
+            const int rc = fetch(t, &b);
+            if (rc == 0) break;
+            if (rc > 0) return rc;
+            ++stats_.slot_waits;
+            BX_TRY(flush_all());
+            if (!inflight_.empty()) retire(true);
+            else if (!writebacks_.empty()) poll_writebacks(true);
+            else return BLASX_ERR_ARENA_TOO_SMALL;
+        }
+        cache_.acquire(b);
+        ps.blocks.push_back(b);
+    }
+    ps.loaded = true;
+    return 0;
+}
+
+// ---------------------------------------------------------------- reservation station ----
+
+void Scheduler::refill_rs() {
+    const size_t ntasks = p_->tasks.size();
+    while ((int)rs_.size() < cfg_.rs && next_task_ < ntasks) {
+        rs_.push_back((int)next_task_++);
+        rs_dirty_ = true;
+    }
+}
+
+bool Scheduler::deps_started(const Task& t) const {
+    for (const StepSpec& s : t.steps)
+        if (s.dep >= 0 && !task_started_[s.dep]) return false;
+    return true;
+}
+
+// Eq. 2: priority = sum over the task's steps of f(A_ik) + f(B_kj), f = 2 for a tile that is in
+// the (single-level) cache and 0 otherwise.
+int64_t Scheduler::priority(const Task& t) const {
+    int64_t pr = 0;
+    for (const StepSpec& s : t.steps) {
+        if (cache_.find(key_of(s.a))) pr += 2;
+        if (cache_.find(key_of(s.b))) pr += 2;
+    }
+    return pr;
+}
+
+// Highest-priority task of the RS whose producers have all started; ties go to queue order.
+// Priorities are refreshed when new tasks have entered the RS (Section IV.C).
+int Scheduler::pick_from_rs() {
+    if (rs_.empty()) return -1;
+    if (rs_dirty_) {
+        rs_prio_.resize(rs_.size());
+        for (size_t q = 0; q < rs_.size(); ++q) rs_prio_[q] = priority(p_->tasks[rs_[q]]);
+        rs_dirty_ = false;
+    }
+    int best = -1;
+    for (size_t q = 0; q < rs_.size(); ++q) {
+        if (!deps_started(p_->tasks[rs_[q]])) continue;
+        if (best < 0 || rs_prio_[q] > rs_prio_[best]) best = (int)q;
+    }
+    if (best < 0) return -1;
+    const int task = rs_[best];
+    rs_.erase(rs_.begin() + best);
+    rs_prio_.erase(rs_prio_.begin() + best);
+    return task;
+}
+
+// ---------------------------------------------------------------- launches ---------------
+
+int Scheduler::add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, double flops, uint64_t nsteps) {
+    if (op.pack.nsteps > 0 && (op.ta != ta || op.tb != tb)) BX_TRY(flush(op));
+    if (op.pack.nsteps == kMaxStepsPerLaunch) BX_TRY(flush(op));
+    if (op.pack.nsteps == 0) {
+        op.ta = ta;
+        op.tb = tb;
+        op.id = next_pack_id_++;
+        op.pack.total_wg = 0;
+    }
+    TileStep& dst = op.pack.step[op.pack.nsteps++];
+    dst = st;
+    dst.wg_begin = op.pack.total_wg;
+    op.pack.total_wg += macro_tiles(st.m, st.n);
+    op.flops += flops;
+    op.steps += nsteps;
+    return 0;
+}
+
+int Scheduler::flush(OpenPack& op) {
+    if (op.pack.nsteps == 0) return 0;
+    // Make the compute stream wait for the inbound copies this launch reads: one wait per
+    // copy stream is enough, on the youngest copy (streams are in order).
+    for (int stream : {(int)STREAM_H2D, (int)STREAM_H2D_B}) {
+        int best = -1;
+        for (int s : op.wait_slots)
+            if (fill_stream_[s] == stream && fill_seq_[s] > compute_waited_[stream] &&
+                (best < 0 || fill_seq_[s] > fill_seq_[best]))
+                best = s;
+        if (best >= 0) {
+            if (be_.stream_wait_event(STREAM_COMPUTE, fill_ev_[best])) return BLASX_ERR_DEVICE;
+            compute_waited_[stream] = fill_seq_[best];
+        }
+    }
+    InFlight f;
+    f.id = op.id;
+    if (cfg_.profile) {
+        f.start_ev = new_event();
+        if (be_.event_record(f.start_ev, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
+    }
+    if (be_.launch(p_->dtype, op.ta, op.tb, op.general, op.pack, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
+    f.done_ev = new_event();
+    if (be_.event_record(f.done_ev, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
+    f.blocks.swap(op.blocks);
+    f.free_slots.swap(op.free_slots);
+    ++stats_.launches;
+    stats_.tile_steps += op.steps;
+    stats_.flops += op.flops;
+    flushed_pack_id_ = std::max(flushed_pack_id_, op.id);
+    const int done_ev = f.done_ev;
+    inflight_.push_back(std::move(f));
+    std::vector<int> finishing;
+    finishing.swap(op.finishing);
+    op.pack.nsteps = 0;
+    op.pack.total_wg = 0;
+    op.wait_slots.clear();
+    op.flops = 0;
+    op.steps = 0;
+    for (int ri : finishing) BX_TRY(finish_task(ri, done_ev));
+    return 0;
+}
+
+int Scheduler::flush_all() {
+    BX_TRY(flush(fast_));
+    BX_TRY(flush(gen_));
+    return 0;
+}
+
+// The last launch of a task has been issued: write the tile back to the host matrix once that
+// launch is done, and let go of it (the paper's ephemeral M state: written back, then invalid).
+int Scheduler::finish_task(int ri, int done_ev) {
+    Running& r = running_[ri];
+    const Task& t = p_->tasks[r.task];
+    const size_t es = p_->esize;
+    const int d2h = be_.num_streams() >= 3 ? STREAM_D2H : STREAM_H2D;
+    if (be_.stream_wait_event(d2h, done_ev)) return BLASX_ERR_DEVICE;
+    if (t.panel >= 0) {
+        // the panel's original tiles must have been read from the host before it is overwritten
+        for (Block* b : panels_[t.panel].blocks)
+            if (fill_seq_[b->slot] > 0) be_.stream_wait_event(d2h, fill_ev_[b->slot]);
+    }
+    if (be_.copy_d2h(t.c_host, (size_t)p_->ldc * es, slot_ptr(r.c_slot), (size_t)T_ * es, (size_t)t.m * es, (size_t)t.n, d2h))
+        return BLASX_ERR_DEVICE;
+    WriteBack w;
+    w.ev = new_event();
+    w.slot = r.c_slot;
+    if (be_.event_record(w.ev, d2h)) return BLASX_ERR_DEVICE;
+    ++stats_.copies_d2h;
+    stats_.bytes_d2h += (uint64_t)t.m * t.n * es;
+    if (p_->results_are_operands) {
+        TileRef c;
+        c.host = t.c_host;
+        c.ld = p_->ldc;
+        c.rows = t.m;
+        c.cols = t.n;
+        w.key = key_of(c);
+        w.block = cache_.adopt(w.key, r.c_slot);
+        if (!w.block) return BLASX_ERR_DEVICE;
+        cache_.acquire(w.block);
+        pending_wb_[w.key] = w.ev;
+    }
+    writebacks_.push_back(w);
+    task_issued_[r.task] = 1;
+    ++stats_.tasks;
+    if (t.panel >= 0) {
+        PanelState& ps = panels_[t.panel];
+        if (--ps.remaining == 0) {
+            for (Block* b : ps.blocks) cache_.release(b);
+            ps.blocks.clear();
+        }
+    }
+    r.done = true;
+    return 0;
+}
+
+int Scheduler::start_task(int task_index, Running* r) {
+    const Task& t = p_->tasks[task_index];
+    if (t.panel >= 0) BX_TRY(ensure_panel(t.panel));
+    int slot = -1;
+    BX_TRY(take_slot_blocking(&slot));
+    *r = Running();
+    r->task = task_index;
+    r->c_slot = slot;
+    if (t.load_c) {
+        TileRef c;
+        c.host = t.c_host;
+        c.ld = p_->ldc;
+        c.rows = t.m;
+        c.cols = t.n;
+        BX_TRY(issue_h2d(c, slot));
+    }
+    task_started_[task_index] = 1;
+    return 0;
+}
+
+// Next launch of one running task: up to kchain consecutive k-steps (Alg. 1 lines 19-25 for one
+// task and one k), operands translated through the cache.  Returns 1 if nothing could be issued
+// because a producer task has not been issued yet.
+int Scheduler::build_chain(int ri) {
+    Running& r = running_[ri];
+    const Task& t = p_->tasks[r.task];
+    const int nsteps = (int)t.steps.size();
+    if (r.next_step >= nsteps && !(r.first && !t.solve)) {
+        if (t.solve && !r.solved) return build_solve(ri);
+        return 1;
+    }
+    TileStep st;
+    std::memset(&st, 0, sizeof(st));
+    Block* held[2 * kMaxChain];
+    int nheld = 0, nseg = 0;
+    double flops = 0;
+    while (nseg < cfg_.kchain && r.next_step + nseg < nsteps) {
+        const StepSpec& s = t.steps[r.next_step + nseg];
+        if (s.dep >= 0) {
+            if (task_final_pack_[s.dep] == 0) break;          // producer's last launch not built yet
+            if (task_final_pack_[s.dep] > flushed_pack_id_) BX_TRY(flush_all());
+        }
+        Block *ba = nullptr, *bb = nullptr;
+        int rc = fetch(s.a, &ba);
+        if (rc == 0) {
+            cache_.acquire(ba);
+            rc = fetch(s.b, &bb);
+            if (rc == 0) cache_.acquire(bb);
+            else cache_.release(ba);
+        }
+        if (rc > 0) return rc;
+        if (rc < 0) {
+            if (nseg > 0) break;          // issue what fits; the rest follows in the next round
+            ++stats_.slot_waits;
+            BX_TRY(flush_all());
+            if (!inflight_.empty()) retire(true);
+            else if (!writebacks_.empty()) poll_writebacks(true);
+            else return BLASX_ERR_ARENA_TOO_SMALL;
+            poll_writebacks(false);
+            continue;
+        }
+        held[nheld++] = ba;
+        held[nheld++] = bb;
+        st.seg[nseg].A = slot_ptr(ba->slot);
+        st.seg[nseg].B = slot_ptr(bb->slot);
+        st.seg[nseg].k = s.k;
+        st.seg[nseg].flags = s.seg_flags;
+        flops += ((s.seg_flags & (TS_TRI_A | TS_TRI_B)) || t.c_flags ? 1.0 : 2.0) * t.m * t.n * s.k;
+        ++nseg;
+    }
+    if (nseg == 0 && nsteps > 0 && r.next_step < nsteps) return 1;   // blocked on a producer
+    st.C = slot_ptr(r.c_slot);
+    st.nseg = nseg;
+    st.lda = st.ldb = st.ldc = T_;
+    st.m = t.m;
+    st.n = t.n;
+    st.flags = (p_->ta ? TS_TRANS_A : 0u) | (p_->tb ? TS_TRANS_B : 0u) | t.c_flags;
+    st.alpha = t.alpha_step;
+    st.beta = r.first ? t.beta_first : 1.0;
+    OpenPack& op = step_is_fast(st, p_->dtype) ? fast_ : gen_;
+    BX_TRY(add_step(op, p_->ta, p_->tb, st, flops, (uint64_t)nseg));
+    for (int q = 0; q < nheld; ++q) {
+        op.blocks.push_back(held[q]);
+        op.wait_slots.push_back(held[q]->slot);
+    }
+    op.wait_slots.push_back(r.c_slot);
+    r.next_step += nseg;
+    r.first = false;
+    r.last_pack = op.id;
+    if (r.next_step >= nsteps && !t.solve) {
+        op.finishing.push_back(ri);
+        task_final_pack_[r.task] = op.id;
+    }
+    return 0;
+}
+
+// TRSM: inverse of a diagonal tile of the triangular matrix, cached under the tile's host
+// address with a tag.  Small diagonal blocks are inverted directly; block pairs are then merged
+// level by level:  inv([L11 0; L21 L22]) = [inv11 0; -inv22 L21 inv11  inv22]  (and the mirror
+// image for an upper triangle), each merge being two tile steps of the GEMM kernel.
+int Scheduler::get_inverse(const Task& t, Block** out) {
+    const int tag = 1 + (int)((t.diag_flags >> 4) & 3u);
+    const TileKey key = key_of(t.diag, tag);
+    if (cache_.find(key)) {
+        bool hit;
+        *out = cache_.translate(key, &hit);
+        return 0;
+    }
+    const int n = t.diag.rows;
+    const bool lower = (t.diag_flags & TS_TRI_LOWER) != 0;
+    Block *src = nullptr, *inv = nullptr;
+    for (;;) {
+        int rc = fetch(t.diag, &src);
+        if (rc == 0) break;
+        if (rc > 0) return rc;
+        BX_TRY(flush_all());
+        if (!inflight_.empty()) retire(true);
+        else if (!writebacks_.empty()) poll_writebacks(true);
+        else return BLASX_ERR_ARENA_TOO_SMALL;
+    }
+    cache_.acquire(src);
+    for (;;) {
+        bool hit;
+        inv = cache_.translate(key, &hit);
+        if (inv) break;
+        BX_TRY(flush_all());
+        if (!inflight_.empty()) retire(true);
+        else if (!writebacks_.empty()) poll_writebacks(true);
+        else return BLASX_ERR_ARENA_TOO_SMALL;
+    }
+    cache_.acquire(inv);
+    int tmp = -1;
+    BX_TRY(take_slot_blocking(&tmp));
+    BX_TRY(flush_all());
+    // the source tile's inbound copy must have landed, and so must any stale copy still
+    // queued into the two slots that are about to be written
+    for (int slot : {src->slot, inv->slot, tmp}) {
+        if (fill_seq_[slot] > compute_waited_[fill_stream_[slot]]) {
+            if (be_.stream_wait_event(STREAM_COMPUTE, fill_ev_[slot])) return BLASX_ERR_DEVICE;
+            compute_waited_[fill_stream_[slot]] = fill_seq_[slot];
+        }
+    }
+    if (be_.launch_trtri_blocks(p_->dtype, slot_ptr(src->slot), T_, slot_ptr(inv->slot), T_, n, kTrtriBlock, t.diag_flags,
+                                STREAM_COMPUTE))
+        return BLASX_ERR_DEVICE;
+    const size_t es = p_->esize;
+    auto at = [&](int slot, int r, int c) { return slot_ptr(slot) + ((size_t)r + (size_t)c * T_) * es; };
+    for (int s = kTrtriBlock; s < n; s *= 2) {
+        for (int phase = 0; phase < 2; ++phase) {
+            for (int o = 0; o + s < n; o += 2 * s) {
+                const int s2 = std::min(s, n - (o + s));   // order of the second block of the pair
+                TileStep st;
+                std::memset(&st, 0, sizeof(st));
+                st.nseg = 1;
+                st.lda = st.ldb = st.ldc = T_;
+                if (lower) {
+                    st.m = s2;
+                    st.n = s;
+                    if (phase == 0) {       // tmp = L21 * inv11
+                        st.C = at(tmp, o + s, o);
+                        st.seg[0] = TileSeg{at(src->slot, o + s, o), at(inv->slot, o, o), s, TS_TRI_B | TS_TRI_LOWER};
+                        st.alpha = 1.0;
+                    } else {                // inv21 = -inv22 * tmp
+                        st.C = at(inv->slot, o + s, o);
+                        st.seg[0] = TileSeg{at(inv->slot, o + s, o + s), at(tmp, o + s, o), s2, TS_TRI_A | TS_TRI_LOWER};
+                        st.alpha = -1.0;
+                    }
+                } else {
+                    st.m = s;
+                    st.n = s2;
+                    if (phase == 0) {       // tmp = U12 * inv22
+                        st.C = at(tmp, o, o + s);
+                        st.seg[0] = TileSeg{at(src->slot, o, o + s), at(inv->slot, o + s, o + s), s2, TS_TRI_B};
+                        st.alpha = 1.0;
+                    } else {                // inv12 = -inv11 * tmp
+                        st.C = at(inv->slot, o, o + s);
+                        st.seg[0] = TileSeg{at(inv->slot, o, o), at(tmp, o, o + s), s, TS_TRI_A};
+                        st.alpha = -1.0;
+                    }
+                }
+                st.beta = 0.0;
+                BX_TRY(add_step(gen_, false, false, st, 1.0 * st.m * st.n * st.seg[0].k, 0));
+            }
+            BX_TRY(flush(gen_));
+        }
+    }
+    // src, inv and tmp stay reserved until the last merge has run: a marker record that
+    // retires after everything issued so far on the compute stream
+    {
+        InFlight f;
+        f.id = next_pack_id_++;
+        f.done_ev = new_event();
+        if (be_.event_record(f.done_ev, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
+        f.blocks.push_back(src);
+        f.blocks.push_back(inv);
+        f.free_slots.push_back(tmp);
+        flushed_pack_id_ = std::max(flushed_pack_id_, f.id);
+        inflight_.push_back(std::move(f));
+    }
+    *out = inv;
+    return 0;
+}
+
+// TRSM diagonal step: X = inv(op(A_ii)) * W (left) or W * inv(op(A_jj)) (right), written to a
+// fresh slot because every output column needs all of W.
+int Scheduler::build_solve(int ri) {
+    Running& r = running_[ri];
+    const Task& t = p_->tasks[r.task];
+    if (r.last_pack > flushed_pack_id_) BX_TRY(flush_all());
+    Block* inv = nullptr;
+    BX_TRY(get_inverse(t, &inv));
+    cache_.acquire(inv);
+    int c2 = -1;
+    {
+        const int rc = take_slot_blocking(&c2);
+        if (rc) {
+            cache_.release(inv);
+            return rc;
+        }
+    }
+    TileStep st;
+    std::memset(&st, 0, sizeof(st));
+    st.C = slot_ptr(c2);
+    st.nseg = 1;
+    st.lda = st.ldb = st.ldc = T_;
+    st.m = t.m;
+    st.n = t.n;
+    const uint32_t low = t.diag_flags & TS_TRI_LOWER;
+    if (!t.solve_on_right) {
+        st.seg[0] = TileSeg{slot_ptr(inv->slot), slot_ptr(r.c_slot), t.m, TS_TRI_A | low};
+        st.flags = p_->ta ? TS_TRANS_A : 0u;
+    } else {
+        st.seg[0] = TileSeg{slot_ptr(r.c_slot), slot_ptr(inv->slot), t.n, TS_TRI_B | low};
+        st.flags = p_->tb ? TS_TRANS_B : 0u;
+    }
+    st.alpha = r.first ? t.beta_first : 1.0;   // a task without update steps still owes the alpha
+    st.beta = 0.0;
+    BX_TRY(add_step(gen_, p_->ta, p_->tb, st, 1.0 * t.m * t.n * st.seg[0].k, 1));
+    gen_.blocks.push_back(inv);
+    gen_.wait_slots.push_back(r.c_slot);
+    gen_.free_slots.push_back(r.c_slot);
+    r.c_slot = c2;
+    r.first = false;
+    r.solved = true;
+    r.last_pack = gen_.id;
+    gen_.finishing.push_back(ri);
+    task_final_pack_[r.task] = gen_.id;
+    return 0;
+}
+
+// ---------------------------------------------------------------- main loop --------------
+
+int Scheduler::run(Problem& p) {
+    const double t0 = now_s();
+    double t_wait = 0;
+    p_ = &p;
+    T_ = p.T;
+    const size_t ntasks = p.tasks.size();
+    next_task_ = 0;
+    rs_.clear();
+    rs_prio_.clear();
+    rs_dirty_ = true;
+    running_.clear();
+    task_started_.assign(ntasks, 0);
+    task_issued_.assign(ntasks, 0);
+    task_final_pack_.assign(ntasks, 0);
+    panels_.assign(p.panels.size(), PanelState());
+    for (size_t q = 0; q < p.panels.size(); ++q) panels_[q].remaining = p.panels[q].ntasks;
+    int rc = 0;
+
+    for (;;) {
+        retire(false);
+        poll_writebacks(false);
+        // keep `group` tasks running: top-priority tasks of the reservation station
+        refill_rs();
+        size_t active = 0;
+        for (const Running& r : running_) active += r.done ? 0 : 1;
+        while ((int)active < cfg_.group) {
+            const int task = pick_from_rs();
+            if (task < 0) break;
+            Running r;
+            rc = start_task(task, &r);
+            if (rc) break;
+            bool placed = false;
+            for (Running& slot : running_)
+                if (slot.done) {
+                    slot = r;
+                    placed = true;
+                    break;
+                }
+            if (!placed) running_.push_back(r);
+            ++active;
+            refill_rs();
+        }
+        if (rc) break;
+        if (active == 0) {
+            if (rs_.empty() && next_task_ >= ntasks) break;
+            rc = BLASX_ERR_DEVICE;   // tasks remain but none can start: broken dependency order
+            break;
+        }
+        // one round: the next chain of every running task (step k of all tasks before k+1)
+        bool progressed = false;
+        for (size_t ri = 0; ri < running_.size() && !rc; ++ri) {
+            if (running_[ri].done) continue;
+            const int brc = build_chain((int)ri);
+            if (brc == 0) progressed = true;
+            else if (brc != 1) rc = brc;
+        }
+        if (rc) break;
+        rc = flush_all();
+        if (rc) break;
+        if (!progressed) {
+            // every running task waits for a producer that is itself not running: cannot happen
+            // with a dependency-ordered queue, but never spin
+            rc = BLASX_ERR_DEVICE;
+            break;
+        }
+        while ((int)inflight_.size() > cfg_.depth) {
+            const double tw = now_s();
+            retire(true);
+            t_wait += now_s() - tw;
+        }
+    }
+
+    // drain: wait for everything that was issued, even after an error
+    {
+        const double tw = now_s();
+        if (rc == 0) rc = flush_all();
+        while (!inflight_.empty()) retire(true);
+        poll_writebacks(true);
+        if (be_.sync_all() && rc == 0) rc = BLASX_ERR_DEVICE;
+        t_wait += now_s() - tw;
+    }
+    for (PanelState& ps : panels_) {
+        for (Block* b : ps.blocks) cache_.release(b);
+        ps.blocks.clear();
+    }
+    for (Running& r : running_)
+        if (!r.done && r.c_slot >= 0) cache_.give_slot(r.c_slot);
+    running_.clear();
+    pending_wb_.clear();
+
+    stats_.hits += cache_.hits;
+    stats_.misses += cache_.misses;
+    stats_.evictions += cache_.evictions;
+    stats_.refetches += cache_.refetches;
+    stats_.peak_slots = std::max<uint64_t>(stats_.peak_slots, cache_.peak_used);
+    cache_.hits = cache_.misses = cache_.evictions = cache_.refetches = 0;
+    const double dt = now_s() - t0;
+    stats_.t_total_s += dt;
+    stats_.t_issue_s += dt - t_wait;
+    p_ = nullptr;
+    return rc;
+}
+
+}  // namespace blasx

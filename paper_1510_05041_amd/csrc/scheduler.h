@@ -1,0 +1,155 @@
+// Dynamic tile scheduler for one GPU (paper Alg. 1, lines 8-25, and Sections IV.C-D).
+//
+// What is kept from the paper: a queue of tile tasks; a reservation station (RS) that buffers
+// upcoming tasks and ranks them by expected cache hits (Eq. 2); a small set of tasks that run
+// together and advance k-step by k-step so that tile copies of one step overlap kernels of
+// others; operand tiles translated through the ALRU cache; reader counts that are dropped
+// only once the device has finished with a tile; result tiles written back and dropped.
+//
+// What differs, because one 1024^3 tile step fills a quarter of an MI355X at best:
+//   - the running tasks share the GPU inside ONE grouped launch per round instead of four
+//     vendor-BLAS calls on four streams, and streams are specialised by role (compute,
+//     inbound copies, outbound copies);
+//   - the paper's per-round StreamsSynch + ReaderUpdate is replaced by an event per launch:
+//     readers are released when that event has completed, the host never drains the device;
+//   - up to `kchain` consecutive k-steps of a task are fused into one launch so the
+//     accumulators stay in registers.
+#pragma once
+#include <stdint.h>
+
+#include <cstring>
+#include <deque>
+#include <unordered_map>
+#include <vector>
+
+#include "alru.h"
+#include "backend.h"
+#include "tasks.h"
+
+namespace blasx {
+
+struct SchedConfig {
+    int group = 16;     // tasks that run together
+    int kchain = 4;     // k-steps fused per launch (1..kMaxChain)
+    int depth = 6;      // launches in flight before the host waits
+    int rs = 32;        // reservation-station size
+    bool profile = false;
+};
+
+struct Stats {
+    uint64_t calls = 0, tasks = 0, tile_steps = 0, launches = 0;
+    uint64_t hits = 0, misses = 0, evictions = 0, refetches = 0;
+    uint64_t copies_h2d = 0, copies_d2h = 0, bytes_h2d = 0, bytes_d2h = 0;
+    uint64_t slot_waits = 0, peak_slots = 0, profiled_launches = 0;
+    double flops = 0, t_total_s = 0, t_issue_s = 0, t_kernel_s = 0;
+};
+
+class Scheduler {
+public:
+    // nslots tile slots of slot_bytes each start at backend.arena().
+    Scheduler(Backend& be, int nslots, size_t slot_bytes, const SchedConfig& cfg, Stats& stats);
+    ~Scheduler();
+    // Runs the whole problem and returns after every result tile is in host memory.
+    // 0 on success, else a BLASX_ERR_* value.
+    int run(Problem& p);
+
+private:
+    struct Running {
+        int task = -1;
+        int next_step = 0;
+        int c_slot = -1;
+        bool first = true;          // no launch issued yet (beta_first applies)
+        bool solved = false;
+        uint64_t last_pack = 0;     // id of the pack holding this task's latest chain
+        bool done = false;
+    };
+    struct OpenPack {
+        OpenPack() { std::memset(&pack, 0, sizeof(pack)); }
+        LaunchPack pack;
+        std::vector<Block*> blocks;     // readers to drop when the launch retires
+        std::vector<int> free_slots;    // raw slots to return when the launch retires
+        std::vector<int> finishing;     // indices into running_ whose last chain is in this pack
+        std::vector<int> wait_slots;    // slots whose inbound copies this launch reads
+        double flops = 0;
+        uint64_t steps = 0;
+        bool general = false;
+        bool ta = false, tb = false;
+        uint64_t id = 0;
+    };
+    struct InFlight {
+        int done_ev = -1, start_ev = -1;
+        std::vector<Block*> blocks;
+        std::vector<int> free_slots;
+        uint64_t id = 0;
+    };
+    struct WriteBack {
+        int ev = -1;
+        int slot = -1;
+        Block* block = nullptr;   // adopted result (TRSM): drop the reader instead of freeing
+        TileKey key;
+    };
+    struct PanelState {
+        std::vector<Block*> blocks;
+        int fill_ev = -1, fill_ev_b = -1;   // last inbound copy of the snapshot per stream
+        int remaining = 0;
+        bool loaded = false;
+    };
+
+    char* slot_ptr(int slot) const { return arena_ + (size_t)slot * slot_bytes_; }
+    TileKey key_of(const TileRef& t, int tag = 0) const;
+    int  new_event();
+    void put_event(int ev) { free_events_.push_back(ev); }
+
+    int  fetch(const TileRef& t, Block** out);               // translate + inbound copy on a miss
+    int  issue_h2d(const TileRef& t, int slot);
+    int  take_slot_blocking(int* slot);
+    int  start_task(int task_index, Running* r);
+    int  ensure_panel(int panel);
+    int  build_chain(int ri);
+    int  build_solve(int ri);
+    int  get_inverse(const Task& t, Block** out);
+    int  add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, double flops, uint64_t nsteps);
+    int  flush(OpenPack& op);
+    int  flush_all();
+    int  finish_task(int ri, int done_ev);
+    bool retire(bool block_on_oldest);
+    void poll_writebacks(bool block);
+    void refill_rs();
+    int  pick_from_rs();
+    bool deps_started(const Task& t) const;
+    int64_t priority(const Task& t) const;
+
+    Backend& be_;
+    Alru cache_;
+    char* arena_;
+    size_t slot_bytes_;
+    SchedConfig cfg_;
+    Stats& stats_;
+    Problem* p_ = nullptr;
+    int T_ = 0;
+
+    std::vector<int> fill_ev_;          // per slot: event of its latest inbound copy
+    std::vector<uint64_t> fill_seq_;    // per slot: sequence number of that copy on its stream
+    std::vector<int> fill_stream_;
+    uint64_t h2d_issued_[4] = {0, 0, 0, 0};      // per stream role
+    uint64_t compute_waited_[4] = {0, 0, 0, 0};
+    int h2d_rr_ = 0;
+
+    size_t next_task_ = 0;
+    std::vector<int> rs_;               // task indices waiting in the reservation station
+    std::vector<int64_t> rs_prio_;      // their priorities (Eq. 2), refreshed when tasks enter
+    bool rs_dirty_ = true;
+    std::vector<Running> running_;
+    std::vector<char> task_started_, task_issued_;   // per task
+    std::vector<uint64_t> task_final_pack_;          // pack id of the launch that finishes it
+    std::vector<PanelState> panels_;
+    OpenPack fast_, gen_;
+    uint64_t next_pack_id_ = 1, flushed_pack_id_ = 0;
+    std::deque<InFlight> inflight_;
+    std::deque<WriteBack> writebacks_;
+    std::unordered_map<TileKey, int, TileKeyHash> pending_wb_;   // host tile -> event of its outbound copy
+    std::vector<int> free_events_;
+    int err_ = 0;
+};
+
+}  // namespace blasx

@@ -1,0 +1,349 @@
+// Tile-step kernels for CDNA4 (gfx950): C <- alpha * op(A) * op(B) + beta * C on HBM-resident
+// tiles (Section III.B, Eq. 1a-1d; the call the paper's Alg. 1 makes once per (i, j, k)).
+//
+// One launch executes a *pack* of tile steps (different output tiles), so that a launch fills
+// the 256 CUs even though a single 1024^3 step only has 64 macro-tiles.  The paper shares the
+// GPU between 4 tasks by running 4 vendor-BLAS calls on 4 streams; here the sharing happens
+// inside one grid instead.
+//
+// Work decomposition
+//   workgroup  = 256 threads = 4 waves (2 x 2), one 128 x 128 macro-tile of one step
+//   wave       = 64 x 64 of C = 4 x 4 MFMA blocks of 16 x 16, accumulators in registers
+//   k loop     = slabs of 16, double buffered in LDS; the next slab is fetched from HBM
+//                into registers while the MFMAs of the current one run
+//   MFMA       = v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32, issued on the transposed
+//                product (a := B fragment, b := A fragment) so that the 16 lanes that share an
+//                accumulator register hold 16 consecutive rows of C: stores to column-major C
+//                are 128-byte (fp64) contiguous runs.
+//   LDS layout = [k][mn] for both operands (mn = row of op(A) / column of op(B)), 128 elements
+//                per k row, mn index XOR-swizzled by 2*((k>>1)&7) so that both the direct
+//                (mn-contiguous source) and the transposing (k-contiguous source) stores are
+//                conflict-free, while a fragment read still touches 16 consecutive elements.
+//   transposes = done by the LDS store pattern (Section III.C: the stored tile is fetched as it
+//                is and transposed inside the kernel).
+//   XCD mapping= hardware deals consecutive workgroup ids round-robin to the 8 XCDs; the
+//                virtual index below gives each XCD a contiguous range of macro-tiles, i.e.
+//                whole steps, so the 64 macro-tiles that share one A and one B tile run under
+//                one L2.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tile_step.h"
+
+namespace blasx {
+
+constexpr int BM = kBM;
+constexpr int BN = kBN;
+constexpr int BK = kBK;
+constexpr int NTHREADS = 256;
+constexpr int NXCD = 8;
+
+template <typename T> struct Mfma;
+
+template <> struct Mfma<double> {
+    typedef double acc_t __attribute__((ext_vector_type(4)));
+    typedef double vec2_t __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ acc_t run(double a, double b, acc_t c) {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+    // accumulator register r of a lane in 16-lane group g holds result row 4*r + g
+    static __device__ __forceinline__ int drow(int r, int g) { return 4 * r + g; }
+};
+
+template <> struct Mfma<float> {
+    typedef float acc_t __attribute__((ext_vector_type(4)));
+    typedef float vec2_t __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ acc_t run(float a, float b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    // accumulator register r of a lane in 16-lane group g holds result row 4*g + r
+    static __device__ __forceinline__ int drow(int r, int g) { return 4 * g + r; }
+};
+
+__device__ __forceinline__ int swz(int l) { return ((l >> 1) & 7) << 1; }
+
+// Value of element (r, c) of a stored square tile under a triangular mask.
+template <typename T>
+__device__ __forceinline__ T tri_value(const T* p, int ld, int r, int c, uint32_t flags) {
+    if (r == c) return (flags & TS_TRI_UNIT) ? T(1) : p[(size_t)r + (size_t)c * ld];
+    const bool inside = (flags & TS_TRI_LOWER) ? (r > c) : (r < c);
+    return inside ? p[(size_t)r + (size_t)c * ld] : T(0);
+}
+
+// One operand slab (16 deep, 128 wide) from HBM into registers.
+//   KCONTIG = false: element (mn, l) is at p[mn + l*ld]  (A not transposed, B transposed)
+//   KCONTIG = true : element (mn, l) is at p[l + mn*ld]  (A transposed, B not transposed)
+// GEN adds bounds (mn < mn_valid, l < k_valid) and the triangular mask; out-of-range is zero.
+template <typename T, bool KCONTIG, bool GEN>
+__device__ __forceinline__ void slab_load(typename Mfma<T>::vec2_t (&reg)[4], const T* __restrict__ p, int ld,
+                                          int mn_base, int k0, int mn_valid, int k_valid, bool tri,
+                                          uint32_t flags, int tid) {
+    typedef typename Mfma<T>::vec2_t V2;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (!KCONTIG) {
+            const int mn = mn_base + (tid & 63) * 2;
+            const int l = k0 + (tid >> 6) + 4 * q;
+            if (!GEN) {
+                reg[q] = *reinterpret_cast<const V2*>(p + (size_t)mn + (size_t)l * ld);
+            } else {
+                V2 v = {T(0), T(0)};
+                if (l < k_valid) {
+                    if (tri) {
+                        if (mn < mn_valid) v.x = tri_value(p, ld, mn, l, flags);
+                        if (mn + 1 < mn_valid) v.y = tri_value(p, ld, mn + 1, l, flags);
+                    } else {
+                        if (mn < mn_valid) v.x = p[(size_t)mn + (size_t)l * ld];
+                        if (mn + 1 < mn_valid) v.y = p[(size_t)mn + 1 + (size_t)l * ld];
+                    }
+                }
+                reg[q] = v;
+            }
+        } else {
+            const int l = k0 + (tid & 7) * 2;
+            const int mn = mn_base + (tid >> 3) + 32 * q;
+            if (!GEN) {
+                reg[q] = *reinterpret_cast<const V2*>(p + (size_t)l + (size_t)mn * ld);
+            } else {
+                V2 v = {T(0), T(0)};
+                if (mn < mn_valid) {
+                    if (tri) {
+                        if (l < k_valid) v.x = tri_value(p, ld, l, mn, flags);
+                        if (l + 1 < k_valid) v.y = tri_value(p, ld, l + 1, mn, flags);
+                    } else {
+                        if (l < k_valid) v.x = p[(size_t)l + (size_t)mn * ld];
+                        if (l + 1 < k_valid) v.y = p[(size_t)l + 1 + (size_t)mn * ld];
+                    }
+                }
+                reg[q] = v;
+            }
+        }
+    }
+}
+
+// Registers into one operand's LDS slab ([BK][128], swizzled).
+template <typename T, bool KCONTIG>
+__device__ __forceinline__ void slab_store(T* __restrict__ lds, const typename Mfma<T>::vec2_t (&reg)[4], int tid) {
+    typedef typename Mfma<T>::vec2_t V2;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (!KCONTIG) {
+            const int mn = (tid & 63) * 2;
+            const int l = (tid >> 6) + 4 * q;
+            *reinterpret_cast<V2*>(lds + l * 128 + (mn ^ swz(l))) = reg[q];
+        } else {
+            const int l = (tid & 7) * 2;
+            const int mn = (tid >> 3) + 32 * q;
+            const int col = mn ^ swz(l);
+            lds[l * 128 + col] = reg[q].x;
+            lds[(l + 1) * 128 + col] = reg[q].y;
+        }
+    }
+}
+
+// Pointer of this thread's first element of an operand slab (fast path only).
+template <typename T, bool KCONTIG>
+__device__ __forceinline__ const T* slab_origin(const T* p, int ld, int mn_base, int tid) {
+    if (!KCONTIG) return p + (size_t)(mn_base + (tid & 63) * 2) + (size_t)(tid >> 6) * ld;
+    return p + (size_t)((tid & 7) * 2) + (size_t)(mn_base + (tid >> 3)) * ld;
+}
+
+template <typename T, bool KCONTIG>
+__device__ __forceinline__ void slab_load_fast(typename Mfma<T>::vec2_t (&reg)[4], const T* __restrict__ origin, int ld) {
+    typedef typename Mfma<T>::vec2_t V2;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        reg[q] = *reinterpret_cast<const V2*>(origin + (size_t)(KCONTIG ? 32 * q : 4 * q) * ld);
+}
+
+template <typename T, bool TA, bool TB, bool GEN>
+__device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j_base) {
+    typedef typename Mfma<T>::acc_t acc_t;
+    typedef typename Mfma<T>::vec2_t V2;
+    // [buffer][operand][k][mn]; always addressed through this array so that every access is a
+    // ds_ instruction (LDS address space known to the compiler).
+    __shared__ __attribute__((aligned(16))) T lds[4 * BK * 128];
+    constexpr int OPERAND = BK * 128, BUFFER = 2 * BK * 128;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 4, r16 = lane & 15;
+    const int wm = wave & 1, wn = wave >> 1;
+
+    T* __restrict__ C = static_cast<T*>(st.C);
+    const int m = st.m, n = st.n;
+    const int lda = st.lda, ldb = st.ldb;
+    const int nseg = st.nseg;
+
+    acc_t acc[4][4];
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 4; ++bj) acc[bi][bj] = acc_t{0, 0, 0, 0};
+
+    // Fragment read offsets: k row l = 4*kk + g, column (r16 ^ swz(l)) = (r16 ^ 2*(g>>1)) ^ 4*kk.
+    const int frag_col = r16 ^ ((g >> 1) << 1);
+    const int fragA = g * 128 + wm * 64, fragB = OPERAND + g * 128 + wn * 64;
+
+    const size_t step_a = TA ? (size_t)BK : (size_t)BK * lda;
+    const size_t step_b = !TB ? (size_t)BK : (size_t)BK * ldb;
+
+    // Prefetch cursor: pair `pseg`, slab `pslab` of it is the next one to fetch from HBM.  The
+    // slab loop runs across the chained pairs without draining the pipeline in between.
+    int pseg = 0, pslab = 0;
+    int pk = nseg > 0 ? st.seg[0].k : 0;
+    uint32_t pflags = nseg > 0 ? st.seg[0].flags : 0;
+    const T* A = nseg > 0 ? static_cast<const T*>(st.seg[0].A) : nullptr;
+    const T* B = nseg > 0 ? static_cast<const T*>(st.seg[0].B) : nullptr;
+    const T* pa = (GEN || nseg == 0) ? nullptr : slab_origin<T, TA>(A, lda, i_base, tid);
+    const T* pb = (GEN || nseg == 0) ? nullptr : slab_origin<T, !TB>(B, ldb, j_base, tid);
+
+    V2 ra[4], rb[4];
+    bool more = nseg > 0;
+    if (more) {
+        if (GEN) {
+            slab_load<T, TA, true>(ra, A, lda, i_base, 0, m, pk, pflags & TS_TRI_A, pflags, tid);
+            slab_load<T, !TB, true>(rb, B, ldb, j_base, 0, n, pk, pflags & TS_TRI_B, pflags, tid);
+        } else {
+            slab_load_fast<T, TA>(ra, pa, lda);
+            slab_load_fast<T, !TB>(rb, pb, ldb);
+        }
+        slab_store<T, TA>(lds, ra, tid);
+        slab_store<T, !TB>(lds + OPERAND, rb, tid);
+    }
+    __syncthreads();
+
+    int cur = 0;
+    while (more) {
+        // advance the prefetch cursor to the slab after the one now in LDS
+        ++pslab;
+        if (pslab * BK >= pk) {
+            ++pseg;
+            pslab = 0;
+            more = pseg < nseg;
+            if (more) {
+                pk = st.seg[pseg].k;
+                pflags = st.seg[pseg].flags;
+                A = static_cast<const T*>(st.seg[pseg].A);
+                B = static_cast<const T*>(st.seg[pseg].B);
+                if (!GEN) {
+                    pa = slab_origin<T, TA>(A, lda, i_base, tid);
+                    pb = slab_origin<T, !TB>(B, ldb, j_base, tid);
+                }
+            }
+        } else if (!GEN) {
+            pa += step_a;
+            pb += step_b;
+        }
+        if (more) {
+            if (GEN) {
+                slab_load<T, TA, true>(ra, A, lda, i_base, pslab * BK, m, pk, pflags & TS_TRI_A, pflags, tid);
+                slab_load<T, !TB, true>(rb, B, ldb, j_base, pslab * BK, n, pk, pflags & TS_TRI_B, pflags, tid);
+            } else {
+                slab_load_fast<T, TA>(ra, pa, lda);
+                slab_load_fast<T, !TB>(rb, pb, ldb);
+            }
+        }
+        // Fragments are double buffered: those of sub-step kk+1 are requested before the MFMAs of kk.
+        T fa[2][4], fb[2][4];
+#pragma unroll
+        for (int bi = 0; bi < 4; ++bi) fa[0][bi] = lds[cur + fragA + bi * 16 + frag_col];
+#pragma unroll
+        for (int bj = 0; bj < 4; ++bj) fb[0][bj] = lds[cur + fragB + bj * 16 + frag_col];
+#pragma unroll
+        for (int kk = 0; kk < BK / 4; ++kk) {
+            const int c = kk & 1, nx = c ^ 1;
+            if (kk + 1 < BK / 4) {
+                const int col = frag_col ^ (4 * (kk + 1));
+#pragma unroll
+                for (int bi = 0; bi < 4; ++bi) fa[nx][bi] = lds[cur + fragA + (kk + 1) * 4 * 128 + bi * 16 + col];
+#pragma unroll
+                for (int bj = 0; bj < 4; ++bj) fb[nx][bj] = lds[cur + fragB + (kk + 1) * 4 * 128 + bj * 16 + col];
+            }
+#pragma unroll
+            for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < 4; ++bj) acc[bi][bj] = Mfma<T>::run(fb[c][bj], fa[c][bi], acc[bi][bj]);
+        }
+        if (more) {
+            slab_store<T, TA>(lds + (cur ^ BUFFER), ra, tid);
+            slab_store<T, !TB>(lds + (cur ^ BUFFER) + OPERAND, rb, tid);
+        }
+        __syncthreads();
+        cur ^= BUFFER;
+    }
+
+    const uint32_t flags = st.flags;
+    const T alpha = (T)st.alpha, beta = (T)st.beta;
+    const bool use_c = (st.beta != 0.0);
+    const int ldc = st.ldc;
+#pragma unroll
+    for (int bj = 0; bj < 4; ++bj)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int j = j_base + wn * 64 + bj * 16 + Mfma<T>::drow(r, g);
+#pragma unroll
+            for (int bi = 0; bi < 4; ++bi) {
+                const int i = i_base + wm * 64 + bi * 16 + r16;
+                if (GEN) {
+                    if (i >= m || j >= n) continue;
+                    if ((flags & TS_C_LOWER) && i < j) continue;
+                    if ((flags & TS_C_UPPER) && i > j) continue;
+                }
+                T* p = C + (size_t)i + (size_t)j * ldc;
+                T v = alpha * acc[bi][bj][r];
+                if (use_c) v += beta * (*p);
+                *p = v;
+            }
+        }
+}
+
+// GEN = false: every step of the pack is made of whole macro-tiles, k is a multiple of 16,
+// operands are 16-byte aligned with even leading dimensions and no mask flag is set (the host
+// checks this with step_is_fast()).  GEN = true handles everything else with predication.
+template <typename T, bool TA, bool TB, bool GEN>
+__global__ __launch_bounds__(NTHREADS, 2) void tile_steps_kernel(const LaunchPack pack) {
+    // XCD-aware virtual workgroup index: XCD x gets the contiguous range [x*per, (x+1)*per).
+    const uint32_t per = gridDim.x / NXCD;
+    const uint32_t v = (blockIdx.x % NXCD) * per + blockIdx.x / NXCD;
+    if (v >= pack.total_wg) return;
+
+    int s = 0;
+    while (s + 1 < pack.nsteps && pack.step[s + 1].wg_begin <= v) ++s;
+    const TileStep& st = pack.step[s];
+
+    const uint32_t local = v - st.wg_begin;
+    const uint32_t tiles_m = (uint32_t)(st.m + BM - 1) / BM;
+    const int i_base = (int)(local % tiles_m) * BM;
+    const int j_base = (int)(local / tiles_m) * BN;
+    macro_tile<T, TA, TB, GEN>(st, i_base, j_base);
+}
+
+// Host-side launcher.  dtype: 0 = fp64, 1 = fp32.  The pack's wg_begin / total_wg must be filled,
+// and `general` must be true unless step_is_fast() holds for every step of the pack.
+hipError_t launch_tile_steps(int dtype, bool ta, bool tb, bool general, const LaunchPack& pack, hipStream_t stream) {
+    if (pack.nsteps <= 0 || pack.total_wg == 0) return hipSuccess;
+    const uint32_t grid = NXCD * ((pack.total_wg + NXCD - 1) / NXCD);
+#define BLASX_LAUNCH(T, TA, TB)                                                                                   \
+    do {                                                                                                          \
+        if (general)                                                                                              \
+            hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, true>), dim3(grid), dim3(NTHREADS), 0, stream, pack); \
+        else                                                                                                      \
+            hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, false>), dim3(grid), dim3(NTHREADS), 0, stream, pack); \
+    } while (0)
+    if (dtype == 0) {
+        if (!ta && !tb) BLASX_LAUNCH(double, false, false);
+        else if (!ta && tb) BLASX_LAUNCH(double, false, true);
+        else if (ta && !tb) BLASX_LAUNCH(double, true, false);
+        else BLASX_LAUNCH(double, true, true);
+    } else {
+        if (!ta && !tb) BLASX_LAUNCH(float, false, false);
+        else if (!ta && tb) BLASX_LAUNCH(float, false, true);
+        else if (ta && !tb) BLASX_LAUNCH(float, true, false);
+        else BLASX_LAUNCH(float, true, true);
+    }
+#undef BLASX_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace blasx

@@ -1,0 +1,85 @@
+// Descriptor of one tile step, shared by the host scheduler and the device kernels.
+//
+// A tile step is the unit of work of the tile algorithms (Section III.B, Eq. 1a-1d):
+//     C <- alpha * op(A) * op(B) + beta * C
+// on one m x n output tile with one k-deep pair of operand tiles.  All three tiles
+// live in HBM, column-major.  A and B are stored as they are in the host matrix; a
+// transposed operand is transposed while it is staged into LDS (Section III.C), never
+// in memory.
+#pragma once
+#include <stdint.h>
+
+namespace blasx {
+
+enum : uint32_t {
+    TS_TRANS_A   = 1u << 0,  // op(A) = A^T: A is stored k x m
+    TS_TRANS_B   = 1u << 1,  // op(B) = B^T: B is stored n x k
+    // Triangular operand (diagonal tiles of TRMM/TRSM, Eq. 1c-1d): only one triangle of the
+    // *stored* square tile is real data; the rest is read as zero (and as one on a unit
+    // diagonal) without touching memory contents' meaning.
+    TS_TRI_A     = 1u << 2,  // the mask applies to A
+    TS_TRI_B     = 1u << 3,  // the mask applies to B
+    TS_TRI_LOWER = 1u << 4,  // stored lower triangle is the data (else upper)
+    TS_TRI_UNIT  = 1u << 5,  // diagonal is taken as one
+    // Output triangle (diagonal tiles of SYRK, Eq. 1b): only this triangle of C is read/written.
+    TS_C_LOWER   = 1u << 6,
+    TS_C_UPPER   = 1u << 7,
+};
+
+// One k-deep pair of operand tiles.  Several of them chained in one TileStep are
+// summed into the same accumulators before C is touched once.
+struct TileSeg {
+    const void* A;
+    const void* B;
+    int32_t  k;              // inner dimension of this pair (> 0)
+    uint32_t flags;          // TS_TRI_* of this pair only
+};
+
+constexpr int kMaxChain = 4;
+
+// C <- alpha * sum_s op(A_s) op(B_s) + beta * C for one output tile.
+struct TileStep {
+    void*    C;
+    TileSeg  seg[kMaxChain];
+    int32_t  nseg;           // 0: C <- beta * C only
+    int32_t  lda, ldb, ldc;  // leading dimensions in elements (same for every pair)
+    int32_t  m, n;           // C is m x n
+    uint32_t flags;          // TS_TRANS_*, TS_C_*
+    uint32_t wg_begin;       // first workgroup (virtual index) of this step within its launch
+    double   alpha, beta;    // beta == 0: C is not read
+};
+
+// Up to this many tile steps travel by value in the kernel arguments of one launch
+// (the whole pack must stay below the 4 KB kernel-argument limit).
+constexpr int kMaxStepsPerLaunch = 26;
+
+struct LaunchPack {
+    int32_t  nsteps;
+    uint32_t total_wg;       // sum over steps of ceil(m/BM)*ceil(n/BN)
+    TileStep step[kMaxStepsPerLaunch];
+};
+static_assert(sizeof(LaunchPack) <= 4096, "launch pack must fit the kernel-argument segment");
+
+constexpr int kBM = 128;     // macro-tile rows of C per workgroup
+constexpr int kBN = 128;     // macro-tile columns of C per workgroup
+constexpr int kBK = 16;      // depth of one LDS slab
+
+inline uint32_t macro_tiles(int m, int n) {
+    return (uint32_t)((m + kBM - 1) / kBM) * (uint32_t)((n + kBN - 1) / kBN);
+}
+
+// True when a step can run in the unpredicated kernel: whole macro-tiles, k a multiple of the
+// slab depth, 16-byte aligned operands with even leading dimensions, no mask flag.
+inline bool step_is_fast(const TileStep& st, int dtype) {
+    const size_t esz = dtype == 0 ? 8 : 4;
+    if (st.m <= 0 || st.n <= 0 || st.m % kBM || st.n % kBN || st.lda % 2 || st.ldb % 2) return false;
+    if (st.flags & ~(TS_TRANS_A | TS_TRANS_B)) return false;
+    for (int s = 0; s < st.nseg; ++s) {
+        const TileSeg& sg = st.seg[s];
+        if (sg.flags || sg.k <= 0 || sg.k % kBK) return false;
+        if ((reinterpret_cast<uintptr_t>(sg.A) | reinterpret_cast<uintptr_t>(sg.B)) % (2 * esz)) return false;
+    }
+    return true;
+}
+
+}  // namespace blasx

@@ -1,0 +1,330 @@
+"""Host logic without a GPU: task builder, ALRU cache and scheduler, linked against the
+host-only device double in tests/sim (lazy, randomly interleaved execution that honours only
+stream order and event waits).  Results are compared with the oracle; counters are compared
+with what the method fixes (bytes moved when everything fits, reuse under a capped cache).
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle as ref
+import synth
+from paper_1510_05041_amd import _build, blasx
+
+ORDERS = [blasx.ColMajor, blasx.RowMajor]
+TRANS = [blasx.NoTrans, blasx.Trans]
+
+
+@pytest.fixture(scope="module")
+def sim():
+    lib = blasx.Library(_build.build_sim())
+    lib._lib.blasx_sim_seed.argtypes = [__import__("ctypes").c_uint64]
+    yield lib
+    lib.shutdown()
+
+
+def setup(sim, T, nstreams=4, arena_tiles=64, cap_tiles=0, seed=1, esize=8, **opts):
+    sim._lib.blasx_sim_seed(seed)
+    sim.init_raw(arena_tiles * T * T * esize, nstreams)
+    sim.set_tile(T)
+    sim.set_cache_bytes(cap_tiles * T * T * esize)
+    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, profile=0)
+    defaults.update(opts)
+    for k, v in defaults.items():
+        sim.set_option(k, v)
+    sim.reset_stats()
+
+
+def store(logical, order, pad=0, dtype=np.float64):
+    r, c = logical.shape
+    if order == blasx.ColMajor:
+        buf = np.full((r + pad, c), np.nan, dtype=dtype, order="F")
+    else:
+        buf = np.full((r, c + pad), np.nan, dtype=dtype, order="C")
+    v = buf[:r, :c]
+    v[...] = logical
+    return v
+
+
+def ld_of(a, order):
+    it = a.itemsize
+    if order == blasx.ColMajor:
+        return max(1, a.strides[1] // it if a.shape[1] > 1 else a.shape[0])
+    return max(1, a.strides[0] // it if a.shape[0] > 1 else a.shape[1])
+
+
+def relerr(got, want):
+    return np.linalg.norm(np.asarray(got, dtype=np.float64) - want) / max(np.linalg.norm(want), 1e-300)
+
+
+# ------------------------------------------------------------------ GEMM ----------
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("ta,tb", list(itertools.product(TRANS, TRANS)))
+@pytest.mark.parametrize("M,N,K", [(48, 48, 48), (37, 53, 41), (16, 80, 5), (1, 1, 1)])
+def test_gemm_matches_oracle(sim, order, ta, tb, M, N, K):
+    setup(sim, T=16, seed=M + N + K + ta + tb + order)
+    rng = np.random.default_rng(7)
+    A = rng.uniform(-1, 1, (M, K) if ta == blasx.NoTrans else (K, M))
+    B = rng.uniform(-1, 1, (K, N) if tb == blasx.NoTrans else (N, K))
+    C = rng.uniform(-1, 1, (M, N))
+    As, Bs, Cs, Cr = store(A, order, 3), store(B, order, 1), store(C, order, 2), store(C, order, 2)
+    sim.dgemm(order, ta, tb, M, N, K, 0.75, As, ld_of(As, order), Bs, ld_of(Bs, order), -0.5, Cs, ld_of(Cs, order))
+    ref.gemm(order, ta, tb, 0.75, As, Bs, -0.5, Cr)
+    assert relerr(Cs, np.asarray(Cr)) < 1e-14
+    st = sim.get_stats()
+    nt = lambda x: -(-x // 16)
+    assert st["tasks"] == nt(M) * nt(N)                       # one task per output tile (Section IV.A)
+    assert st["tile_steps"] == nt(M) * nt(N) * nt(K)
+    assert st["bytes_d2h"] == 8 * M * N
+    # everything fits: every tile of A, B and C crosses the link exactly once
+    assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N)
+    assert st["evictions"] == 0 and st["refetches"] == 0
+
+
+def test_gemm_integer_inputs_are_bit_exact_across_tilings(sim):
+    M, N, K = 70, 45, 90
+    A = synth.matrix(M, K, 3, 0, integers=True)
+    B = synth.matrix(K, N, 3, 1, integers=True)
+    C = synth.matrix(M, N, 3, 2, integers=True)
+    want = 2.0 * (np.asarray(A) @ np.asarray(B)) - np.asarray(C)
+    for T, kchain, group in [(16, 1, 1), (16, 4, 7), (32, 3, 4), (48, 2, 2), (128, 1, 4)]:
+        setup(sim, T=T, kchain=kchain, group=group, seed=T + kchain)
+        Cs = C.copy(order="F")
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 2.0, A, M, B, K, -1.0, Cs, M)
+        assert np.array_equal(Cs, want), (T, kchain, group)
+
+
+def test_gemm_beta_zero_never_reads_c_and_alpha_zero_never_reads_ab(sim):
+    setup(sim, T=16)
+    rng = np.random.default_rng(1)
+    M, N, K = 40, 24, 33
+    A, B = np.asfortranarray(rng.uniform(-1, 1, (M, K))), np.asfortranarray(rng.uniform(-1, 1, (K, N)))
+    Cs = np.full((M, N), np.nan, order="F")
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 1.0, A, M, B, K, 0.0, Cs, M)
+    assert relerr(Cs, A @ B) < 1e-14
+    assert sim.get_stats()["bytes_h2d"] == 8 * (M * K + K * N)         # C was not fetched
+    C = np.asfortranarray(rng.uniform(-1, 1, (M, N)))
+    Cs = C.copy(order="F")
+    nan = np.full((64, 64), np.nan, order="F")
+    sim.reset_stats()
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 0.0, nan, 64, nan, 64, 0.5, Cs, M)
+    assert np.array_equal(Cs, 0.5 * C)
+    assert sim.get_stats()["bytes_h2d"] == 8 * M * N
+    Cs = np.full((M, N), np.nan, order="F")
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 0.0, nan, 64, nan, 64, 0.0, Cs, M)
+    assert np.array_equal(Cs, np.zeros((M, N)))
+    # quick returns leave C alone and need no device
+    Cs = C.copy(order="F")
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, 0, 1.0, A, M, B, 1, 1.0, Cs, M)
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 0.0, A, M, B, K, 1.0, Cs, M)
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 0, N, K, 1.0, A, M, B, K, 0.0, Cs, M)
+    assert np.array_equal(Cs, C)
+
+
+def test_sgemm_matches_oracle(sim):
+    setup(sim, T=32, esize=4)
+    rng = np.random.default_rng(2)
+    M, N, K = 75, 66, 100
+    A = np.asfortranarray(rng.uniform(-1, 1, (M, K)).astype(np.float32))
+    B = np.asfortranarray(rng.uniform(-1, 1, (N, K)).astype(np.float32))
+    C = np.asfortranarray(rng.uniform(-1, 1, (M, N)).astype(np.float32))
+    Cs, Cr = C.copy(order="F"), C.copy(order="F")
+    sim.sgemm(blasx.ColMajor, blasx.NoTrans, blasx.Trans, M, N, K, 1.0, A, M, B, N, 1.0, Cs, M)
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, A, B, 1.0, Cr)
+    assert relerr(Cs, Cr.astype(np.float64)) < 1e-6
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_gemm_capped_cache_evicts_and_stays_correct(sim, seed):
+    """Out-of-core case in miniature: 12x12x12 tiles through a 20-slot cache."""
+    T, n = 16, 12 * 16
+    setup(sim, T=T, arena_tiles=64, cap_tiles=20, seed=100 + seed, group=4, kchain=2, depth=2 + seed % 3,
+          nstreams=2 + seed % 3)
+    A = synth.matrix(n, n, seed, 0)
+    B = synth.matrix(n, n, seed, 1)
+    C = synth.matrix(n, n, seed, 2)
+    Cs, Cr = C.copy(order="F"), C.copy(order="F")
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 0.0, Cs, n)
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.NoTrans, 1.0, A, B, 0.0, Cr)
+    assert relerr(Cs, Cr) < 1e-14
+    st = sim.get_stats()
+    assert st["peak_slots"] <= 20
+    assert st["evictions"] > 0 and st["refetches"] > 0
+    distinct = 2 * 12 * 12                                   # tiles of A and B
+    assert st["misses"] == distinct + st["refetches"]
+    assert st["hits"] + st["misses"] >= 2 * 12 ** 3           # two translations per tile step (+ retries)
+    assert not sim._lib.blasx_sim_deadlocked()
+
+
+def test_arena_too_small_is_an_error_not_a_hang(sim):
+    setup(sim, T=16, arena_tiles=3)
+    A = synth.matrix(64, 64, 0, 0)
+    C = np.zeros((64, 64), order="F")
+    rc = sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 64, 64, 64, 1.0, A, 64, A, 64, 0.0, C, 64, check=False)
+    assert rc == 2
+
+
+def test_argument_errors_follow_the_prototype_positions(sim):
+    setup(sim, T=16)
+    a = np.zeros((8, 8), order="F")
+    g = lambda *args: sim.dgemm(*args, check=False)
+    CM, NT = blasx.ColMajor, blasx.NoTrans
+    assert g(7, NT, NT, 8, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 8) == -1
+    assert g(CM, 5, NT, 8, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 8) == -2
+    assert g(CM, NT, 5, 8, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 8) == -3
+    assert g(CM, NT, NT, -1, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 8) == -4
+    assert g(CM, NT, NT, 8, -1, 8, 1.0, a, 8, a, 8, 0.0, a, 8) == -5
+    assert g(CM, NT, NT, 8, 8, -1, 1.0, a, 8, a, 8, 0.0, a, 8) == -6
+    assert g(CM, NT, NT, 8, 8, 8, 1.0, a, 7, a, 8, 0.0, a, 8) == -9
+    assert g(CM, NT, NT, 8, 8, 8, 1.0, a, 8, a, 7, 0.0, a, 8) == -11
+    assert g(CM, NT, NT, 8, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 7) == -14
+    assert sim.dsyrk(CM, 0, NT, 8, 8, 1.0, a, 8, 0.0, a, 8, check=False) == -2
+    assert sim.dtrsm(CM, blasx.Left, blasx.Lower, NT, 0, 8, 8, 1.0, a, 8, a, 8, check=False) == -5
+    assert sim.dtrmm(CM, blasx.Left, blasx.Lower, NT, blasx.Unit, 8, 8, 1.0, a, 4, a, 8, check=False) == -10
+    assert sim.set_option.__self__._lib.blasx_set_tile(20) == 4
+
+
+# ------------------------------------------------------------------ SYRK ----------
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("uplo", [blasx.Upper, blasx.Lower])
+@pytest.mark.parametrize("trans", TRANS)
+@pytest.mark.parametrize("beta", [0.0, 0.7])
+def test_syrk_matches_oracle_and_leaves_other_triangle(sim, order, uplo, trans, beta):
+    setup(sim, T=16, seed=uplo + trans + order)
+    rng = np.random.default_rng(3)
+    N, K = 57, 38
+    A = rng.uniform(-1, 1, (N, K) if trans == blasx.NoTrans else (K, N))
+    C = rng.uniform(-1, 1, (N, N))
+    other = np.triu_indices(N, 1) if uplo == blasx.Lower else np.tril_indices(N, -1)
+    C[other] = 777.125
+    As, Cs, Cr = store(A, order, 1), store(C, order, 2), store(C, order, 2)
+    sim.dsyrk(order, uplo, trans, N, K, 1.5, As, ld_of(As, order), beta, Cs, ld_of(Cs, order))
+    ref.syrk(order, uplo, trans, 1.5, As, beta, Cr)
+    assert np.all(np.asarray(Cs)[other] == 777.125)
+    assert relerr(Cs, np.asarray(Cr)) < 1e-14
+    nt = -(-N // 16)
+    assert sim.get_stats()["tasks"] == nt * (nt + 1) // 2
+
+
+# ------------------------------------------------------------------ TRMM / TRSM ---
+
+FLAGS = list(itertools.product([blasx.Left, blasx.Right], [blasx.Upper, blasx.Lower], TRANS, [blasx.NonUnit, blasx.Unit]))
+
+
+def poisoned(rng, n, uplo, diag, dominant=False):
+    A = rng.uniform(-1, 1, (n, n))
+    A[np.diag_indices(n)] = (n + rng.uniform(0, 1, n)) if dominant else rng.uniform(1, 2, n)
+    P = A.copy()
+    for r in range(n):
+        for c in range(n):
+            outside = (r < c) if uplo == blasx.Lower else (r > c)
+            if outside or (r == c and diag == blasx.Unit):
+                P[r, c] = np.nan
+    return P
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS)
+def test_trmm_matches_oracle(sim, order, side, uplo, trans, diag):
+    setup(sim, T=16, seed=side + uplo + trans + diag + order, group=5)
+    rng = np.random.default_rng(4)
+    M, N = 52, 39
+    P = poisoned(rng, M if side == blasx.Left else N, uplo, diag)
+    B = rng.uniform(-1, 1, (M, N))
+    Ps, Bs, Br = store(P, order, 2), store(B, order, 1), store(B, order, 1)
+    sim.dtrmm(order, side, uplo, trans, diag, M, N, -0.8, Ps, ld_of(Ps, order), Bs, ld_of(Bs, order))
+    ref.trmm(order, side, uplo, trans, diag, -0.8, Ps, Br)
+    assert np.all(np.isfinite(np.asarray(Bs)))
+    assert relerr(Bs, np.asarray(Br)) < 1e-14
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS)
+def test_trsm_matches_oracle_and_residual(sim, order, side, uplo, trans, diag):
+    setup(sim, T=16, seed=3 * side + uplo + trans + diag + order, group=4)
+    rng = np.random.default_rng(5)
+    M, N = 45, 58
+    n = M if side == blasx.Left else N
+    P = poisoned(rng, n, uplo, diag, dominant=True)
+    if diag == blasx.Unit:          # keep the unit-diagonal system well conditioned
+        P = np.where(np.isnan(P), P, P / n)
+    B = rng.uniform(-1, 1, (M, N))
+    Ps, Bs, Br = store(P, order, 1), store(B, order, 2), store(B, order, 2)
+    sim.dtrsm(order, side, uplo, trans, diag, M, N, 1.25, Ps, ld_of(Ps, order), Bs, ld_of(Bs, order))
+    ref.trsm(order, side, uplo, trans, diag, 1.25, Ps, Br)
+    X = np.asarray(Bs)
+    assert np.all(np.isfinite(X))
+    assert relerr(X, np.asarray(Br)) < 1e-13
+    # residual ||op(A) X - alpha B|| / (||A|| ||X||), formed by the oracle's TRMM
+    R = store(X, order)
+    ref.trmm(order, side, uplo, trans, diag, 1.0, Ps, R)
+    Tn = np.linalg.norm(np.nan_to_num(P)) + (np.sqrt(n) if diag == blasx.Unit else 0)
+    assert np.linalg.norm(np.asarray(R) - 1.25 * B) / (Tn * np.linalg.norm(X)) < 1e-13
+
+
+def test_trsm_large_tile_inverse_levels(sim):
+    """A diagonal tile larger than the directly inverted blocks exercises the merge levels."""
+    setup(sim, T=96, seed=9, group=3, arena_tiles=40)
+    rng = np.random.default_rng(6)
+    M, N = 200, 100
+    for uplo in (blasx.Lower, blasx.Upper):
+        P = poisoned(rng, M, uplo, blasx.NonUnit, dominant=True)
+        B = np.asfortranarray(rng.uniform(-1, 1, (M, N)))
+        Ps, Bs, Br = store(P, blasx.ColMajor), B.copy(order="F"), B.copy(order="F")
+        sim.dtrsm(blasx.ColMajor, blasx.Left, uplo, blasx.NoTrans, blasx.NonUnit, M, N, 1.0, Ps, M, Bs, M)
+        ref.trsm(ref.ColMajor, ref.Left, uplo, ref.NoTrans, ref.NonUnit, 1.0, Ps, Br)
+        assert relerr(Bs, Br) < 1e-13
+
+
+def test_trsm_alpha_zero_gives_zero_without_reading_a(sim):
+    setup(sim, T=16)
+    B = np.asfortranarray(np.random.default_rng(0).uniform(-1, 1, (30, 20)))
+    nan = np.full((30, 30), np.nan, order="F")
+    sim.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, 30, 20, 0.0, nan, 30, B, 30)
+    assert np.array_equal(B, np.zeros((30, 20)))
+
+
+# ------------------------------------------------------------------ structure -----
+
+def test_tile_counts_match_the_papers_formulas(sim):
+    """tests/golden/tile_counts.txt: Section III.A tile counts, Section IV.A degree of parallelism."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "tile_counts.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        rows, cols, T, square, nonsquare, dop = map(int, line.split())
+        assert (rows // T) * (cols // T) == square
+        assert -(-rows // T) * -(-cols // T) - square == nonsquare
+        assert square + nonsquare == dop
+        if rows * cols <= 300 * 300:        # the task builder makes exactly `dop` tasks
+            setup(sim, T=max(16, T - T % 16) if T >= 16 else 16)
+            Teff = sim.get_option("tile")
+            A = np.zeros((rows, 16), order="F")
+            B = np.zeros((16, cols), order="F")
+            C = np.zeros((rows, cols), order="F")
+            sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, rows, cols, 16, 1.0, A, rows, B, 16, 0.0, C, rows)
+            assert sim.get_stats()["tasks"] == -(-rows // Teff) * -(-cols // Teff)
+
+
+def test_run_to_run_reproducible_and_interleaving_independent(sim):
+    n = 96
+    A, B = synth.matrix(n, n, 11, 0), synth.matrix(n, n, 11, 1)
+    outs = []
+    # With room for every tile no scheduling decision depends on device timing, so the grouping
+    # of k-steps -- and with it every rounding -- is the same whatever the interleaving.
+    for seed in (1, 2, 3):
+        setup(sim, T=16, seed=seed, group=6, kchain=3, arena_tiles=128)
+        C = np.zeros((n, n), order="F")
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 0.0, C, n)
+        outs.append(C)
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    # Under slot pressure a chain may be cut where a tile was not yet available: same sums,
+    # possibly grouped differently, i.e. equal up to rounding.
+    setup(sim, T=16, seed=4, group=6, kchain=3, arena_tiles=40)
+    C = np.zeros((n, n), order="F")
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 0.0, C, n)
+    assert relerr(C, outs[0]) < 1e-15
