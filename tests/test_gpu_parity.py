@@ -1,0 +1,296 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, same seeded inputs.
+
+Small and ragged cases compare every element; the benchmark-sized cases compare sampled
+elements of 64 sampled output tiles (the oracle computes each sampled element from the rows of
+A and columns of B it needs).  Gates: normwise relative error 1e-13 (fp64), 1e-5 (fp32); TRSM
+also by the residual ||op(A) X - alpha B|| / (||A|| ||X||) <= 1e-13.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle as ref
+import synth
+from paper_1510_05041_amd import blasx
+
+pytestmark = pytest.mark.gpu
+
+TOL64, TOL32 = 1e-13, 1e-5
+TRANS = [blasx.NoTrans, blasx.Trans]
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    assert torch.cuda.is_available()
+    L = blasx.default()
+    yield L
+    L.shutdown()
+
+
+def configure(L, T, nstreams=4, arena_gb=2.0, cap_bytes=0, **opts):
+    L.init(int(arena_gb * 2 ** 30), nstreams=nstreams)
+    L.set_tile(T)
+    L.set_cache_bytes(cap_bytes)
+    defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, profile=0)
+    defaults.update(opts)
+    for k, v in defaults.items():
+        L.set_option(k, v)
+    L.reset_stats()
+
+
+def pinned(rows, cols, seed, mat, dtype=np.float64, ld=None, integers=False):
+    a, owner = blasx.pinned_matrix(rows, cols, dtype=dtype, ld=ld)
+    if rows and cols:
+        synth.fill(a, seed, mat, integers=integers)
+    return a, owner
+
+
+def relerr(got, want):
+    want = np.asarray(want, dtype=np.float64)
+    return np.linalg.norm(np.asarray(got, dtype=np.float64) - want) / max(np.linalg.norm(want), 1e-300)
+
+
+# ------------------------------------------------------------------ small, full compare --
+
+def test_config1_dgemm_1024_tile256_two_streams_full_output(lib):
+    """DGEMM NN, M=N=K=1024, uniform[-1,1] seed 0, alpha=1, beta=0.5, T=256, 2 streams."""
+    n = 1024
+    configure(lib, T=256, nstreams=2, arena_gb=0.25)
+    A, ka = pinned(n, n, 0, synth.MAT_A)
+    B, kb = pinned(n, n, 0, synth.MAT_B)
+    C, kc = pinned(n, n, 0, synth.MAT_C)
+    want = np.array(C, order="F")
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 0.5, C, n)
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.NoTrans, 1.0, np.asarray(A), np.asarray(B), 0.5, want)
+    assert relerr(C, want) < TOL64
+    st = lib.get_stats()
+    assert st["tasks"] == 16 and st["tile_steps"] == 64
+    assert st["bytes_h2d"] == 3 * 8 * n * n and st["bytes_d2h"] == 8 * n * n
+
+
+@pytest.mark.parametrize("order", [blasx.ColMajor, blasx.RowMajor])
+@pytest.mark.parametrize("ta,tb", list(itertools.product(TRANS, TRANS)))
+def test_dgemm_ragged_all_transposes(lib, order, ta, tb):
+    """Several tiles, ragged tails in every dimension, padded leading dimensions."""
+    M, N, K = 389, 270, 333
+    configure(lib, T=128, arena_gb=0.25, group=5, kchain=3)
+    rng = np.random.default_rng(M + ta + 2 * tb + order)
+    shape_a = (M, K) if ta == blasx.NoTrans else (K, M)
+    shape_b = (K, N) if tb == blasx.NoTrans else (N, K)
+
+    def stored(shape, pad):
+        """(logical view, array whose address is passed, leading dimension, owner)."""
+        r, c = shape
+        if order == blasx.ColMajor:
+            v, owner = blasx.pinned_matrix(r, c, ld=r + pad)
+            logical = v
+        else:   # a row-major r x c matrix is the column-major c x r matrix of its transpose
+            v, owner = blasx.pinned_matrix(c, r, ld=c + pad)
+            logical = v.T
+        logical[...] = rng.uniform(-1, 1, (r, c))
+        return logical, v, v.strides[1] // 8, owner
+
+    A, pa, lda, ka = stored(shape_a, 3)
+    B, pb, ldb, kb = stored(shape_b, 0)
+    C, pc, ldc, kc = stored((M, N), 5)
+    want = np.array(C, order="F")
+    lib.dgemm(order, ta, tb, M, N, K, -0.75, pa, lda, pb, ldb, 0.3, pc, ldc)
+    opa = np.asarray(A) if ta == blasx.NoTrans else np.asarray(A).T
+    opb = np.asarray(B) if tb == blasx.NoTrans else np.asarray(B).T
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.NoTrans, -0.75, np.asfortranarray(opa), np.asfortranarray(opb), 0.3, want)
+    assert relerr(C, want) < TOL64
+
+
+def test_dgemm_integer_inputs_bit_exact(lib):
+    M, N, K = 640, 384, 1000
+    configure(lib, T=256, arena_gb=0.25)
+    A, ka = pinned(M, K, 3, 0, integers=True)
+    B, kb = pinned(K, N, 3, 1, integers=True)
+    C, kc = pinned(M, N, 3, 2, integers=True)
+    want = 2.0 * (np.asarray(A) @ np.asarray(B)) - np.asarray(C)
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 2.0, A, M, B, K, -1.0, C, M)
+    assert np.array_equal(np.asarray(C), want)
+
+
+def test_dgemm_beta_zero_ignores_nan_and_empty_inputs(lib):
+    M, N, K = 300, 200, 260
+    configure(lib, T=128, arena_gb=0.25)
+    A, ka = pinned(M, K, 4, 0)
+    B, kb = pinned(K, N, 4, 1)
+    C, kc = blasx.pinned_matrix(M, N)
+    C[...] = np.nan
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 1.0, A, M, B, K, 0.0, C, M)
+    want = np.zeros((M, N), order="F")
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.NoTrans, 1.0, np.asarray(A), np.asarray(B), 0.0, want)
+    assert relerr(C, want) < TOL64
+    before = np.array(C)
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 0, N, K, 1.0, A, M, B, K, 0.0, C, M)
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, 0, 1.0, A, M, B, 1, 1.0, C, M)
+    assert np.array_equal(np.asarray(C), before)
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, 0, 1.0, A, M, B, 1, 2.0, C, M)
+    assert np.array_equal(np.asarray(C), 2.0 * before)
+
+
+def test_dgemm_pageable_host_memory(lib):
+    """Plain numpy (not page-locked) matrices still work, only without asynchronous DMA."""
+    n = 512
+    configure(lib, T=128, arena_gb=0.25)
+    A, B, C = synth.matrix(n, n, 5, 0), synth.matrix(n, n, 5, 1), synth.matrix(n, n, 5, 2)
+    want = C.copy(order="F")
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.Trans, n, n, n, 1.0, A, n, B, n, 1.0, C, n)
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, A, B, 1.0, want)
+    assert relerr(C, want) < TOL64
+
+
+def test_sgemm_small_full_compare(lib):
+    M, N, K = 700, 520, 900
+    configure(lib, T=256, arena_gb=0.25)
+    A, ka = pinned(M, K, 6, 0, dtype=np.float32)
+    B, kb = pinned(N, K, 6, 1, dtype=np.float32)
+    C, kc = pinned(M, N, 6, 2, dtype=np.float32)
+    want = np.array(C, order="F")
+    lib.sgemm(blasx.ColMajor, blasx.NoTrans, blasx.Trans, M, N, K, 1.0, A, M, B, N, 1.0, C, M)
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, np.asarray(A), np.asarray(B), 1.0, want)
+    assert relerr(C, want) < TOL32
+
+
+def test_dgemm_capped_cache_eviction(lib):
+    """Tile cache capped to 40 slots while A and B have 128 tiles: ALRU must evict and refetch."""
+    n, T = 2048, 256
+    configure(lib, T=T, arena_gb=0.25, cap_bytes=40 * T * T * 8, group=8, kchain=2)
+    A, ka = pinned(n, n, 7, 0)
+    B, kb = pinned(n, n, 7, 1)
+    C, kc = pinned(n, n, 7, 2)
+    want = np.array(C, order="F")
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 1.0, C, n)
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.NoTrans, 1.0, np.asarray(A), np.asarray(B), 1.0, want)
+    assert relerr(C, want) < TOL64
+    st = lib.get_stats()
+    assert st["peak_slots"] <= 40 and st["evictions"] > 0 and st["refetches"] > 0
+    assert st["misses"] == 128 + st["refetches"]
+
+
+def test_run_to_run_bit_reproducible(lib):
+    n = 1536
+    configure(lib, T=256, arena_gb=0.5)
+    A, ka = pinned(n, n, 8, 0)
+    B, kb = pinned(n, n, 8, 1)
+    outs = []
+    for _ in range(3):
+        C, kc = blasx.pinned_matrix(n, n)
+        C[...] = 0
+        lib.dgemm(blasx.ColMajor, blasx.Trans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 0.0, C, n)
+        outs.append(np.array(C))
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+# ------------------------------------------------------------------ SYRK / TRMM / TRSM ---
+
+@pytest.mark.parametrize("uplo", [blasx.Upper, blasx.Lower])
+@pytest.mark.parametrize("trans", TRANS)
+def test_dsyrk_small_full_compare(lib, uplo, trans):
+    N, K = 650, 410
+    configure(lib, T=128, arena_gb=0.25, group=6)
+    A, ka = pinned(*((N, K) if trans == blasx.NoTrans else (K, N)), 9, 0)
+    C, kc = pinned(N, N, 9, 2)
+    other = np.triu_indices(N, 1) if uplo == blasx.Lower else np.tril_indices(N, -1)
+    C[other] = 4321.5
+    want = np.array(C, order="F")
+    lib.dsyrk(blasx.ColMajor, uplo, trans, N, K, 0.9, A, A.shape[0], 1.0, C, N)
+    ref.syrk(ref.ColMajor, uplo, trans, 0.9, np.asarray(A), 1.0, want)
+    assert np.all(np.asarray(C)[other] == 4321.5)
+    assert relerr(C, want) < TOL64
+
+
+FLAGS = list(itertools.product([blasx.Left, blasx.Right], [blasx.Upper, blasx.Lower], TRANS, [blasx.NonUnit, blasx.Unit]))
+
+
+def triangular(n, seed, uplo, diag):
+    A, ka = pinned(n, n, seed, 0)
+    synth.dominant_diag(A, seed, 0)
+    if diag == blasx.Unit:
+        A[...] = np.asarray(A) / n
+    outside = np.triu_indices(n, 1) if uplo == blasx.Lower else np.tril_indices(n, -1)
+    A[outside] = np.nan                      # never read
+    if diag == blasx.Unit:
+        A[np.diag_indices(n)] = np.nan       # never read either
+    return A, ka
+
+
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS)
+def test_dtrmm_small_full_compare(lib, side, uplo, trans, diag):
+    M, N = 530, 390
+    configure(lib, T=128, arena_gb=0.25, group=6)
+    A, ka = triangular(M if side == blasx.Left else N, 10, uplo, diag)
+    B, kb = pinned(M, N, 10, 1)
+    want = np.array(B, order="F")
+    lib.dtrmm(blasx.ColMajor, side, uplo, trans, diag, M, N, 1.1, A, A.shape[0], B, M)
+    ref.trmm(ref.ColMajor, side, uplo, trans, diag, 1.1, np.asarray(A), want)
+    assert np.all(np.isfinite(np.asarray(B)))
+    assert relerr(B, want) < TOL64
+
+
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS)
+def test_dtrsm_small_full_compare_and_residual(lib, side, uplo, trans, diag):
+    M, N = 530, 390
+    configure(lib, T=128, arena_gb=0.25, group=6)
+    n = M if side == blasx.Left else N
+    A, ka = triangular(n, 11, uplo, diag)
+    B, kb = pinned(M, N, 11, 1)
+    B0 = np.array(B, order="F")
+    want = np.array(B, order="F")
+    lib.dtrsm(blasx.ColMajor, side, uplo, trans, diag, M, N, 0.7, A, n, B, M)
+    ref.trsm(ref.ColMajor, side, uplo, trans, diag, 0.7, np.asarray(A), want)
+    X = np.array(B, order="F")
+    assert np.all(np.isfinite(X))
+    assert relerr(X, want) < TOL64
+    R = X.copy(order="F")
+    ref.trmm(ref.ColMajor, side, uplo, trans, diag, 1.0, np.asarray(A), R)
+    norm_a = np.linalg.norm(np.nan_to_num(np.asarray(A))) + (np.sqrt(n) if diag == blasx.Unit else 0.0)
+    assert np.linalg.norm(R - 0.7 * B0) / (norm_a * np.linalg.norm(X)) < TOL64
+
+
+# ------------------------------------------------------------------ benchmark sizes, sampled --
+
+def sampled_positions(T, rows, cols, rng, count=8):
+    """Tile-local row and column positions: edges of the tile and of the 128-wide macro-tiles, plus random ones."""
+    def pick(extent):
+        fixed = [p for p in (0, 127, 128, extent - 1) if 0 <= p < extent]
+        rand = rng.integers(0, extent, size=max(0, count - len(fixed))).tolist()
+        return sorted(set(fixed + rand))
+    return pick(rows), pick(cols)
+
+
+def check_gemm_sampled(ta, tb, M, N, K, alpha, A, B, beta, C_before_fn, C, T, seed, tol, dtype=np.float64):
+    """Oracle on sampled elements of 64 sampled output tiles; returns the worst tile error."""
+    rng = np.random.default_rng(seed)
+    ntm, ntn = -(-M // T), -(-N // T)
+    worst = 0.0
+    for (ti, tj) in synth.sample_tiles(ntm, ntn, 64, seed):
+        rows, cols = sampled_positions(T, min(T, M - ti * T), min(T, N - tj * T), rng)
+        gi = np.array(rows) + ti * T
+        gj = np.array(cols) + tj * T
+        a = np.asarray(A[gi, :] if ta == blasx.NoTrans else A[:, gi].T, dtype=dtype, order="F")
+        b = np.asarray(B[:, gj] if tb == blasx.NoTrans else B[gj, :].T, dtype=dtype, order="F")
+        want = np.asfortranarray(C_before_fn(gi, gj).astype(dtype))
+        ref.gemm(ref.ColMajor, ref.NoTrans, ref.NoTrans, alpha, a, b, beta, want)
+        got = np.asarray(C)[np.ix_(gi, gj)]
+        worst = max(worst, relerr(got, want))
+    assert worst < tol, worst
+    return worst
+
+
+@pytest.mark.parametrize("n", [4096, 8192])
+def test_config2_dgemm_square_sampled(lib, n):
+    """DGEMM NN, alpha=beta=1, T=1024, 4 streams, host-resident; 64 sampled tiles."""
+    configure(lib, T=1024, nstreams=4, arena_gb=8.0)
+    A, ka = pinned(n, n, 0, synth.MAT_A)
+    B, kb = pinned(n, n, 0, synth.MAT_B)
+    C, kc = pinned(n, n, 0, synth.MAT_C)
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 1.0, C, n)
+    before = lambda gi, gj: np.array([[synth.element(0, synth.MAT_C, int(i), int(j), n) for j in gj] for i in gi])
+    check_gemm_sampled(blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, B, 1.0, before, C, 1024, n, TOL64)
+    st = lib.get_stats()
+    assert st["bytes_h2d"] == 3 * 8 * n * n and st["evictions"] == 0
