@@ -20,11 +20,12 @@ if ROOT not in sys.path:
 FP64_MFMA_PEAK_TFLOPS = 78.6     # MI355X dense FP64 matrix peak (published)
 
 
-def cpu_baseline(np, oracle, A, B, n, rows=1024, cols=192):
+def cpu_baseline(np, oracle, A, B, n, rows=2048, cols=8192):
     """The oracle, as it stands, on a bounded sample of the same workload: a rows x cols block of the
     output, full inner dimension (2*rows*cols*n flop)."""
-    a = np.asfortranarray(A[:rows, :])
-    b = np.asfortranarray(B[:, :cols])
+    rows, cols = min(rows, n), min(cols, n)
+    a = A[:rows, :]          # views: the oracle takes the leading dimension from the strides
+    b = B[:, :cols]
     c = np.zeros((rows, cols), order="F")
     t0 = time.perf_counter()
     oracle.gemm(oracle.ColMajor, oracle.NoTrans, oracle.NoTrans, 1.0, a, b, 0.0, c)
