@@ -4,5 +4,5 @@
 built by ``__graft_entry__.build()`` into ``paper_1510_05041_amd/libblasx.so``.
 """
 from . import blasx  # noqa: F401
-from .blasx import (BlasxError, ColMajor, ConjTrans, Left, Library, Lower, NonUnit, NoTrans, Right,  # noqa: F401
+from .blasx import (BlasxError, HostBuffer, ColMajor, ConjTrans, Left, Library, Lower, NonUnit, NoTrans, Right,  # noqa: F401
                     RowMajor, Trans, Unit, Upper, default, pinned_matrix)

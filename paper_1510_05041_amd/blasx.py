@@ -185,16 +185,39 @@ class Library:
         return rc
 
 
-def pinned_matrix(rows, cols, dtype=np.float64, ld=None):
-    """Column-major rows x cols numpy view (leading dimension ld) of a page-locked torch buffer.
+class HostBuffer:
+    """Page-locked host memory from blasx_host_alloc, released when the object dies."""
 
-    Returns (view, owner); keep ``owner`` alive as long as the view is used.
+    def __init__(self, lib, nbytes):
+        self._lib = lib
+        self.nbytes = int(nbytes)
+        self.ptr = lib.host_alloc(max(self.nbytes, 8))
+
+    def free(self):
+        if self.ptr:
+            self._lib.host_free(self.ptr)
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def pinned_matrix(rows, cols, dtype=np.float64, ld=None, lib=None):
+    """Column-major rows x cols numpy view (leading dimension ld) of page-locked host memory.
+
+    Returns (view, owner); keep ``owner`` alive as long as the view is used (``owner.free()``
+    releases the memory at once).
     """
-    import torch
+    lib = lib or default()
     ld = max(rows, 1) if ld is None else ld
-    tdt = {np.dtype(np.float64): torch.float64, np.dtype(np.float32): torch.float32}[np.dtype(dtype)]
-    owner = torch.empty(int(ld) * int(max(cols, 1)), dtype=tdt, pin_memory=True)
-    flat = owner.numpy()
+    dt = np.dtype(dtype)
+    count = int(ld) * int(max(cols, 1))
+    owner = HostBuffer(lib, count * dt.itemsize)
+    raw = (ctypes.c_char * (count * dt.itemsize)).from_address(owner.ptr)
+    flat = np.frombuffer(raw, dtype=dt, count=count)
     view = flat.reshape((max(cols, 1), ld)).T[:rows, :cols]
     return view, owner
 

@@ -294,3 +294,134 @@ def test_config2_dgemm_square_sampled(lib, n):
     check_gemm_sampled(blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, B, 1.0, before, C, 1024, n, TOL64)
     st = lib.get_stats()
     assert st["bytes_h2d"] == 3 * 8 * n * n and st["evictions"] == 0
+
+
+def report(name, lib, flop, seconds):
+    st = lib.get_stats()
+    print("\n[result] %s: %.3f s, %.1f TFLOP/s; h2d %.2f GB d2h %.2f GB; hits %d misses %d evictions %d refetches %d "
+          "slot_waits %d peak_slots %d launches %d" % (
+              name, seconds, flop / seconds / 1e12, st["bytes_h2d"] / 1e9, st["bytes_d2h"] / 1e9, st["hits"], st["misses"],
+              st["evictions"], st["refetches"], st["slot_waits"], st["peak_slots"], st["launches"]), flush=True)
+    return st
+
+
+def timed(fn):
+    import time
+    t0 = time.perf_counter()
+    fn()
+    return time.perf_counter() - t0
+
+
+def c_before(seed, mat, rows):
+    return lambda gi, gj: np.array([[synth.element(seed, mat, int(i), int(j), rows) for j in gj] for i in gi])
+
+
+@pytest.mark.parametrize("n", [16384, 32768])
+def test_config2_dgemm_large_sampled(lib, n):
+    """The benchmark workload itself (N=32768) and the size below it, in the launch configuration bench.py times."""
+    configure(lib, T=1024, nstreams=4, arena_gb=(2 * 8 * n * n + 160 * 8 * 2 ** 20) / 2 ** 30)
+    A, ka = pinned(n, n, 0, synth.MAT_A)
+    B, kb = pinned(n, n, 0, synth.MAT_B)
+    C, kc = pinned(n, n, 0, synth.MAT_C)
+    dt = timed(lambda: lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 1.0, C, n))
+    st = report("cfg2 DGEMM NN N=%d T=1024" % n, lib, 2.0 * n ** 3, dt)
+    check_gemm_sampled(blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, B, 1.0, c_before(0, synth.MAT_C, n), C, 1024, n, TOL64)
+    assert st["bytes_h2d"] == 3 * 8 * n * n and st["bytes_d2h"] == 8 * n * n and st["evictions"] == 0
+
+
+def test_config3_out_of_core_dgemm_capped_cache(lib):
+    """M=N=K=49152 fp64 (58 GB of operands), beta=0, T=2048, tile cache capped at 8 GB: ALRU eviction and reuse."""
+    import psutil
+    n, T = 49152, 2048
+    if psutil.virtual_memory().available < 3 * 8 * n * n * 1.15:
+        n = 32768           # same cap and tile on the largest size the host can page-lock
+    configure(lib, T=T, nstreams=4, arena_gb=8.0, cap_bytes=8 * 2 ** 30, group=16, kchain=2, depth=3)
+    A, ka = pinned(n, n, 0, synth.MAT_A)
+    B, kb = pinned(n, n, 0, synth.MAT_B)
+    C, kc = blasx.pinned_matrix(n, n)
+    dt = timed(lambda: lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 0.0, C, n))
+    st = report("cfg3 out-of-core DGEMM N=%d T=2048 cap 8 GB" % n, lib, 2.0 * n ** 3, dt)
+    check_gemm_sampled(blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, B, 0.0, lambda gi, gj: np.zeros((len(gi), len(gj))),
+                       C, T, 3, TOL64)
+    nt = n // T
+    assert st["peak_slots"] <= 256
+    assert st["evictions"] > 0 and st["refetches"] > 0
+    assert st["misses"] == 2 * nt * nt + st["refetches"]
+    assert st["bytes_d2h"] == 8 * n * n
+
+
+def test_config4_dsyrk_lower_notrans_sampled(lib):
+    """DSYRK Lower/NoTrans N=16384 K=8192, alpha=1, beta=1 (beta is not stated in the workload list; 1 as in the GEMM sweep)."""
+    N, K, T = 16384, 8192, 1024
+    configure(lib, T=T, nstreams=4, arena_gb=8.0)
+    A, ka = pinned(N, K, 4, synth.MAT_A)
+    C, kc = pinned(N, N, 4, synth.MAT_C)
+    dt = timed(lambda: lib.dsyrk(blasx.ColMajor, blasx.Lower, blasx.NoTrans, N, K, 1.0, A, N, 1.0, C, N))
+    report("cfg4 DSYRK L/N N=16384 K=8192", lib, 1.0 * N * (N + 1) * K, dt)
+    rng = np.random.default_rng(4)
+    nt = N // T
+    before = c_before(4, synth.MAT_C, N)
+    worst, seen = 0.0, 0
+    for (ti, tj) in synth.sample_tiles(nt, nt, 64, 4):
+        rows, cols = sampled_positions(T, T, T, rng)
+        gi, gj = np.array(rows) + ti * T, np.array(cols) + tj * T
+        got = np.asarray(C)[np.ix_(gi, gj)]
+        c0 = before(gi, gj)
+        if ti < tj:                                    # upper triangle: must be bit-identical
+            assert np.array_equal(got, c0)
+            continue
+        want = np.asfortranarray(c0)
+        ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, np.asfortranarray(A[gi, :]), np.asfortranarray(A[gj, :]), 1.0, want)
+        mask = (gi[:, None] >= gj[None, :])            # inside a diagonal tile only the lower part is written
+        assert np.array_equal(got[~mask], c0[~mask])
+        worst = max(worst, relerr(got[mask], want[mask]))
+        seen += 1
+    assert seen > 10 and worst < TOL64, worst
+
+
+def test_config4_dtrsm_left_lower_notrans_nonunit_residual(lib):
+    """DTRSM Left/Lower/NoTrans/NonUnit M=N=16384, A with diag = N + uniform[0,1], alpha=1; residual on sampled columns."""
+    M = N = 16384
+    T = 1024
+    configure(lib, T=T, nstreams=4, arena_gb=12.0)
+    A, ka = pinned(M, M, 5, synth.MAT_A)
+    synth.dominant_diag(A, 5, synth.MAT_A)
+    B, kb = pinned(M, N, 5, synth.MAT_B)
+    dt = timed(lambda: lib.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, M, N, 1.0, A, M, B, M))
+    report("cfg4 DTRSM L/L/N/N M=N=16384", lib, 1.0 * M * M * N, dt)
+    cols = np.random.default_rng(5).choice(N, 16, replace=False)
+    X = np.asfortranarray(np.asarray(B)[:, cols])
+    assert np.all(np.isfinite(X))
+    R = X.copy(order="F")
+    ref.trmm(ref.ColMajor, ref.Left, ref.Lower, ref.NoTrans, ref.NonUnit, 1.0, np.asarray(A), R)
+    B0 = np.array([[synth.element(5, synth.MAT_B, i, int(j), M) for j in cols] for i in range(M)])
+    norm_a = np.sqrt(sum(float(np.dot(A[j:, j], A[j:, j])) for j in range(M)))
+    res = np.linalg.norm(R - B0) / (norm_a * np.linalg.norm(X))
+    assert res < TOL64, res
+
+
+def test_config5a_dgemm_trans_notrans_long_k_sampled(lib):
+    """DGEMM Trans/NoTrans M=N=8192 K=65536 (A stored 65536 x 8192), alpha=beta=1, T=1024."""
+    M = N = 8192
+    K, T = 65536, 1024
+    configure(lib, T=T, nstreams=4, arena_gb=10.0)
+    A, ka = pinned(K, M, 6, synth.MAT_A)
+    B, kb = pinned(K, N, 6, synth.MAT_B)
+    C, kc = pinned(M, N, 6, synth.MAT_C)
+    dt = timed(lambda: lib.dgemm(blasx.ColMajor, blasx.Trans, blasx.NoTrans, M, N, K, 1.0, A, K, B, K, 1.0, C, M))
+    report("cfg5a DGEMM TN 8192x8192x65536", lib, 2.0 * M * N * K, dt)
+    check_gemm_sampled(blasx.Trans, blasx.NoTrans, M, N, K, 1.0, A, B, 1.0, c_before(6, synth.MAT_C, M), C, T, 6, TOL64)
+
+
+def test_config5b_sgemm_notrans_trans_sampled(lib):
+    """SGEMM NoTrans/Trans M=N=K=32768 fp32, alpha=beta=1, T=2048."""
+    n, T = 32768, 2048
+    configure(lib, T=T, nstreams=4, arena_gb=(2 * 4 * n * n + 64 * 4 * T * T) / 2 ** 30)
+    A, ka = pinned(n, n, 7, synth.MAT_A, dtype=np.float32)
+    B, kb = pinned(n, n, 7, synth.MAT_B, dtype=np.float32)
+    C, kc = pinned(n, n, 7, synth.MAT_C, dtype=np.float32)
+    dt = timed(lambda: lib.sgemm(blasx.ColMajor, blasx.NoTrans, blasx.Trans, n, n, n, 1.0, A, n, B, n, 1.0, C, n))
+    report("cfg5b SGEMM NT N=32768 T=2048", lib, 2.0 * n ** 3, dt)
+    before = lambda gi, gj: np.array([[np.float32(synth.element(7, synth.MAT_C, int(i), int(j), n)) for j in gj] for i in gi],
+                                     dtype=np.float32)
+    check_gemm_sampled(blasx.NoTrans, blasx.Trans, n, n, n, 1.0, A, B, 1.0, before, C, T, 7, TOL32, dtype=np.float32)
