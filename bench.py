@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--arena-gb", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check", action="store_true", help="also compare sampled outputs with the oracle")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the benchmark, run plain device copies of a known size (1 GiB read + 1 GiB written "
+                         "per dispatch) so that HBM byte counters can be scaled")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -69,6 +72,15 @@ def main():
         print("bench.py: no GPU visible; the HIP library cannot run", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(2 ** 27, dtype=torch.float64, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_dispatch": 2 ** 30, "bytes_written_per_dispatch": 2 ** 30,
+                                               "dispatches": 4}}))
+        return
     lib = blasx.default()                      # raises if libblasx.so is not built
 
     n, T = args.n, args.tile
@@ -124,6 +136,13 @@ def main():
     flop_per_launch = st["flops"] / max(1, st["launches"])
     achieved = flop_per_launch / avg_launch_s / 1e12 if avg_launch_s > 0 else 0.0
 
+    # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command, scaled by the
+    # same counters on a plain 1 GiB device copy (profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md); they are
+    # a property of the launch shape, so they are only quoted for the shape they were measured on.
+    traffic = None
+    if (n, T, lib.get_option("group"), lib.get_option("kchain")) == (32768, 1024, 16, 4):
+        traffic = {"hbm_bytes_per_launch": 1.90e9, "read": 1.767e9, "write": 0.1345e9, "algorithmic": 1.342e9,
+                   "source": "profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md"}
     out = {
         "metric": "host-resident DGEMM GFLOP/s on 1 MI355X", "value": round(gflops, 1), "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 2),
@@ -139,7 +158,7 @@ def main():
         },
         "roofline": {
             "bound": "mfma", "achieved": round(achieved, 2), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(achieved / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+            "frac": round(achieved / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
             "kernel": "tile_steps_kernel<double,NN,fast>", "launches": st["launches"],
             "flop_per_launch": flop_per_launch, "avg_launch_ms": round(avg_launch_s * 1e3, 4),
         },
