@@ -298,11 +298,210 @@ __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// fp64 fast path: operand slabs go from HBM straight into LDS (global_load_lds_dwordx4), with
+// no staging registers and no LDS store instructions, two stages deep.
+//
+// A 16-byte chunk is the unit of both the copy and the layout; lane L of a wave-wide copy always
+// lands at chunk L of the 1 KB window the instruction names, but WHICH 16 bytes of the operand a
+// lane fetches is free, and that choice makes the layout:
+//   mn-contiguous source (A not transposed / B transposed): chunk (k, u) = elements mn = 2u, 2u+1 of
+//     k row k at chunk index k*64 + u: plain [k][128] doubles; an instruction copies one k row
+//     (1 KB contiguous in HBM); a fragment is a ds_read_b64 of 16 consecutive doubles.
+//   k-contiguous source (A transposed / B not transposed): chunk (mn, q) = k = 2q, 2q+1 of column mn
+//     at chunk index mn*8 + (q ^ (mn & 7)); an instruction copies 8 columns x 128 contiguous bytes;
+//     a fragment is a ds_read_b128 that yields two k values, and the XOR spreads the 16 lanes of a
+//     fragment read over all banks.
+// Each MFMA consumes k = 8c + 2g + h (c: half of the slab, g: 16-lane group, h: which of the pair),
+// the same assignment for both operands, so either layout pairs with either.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+// The fast path runs 512 threads = 8 waves (2 x 4) per workgroup, each wave owning 64 x 32 of the
+// macro-tile (64 accumulator registers), two workgroups per CU = 4 waves per SIMD to cover
+// barrier and LDS latencies.
+constexpr int FAST_THREADS = 512;
+constexpr int FAST_WAVES = 8;
+constexpr int DMA_PER_WAVE = 16 / FAST_WAVES;   // wave-wide copies per operand slab and wave
+
+template <bool KCONTIG>
+__device__ __forceinline__ const double* dma_origin(const double* p, int ld, int mn_base, int wave, int lane) {
+    if (!KCONTIG) return p + (size_t)(mn_base + 2 * lane) + (size_t)(wave * DMA_PER_WAVE) * ld;
+    const int m = lane >> 3, q = (lane & 7) ^ m;
+    return p + (size_t)(2 * q) + (size_t)(mn_base + wave * DMA_PER_WAVE * 8 + m) * ld;
+}
+
+// This wave's copies of one operand slab: rows 2*wave, 2*wave+1 (mn-contiguous) or columns
+// 16*wave .. 16*wave+15 (k-contiguous).  `stage` is the operand's 16 KB LDS window.
+template <bool KCONTIG>
+__device__ __forceinline__ void dma_slab(const double* origin, int ld, double* stage, int wave) {
+#pragma unroll
+    for (int i = 0; i < DMA_PER_WAVE; ++i) {
+        const double* src = origin + (size_t)(KCONTIG ? 8 * i : i) * ld;
+        double* dst = stage + (wave * DMA_PER_WAVE + i) * 128;
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
+    }
+}
+
+// Fragments of MFMA group (c, h): one double per 16 x 16 block, k = 8c + 2g + h.
+template <bool KCONTIG, int NB>
+__device__ __forceinline__ void frag_read(double (&f)[NB], const double* stage, int c, int h, int base, int g, int r16) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (!KCONTIG) {
+            f[b] = stage[(8 * c + 2 * g + h) * 128 + base + b * 16 + r16];
+        } else {
+            const int mn = base + b * 16 + r16;
+            f[b] = stage[(mn * 8 + ((4 * c + g) ^ (r16 & 7))) * 2 + h];
+        }
+    }
+}
+
+template <bool TA, bool TB>
+__device__ __forceinline__ void compute_stage(Mfma<double>::acc_t (&acc)[4][2], const double* sa, const double* sb,
+                                              int wm, int wn, int g, int r16) {
+    // fragments are double buffered: those of group t+1 are requested before the MFMAs of group t
+    double fa[2][4], fb[2][2];
+    frag_read<TA, 4>(fa[0], sa, 0, 0, wm * 64, g, r16);
+    frag_read<!TB, 2>(fb[0], sb, 0, 0, wn * 32, g, r16);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int cur = t & 1, nx = cur ^ 1;
+        if (t + 1 < 4) {
+            frag_read<TA, 4>(fa[nx], sa, (t + 1) >> 1, (t + 1) & 1, wm * 64, g, r16);
+            frag_read<!TB, 2>(fb[nx], sb, (t + 1) >> 1, (t + 1) & 1, wn * 32, g, r16);
+        }
+#pragma unroll
+        for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = Mfma<double>::run(fb[cur][bj], fa[cur][bi], acc[bi][bj]);
+    }
+}
+
+template <bool TA, bool TB>
+__device__ __forceinline__ void macro_tile_fast_f64(const TileStep& st, int i_base, int j_base) {
+    typedef Mfma<double>::acc_t acc_t;
+    // two stages, one array per stage and operand so that the compiler can tell a copy into one
+    // stage from the fragment reads of the other
+    __shared__ __attribute__((aligned(1024))) double sA0[BK * 128], sB0[BK * 128], sA1[BK * 128], sB1[BK * 128];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS windows in SGPRs
+    const int g = lane >> 4, r16 = lane & 15;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int lda = st.lda, ldb = st.ldb;
+    const int nseg = st.nseg;
+
+    acc_t acc[4][2];
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = acc_t{0, 0, 0, 0};
+
+    const size_t step_a = TA ? (size_t)BK : (size_t)BK * lda;
+    const size_t step_b = !TB ? (size_t)BK : (size_t)BK * ldb;
+
+    int pseg = 0, pslab = 0;
+    int pk = nseg > 0 ? st.seg[0].k : 0;
+    const double* pa = nullptr;
+    const double* pb = nullptr;
+    bool more = nseg > 0;
+    if (more) {
+        pa = dma_origin<TA>(static_cast<const double*>(st.seg[0].A), lda, i_base, wave, lane);
+        pb = dma_origin<!TB>(static_cast<const double*>(st.seg[0].B), ldb, j_base, wave, lane);
+        dma_slab<TA>(pa, lda, sA0, wave);
+        dma_slab<!TB>(pb, ldb, sB0, wave);
+    }
+    // advance the copy cursor to the next slab of the chain; false when the chain is exhausted
+    auto advance = [&]() -> bool {
+        ++pslab;
+        if (pslab * BK >= pk) {
+            ++pseg;
+            pslab = 0;
+            if (pseg >= nseg) return false;
+            pk = st.seg[pseg].k;
+            pa = dma_origin<TA>(static_cast<const double*>(st.seg[pseg].A), lda, i_base, wave, lane);
+            pb = dma_origin<!TB>(static_cast<const double*>(st.seg[pseg].B), ldb, j_base, wave, lane);
+        } else {
+            pa += step_a;
+            pb += step_b;
+        }
+        return true;
+    };
+    int total = 0;
+    for (int q = 0; q < nseg; ++q) total += st.seg[q].k / BK;
+    // Slabs are processed in pairs (stage 0, then stage 1) with no exit in between, so that the
+    // accumulators stay in one set of registers (the host only sends chains with an even count:
+    // every k is a multiple of 32).
+    for (int pair = 0; pair < total / 2; ++pair) {
+        // stage 0 holds the current slab once every wave's copies have landed
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __syncthreads();
+        advance();
+        dma_slab<TA>(pa, lda, sA1, wave);
+        dma_slab<!TB>(pb, ldb, sB1, wave);
+        compute_stage<TA, TB>(acc, sA0, sB0, wm, wn, g, r16);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (advance()) {
+            dma_slab<TA>(pa, lda, sA0, wave);
+            dma_slab<!TB>(pb, ldb, sB0, wave);
+        }
+        compute_stage<TA, TB>(acc, sA1, sB1, wm, wn, g, r16);
+    }
+
+    double* __restrict__ C = static_cast<double*>(st.C);
+    const double alpha = st.alpha, beta = st.beta;
+    const bool use_c = (st.beta != 0.0);
+    const int ldc = st.ldc;
+#pragma unroll
+    for (int bj = 0; bj < 2; ++bj) {
+        // one 16-column block at a time keeps the C values in flight to 32 registers
+        double cv[4][4];
+        if (use_c) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int bi = 0; bi < 4; ++bi)
+                    cv[r][bi] = C[(size_t)(i_base + wm * 64 + bi * 16 + r16) +
+                                  (size_t)(j_base + wn * 32 + bj * 16 + Mfma<double>::drow(r, g)) * ldc];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int bi = 0; bi < 4; ++bi) {
+                double v = alpha * acc[bi][bj][r];
+                if (use_c) v += beta * cv[r][bi];
+                C[(size_t)(i_base + wm * 64 + bi * 16 + r16) +
+                  (size_t)(j_base + wn * 32 + bj * 16 + Mfma<double>::drow(r, g)) * ldc] = v;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <typename T, bool TA, bool TB, bool GEN>
+struct MacroTile {
+    static __device__ __forceinline__ void run(const TileStep& st, int i_base, int j_base) {
+        macro_tile<T, TA, TB, GEN>(st, i_base, j_base);
+    }
+};
+template <bool TA, bool TB>
+struct MacroTile<double, TA, TB, false> {
+    static __device__ __forceinline__ void run(const TileStep& st, int i_base, int j_base) {
+        macro_tile_fast_f64<TA, TB>(st, i_base, j_base);
+    }
+};
+
 // GEN = false: every step of the pack is made of whole macro-tiles, k is a multiple of 16,
 // operands are 16-byte aligned with even leading dimensions and no mask flag is set (the host
 // checks this with step_is_fast()).  GEN = true handles everything else with predication.
+template <typename T, bool GEN>
+constexpr int kernel_threads() { return (sizeof(T) == 8 && !GEN) ? FAST_THREADS : NTHREADS; }
+
 template <typename T, bool TA, bool TB, bool GEN>
-__global__ __launch_bounds__(NTHREADS, 2) void tile_steps_kernel(const LaunchPack pack) {
+__global__ __launch_bounds__((kernel_threads<T, GEN>()), (kernel_threads<T, GEN>() == FAST_THREADS ? 4 : 2))
+void tile_steps_kernel(const LaunchPack pack) {
     // XCD-aware virtual workgroup index: XCD x gets the contiguous range [x*per, (x+1)*per).
     const uint32_t per = gridDim.x / NXCD;
     const uint32_t v = (blockIdx.x % NXCD) * per + blockIdx.x / NXCD;
@@ -316,7 +515,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void tile_steps_kernel(const LaunchPac
     const uint32_t tiles_m = (uint32_t)(st.m + BM - 1) / BM;
     const int i_base = (int)(local % tiles_m) * BM;
     const int j_base = (int)(local / tiles_m) * BN;
-    macro_tile<T, TA, TB, GEN>(st, i_base, j_base);
+    MacroTile<T, TA, TB, GEN>::run(st, i_base, j_base);
 }
 
 // Host-side launcher.  dtype: 0 = fp64, 1 = fp32.  The pack's wg_begin / total_wg must be filled,
@@ -329,7 +528,7 @@ hipError_t launch_tile_steps(int dtype, bool ta, bool tb, bool general, const La
         if (general)                                                                                              \
             hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, true>), dim3(grid), dim3(NTHREADS), 0, stream, pack); \
         else                                                                                                      \
-            hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, false>), dim3(grid), dim3(NTHREADS), 0, stream, pack); \
+            hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, false>), dim3(grid), dim3(kernel_threads<T, false>()), 0, stream, pack); \
     } while (0)
     if (dtype == 0) {
         if (!ta && !tb) BLASX_LAUNCH(double, false, false);

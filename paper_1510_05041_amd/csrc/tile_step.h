@@ -69,14 +69,14 @@ inline uint32_t macro_tiles(int m, int n) {
 }
 
 // True when a step can run in the unpredicated kernel: whole macro-tiles, k a multiple of the
-// slab depth, 16-byte aligned operands with even leading dimensions, no mask flag.
+// slab depth (fp64: of two slabs, the kernel works on slab pairs), 16-byte aligned operands with even leading dimensions, no mask flag.
 inline bool step_is_fast(const TileStep& st, int dtype) {
     const size_t esz = dtype == 0 ? 8 : 4;
     if (st.m <= 0 || st.n <= 0 || st.m % kBM || st.n % kBN || st.lda % 2 || st.ldb % 2) return false;
     if (st.flags & ~(TS_TRANS_A | TS_TRANS_B)) return false;
     for (int s = 0; s < st.nseg; ++s) {
         const TileSeg& sg = st.seg[s];
-        if (sg.flags || sg.k <= 0 || sg.k % kBK) return false;
+        if (sg.flags || sg.k <= 0 || sg.k % (dtype == 0 ? 2 * kBK : kBK)) return false;
         if ((reinterpret_cast<uintptr_t>(sg.A) | reinterpret_cast<uintptr_t>(sg.B)) % (2 * esz)) return false;
     }
     return true;
