@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--kchain", type=int, default=None)
     ap.add_argument("--depth", type=int, default=None)
     ap.add_argument("--sb", type=int, nargs=2, default=None)
+    ap.add_argument("--shells", type=int, default=None)
+    ap.add_argument("--rs", type=int, default=None)
     ap.add_argument("--arena-gb", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check", action="store_true", help="also compare sampled outputs with the oracle")
@@ -96,7 +98,8 @@ def main():
     lib.init(arena, nstreams=args.streams)
     lib.set_tile(T)
     lib.set_cache_bytes(0)
-    for name, val in (("group", args.group), ("kchain", args.kchain), ("depth", args.depth)):
+    for name, val in (("group", args.group), ("kchain", args.kchain), ("depth", args.depth), ("shells", args.shells),
+                      ("rs", args.rs)):
         if val is not None:
             lib.set_option(name, val)
     if args.sb:
@@ -154,6 +157,7 @@ def main():
                         "(inbound tile copies, kernels, write-back)" % (n, T, args.streams),
             "n": n, "tile": T, "streams": args.streams, "group": lib.get_option("group"), "kchain": lib.get_option("kchain"),
             "depth": lib.get_option("depth"), "superblock": [lib.get_option("sb_rows"), lib.get_option("sb_cols")],
+            "shells": lib.get_option("shells"),
             "arena_bytes": arena,
         },
         "roofline": {

@@ -107,6 +107,7 @@ int blasx_set_cache_bytes(size_t cap);
  *   "depth"    launches the host may run ahead of the device (>= 1)
  *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)
  *   "sb_rows", "sb_cols"  super-block shape used to order the task queue
+ *   "shells"   1: super-blocks are visited in growing square shells, 0: block row by block row
  *   "profile"  1: time every launch with events (adds two event records per launch)
  * Returns BLASX_ERR_CONFIG for an unknown name or an out-of-range value. */
 int blasx_set_option(const char* name, long value);

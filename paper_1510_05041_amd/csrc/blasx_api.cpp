@@ -220,6 +220,7 @@ int blasx_set_option(const char* name, long value) {
     else if (n == "rs") { if (value < 1 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.rs = (int)value; }
     else if (n == "sb_rows") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_rows = (int)value; }
     else if (n == "sb_cols") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_cols = (int)value; }
+    else if (n == "shells") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.order.shells = (int)value; }
     else if (n == "profile") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.profile = value != 0; }
     else return BLASX_ERR_CONFIG;
     return 0;
@@ -235,6 +236,7 @@ long blasx_get_option(const char* name) {
     if (n == "rs") return L.cfg.rs;
     if (n == "sb_rows") return L.order.sb_rows;
     if (n == "sb_cols") return L.order.sb_cols;
+    if (n == "shells") return L.order.shells;
     if (n == "profile") return L.cfg.profile ? 1 : 0;
     if (n == "tile") return L.T;
     return -1;

@@ -252,7 +252,9 @@ int Scheduler::pick_from_rs() {
 
 int Scheduler::add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, double flops, uint64_t nsteps) {
     if (op.pack.nsteps > 0 && (op.ta != ta || op.tb != tb)) BX_TRY(flush(op));
-    if (op.pack.nsteps == kMaxStepsPerLaunch) BX_TRY(flush(op));
+    // A launch is cut at 24 steps rather than at the 26 that fit: 8 whole-tile steps of 64 macro-tiles
+    // fill the 512 workgroup slots of the chip once, so multiples of 8 leave no partial wave of workgroups.
+    if (op.pack.nsteps == (kMaxStepsPerLaunch / 8) * 8) BX_TRY(flush(op));
     if (op.pack.nsteps == 0) {
         op.ta = ta;
         op.tb = tb;

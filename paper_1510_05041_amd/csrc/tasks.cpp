@@ -21,21 +21,34 @@ TileRef stored_tile(const void* base, int64_t ld, size_t esize, int T, int tr, i
     return t;
 }
 
-// Queue order of output tiles: super-blocks of sb_rows x sb_cols tiles, block rows top to
-// bottom, block columns in a serpentine, tiles row by row inside a super-block.  Tasks that
-// are neighbours in the queue then share A row tiles and B column tiles.
+// Queue order of output tiles: super-blocks of sb_rows x sb_cols tiles, tiles row by row inside a
+// super-block, so that tasks that are neighbours in the queue share A row tiles and B column
+// tiles.  The super-blocks themselves are visited either block row by block row in a serpentine,
+// or in growing square shells (shell s = down block column s, then back along block row s): a
+// shell needs one new block row of A and one new block column of B but holds 2s+1 super-blocks,
+// so the inbound traffic is spread over the whole run instead of all of B being needed during
+// the first block row.
 std::vector<std::pair<int, int>> superblock_order(int nti, int ntj, const OrderOpts& oo,
                                                   const std::function<bool(int, int)>& keep) {
     std::vector<std::pair<int, int>> out;
     const int sr = std::max(1, oo.sb_rows), sc = std::max(1, oo.sb_cols);
     const int nbi = cdiv(nti, sr), nbj = cdiv(ntj, sc);
-    for (int bi = 0; bi < nbi; ++bi)
-        for (int q = 0; q < nbj; ++q) {
-            const int bj = (bi & 1) ? nbj - 1 - q : q;
-            for (int i = bi * sr; i < std::min(nti, (bi + 1) * sr); ++i)
-                for (int j = bj * sc; j < std::min(ntj, (bj + 1) * sc); ++j)
-                    if (keep(i, j)) out.emplace_back(i, j);
+    std::vector<std::pair<int, int>> blocks;
+    if (oo.shells) {
+        for (int s = 0; s < std::max(nbi, nbj); ++s) {
+            if (s < nbj)
+                for (int bi = 0; bi <= std::min(s, nbi - 1); ++bi) blocks.emplace_back(bi, s);
+            if (s < nbi)
+                for (int bj = std::min(s, nbj) - 1; bj >= 0; --bj) blocks.emplace_back(s, bj);
         }
+    } else {
+        for (int bi = 0; bi < nbi; ++bi)
+            for (int q = 0; q < nbj; ++q) blocks.emplace_back(bi, (bi & 1) ? nbj - 1 - q : q);
+    }
+    for (auto b : blocks)
+        for (int i = b.first * sr; i < std::min(nti, (b.first + 1) * sr); ++i)
+            for (int j = b.second * sc; j < std::min(ntj, (b.second + 1) * sc); ++j)
+                if (keep(i, j)) out.emplace_back(i, j);
     return out;
 }
 

@@ -72,6 +72,7 @@ struct Problem {
 
 struct OrderOpts {
     int sb_rows = 4, sb_cols = 4;   // super-block shape for the queue order
+    int shells = 1;                 // 1: super-blocks in growing square shells, 0: row by row (serpentine)
 };
 
 // C (M x N) <- alpha op(A) op(B) + beta C.
