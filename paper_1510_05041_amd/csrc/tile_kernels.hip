@@ -1,30 +1,29 @@
-// Tile-step kernels for CDNA4 (gfx950): C <- alpha * op(A) * op(B) + beta * C on HBM-resident
-// tiles (Section III.B, Eq. 1a-1d; the call the paper's Alg. 1 makes once per (i, j, k)).
+// Tile-step kernels for CDNA4 (gfx950): C <- alpha * sum_s op(A_s) * op(B_s) + beta * C on
+// HBM-resident tiles (Section III.B, Eq. 1a-1d; the call the paper's Alg. 1 makes once per
+// (i, j, k), here with up to four chained k-steps per call).
 //
 // One launch executes a *pack* of tile steps (different output tiles), so that a launch fills
 // the 256 CUs even though a single 1024^3 step only has 64 macro-tiles.  The paper shares the
 // GPU between 4 tasks by running 4 vendor-BLAS calls on 4 streams; here the sharing happens
 // inside one grid instead.
 //
-// Work decomposition
-//   workgroup  = 256 threads = 4 waves (2 x 2), one 128 x 128 macro-tile of one step
-//   wave       = 64 x 64 of C = 4 x 4 MFMA blocks of 16 x 16, accumulators in registers
-//   k loop     = slabs of 16, double buffered in LDS; the next slab is fetched from HBM
-//                into registers while the MFMAs of the current one run
+// Common to both paths
+//   macro-tile = 128 x 128 of C per workgroup
 //   MFMA       = v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32, issued on the transposed
 //                product (a := B fragment, b := A fragment) so that the 16 lanes that share an
 //                accumulator register hold 16 consecutive rows of C: stores to column-major C
 //                are 128-byte (fp64) contiguous runs.
-//   LDS layout = [k][mn] for both operands (mn = row of op(A) / column of op(B)), 128 elements
-//                per k row, mn index XOR-swizzled by 2*((k>>1)&7) so that both the direct
-//                (mn-contiguous source) and the transposing (k-contiguous source) stores are
-//                conflict-free, while a fragment read still touches 16 consecutive elements.
-//   transposes = done by the LDS store pattern (Section III.C: the stored tile is fetched as it
-//                is and transposed inside the kernel).
+//   transposes = never in memory (Section III.C: the stored tile is fetched as it is and
+//                transposed on its way through LDS).
 //   XCD mapping= hardware deals consecutive workgroup ids round-robin to the 8 XCDs; the
-//                virtual index below gives each XCD a contiguous range of macro-tiles, i.e.
-//                whole steps, so the 64 macro-tiles that share one A and one B tile run under
-//                one L2.
+//                virtual index gives each XCD a contiguous range of macro-tiles, i.e. whole
+//                steps, so the 64 macro-tiles that share one A and one B tile run under one L2.
+//
+// General path (macro_tile): any extents, alignment and masks.  256 threads = 4 waves (2 x 2) of
+//   64 x 64; k slabs of 16 are fetched into registers with bounds and triangle predicates and
+//   stored to a double-buffered LDS layout [k][mn] whose mn index is XOR-swizzled by
+//   2*((k>>1)&7), so that both the direct and the transposing stores are conflict-free.
+// Fast path (macro_tile_fast): see the comment above it.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -70,54 +69,44 @@ __device__ __forceinline__ T tri_value(const T* p, int ld, int r, int c, uint32_
     return inside ? p[(size_t)r + (size_t)c * ld] : T(0);
 }
 
-// One operand slab (16 deep, 128 wide) from HBM into registers.
+// One operand slab (16 deep, 128 wide) from HBM into registers, with bounds (mn < mn_valid,
+// l < k_valid; out of range reads as zero) and the optional triangular mask.
 //   KCONTIG = false: element (mn, l) is at p[mn + l*ld]  (A not transposed, B transposed)
 //   KCONTIG = true : element (mn, l) is at p[l + mn*ld]  (A transposed, B not transposed)
-// GEN adds bounds (mn < mn_valid, l < k_valid) and the triangular mask; out-of-range is zero.
-template <typename T, bool KCONTIG, bool GEN>
+template <typename T, bool KCONTIG>
 __device__ __forceinline__ void slab_load(typename Mfma<T>::vec2_t (&reg)[4], const T* __restrict__ p, int ld,
                                           int mn_base, int k0, int mn_valid, int k_valid, bool tri,
                                           uint32_t flags, int tid) {
     typedef typename Mfma<T>::vec2_t V2;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
+        V2 v = {T(0), T(0)};
         if (!KCONTIG) {
             const int mn = mn_base + (tid & 63) * 2;
             const int l = k0 + (tid >> 6) + 4 * q;
-            if (!GEN) {
-                reg[q] = *reinterpret_cast<const V2*>(p + (size_t)mn + (size_t)l * ld);
-            } else {
-                V2 v = {T(0), T(0)};
-                if (l < k_valid) {
-                    if (tri) {
-                        if (mn < mn_valid) v.x = tri_value(p, ld, mn, l, flags);
-                        if (mn + 1 < mn_valid) v.y = tri_value(p, ld, mn + 1, l, flags);
-                    } else {
-                        if (mn < mn_valid) v.x = p[(size_t)mn + (size_t)l * ld];
-                        if (mn + 1 < mn_valid) v.y = p[(size_t)mn + 1 + (size_t)l * ld];
-                    }
+            if (l < k_valid) {
+                if (tri) {
+                    if (mn < mn_valid) v.x = tri_value(p, ld, mn, l, flags);
+                    if (mn + 1 < mn_valid) v.y = tri_value(p, ld, mn + 1, l, flags);
+                } else {
+                    if (mn < mn_valid) v.x = p[(size_t)mn + (size_t)l * ld];
+                    if (mn + 1 < mn_valid) v.y = p[(size_t)mn + 1 + (size_t)l * ld];
                 }
-                reg[q] = v;
             }
         } else {
             const int l = k0 + (tid & 7) * 2;
             const int mn = mn_base + (tid >> 3) + 32 * q;
-            if (!GEN) {
-                reg[q] = *reinterpret_cast<const V2*>(p + (size_t)l + (size_t)mn * ld);
-            } else {
-                V2 v = {T(0), T(0)};
-                if (mn < mn_valid) {
-                    if (tri) {
-                        if (l < k_valid) v.x = tri_value(p, ld, l, mn, flags);
-                        if (l + 1 < k_valid) v.y = tri_value(p, ld, l + 1, mn, flags);
-                    } else {
-                        if (l < k_valid) v.x = p[(size_t)l + (size_t)mn * ld];
-                        if (l + 1 < k_valid) v.y = p[(size_t)l + 1 + (size_t)mn * ld];
-                    }
+            if (mn < mn_valid) {
+                if (tri) {
+                    if (l < k_valid) v.x = tri_value(p, ld, l, mn, flags);
+                    if (l + 1 < k_valid) v.y = tri_value(p, ld, l + 1, mn, flags);
+                } else {
+                    if (l < k_valid) v.x = p[(size_t)l + (size_t)mn * ld];
+                    if (l + 1 < k_valid) v.y = p[(size_t)l + 1 + (size_t)mn * ld];
                 }
-                reg[q] = v;
             }
         }
+        reg[q] = v;
     }
 }
 
@@ -141,22 +130,8 @@ __device__ __forceinline__ void slab_store(T* __restrict__ lds, const typename M
     }
 }
 
-// Pointer of this thread's first element of an operand slab (fast path only).
-template <typename T, bool KCONTIG>
-__device__ __forceinline__ const T* slab_origin(const T* p, int ld, int mn_base, int tid) {
-    if (!KCONTIG) return p + (size_t)(mn_base + (tid & 63) * 2) + (size_t)(tid >> 6) * ld;
-    return p + (size_t)((tid & 7) * 2) + (size_t)(mn_base + (tid >> 3)) * ld;
-}
-
-template <typename T, bool KCONTIG>
-__device__ __forceinline__ void slab_load_fast(typename Mfma<T>::vec2_t (&reg)[4], const T* __restrict__ origin, int ld) {
-    typedef typename Mfma<T>::vec2_t V2;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        reg[q] = *reinterpret_cast<const V2*>(origin + (size_t)(KCONTIG ? 32 * q : 4 * q) * ld);
-}
-
-template <typename T, bool TA, bool TB, bool GEN>
+// General path: one 128 x 128 macro-tile of one step, any extents and masks.
+template <typename T, bool TA, bool TB>
 __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j_base) {
     typedef typename Mfma<T>::acc_t acc_t;
     typedef typename Mfma<T>::vec2_t V2;
@@ -185,9 +160,6 @@ __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j
     const int frag_col = r16 ^ ((g >> 1) << 1);
     const int fragA = g * 128 + wm * 64, fragB = OPERAND + g * 128 + wn * 64;
 
-    const size_t step_a = TA ? (size_t)BK : (size_t)BK * lda;
-    const size_t step_b = !TB ? (size_t)BK : (size_t)BK * ldb;
-
     // Prefetch cursor: pair `pseg`, slab `pslab` of it is the next one to fetch from HBM.  The
     // slab loop runs across the chained pairs without draining the pipeline in between.
     int pseg = 0, pslab = 0;
@@ -195,19 +167,12 @@ __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j
     uint32_t pflags = nseg > 0 ? st.seg[0].flags : 0;
     const T* A = nseg > 0 ? static_cast<const T*>(st.seg[0].A) : nullptr;
     const T* B = nseg > 0 ? static_cast<const T*>(st.seg[0].B) : nullptr;
-    const T* pa = (GEN || nseg == 0) ? nullptr : slab_origin<T, TA>(A, lda, i_base, tid);
-    const T* pb = (GEN || nseg == 0) ? nullptr : slab_origin<T, !TB>(B, ldb, j_base, tid);
 
     V2 ra[4], rb[4];
     bool more = nseg > 0;
     if (more) {
-        if (GEN) {
-            slab_load<T, TA, true>(ra, A, lda, i_base, 0, m, pk, pflags & TS_TRI_A, pflags, tid);
-            slab_load<T, !TB, true>(rb, B, ldb, j_base, 0, n, pk, pflags & TS_TRI_B, pflags, tid);
-        } else {
-            slab_load_fast<T, TA>(ra, pa, lda);
-            slab_load_fast<T, !TB>(rb, pb, ldb);
-        }
+        slab_load<T, TA>(ra, A, lda, i_base, 0, m, pk, pflags & TS_TRI_A, pflags, tid);
+        slab_load<T, !TB>(rb, B, ldb, j_base, 0, n, pk, pflags & TS_TRI_B, pflags, tid);
         slab_store<T, TA>(lds, ra, tid);
         slab_store<T, !TB>(lds + OPERAND, rb, tid);
     }
@@ -226,23 +191,11 @@ __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j
                 pflags = st.seg[pseg].flags;
                 A = static_cast<const T*>(st.seg[pseg].A);
                 B = static_cast<const T*>(st.seg[pseg].B);
-                if (!GEN) {
-                    pa = slab_origin<T, TA>(A, lda, i_base, tid);
-                    pb = slab_origin<T, !TB>(B, ldb, j_base, tid);
-                }
             }
-        } else if (!GEN) {
-            pa += step_a;
-            pb += step_b;
         }
         if (more) {
-            if (GEN) {
-                slab_load<T, TA, true>(ra, A, lda, i_base, pslab * BK, m, pk, pflags & TS_TRI_A, pflags, tid);
-                slab_load<T, !TB, true>(rb, B, ldb, j_base, pslab * BK, n, pk, pflags & TS_TRI_B, pflags, tid);
-            } else {
-                slab_load_fast<T, TA>(ra, pa, lda);
-                slab_load_fast<T, !TB>(rb, pb, ldb);
-            }
+            slab_load<T, TA>(ra, A, lda, i_base, pslab * BK, m, pk, pflags & TS_TRI_A, pflags, tid);
+            slab_load<T, !TB>(rb, B, ldb, j_base, pslab * BK, n, pk, pflags & TS_TRI_B, pflags, tid);
         }
         // Fragments are double buffered: those of sub-step kk+1 are requested before the MFMAs of kk.
         T fa[2][4], fb[2][4];
@@ -285,11 +238,9 @@ __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j
 #pragma unroll
             for (int bi = 0; bi < 4; ++bi) {
                 const int i = i_base + wm * 64 + bi * 16 + r16;
-                if (GEN) {
-                    if (i >= m || j >= n) continue;
-                    if ((flags & TS_C_LOWER) && i < j) continue;
-                    if ((flags & TS_C_UPPER) && i > j) continue;
-                }
+                if (i >= m || j >= n) continue;
+                if ((flags & TS_C_LOWER) && i < j) continue;
+                if ((flags & TS_C_UPPER) && i > j) continue;
                 T* p = C + (size_t)i + (size_t)j * ldc;
                 T v = alpha * acc[bi][bj][r];
                 if (use_c) v += beta * (*p);
@@ -299,91 +250,109 @@ __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j
 }
 
 // ---------------------------------------------------------------------------------------------
-// fp64 fast path: operand slabs go from HBM straight into LDS (global_load_lds_dwordx4), with
-// no staging registers and no LDS store instructions, two stages deep.
+// Fast path: operand slabs go from HBM straight into LDS (global_load_lds_dwordx4), with no
+// staging registers and no LDS store instructions, two stages deep.
 //
-// A 16-byte chunk is the unit of both the copy and the layout; lane L of a wave-wide copy always
-// lands at chunk L of the 1 KB window the instruction names, but WHICH 16 bytes of the operand a
-// lane fetches is free, and that choice makes the layout:
-//   mn-contiguous source (A not transposed / B transposed): chunk (k, u) = elements mn = 2u, 2u+1 of
-//     k row k at chunk index k*64 + u: plain [k][128] doubles; an instruction copies one k row
-//     (1 KB contiguous in HBM); a fragment is a ds_read_b64 of 16 consecutive doubles.
-//   k-contiguous source (A transposed / B not transposed): chunk (mn, q) = k = 2q, 2q+1 of column mn
-//     at chunk index mn*8 + (q ^ (mn & 7)); an instruction copies 8 columns x 128 contiguous bytes;
-//     a fragment is a ds_read_b128 that yields two k values, and the XOR spreads the 16 lanes of a
-//     fragment read over all banks.
-// Each MFMA consumes k = 8c + 2g + h (c: half of the slab, g: 16-lane group, h: which of the pair),
-// the same assignment for both operands, so either layout pairs with either.
+// A 16-byte chunk (EPC = 2 doubles or 4 floats) is the unit of both the copy and the layout; a
+// slab is 8 chunks deep (16 k in fp64, 32 k in fp32) and 128 wide, 16 KB per operand.  Lane L of a
+// wave-wide copy always lands at chunk L of the 1 KB window the instruction names, but WHICH 16
+// bytes of the operand a lane fetches is free, and that choice makes the layout:
+//   mn-contiguous source (A not transposed / B transposed): plain [k][128] rows; an instruction
+//     copies one (fp64) or two (fp32) whole k rows, contiguous in HBM; a fragment is a read of 16
+//     consecutive elements.
+//   k-contiguous source (A transposed / B not transposed): chunk (mn, q) = k = EPC*q .. EPC*q+EPC-1
+//     of column mn at chunk index mn*8 + (q ^ (mn & 7)); an instruction copies 8 columns x 128
+//     contiguous bytes; a fragment read yields EPC consecutive k values, and the XOR spreads the 16
+//     lanes of a fragment read over all banks.
+// MFMA group (c, h) consumes k = 4*EPC*c + EPC*g + h in lane group g (c: half of the slab, h:
+// position in the chunk), the same assignment for both operands, so either layout pairs with
+// either and the four transpose variants run at the same speed.
+//
+// Shape: 512 threads = 8 waves (2 x 4) per workgroup, each wave owning 64 x 32 of the macro-tile
+// (4 x 2 MFMA blocks), two workgroups per CU = 4 waves per SIMD to cover barrier and LDS latencies.
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
-// The fast path runs 512 threads = 8 waves (2 x 4) per workgroup, each wave owning 64 x 32 of the
-// macro-tile (64 accumulator registers), two workgroups per CU = 4 waves per SIMD to cover
-// barrier and LDS latencies.
 constexpr int FAST_THREADS = 512;
 constexpr int FAST_WAVES = 8;
 constexpr int DMA_PER_WAVE = 16 / FAST_WAVES;   // wave-wide copies per operand slab and wave
 
-template <bool KCONTIG>
-__device__ __forceinline__ const double* dma_origin(const double* p, int ld, int mn_base, int wave, int lane) {
-    if (!KCONTIG) return p + (size_t)(mn_base + 2 * lane) + (size_t)(wave * DMA_PER_WAVE) * ld;
+template <typename T> struct FastShape {
+    static constexpr int EPC = 16 / (int)sizeof(T);      // elements per 16-byte chunk
+    static constexpr int SLAB_K = 8 * EPC;               // k depth of one slab
+    static constexpr int ROWS_PER_COPY = 1024 / (128 * (int)sizeof(T));   // k rows one wave-wide copy covers
+    static constexpr int LANES_PER_ROW = 64 / ROWS_PER_COPY;
+    static constexpr int STAGE = 128 * SLAB_K;           // elements per operand stage (16 KB)
+};
+
+template <typename T, bool KCONTIG>
+__device__ __forceinline__ const T* dma_origin(const T* p, int ld, int mn_base, int wave, int lane) {
+    typedef FastShape<T> S;
+    if (!KCONTIG) {
+        const int row = wave * DMA_PER_WAVE * S::ROWS_PER_COPY + lane / S::LANES_PER_ROW;
+        return p + (size_t)(mn_base + (lane % S::LANES_PER_ROW) * S::EPC) + (size_t)row * ld;
+    }
     const int m = lane >> 3, q = (lane & 7) ^ m;
-    return p + (size_t)(2 * q) + (size_t)(mn_base + wave * DMA_PER_WAVE * 8 + m) * ld;
+    return p + (size_t)(S::EPC * q) + (size_t)(mn_base + wave * DMA_PER_WAVE * 8 + m) * ld;
 }
 
-// This wave's copies of one operand slab: rows 2*wave, 2*wave+1 (mn-contiguous) or columns
-// 16*wave .. 16*wave+15 (k-contiguous).  `stage` is the operand's 16 KB LDS window.
-template <bool KCONTIG>
-__device__ __forceinline__ void dma_slab(const double* origin, int ld, double* stage, int wave) {
+// This wave's copies of one operand slab into the operand's 16 KB LDS window `stage`.
+template <typename T, bool KCONTIG>
+__device__ __forceinline__ void dma_slab(const T* origin, int ld, T* stage, int wave) {
+    typedef FastShape<T> S;
 #pragma unroll
     for (int i = 0; i < DMA_PER_WAVE; ++i) {
-        const double* src = origin + (size_t)(KCONTIG ? 8 * i : i) * ld;
-        double* dst = stage + (wave * DMA_PER_WAVE + i) * 128;
+        const T* src = origin + (size_t)(KCONTIG ? 8 * i : S::ROWS_PER_COPY * i) * ld;
+        T* dst = stage + (wave * DMA_PER_WAVE + i) * (1024 / (int)sizeof(T));
         __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
     }
 }
 
-// Fragments of MFMA group (c, h): one double per 16 x 16 block, k = 8c + 2g + h.
-template <bool KCONTIG, int NB>
-__device__ __forceinline__ void frag_read(double (&f)[NB], const double* stage, int c, int h, int base, int g, int r16) {
+// Fragments of MFMA group (c, h): one element per 16 x 16 block.
+template <typename T, bool KCONTIG, int NB>
+__device__ __forceinline__ void frag_read(T (&f)[NB], const T* stage, int c, int h, int base, int g, int r16) {
+    typedef FastShape<T> S;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (!KCONTIG) {
-            f[b] = stage[(8 * c + 2 * g + h) * 128 + base + b * 16 + r16];
+            f[b] = stage[(4 * S::EPC * c + S::EPC * g + h) * 128 + base + b * 16 + r16];
         } else {
             const int mn = base + b * 16 + r16;
-            f[b] = stage[(mn * 8 + ((4 * c + g) ^ (r16 & 7))) * 2 + h];
+            f[b] = stage[(mn * 8 + ((4 * c + g) ^ (r16 & 7))) * S::EPC + h];
         }
     }
 }
 
-template <bool TA, bool TB>
-__device__ __forceinline__ void compute_stage(Mfma<double>::acc_t (&acc)[4][2], const double* sa, const double* sb,
+template <typename T, bool TA, bool TB>
+__device__ __forceinline__ void compute_stage(typename Mfma<T>::acc_t (&acc)[4][2], const T* sa, const T* sb,
                                               int wm, int wn, int g, int r16) {
+    typedef FastShape<T> S;
+    constexpr int NGROUP = 2 * S::EPC;
     // fragments are double buffered: those of group t+1 are requested before the MFMAs of group t
-    double fa[2][4], fb[2][2];
-    frag_read<TA, 4>(fa[0], sa, 0, 0, wm * 64, g, r16);
-    frag_read<!TB, 2>(fb[0], sb, 0, 0, wn * 32, g, r16);
+    T fa[2][4], fb[2][2];
+    frag_read<T, TA, 4>(fa[0], sa, 0, 0, wm * 64, g, r16);
+    frag_read<T, !TB, 2>(fb[0], sb, 0, 0, wn * 32, g, r16);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < NGROUP; ++t) {
         const int cur = t & 1, nx = cur ^ 1;
-        if (t + 1 < 4) {
-            frag_read<TA, 4>(fa[nx], sa, (t + 1) >> 1, (t + 1) & 1, wm * 64, g, r16);
-            frag_read<!TB, 2>(fb[nx], sb, (t + 1) >> 1, (t + 1) & 1, wn * 32, g, r16);
+        if (t + 1 < NGROUP) {
+            frag_read<T, TA, 4>(fa[nx], sa, (t + 1) / S::EPC, (t + 1) % S::EPC, wm * 64, g, r16);
+            frag_read<T, !TB, 2>(fb[nx], sb, (t + 1) / S::EPC, (t + 1) % S::EPC, wn * 32, g, r16);
         }
 #pragma unroll
         for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
-            for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = Mfma<double>::run(fb[cur][bj], fa[cur][bi], acc[bi][bj]);
+            for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = Mfma<T>::run(fb[cur][bj], fa[cur][bi], acc[bi][bj]);
     }
 }
 
-template <bool TA, bool TB>
-__device__ __forceinline__ void macro_tile_fast_f64(const TileStep& st, int i_base, int j_base) {
-    typedef Mfma<double>::acc_t acc_t;
+template <typename T, bool TA, bool TB>
+__device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, int j_base) {
+    typedef typename Mfma<T>::acc_t acc_t;
+    typedef FastShape<T> S;
     // two stages, one array per stage and operand so that the compiler can tell a copy into one
     // stage from the fragment reads of the other
-    __shared__ __attribute__((aligned(1024))) double sA0[BK * 128], sB0[BK * 128], sA1[BK * 128], sB1[BK * 128];
+    __shared__ __attribute__((aligned(1024))) T sA0[S::STAGE], sB0[S::STAGE], sA1[S::STAGE], sB1[S::STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -399,30 +368,29 @@ __device__ __forceinline__ void macro_tile_fast_f64(const TileStep& st, int i_ba
 #pragma unroll
         for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = acc_t{0, 0, 0, 0};
 
-    const size_t step_a = TA ? (size_t)BK : (size_t)BK * lda;
-    const size_t step_b = !TB ? (size_t)BK : (size_t)BK * ldb;
+    const size_t step_a = TA ? (size_t)S::SLAB_K : (size_t)S::SLAB_K * lda;
+    const size_t step_b = !TB ? (size_t)S::SLAB_K : (size_t)S::SLAB_K * ldb;
 
     int pseg = 0, pslab = 0;
     int pk = nseg > 0 ? st.seg[0].k : 0;
-    const double* pa = nullptr;
-    const double* pb = nullptr;
-    bool more = nseg > 0;
-    if (more) {
-        pa = dma_origin<TA>(static_cast<const double*>(st.seg[0].A), lda, i_base, wave, lane);
-        pb = dma_origin<!TB>(static_cast<const double*>(st.seg[0].B), ldb, j_base, wave, lane);
-        dma_slab<TA>(pa, lda, sA0, wave);
-        dma_slab<!TB>(pb, ldb, sB0, wave);
+    const T* pa = nullptr;
+    const T* pb = nullptr;
+    if (nseg > 0) {
+        pa = dma_origin<T, TA>(static_cast<const T*>(st.seg[0].A), lda, i_base, wave, lane);
+        pb = dma_origin<T, !TB>(static_cast<const T*>(st.seg[0].B), ldb, j_base, wave, lane);
+        dma_slab<T, TA>(pa, lda, sA0, wave);
+        dma_slab<T, !TB>(pb, ldb, sB0, wave);
     }
     // advance the copy cursor to the next slab of the chain; false when the chain is exhausted
     auto advance = [&]() -> bool {
         ++pslab;
-        if (pslab * BK >= pk) {
+        if (pslab * S::SLAB_K >= pk) {
             ++pseg;
             pslab = 0;
             if (pseg >= nseg) return false;
             pk = st.seg[pseg].k;
-            pa = dma_origin<TA>(static_cast<const double*>(st.seg[pseg].A), lda, i_base, wave, lane);
-            pb = dma_origin<!TB>(static_cast<const double*>(st.seg[pseg].B), ldb, j_base, wave, lane);
+            pa = dma_origin<T, TA>(static_cast<const T*>(st.seg[pseg].A), lda, i_base, wave, lane);
+            pb = dma_origin<T, !TB>(static_cast<const T*>(st.seg[pseg].B), ldb, j_base, wave, lane);
         } else {
             pa += step_a;
             pb += step_b;
@@ -430,51 +398,51 @@ __device__ __forceinline__ void macro_tile_fast_f64(const TileStep& st, int i_ba
         return true;
     };
     int total = 0;
-    for (int q = 0; q < nseg; ++q) total += st.seg[q].k / BK;
+    for (int q = 0; q < nseg; ++q) total += st.seg[q].k / S::SLAB_K;
     // Slabs are processed in pairs (stage 0, then stage 1) with no exit in between, so that the
     // accumulators stay in one set of registers (the host only sends chains with an even count:
-    // every k is a multiple of 32).
+    // every k is a multiple of two slabs).
     for (int pair = 0; pair < total / 2; ++pair) {
         // stage 0 holds the current slab once every wave's copies have landed
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __syncthreads();
         advance();
-        dma_slab<TA>(pa, lda, sA1, wave);
-        dma_slab<!TB>(pb, ldb, sB1, wave);
-        compute_stage<TA, TB>(acc, sA0, sB0, wm, wn, g, r16);
+        dma_slab<T, TA>(pa, lda, sA1, wave);
+        dma_slab<T, !TB>(pb, ldb, sB1, wave);
+        compute_stage<T, TA, TB>(acc, sA0, sB0, wm, wn, g, r16);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
         if (advance()) {
-            dma_slab<TA>(pa, lda, sA0, wave);
-            dma_slab<!TB>(pb, ldb, sB0, wave);
+            dma_slab<T, TA>(pa, lda, sA0, wave);
+            dma_slab<T, !TB>(pb, ldb, sB0, wave);
         }
-        compute_stage<TA, TB>(acc, sA1, sB1, wm, wn, g, r16);
+        compute_stage<T, TA, TB>(acc, sA1, sB1, wm, wn, g, r16);
     }
 
-    double* __restrict__ C = static_cast<double*>(st.C);
-    const double alpha = st.alpha, beta = st.beta;
+    T* __restrict__ C = static_cast<T*>(st.C);
+    const T alpha = (T)st.alpha, beta = (T)st.beta;
     const bool use_c = (st.beta != 0.0);
     const int ldc = st.ldc;
 #pragma unroll
     for (int bj = 0; bj < 2; ++bj) {
-        // one 16-column block at a time keeps the C values in flight to 32 registers
-        double cv[4][4];
+        // one 16-column block at a time keeps the C values in flight to 16 elements per lane
+        T cv[4][4];
         if (use_c) {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
 #pragma unroll
                 for (int bi = 0; bi < 4; ++bi)
                     cv[r][bi] = C[(size_t)(i_base + wm * 64 + bi * 16 + r16) +
-                                  (size_t)(j_base + wn * 32 + bj * 16 + Mfma<double>::drow(r, g)) * ldc];
+                                  (size_t)(j_base + wn * 32 + bj * 16 + Mfma<T>::drow(r, g)) * ldc];
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int bi = 0; bi < 4; ++bi) {
-                double v = alpha * acc[bi][bj][r];
+                T v = alpha * acc[bi][bj][r];
                 if (use_c) v += beta * cv[r][bi];
                 C[(size_t)(i_base + wm * 64 + bi * 16 + r16) +
-                  (size_t)(j_base + wn * 32 + bj * 16 + Mfma<double>::drow(r, g)) * ldc] = v;
+                  (size_t)(j_base + wn * 32 + bj * 16 + Mfma<T>::drow(r, g)) * ldc] = v;
             }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -483,21 +451,21 @@ __device__ __forceinline__ void macro_tile_fast_f64(const TileStep& st, int i_ba
 template <typename T, bool TA, bool TB, bool GEN>
 struct MacroTile {
     static __device__ __forceinline__ void run(const TileStep& st, int i_base, int j_base) {
-        macro_tile<T, TA, TB, GEN>(st, i_base, j_base);
+        macro_tile<T, TA, TB>(st, i_base, j_base);
     }
 };
-template <bool TA, bool TB>
-struct MacroTile<double, TA, TB, false> {
+template <typename T, bool TA, bool TB>
+struct MacroTile<T, TA, TB, false> {
     static __device__ __forceinline__ void run(const TileStep& st, int i_base, int j_base) {
-        macro_tile_fast_f64<TA, TB>(st, i_base, j_base);
+        macro_tile_fast<T, TA, TB>(st, i_base, j_base);
     }
 };
 
-// GEN = false: every step of the pack is made of whole macro-tiles, k is a multiple of 16,
-// operands are 16-byte aligned with even leading dimensions and no mask flag is set (the host
-// checks this with step_is_fast()).  GEN = true handles everything else with predication.
+// GEN = false: the host has checked with step_is_fast() that every step of the pack is made of
+// whole macro-tiles with aligned operands, whole slab pairs in k and no mask flag.
+// GEN = true handles everything else with predication.
 template <typename T, bool GEN>
-constexpr int kernel_threads() { return (sizeof(T) == 8 && !GEN) ? FAST_THREADS : NTHREADS; }
+constexpr int kernel_threads() { return GEN ? NTHREADS : FAST_THREADS; }
 
 template <typename T, bool TA, bool TB, bool GEN>
 __global__ __launch_bounds__((kernel_threads<T, GEN>()), (kernel_threads<T, GEN>() == FAST_THREADS ? 4 : 2))

@@ -68,16 +68,17 @@ inline uint32_t macro_tiles(int m, int n) {
     return (uint32_t)((m + kBM - 1) / kBM) * (uint32_t)((n + kBN - 1) / kBN);
 }
 
-// True when a step can run in the unpredicated kernel: whole macro-tiles, k a multiple of the
-// slab depth (fp64: of two slabs, the kernel works on slab pairs), 16-byte aligned operands with even leading dimensions, no mask flag.
+// True when a step can run in the unpredicated kernel: whole macro-tiles, every k a multiple of
+// two slabs (a slab is 8 sixteen-byte chunks deep: 16 k in fp64, 32 k in fp32; the kernel works on
+// slab pairs), operands 16-byte aligned with leading dimensions that keep columns aligned, no mask flag.
 inline bool step_is_fast(const TileStep& st, int dtype) {
-    const size_t esz = dtype == 0 ? 8 : 4;
-    if (st.m <= 0 || st.n <= 0 || st.m % kBM || st.n % kBN || st.lda % 2 || st.ldb % 2) return false;
+    const int epc = dtype == 0 ? 2 : 4;          // elements per 16-byte chunk
+    if (st.m <= 0 || st.n <= 0 || st.m % kBM || st.n % kBN || st.lda % epc || st.ldb % epc) return false;
     if (st.flags & ~(TS_TRANS_A | TS_TRANS_B)) return false;
     for (int s = 0; s < st.nseg; ++s) {
         const TileSeg& sg = st.seg[s];
-        if (sg.flags || sg.k <= 0 || sg.k % (dtype == 0 ? 2 * kBK : kBK)) return false;
-        if ((reinterpret_cast<uintptr_t>(sg.A) | reinterpret_cast<uintptr_t>(sg.B)) % (2 * esz)) return false;
+        if (sg.flags || sg.k <= 0 || sg.k % (16 * epc)) return false;
+        if ((reinterpret_cast<uintptr_t>(sg.A) | reinterpret_cast<uintptr_t>(sg.B)) % 16) return false;
     }
     return true;
 }
