@@ -423,6 +423,8 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     const T alpha = (T)st.alpha, beta = (T)st.beta;
     const bool use_c = (st.beta != 0.0);
     const int ldc = st.ldc;
+    // Output-triangle mask (diagonal tiles of SYRK): +1 keeps i >= j, -1 keeps i <= j, 0 keeps all.
+    const int tri = (st.flags & TS_C_LOWER) ? 1 : ((st.flags & TS_C_UPPER) ? -1 : 0);
 #pragma unroll
     for (int bj = 0; bj < 2; ++bj) {
         // one 16-column block at a time keeps the C values in flight to 16 elements per lane
@@ -431,18 +433,21 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
 #pragma unroll
             for (int r = 0; r < 4; ++r)
 #pragma unroll
-                for (int bi = 0; bi < 4; ++bi)
-                    cv[r][bi] = C[(size_t)(i_base + wm * 64 + bi * 16 + r16) +
-                                  (size_t)(j_base + wn * 32 + bj * 16 + Mfma<T>::drow(r, g)) * ldc];
+                for (int bi = 0; bi < 4; ++bi) {
+                    const int i = i_base + wm * 64 + bi * 16 + r16;
+                    const int j = j_base + wn * 32 + bj * 16 + Mfma<T>::drow(r, g);
+                    cv[r][bi] = (tri * (i - j) >= 0) ? C[(size_t)i + (size_t)j * ldc] : T(0);
+                }
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int bi = 0; bi < 4; ++bi) {
+                const int i = i_base + wm * 64 + bi * 16 + r16;
+                const int j = j_base + wn * 32 + bj * 16 + Mfma<T>::drow(r, g);
                 T v = alpha * acc[bi][bj][r];
                 if (use_c) v += beta * cv[r][bi];
-                C[(size_t)(i_base + wm * 64 + bi * 16 + r16) +
-                  (size_t)(j_base + wn * 32 + bj * 16 + Mfma<T>::drow(r, g)) * ldc] = v;
+                if (tri * (i - j) >= 0) C[(size_t)i + (size_t)j * ldc] = v;
             }
         __builtin_amdgcn_sched_barrier(0);
     }

@@ -70,11 +70,12 @@ inline uint32_t macro_tiles(int m, int n) {
 
 // True when a step can run in the unpredicated kernel: whole macro-tiles, every k a multiple of
 // two slabs (a slab is 8 sixteen-byte chunks deep: 16 k in fp64, 32 k in fp32; the kernel works on
-// slab pairs), operands 16-byte aligned with leading dimensions that keep columns aligned, no mask flag.
+// slab pairs), operands 16-byte aligned with leading dimensions that keep columns aligned, no operand
+// mask (the output-triangle mask only touches the epilogue and is allowed).
 inline bool step_is_fast(const TileStep& st, int dtype) {
     const int epc = dtype == 0 ? 2 : 4;          // elements per 16-byte chunk
     if (st.m <= 0 || st.n <= 0 || st.m % kBM || st.n % kBN || st.lda % epc || st.ldb % epc) return false;
-    if (st.flags & ~(TS_TRANS_A | TS_TRANS_B)) return false;
+    if (st.flags & ~(TS_TRANS_A | TS_TRANS_B | TS_C_LOWER | TS_C_UPPER)) return false;
     for (int s = 0; s < st.nseg; ++s) {
         const TileSeg& sg = st.seg[s];
         if (sg.flags || sg.k <= 0 || sg.k % (16 * epc)) return false;
