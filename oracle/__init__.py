@@ -37,8 +37,11 @@ def build(force=False):
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB_PATH)
+        # tests/test_oracle_mutants.py points this at deliberately broken builds to show that the pins notice
+        override = os.environ.get("ORACLE_LIB_OVERRIDE")
+        if not override:
+            build()
+        lib = ctypes.CDLL(override or _LIB_PATH)
         ci, cd, vp = ctypes.c_int, ctypes.c_double, ctypes.c_void_p
         for n in ("ref_dgemm", "ref_sgemm"):
             getattr(lib, n).argtypes = [ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci, cd, vp, ci]
