@@ -26,7 +26,7 @@ public:
                          size_t width, size_t height, int stream) = 0;
     virtual int copy_d2h(void* host_dst, size_t dpitch, const void* dev_src, size_t spitch,
                          size_t width, size_t height, int stream) = 0;
-    virtual int launch(int dtype, bool ta, bool tb, bool general, const LaunchPack& pack, int stream) = 0;
+    virtual int launch(int dtype, bool ta, bool tb, int mode, const LaunchPack& pack, int stream) = 0;   // mode: step_mode()
     // Invert the nb x nb diagonal blocks of an n x n triangular tile (device pointers, column-
     // major); flags: TS_TRI_LOWER / TS_TRI_UNIT of the source.  Used by the TRSM diagonal step.
     virtual int launch_trtri_blocks(int dtype, const void* tri, int ld_tri, void* inv, int ld_inv, int n, int nb,

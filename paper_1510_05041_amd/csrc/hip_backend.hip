@@ -9,7 +9,7 @@
 
 namespace blasx {
 
-hipError_t launch_tile_steps(int dtype, bool ta, bool tb, bool general, const LaunchPack& pack, hipStream_t stream);
+hipError_t launch_tile_steps(int dtype, bool ta, bool tb, int mode, const LaunchPack& pack, hipStream_t stream);
 
 // Inverse of the nb x nb diagonal blocks of a triangular tile (the base case of the TRSM
 // diagonal step; paper Eq. 1c needs A_ii^{-1}).  One wave per block, thread c solves for
@@ -115,8 +115,8 @@ public:
         HB_CHECK(hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, hipMemcpyDeviceToHost, stream(s)));
         return 0;
     }
-    int launch(int dtype, bool ta, bool tb, bool general, const LaunchPack& pack, int s) override {
-        HB_CHECK(launch_tile_steps(dtype, ta, tb, general, pack, stream(s)));
+    int launch(int dtype, bool ta, bool tb, int mode, const LaunchPack& pack, int s) override {
+        HB_CHECK(launch_tile_steps(dtype, ta, tb, mode, pack, stream(s)));
         return 0;
     }
     int launch_trtri_blocks(int dtype, const void* tri, int ld_tri, void* inv, int ld_inv, int n, int nb, uint32_t flags,

@@ -30,8 +30,7 @@ Scheduler::Scheduler(Backend& be, int nslots, size_t slot_bytes, const SchedConf
     cfg_.group = std::max(1, cfg_.group);
     cfg_.depth = std::max(1, cfg_.depth);
     cfg_.rs = std::max(cfg_.rs, cfg_.group);
-    fast_.general = false;
-    gen_.general = true;
+    for (int q = 0; q < 3; ++q) packs_[q].mode = q;
 }
 
 Scheduler::~Scheduler() {
@@ -291,7 +290,7 @@ int Scheduler::flush(OpenPack& op) {
         f.start_ev = new_event();
         if (be_.event_record(f.start_ev, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
     }
-    if (be_.launch(p_->dtype, op.ta, op.tb, op.general, op.pack, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
+    if (be_.launch(p_->dtype, op.ta, op.tb, op.mode, op.pack, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
     f.done_ev = new_event();
     if (be_.event_record(f.done_ev, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
     f.blocks.swap(op.blocks);
@@ -314,8 +313,7 @@ int Scheduler::flush(OpenPack& op) {
 }
 
 int Scheduler::flush_all() {
-    BX_TRY(flush(fast_));
-    BX_TRY(flush(gen_));
+    for (int q = 0; q < 3; ++q) BX_TRY(flush(packs_[q]));
     return 0;
 }
 
@@ -445,7 +443,7 @@ int Scheduler::build_chain(int ri) {
     st.flags = (p_->ta ? TS_TRANS_A : 0u) | (p_->tb ? TS_TRANS_B : 0u) | t.c_flags;
     st.alpha = t.alpha_step;
     st.beta = r.first ? t.beta_first : 1.0;
-    OpenPack& op = step_is_fast(st, p_->dtype) ? fast_ : gen_;
+    OpenPack& op = packs_[step_mode(st, p_->dtype)];
     BX_TRY(add_step(op, p_->ta, p_->tb, st, flops, (uint64_t)nseg));
     for (int q = 0; q < nheld; ++q) {
         op.blocks.push_back(held[q]);
@@ -547,9 +545,9 @@ int Scheduler::get_inverse(const Task& t, Block** out) {
                     }
                 }
                 st.beta = 0.0;
-                BX_TRY(add_step(gen_, false, false, st, 1.0 * st.m * st.n * st.seg[0].k, 0));
+                BX_TRY(add_step(packs_[step_mode(st, p_->dtype)], false, false, st, 1.0 * st.m * st.n * st.seg[0].k, 0));
             }
-            BX_TRY(flush(gen_));
+            BX_TRY(flush_all());
         }
     }
     // src, inv and tmp stay reserved until the last merge has run: a marker record that
@@ -603,16 +601,17 @@ int Scheduler::build_solve(int ri) {
     }
     st.alpha = r.first ? t.beta_first : 1.0;   // a task without update steps still owes the alpha
     st.beta = 0.0;
-    BX_TRY(add_step(gen_, p_->ta, p_->tb, st, 1.0 * t.m * t.n * st.seg[0].k, 1));
-    gen_.blocks.push_back(inv);
-    gen_.wait_slots.push_back(r.c_slot);
-    gen_.free_slots.push_back(r.c_slot);
+    OpenPack& op = packs_[step_mode(st, p_->dtype)];
+    BX_TRY(add_step(op, p_->ta, p_->tb, st, 1.0 * t.m * t.n * st.seg[0].k, 1));
+    op.blocks.push_back(inv);
+    op.wait_slots.push_back(r.c_slot);
+    op.free_slots.push_back(r.c_slot);
     r.c_slot = c2;
     r.first = false;
     r.solved = true;
-    r.last_pack = gen_.id;
-    gen_.finishing.push_back(ri);
-    task_final_pack_[r.task] = gen_.id;
+    r.last_pack = op.id;
+    op.finishing.push_back(ri);
+    task_final_pack_[r.task] = op.id;
     return 0;
 }
 

@@ -72,7 +72,7 @@ private:
         std::vector<int> wait_slots;    // slots whose inbound copies this launch reads
         double flops = 0;
         uint64_t steps = 0;
-        bool general = false;
+        int mode = 0;                   // kernel instantiation: step_mode()
         bool ta = false, tb = false;
         uint64_t id = 0;
     };
@@ -143,7 +143,7 @@ private:
     std::vector<char> task_started_, task_issued_;   // per task
     std::vector<uint64_t> task_final_pack_;          // pack id of the launch that finishes it
     std::vector<PanelState> panels_;
-    OpenPack fast_, gen_;
+    OpenPack packs_[3];                 // open launch packs, one per kernel mode
     uint64_t next_pack_id_ = 1, flushed_pack_id_ = 0;
     std::deque<InFlight> inflight_;
     std::deque<WriteBack> writebacks_;

@@ -323,22 +323,52 @@ __device__ __forceinline__ void frag_read(T (&f)[NB], const T* stage, int c, int
     }
 }
 
-template <typename T, bool TA, bool TB>
+// Element (r, c) of a stored triangular tile, given the value v that memory holds there.
+template <typename T>
+__device__ __forceinline__ T tri_select(T v, int r, int c, uint32_t flags) {
+    if (r == c) return (flags & TS_TRI_UNIT) ? T(1) : v;
+    const bool inside = (flags & TS_TRI_LOWER) ? (r > c) : (r < c);
+    return inside ? v : T(0);
+}
+
+// MFMAs of one slab.  MASK: one operand of this chained pair is a diagonal tile of a triangular
+// matrix (sflags says which and how); its fragments are masked on their way out of LDS, so what
+// the other triangle holds in memory never reaches an MFMA.  k0 = k offset of the slab in the pair.
+template <typename T, bool TA, bool TB, bool MASK>
 __device__ __forceinline__ void compute_stage(typename Mfma<T>::acc_t (&acc)[4][2], const T* sa, const T* sb,
-                                              int wm, int wn, int g, int r16) {
+                                              int wm, int wn, int g, int r16, uint32_t sflags, int k0,
+                                              int i_base, int j_base) {
     typedef FastShape<T> S;
     constexpr int NGROUP = 2 * S::EPC;
+    auto load_group = [&](T (&fa)[4], T (&fb)[2], int t) {
+        const int c = t / S::EPC, h = t % S::EPC;
+        frag_read<T, TA, 4>(fa, sa, c, h, wm * 64, g, r16);
+        frag_read<T, !TB, 2>(fb, sb, c, h, wn * 32, g, r16);
+        if (MASK) {
+            const int kg = k0 + 4 * S::EPC * c + S::EPC * g + h;
+            if (sflags & TS_TRI_A) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int i = i_base + wm * 64 + b * 16 + r16;
+                    fa[b] = TA ? tri_select(fa[b], kg, i, sflags) : tri_select(fa[b], i, kg, sflags);
+                }
+            }
+            if (sflags & TS_TRI_B) {
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    const int j = j_base + wn * 32 + b * 16 + r16;
+                    fb[b] = TB ? tri_select(fb[b], j, kg, sflags) : tri_select(fb[b], kg, j, sflags);
+                }
+            }
+        }
+    };
     // fragments are double buffered: those of group t+1 are requested before the MFMAs of group t
     T fa[2][4], fb[2][2];
-    frag_read<T, TA, 4>(fa[0], sa, 0, 0, wm * 64, g, r16);
-    frag_read<T, !TB, 2>(fb[0], sb, 0, 0, wn * 32, g, r16);
+    load_group(fa[0], fb[0], 0);
 #pragma unroll
     for (int t = 0; t < NGROUP; ++t) {
         const int cur = t & 1, nx = cur ^ 1;
-        if (t + 1 < NGROUP) {
-            frag_read<T, TA, 4>(fa[nx], sa, (t + 1) / S::EPC, (t + 1) % S::EPC, wm * 64, g, r16);
-            frag_read<T, !TB, 2>(fb[nx], sb, (t + 1) / S::EPC, (t + 1) % S::EPC, wn * 32, g, r16);
-        }
+        if (t + 1 < NGROUP) load_group(fa[nx], fb[nx], t + 1);
 #pragma unroll
         for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
@@ -346,7 +376,9 @@ __device__ __forceinline__ void compute_stage(typename Mfma<T>::acc_t (&acc)[4][
     }
 }
 
-template <typename T, bool TA, bool TB>
+// MASK: the pack holds steps with triangular operands (separate kernel instantiation, so that
+// the plain one carries no trace of the masking code).
+template <typename T, bool TA, bool TB, bool MASK>
 __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, int j_base) {
     typedef typename Mfma<T>::acc_t acc_t;
     typedef FastShape<T> S;
@@ -399,6 +431,22 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     };
     int total = 0;
     for (int q = 0; q < nseg; ++q) total += st.seg[q].k / S::SLAB_K;
+    // Compute cursor: the slab now being multiplied (one behind the copy cursor).
+    int cseg = 0, cslab = 0;
+    int ck = pk;
+    uint32_t cflags = nseg > 0 ? st.seg[0].flags : 0;
+    auto multiply = [&](const T* sa, const T* sb) {
+        compute_stage<T, TA, TB, MASK>(acc, sa, sb, wm, wn, g, r16, cflags, cslab * S::SLAB_K, i_base, j_base);
+        if (MASK) {
+            ++cslab;
+            if (cslab * S::SLAB_K >= ck && cseg + 1 < nseg) {
+                ++cseg;
+                cslab = 0;
+                ck = st.seg[cseg].k;
+                cflags = st.seg[cseg].flags;
+            }
+        }
+    };
     // Slabs are processed in pairs (stage 0, then stage 1) with no exit in between, so that the
     // accumulators stay in one set of registers (the host only sends chains with an even count:
     // every k is a multiple of two slabs).
@@ -409,14 +457,14 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
         advance();
         dma_slab<T, TA>(pa, lda, sA1, wave);
         dma_slab<T, !TB>(pb, ldb, sB1, wave);
-        compute_stage<T, TA, TB>(acc, sA0, sB0, wm, wn, g, r16);
+        multiply(sA0, sB0);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
         if (advance()) {
             dma_slab<T, TA>(pa, lda, sA0, wave);
             dma_slab<T, !TB>(pb, ldb, sB0, wave);
         }
-        compute_stage<T, TA, TB>(acc, sA1, sB1, wm, wn, g, r16);
+        multiply(sA1, sB1);
     }
 
     T* __restrict__ C = static_cast<T*>(st.C);
@@ -453,27 +501,17 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     }
 }
 
-template <typename T, bool TA, bool TB, bool GEN>
-struct MacroTile {
-    static __device__ __forceinline__ void run(const TileStep& st, int i_base, int j_base) {
-        macro_tile<T, TA, TB>(st, i_base, j_base);
-    }
-};
-template <typename T, bool TA, bool TB>
-struct MacroTile<T, TA, TB, false> {
-    static __device__ __forceinline__ void run(const TileStep& st, int i_base, int j_base) {
-        macro_tile_fast<T, TA, TB>(st, i_base, j_base);
-    }
-};
+// MODE 0: fast path (the host has checked with step_is_fast() that every step of the pack is made
+//         of whole macro-tiles with aligned operands and whole slab pairs in k), no operand masks;
+// MODE 1: fast path with triangular operand masks;
+// MODE 2: general path, everything else with predication.
+enum { MODE_FAST = 0, MODE_FAST_MASKED = 1, MODE_GENERAL = 2 };
 
-// GEN = false: the host has checked with step_is_fast() that every step of the pack is made of
-// whole macro-tiles with aligned operands, whole slab pairs in k and no mask flag.
-// GEN = true handles everything else with predication.
-template <typename T, bool GEN>
-constexpr int kernel_threads() { return GEN ? NTHREADS : FAST_THREADS; }
+template <int MODE>
+constexpr int kernel_threads() { return MODE == MODE_GENERAL ? NTHREADS : FAST_THREADS; }
 
-template <typename T, bool TA, bool TB, bool GEN>
-__global__ __launch_bounds__((kernel_threads<T, GEN>()), (kernel_threads<T, GEN>() == FAST_THREADS ? 4 : 2))
+template <typename T, bool TA, bool TB, int MODE>
+__global__ __launch_bounds__((kernel_threads<MODE>()), (MODE == MODE_GENERAL ? 2 : 4))
 void tile_steps_kernel(const LaunchPack pack) {
     // XCD-aware virtual workgroup index: XCD x gets the contiguous range [x*per, (x+1)*per).
     const uint32_t per = gridDim.x / NXCD;
@@ -488,20 +526,24 @@ void tile_steps_kernel(const LaunchPack pack) {
     const uint32_t tiles_m = (uint32_t)(st.m + BM - 1) / BM;
     const int i_base = (int)(local % tiles_m) * BM;
     const int j_base = (int)(local / tiles_m) * BN;
-    MacroTile<T, TA, TB, GEN>::run(st, i_base, j_base);
+    if (MODE == MODE_GENERAL)
+        macro_tile<T, TA, TB>(st, i_base, j_base);
+    else
+        macro_tile_fast<T, TA, TB, MODE == MODE_FAST_MASKED>(st, i_base, j_base);
 }
 
-// Host-side launcher.  dtype: 0 = fp64, 1 = fp32.  The pack's wg_begin / total_wg must be filled,
-// and `general` must be true unless step_is_fast() holds for every step of the pack.
-hipError_t launch_tile_steps(int dtype, bool ta, bool tb, bool general, const LaunchPack& pack, hipStream_t stream) {
+// Host-side launcher.  dtype: 0 = fp64, 1 = fp32; mode: see above.  The pack's wg_begin / total_wg
+// must be filled, and mode must be MODE_GENERAL unless step_is_fast() holds for every step.
+hipError_t launch_tile_steps(int dtype, bool ta, bool tb, int mode, const LaunchPack& pack, hipStream_t stream) {
     if (pack.nsteps <= 0 || pack.total_wg == 0) return hipSuccess;
     const uint32_t grid = NXCD * ((pack.total_wg + NXCD - 1) / NXCD);
-#define BLASX_LAUNCH(T, TA, TB)                                                                                   \
-    do {                                                                                                          \
-        if (general)                                                                                              \
-            hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, true>), dim3(grid), dim3(NTHREADS), 0, stream, pack); \
-        else                                                                                                      \
-            hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, false>), dim3(grid), dim3(kernel_threads<T, false>()), 0, stream, pack); \
+#define BLASX_LAUNCH_MODE(T, TA, TB, MODE) \
+    hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, MODE>), dim3(grid), dim3(kernel_threads<MODE>()), 0, stream, pack)
+#define BLASX_LAUNCH(T, TA, TB)                                             \
+    do {                                                                    \
+        if (mode == MODE_FAST) BLASX_LAUNCH_MODE(T, TA, TB, MODE_FAST);     \
+        else if (mode == MODE_FAST_MASKED) BLASX_LAUNCH_MODE(T, TA, TB, MODE_FAST_MASKED); \
+        else BLASX_LAUNCH_MODE(T, TA, TB, MODE_GENERAL);                    \
     } while (0)
     if (dtype == 0) {
         if (!ta && !tb) BLASX_LAUNCH(double, false, false);
@@ -515,6 +557,7 @@ hipError_t launch_tile_steps(int dtype, bool ta, bool tb, bool general, const La
         else BLASX_LAUNCH(float, true, true);
     }
 #undef BLASX_LAUNCH
+#undef BLASX_LAUNCH_MODE
     return hipGetLastError();
 }
 

@@ -70,18 +70,26 @@ inline uint32_t macro_tiles(int m, int n) {
 
 // True when a step can run in the unpredicated kernel: whole macro-tiles, every k a multiple of
 // two slabs (a slab is 8 sixteen-byte chunks deep: 16 k in fp64, 32 k in fp32; the kernel works on
-// slab pairs), operands 16-byte aligned with leading dimensions that keep columns aligned, no operand
-// mask (the output-triangle mask only touches the epilogue and is allowed).
+// slab pairs), operands 16-byte aligned with leading dimensions that keep columns aligned.  Masks are
+// fine: operand masks are applied to fragments, the output-triangle mask in the epilogue.
 inline bool step_is_fast(const TileStep& st, int dtype) {
     const int epc = dtype == 0 ? 2 : 4;          // elements per 16-byte chunk
     if (st.m <= 0 || st.n <= 0 || st.m % kBM || st.n % kBN || st.lda % epc || st.ldb % epc) return false;
     if (st.flags & ~(TS_TRANS_A | TS_TRANS_B | TS_C_LOWER | TS_C_UPPER)) return false;
     for (int s = 0; s < st.nseg; ++s) {
         const TileSeg& sg = st.seg[s];
-        if (sg.flags || sg.k <= 0 || sg.k % (16 * epc)) return false;
+        if (sg.k <= 0 || sg.k % (16 * epc)) return false;
         if ((reinterpret_cast<uintptr_t>(sg.A) | reinterpret_cast<uintptr_t>(sg.B)) % 16) return false;
     }
     return true;
+}
+
+// Which kernel instantiation a step needs: 0 = fast, 1 = fast with operand masks, 2 = general.
+inline int step_mode(const TileStep& st, int dtype) {
+    if (!step_is_fast(st, dtype)) return 2;
+    for (int s = 0; s < st.nseg; ++s)
+        if (st.seg[s].flags) return 1;
+    return 0;
 }
 
 }  // namespace blasx

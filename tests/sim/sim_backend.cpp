@@ -135,14 +135,13 @@ public:
     int copy_d2h(void* dst, size_t dp, const void* src, size_t sp, size_t w, size_t h, int s) override {
         return copy(dst, dp, src, sp, w, h, s);
     }
-    int launch(int dtype, bool ta, bool tb, bool general, const LaunchPack& pack, int s) override {
-        // what the unpredicated kernel assumes must hold for every step of a non-general pack
-        if (!general)
-            for (int q = 0; q < pack.nsteps; ++q)
-                if (!step_is_fast(pack.step[q], dtype)) {
-                    err_ = "fast launch with a step that needs the general kernel";
-                    return 1;
-                }
+    int launch(int dtype, bool ta, bool tb, int mode, const LaunchPack& pack, int s) override {
+        // what each kernel instantiation assumes must hold for every step of its pack
+        for (int q = 0; q < pack.nsteps; ++q)
+            if (step_mode(pack.step[q], dtype) > mode) {
+                err_ = "launch mode does not cover a step of the pack";
+                return 1;
+            }
         Op op;
         op.kind = Op::LAUNCH;
         op.dtype = dtype;
