@@ -67,6 +67,8 @@ int blasx_sgemm(int Order, int TransA, int TransB, int M, int N, int K, float al
  * the host matrix is left bit-identical. */
 int blasx_dsyrk(int Order, int Uplo, int Trans, int N, int K, double alpha,
                 const double* A, int lda, double beta, double* C, int ldc);
+int blasx_ssyrk(int Order, int Uplo, int Trans, int N, int K, float alpha,
+                const float* A, int lda, float beta, float* C, int ldc);
 
 /* Solve op(A) * X = alpha * B (Side = left, A is M x M) or X * op(A) = alpha * B (right,
  * A is N x N); X overwrites B (M x N).                                  (paper Eq. 1c, with
@@ -74,11 +76,15 @@ int blasx_dsyrk(int Order, int Uplo, int Trans, int N, int K, double alpha,
  * Diag = unit the diagonal is not read either. */
 int blasx_dtrsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha,
                 const double* A, int lda, double* B, int ldb);
+int blasx_strsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, float alpha,
+                const float* A, int lda, float* B, int ldb);
 
 /* B <- alpha * op(A) * B (left) or alpha * B * op(A) (right)            (paper Eq. 1d, alpha on
  * every term).  Same triangle rules as blasx_dtrsm. */
 int blasx_dtrmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha,
                 const double* A, int lda, double* B, int ldb);
+int blasx_strmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, float alpha,
+                const float* A, int lda, float* B, int ldb);
 
 /* ------------------------------------------------------------------ run-time control -- */
 

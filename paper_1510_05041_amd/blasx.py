@@ -64,8 +64,11 @@ class Library:
         lib.blasx_dgemm.argtypes = [ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci, cd, vp, ci]
         lib.blasx_sgemm.argtypes = [ci, ci, ci, ci, ci, ci, cf, vp, ci, vp, ci, cf, vp, ci]
         lib.blasx_dsyrk.argtypes = [ci, ci, ci, ci, ci, cd, vp, ci, cd, vp, ci]
+        lib.blasx_ssyrk.argtypes = [ci, ci, ci, ci, ci, cf, vp, ci, cf, vp, ci]
         lib.blasx_dtrsm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci]
+        lib.blasx_strsm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cf, vp, ci, vp, ci]
         lib.blasx_dtrmm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci]
+        lib.blasx_strmm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cf, vp, ci, vp, ci]
         lib.blasx_init.argtypes = [vp, sz, ctypes.POINTER(vp), ci]
         lib.blasx_set_tile.argtypes = [ci]
         lib.blasx_set_cache_bytes.argtypes = [sz]
@@ -170,6 +173,24 @@ class Library:
         rc = self._lib.blasx_dsyrk(Order, Uplo, Trans_, N, K, alpha, _ptr(A), lda, beta, _ptr(C), ldc)
         if check:
             self._check("blasx_dsyrk", rc)
+        return rc
+
+    def ssyrk(self, Order, Uplo, Trans_, N, K, alpha, A, lda, beta, C, ldc, check=True):
+        rc = self._lib.blasx_ssyrk(Order, Uplo, Trans_, N, K, alpha, _ptr(A), lda, beta, _ptr(C), ldc)
+        if check:
+            self._check("blasx_ssyrk", rc)
+        return rc
+
+    def strsm(self, Order, Side, Uplo, TransA, Diag, M, N, alpha, A, lda, B, ldb, check=True):
+        rc = self._lib.blasx_strsm(Order, Side, Uplo, TransA, Diag, M, N, alpha, _ptr(A), lda, _ptr(B), ldb)
+        if check:
+            self._check("blasx_strsm", rc)
+        return rc
+
+    def strmm(self, Order, Side, Uplo, TransA, Diag, M, N, alpha, A, lda, B, ldb, check=True):
+        rc = self._lib.blasx_strmm(Order, Side, Uplo, TransA, Diag, M, N, alpha, _ptr(A), lda, _ptr(B), ldb)
+        if check:
+            self._check("blasx_strmm", rc)
         return rc
 
     def dtrsm(self, Order, Side, Uplo, TransA, Diag, M, N, alpha, A, lda, B, ldb, check=True):

@@ -104,22 +104,8 @@ int tri_check(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N,
     return 0;
 }
 
-}  // namespace
-
-extern "C" {
-
-int blasx_dgemm(int Order, int TransA, int TransB, int M, int N, int K, double alpha, const double* A, int lda,
-                const double* B, int ldb, double beta, double* C, int ldc) {
-    return gemm_impl<double>(0, Order, TransA, TransB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
-}
-
-int blasx_sgemm(int Order, int TransA, int TransB, int M, int N, int K, float alpha, const float* A, int lda,
-                const float* B, int ldb, float beta, float* C, int ldc) {
-    return gemm_impl<float>(1, Order, TransA, TransB, M, N, K, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc);
-}
-
-int blasx_dsyrk(int Order, int Uplo, int Trans, int N, int K, double alpha, const double* A, int lda, double beta,
-                double* C, int ldc) {
+int syrk_impl(int dtype, int Order, int Uplo, int Trans, int N, int K, double alpha, const void* A, int lda, double beta,
+              void* C, int ldc) {
     if (Order != BLASX_ROW_MAJOR && Order != BLASX_COL_MAJOR) return -1;
     if (Uplo != BLASX_UPPER && Uplo != BLASX_LOWER) return -2;
     if (!ok_trans(Trans)) return -3;
@@ -139,12 +125,12 @@ int blasx_dsyrk(int Order, int Uplo, int Trans, int N, int K, double alpha, cons
     // transposition flag both flip
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     const bool trans = col ? is_trans(Trans) : !is_trans(Trans);
-    build_syrk(p, 0, lib().T, lower, trans, N, K, alpha, A, lda, beta, C, ldc, lib().order);
+    build_syrk(p, dtype, lib().T, lower, trans, N, K, alpha, A, lda, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
-int blasx_dtrmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const double* A, int lda,
-                double* B, int ldb) {
+int trmm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const void* A,
+              int lda, void* B, int ldb) {
     const int chk = tri_check(Order, Side, Uplo, TransA, Diag, M, N, A, lda, B, ldb);
     if (chk) return chk;
     if (M == 0 || N == 0) return 0;
@@ -154,13 +140,13 @@ int blasx_dtrmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int 
     const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     Problem p;
-    build_trmm(p, 0, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+    build_trmm(p, dtype, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
                ldb, lib().order);
     return run_problem(p);
 }
 
-int blasx_dtrsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const double* A, int lda,
-                double* B, int ldb) {
+int trsm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const void* A,
+              int lda, void* B, int ldb) {
     const int chk = tri_check(Order, Side, Uplo, TransA, Diag, M, N, A, lda, B, ldb);
     if (chk) return chk;
     if (M == 0 || N == 0) return 0;
@@ -171,13 +157,54 @@ int blasx_dtrsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int 
     Problem p;
     if (alpha == 0.0) {
         // X = 0 and A is not read: a TRMM with no steps writes zero tiles
-        build_trmm(p, 0, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, 0.0, A, lda, B,
+        build_trmm(p, dtype, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, 0.0, A, lda, B,
                    ldb, lib().order);
     } else {
-        build_trsm(p, 0, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+        build_trsm(p, dtype, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
                    ldb, lib().order);
     }
     return run_problem(p);
+}
+
+}  // namespace
+
+extern "C" {
+
+int blasx_dgemm(int Order, int TransA, int TransB, int M, int N, int K, double alpha, const double* A, int lda,
+                const double* B, int ldb, double beta, double* C, int ldc) {
+    return gemm_impl<double>(0, Order, TransA, TransB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+int blasx_sgemm(int Order, int TransA, int TransB, int M, int N, int K, float alpha, const float* A, int lda,
+                const float* B, int ldb, float beta, float* C, int ldc) {
+    return gemm_impl<float>(1, Order, TransA, TransB, M, N, K, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc);
+}
+
+int blasx_dsyrk(int Order, int Uplo, int Trans, int N, int K, double alpha, const double* A, int lda, double beta,
+                double* C, int ldc) {
+    return syrk_impl(0, Order, Uplo, Trans, N, K, alpha, A, lda, beta, C, ldc);
+}
+int blasx_ssyrk(int Order, int Uplo, int Trans, int N, int K, float alpha, const float* A, int lda, float beta,
+                float* C, int ldc) {
+    return syrk_impl(1, Order, Uplo, Trans, N, K, (double)alpha, A, lda, (double)beta, C, ldc);
+}
+
+int blasx_dtrmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const double* A, int lda,
+                double* B, int ldb) {
+    return trmm_impl(0, Order, Side, Uplo, TransA, Diag, M, N, alpha, A, lda, B, ldb);
+}
+int blasx_strmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, float alpha, const float* A, int lda,
+                float* B, int ldb) {
+    return trmm_impl(1, Order, Side, Uplo, TransA, Diag, M, N, (double)alpha, A, lda, B, ldb);
+}
+
+int blasx_dtrsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const double* A, int lda,
+                double* B, int ldb) {
+    return trsm_impl(0, Order, Side, Uplo, TransA, Diag, M, N, alpha, A, lda, B, ldb);
+}
+int blasx_strsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, float alpha, const float* A, int lda,
+                float* B, int ldb) {
+    return trsm_impl(1, Order, Side, Uplo, TransA, Diag, M, N, (double)alpha, A, lda, B, ldb);
 }
 
 int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int nstreams) {

@@ -425,3 +425,31 @@ def test_config5b_sgemm_notrans_trans_sampled(lib):
     before = lambda gi, gj: np.array([[np.float32(synth.element(7, synth.MAT_C, int(i), int(j), n)) for j in gj] for i in gi],
                                      dtype=np.float32)
     check_gemm_sampled(blasx.NoTrans, blasx.Trans, n, n, n, 1.0, A, B, 1.0, before, C, T, 7, TOL32, dtype=np.float32)
+
+
+# ------------------------------------------------------------------ single-precision variants --
+
+def test_single_precision_syrk_trmm_trsm(lib):
+    """The fp32 entry points share the task builders and kernels of the fp64 ones."""
+    N, K = 900, 640
+    configure(lib, T=256, arena_gb=0.25, group=6)
+    A, ka = pinned(N, K, 12, 0, dtype=np.float32)
+    C, kc = pinned(N, N, 12, 2, dtype=np.float32)
+    want = np.array(C, order="F")
+    lib.ssyrk(blasx.ColMajor, blasx.Lower, blasx.NoTrans, N, K, 1.0, A, N, 1.0, C, N)
+    ref.syrk(ref.ColMajor, ref.Lower, ref.NoTrans, 1.0, np.asarray(A), 1.0, want)
+    assert relerr(C, want) < TOL32
+    M, Nb = 768, 520
+    T64, kt = triangular(M, 13, blasx.Upper, blasx.NonUnit)
+    T32, k32 = blasx.pinned_matrix(M, M, dtype=np.float32)
+    T32[...] = np.asarray(T64).astype(np.float32)
+    B, kb = pinned(M, Nb, 13, 1, dtype=np.float32)
+    want = np.array(B, order="F")
+    lib.strmm(blasx.ColMajor, blasx.Left, blasx.Upper, blasx.Trans, blasx.NonUnit, M, Nb, 1.0, T32, M, B, M)
+    ref.trmm(ref.ColMajor, ref.Left, ref.Upper, ref.Trans, ref.NonUnit, 1.0, np.asarray(T32), want)
+    assert relerr(B, want) < TOL32
+    synth.fill(B, 13, 1)
+    want = np.array(B, order="F")
+    lib.strsm(blasx.ColMajor, blasx.Left, blasx.Upper, blasx.NoTrans, blasx.NonUnit, M, Nb, 1.0, T32, M, B, M)
+    ref.trsm(ref.ColMajor, ref.Left, ref.Upper, ref.NoTrans, ref.NonUnit, 1.0, np.asarray(T32), want)
+    assert relerr(B, want) < TOL32

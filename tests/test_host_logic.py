@@ -328,3 +328,39 @@ def test_run_to_run_reproducible_and_interleaving_independent(sim):
     C = np.zeros((n, n), order="F")
     sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 0.0, C, n)
     assert relerr(C, outs[0]) < 1e-15
+
+
+# ------------------------------------------------------------------ single precision ------
+
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS[::3])
+def test_single_precision_triangular_routines(sim, side, uplo, trans, diag):
+    setup(sim, T=16, esize=4, seed=side + uplo + trans + diag)
+    rng = np.random.default_rng(8)
+    M, N = 40, 33
+    n = M if side == blasx.Left else N
+    P = poisoned(rng, n, uplo, diag, dominant=True).astype(np.float32)
+    if diag == blasx.Unit:
+        P = np.where(np.isnan(P), P, P / n).astype(np.float32)
+    B = rng.uniform(-1, 1, (M, N)).astype(np.float32)
+    Ps = store(P, blasx.ColMajor, 1, dtype=np.float32)
+    Bs, Br = store(B, blasx.ColMajor, dtype=np.float32), store(B, blasx.ColMajor, dtype=np.float32)
+    sim.strmm(blasx.ColMajor, side, uplo, trans, diag, M, N, 0.5, Ps, ld_of(Ps, blasx.ColMajor), Bs, M)
+    ref.trmm(ref.ColMajor, side, uplo, trans, diag, 0.5, Ps, Br)
+    assert relerr(Bs, np.asarray(Br, dtype=np.float64)) < 1e-5
+    Bs, Br = store(B, blasx.ColMajor, dtype=np.float32), store(B, blasx.ColMajor, dtype=np.float32)
+    sim.strsm(blasx.ColMajor, side, uplo, trans, diag, M, N, 2.0, Ps, ld_of(Ps, blasx.ColMajor), Bs, M)
+    ref.trsm(ref.ColMajor, side, uplo, trans, diag, 2.0, Ps, Br)
+    assert relerr(Bs, np.asarray(Br, dtype=np.float64)) < 1e-5
+
+
+def test_ssyrk_matches_oracle(sim):
+    setup(sim, T=16, esize=4)
+    rng = np.random.default_rng(9)
+    N, K = 50, 37
+    A = np.asfortranarray(rng.uniform(-1, 1, (K, N)).astype(np.float32))
+    C = np.asfortranarray(rng.uniform(-1, 1, (N, N)).astype(np.float32))
+    Cs, Cr = C.copy(order="F"), C.copy(order="F")
+    sim.ssyrk(blasx.ColMajor, blasx.Upper, blasx.Trans, N, K, 1.0, A, K, 0.5, Cs, N)
+    ref.syrk(ref.ColMajor, ref.Upper, ref.Trans, 1.0, A, 0.5, Cr)
+    assert relerr(Cs, Cr.astype(np.float64)) < 1e-6
+    assert np.array_equal(np.tril(Cs, -1), np.tril(C, -1))
