@@ -47,6 +47,10 @@ def _load():
             getattr(lib, n).argtypes = [ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci, cd, vp, ci]
         for n in ("ref_dsyrk", "ref_ssyrk"):
             getattr(lib, n).argtypes = [ci, ci, ci, ci, ci, cd, vp, ci, cd, vp, ci]
+        for n in ("ref_dsyr2k", "ref_ssyr2k"):
+            getattr(lib, n).argtypes = [ci, ci, ci, ci, ci, cd, vp, ci, vp, ci, cd, vp, ci]
+        for n in ("ref_dsymm", "ref_ssymm"):
+            getattr(lib, n).argtypes = [ci, ci, ci, ci, ci, cd, vp, ci, vp, ci, cd, vp, ci]
         for n in ("ref_dtrmm", "ref_strmm", "ref_dtrsm", "ref_strsm"):
             getattr(lib, n).argtypes = [ci, ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci]
         lib.ref_max_threads.restype = ci
@@ -106,6 +110,33 @@ def syrk(order, uplo, trans, alpha, A, beta, C):
     rc = fn(order, uplo, trans, N, K, alpha, pa, lda, beta, pc, ldc)
     if rc:
         raise ValueError("oracle syrk: rc=%d" % rc)
+    return C
+
+
+def syr2k(order, uplo, trans, alpha, A, B, beta, C):
+    """Triangle ``uplo`` of C <- alpha (A B^T + B A^T) (or A^T B + B^T A) + beta C in place (Eq. 1e)."""
+    N = C.shape[0]
+    K = A.shape[1] if trans == NoTrans else A.shape[0]
+    pa, lda = _layout(A, order)
+    pb, ldb = _layout(B, order)
+    pc, ldc = _layout(C, order)
+    fn = getattr(_load(), "ref_%ssyr2k" % _prefix(A, B, C))
+    rc = fn(order, uplo, trans, N, K, alpha, pa, lda, pb, ldb, beta, pc, ldc)
+    if rc:
+        raise ValueError("oracle syr2k: rc=%d" % rc)
+    return C
+
+
+def symm(order, side, uplo, alpha, A, B, beta, C):
+    """C <- alpha A B + beta C (left) or alpha B A + beta C (right), A symmetric, one triangle stored (Eq. 1f)."""
+    M, N = C.shape
+    pa, lda = _layout(A, order)
+    pb, ldb = _layout(B, order)
+    pc, ldc = _layout(C, order)
+    fn = getattr(_load(), "ref_%ssymm" % _prefix(A, B, C))
+    rc = fn(order, side, uplo, M, N, alpha, pa, lda, pb, ldb, beta, pc, ldc)
+    if rc:
+        raise ValueError("oracle symm: rc=%d" % rc)
     return C
 
 

@@ -2,7 +2,7 @@
  * ORACLE -- test infrastructure only.
  *
  * Plain, slow, un-tiled CPU definitions of the level-3 BLAS routines that the
- * tile algorithms of the paper (Section III.B, Eq. 1a-1d) must reproduce.  The
+ * tile algorithms of the paper (Section III.B, Eq. 1a-1f) must reproduce.  The
  * tile method is exact up to the order of floating-point summation, so the
  * oracle is the textbook definition of each routine written out as loops over
  * whole matrices: no tiling, no blocking, no reordering beyond "sum over l in
@@ -133,6 +133,88 @@ int NAME(int order, int uplo, int trans, int N, int K, double alpha,            
 
 DEFINE_SYRK(ref_dsyrk, double)
 DEFINE_SYRK(ref_ssyrk, float)
+
+/* ----------------------------------------------------------------- SYR2K --
+ * trans = N:  C <- alpha * (A * B^T + B * A^T) + beta * C,  A and B are N x K
+ * trans = T:  C <- alpha * (A^T * B + B^T * A) + beta * C,  A and B are K x N
+ * Only the uplo triangle of C is read or written (Eq. 1e with a single tile).
+ */
+#define DEFINE_SYR2K(NAME, T)                                                       \
+int NAME(int order, int uplo, int trans, int N, int K, double alpha,                \
+         const T *A, int lda, const T *B, int ldb, double beta, T *C, int ldc)      \
+{                                                                                   \
+    if (order != ROW && order != COL) return -1;                                    \
+    if (uplo != UP && uplo != LO) return -2;                                        \
+    if (trans != NOTR && !is_tr(trans)) return -3;                                  \
+    if (N < 0) return -4;                                                           \
+    if (K < 0) return -5;                                                           \
+    _Pragma("omp parallel for schedule(dynamic, 1)")                                \
+    for (long j = 0; j < N; ++j) {                                                  \
+        long i0 = (uplo == LO) ? j : 0;                                             \
+        long i1 = (uplo == LO) ? N : j + 1;                                         \
+        for (long i = i0; i < i1; ++i) {                                            \
+            double s = 0.0;                                                         \
+            if (alpha != 0.0)                                                       \
+                for (long l = 0; l < K; ++l) {                                      \
+                    double ai = is_tr(trans) ? (double)A[at(order, l, i, lda)] : (double)A[at(order, i, l, lda)]; \
+                    double aj = is_tr(trans) ? (double)A[at(order, l, j, lda)] : (double)A[at(order, j, l, lda)]; \
+                    double bi = is_tr(trans) ? (double)B[at(order, l, i, ldb)] : (double)B[at(order, i, l, ldb)]; \
+                    double bj = is_tr(trans) ? (double)B[at(order, l, j, ldb)] : (double)B[at(order, j, l, ldb)]; \
+                    s += ai * bj + bi * aj;                                         \
+                }                                                                   \
+            size_t p = at(order, i, j, ldc);                                        \
+            double v = (alpha != 0.0) ? alpha * s : 0.0;                            \
+            if (beta != 0.0) v += beta * (double)C[p];                              \
+            C[p] = (T)v;                                                            \
+        }                                                                           \
+    }                                                                               \
+    return 0;                                                                       \
+}
+
+DEFINE_SYR2K(ref_dsyr2k, double)
+DEFINE_SYR2K(ref_ssyr2k, float)
+
+/* ------------------------------------------------------------------ SYMM --
+ * side = L:  C <- alpha * A * B + beta * C,  A is M x M symmetric
+ * side = R:  C <- alpha * B * A + beta * C,  A is N x N symmetric
+ * Only the uplo triangle of A (with its diagonal) is read; the rest of the
+ * symmetric matrix is taken from it by reflection (Eq. 1f with a single tile).
+ */
+#define DEFINE_SYMM(NAME, T)                                                        \
+int NAME(int order, int side, int uplo, int M, int N, double alpha,                 \
+         const T *A, int lda, const T *B, int ldb, double beta, T *C, int ldc)      \
+{                                                                                   \
+    if (order != ROW && order != COL) return -1;                                    \
+    if (side != LEFT && side != RIGHT) return -2;                                   \
+    if (uplo != UP && uplo != LO) return -3;                                        \
+    if (M < 0) return -4;                                                           \
+    if (N < 0) return -5;                                                           \
+    _Pragma("omp parallel for schedule(dynamic, 1)")                                \
+    for (long j = 0; j < N; ++j) {                                                  \
+        for (long i = 0; i < M; ++i) {                                              \
+            double s = 0.0;                                                         \
+            if (alpha != 0.0) {                                                     \
+                long n = (side == LEFT) ? M : N;                                    \
+                for (long l = 0; l < n; ++l) {                                      \
+                    /* element (r, c) of the symmetric matrix */                    \
+                    long r = (side == LEFT) ? i : l, c = (side == LEFT) ? l : j;    \
+                    int stored = (uplo == LO) ? (r >= c) : (r <= c);                \
+                    double a = stored ? (double)A[at(order, r, c, lda)] : (double)A[at(order, c, r, lda)]; \
+                    double b = (side == LEFT) ? (double)B[at(order, l, j, ldb)] : (double)B[at(order, i, l, ldb)]; \
+                    s += (side == LEFT) ? a * b : b * a;                            \
+                }                                                                   \
+            }                                                                       \
+            size_t p = at(order, i, j, ldc);                                        \
+            double v = (alpha != 0.0) ? alpha * s : 0.0;                            \
+            if (beta != 0.0) v += beta * (double)C[p];                              \
+            C[p] = (T)v;                                                            \
+        }                                                                           \
+    }                                                                               \
+    return 0;                                                                       \
+}
+
+DEFINE_SYMM(ref_dsymm, double)
+DEFINE_SYMM(ref_ssymm, float)
 
 /* -------------------------------------------------- triangular operand ----
  * tri(r,c): the triangular matrix that A stands for -- the named triangle of

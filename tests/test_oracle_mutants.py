@@ -21,6 +21,10 @@ MUTANTS = {
     "row_major_index_swapped": ("                        : (size_t)r * (size_t)ld + (size_t)c;", "                        : (size_t)c * (size_t)ld + (size_t)r;"),
     "syrk_writes_whole_matrix": ("long i0 = (uplo == LO) ? j : 0;", "long i0 = 0;"),
     "syrk_wrong_triangle": ("long i1 = (uplo == LO) ? N : j + 1;", "long i1 = (uplo == LO) ? N : j;"),
+    "syr2k_drops_second_product": ("s += ai * bj + bi * aj;", "s += ai * bj;"),
+    "syr2k_same_product_twice": ("s += ai * bj + bi * aj;", "s += ai * bj + ai * bj;"),
+    "symm_reads_other_triangle": ("int stored = (uplo == LO) ? (r >= c) : (r <= c);", "int stored = 1;"),
+    "symm_right_uses_left_indices": ("long r = (side == LEFT) ? i : l, c = (side == LEFT) ? l : j;", "long r = i, c = l;"),
     "tri_reads_unit_diagonal": ("if (r == c) return diag == UNIT ? 1.0 : (double)A[at(order, r, r, lda)];", "if (r == c) return (double)A[at(order, r, r, lda)];"),
     "tri_wrong_triangle": ("int inside = (uplo == LO) ? (r > c) : (r < c);", "int inside = (uplo == LO) ? (r < c) : (r > c);"),
     "tri_ignores_transpose": ("return is_tr(trans) ? tri_##SFX(order, uplo, diag, A, lda, c, r)", "return is_tr(trans) ? tri_##SFX(order, uplo, diag, A, lda, r, c)"),

@@ -392,3 +392,92 @@ def test_generator_is_element_addressable_and_in_range():
     assert np.array_equal(Af, A.astype(np.float32))
     assert not np.array_equal(synth.matrix(8, 8, 0, 0), synth.matrix(8, 8, 0, 1))
     assert not np.array_equal(synth.matrix(8, 8, 0, 0), synth.matrix(8, 8, 1, 0))
+
+
+# ------------------------------------------------------- SYR2K / SYMM -----
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("uplo", [ref.Upper, ref.Lower])
+@pytest.mark.parametrize("trans", TRANS)
+def test_syr2k_exact_and_other_triangle_untouched(order, uplo, trans):
+    rng = np.random.default_rng(50 + uplo + trans + order)
+    N, K = 6, 4
+    shape = (N, K) if trans == ref.NoTrans else (K, N)
+    A, B = rnd(rng, *shape), rnd(rng, *shape)
+    C = rnd(rng, N, N)
+    Cin = C.copy()
+    outside = [(i, j) for i in range(N) for j in range(N) if ((i < j) if uplo == ref.Lower else (i > j))]
+    for (i, j) in outside:
+        Cin[i, j] = -999.25
+    alpha, beta = 0.7, -0.4
+    Cs = store(Cin, order, 1)
+    ref.syr2k(order, uplo, trans, alpha, store(A, order, 2), store(B, order), beta, Cs)
+    Ae = exact.frac(A) if trans == ref.NoTrans else exact.transpose(exact.frac(A))
+    Be = exact.frac(B) if trans == ref.NoTrans else exact.transpose(exact.frac(B))
+    P1, P2 = exact.matmul(Ae, exact.transpose(Be)), exact.matmul(Be, exact.transpose(Ae))
+    Q = exact.abs_matmul(Ae, exact.transpose(Be))
+    for i in range(N):
+        for j in range(N):
+            if (i, j) in outside:
+                assert Cs[i, j] == -999.25
+                continue
+            want = Fraction(alpha) * (P1[i][j] + P2[i][j]) + Fraction(beta) * Fraction(float(C[i, j]))
+            bound = (2 * K + 6) * U * float(2 * abs(Fraction(alpha)) * Q[i][j] + abs(beta * C[i, j])) + 1e-300
+            assert abs(Fraction(float(Cs[i, j])) - want) <= bound + 4 * U * float(abs(want))
+
+
+def test_syr2k_with_b_equal_a_is_twice_syrk_and_result_is_symmetric():
+    N, K = 7, 5
+    A = np.asarray(synth.matrix(N, K, 51, 0, integers=True))
+    B = np.asarray(synth.matrix(N, K, 51, 1, integers=True))
+    C2 = np.zeros((N, N), order="F")
+    ref.syr2k(ref.ColMajor, ref.Lower, ref.NoTrans, 1.0, store(A, ref.ColMajor), store(A, ref.ColMajor), 0.0, C2)
+    C1 = np.zeros((N, N), order="F")
+    ref.syrk(ref.ColMajor, ref.Lower, ref.NoTrans, 2.0, store(A, ref.ColMajor), 0.0, C1)
+    assert np.array_equal(np.tril(C2), np.tril(C1))
+    lo, up = np.zeros((N, N), order="F"), np.zeros((N, N), order="F")
+    ref.syr2k(ref.ColMajor, ref.Lower, ref.NoTrans, 1.0, store(A, ref.ColMajor), store(B, ref.ColMajor), 0.0, lo)
+    ref.syr2k(ref.ColMajor, ref.Upper, ref.NoTrans, 1.0, store(A, ref.ColMajor), store(B, ref.ColMajor), 0.0, up)
+    assert np.array_equal(np.tril(lo), np.triu(up).T)
+    assert np.array_equal(np.tril(lo), np.tril(A @ B.T + B @ A.T))        # integers: exact
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("side", [ref.Left, ref.Right])
+@pytest.mark.parametrize("uplo", [ref.Upper, ref.Lower])
+def test_symm_exact_with_poisoned_other_triangle(order, side, uplo):
+    rng = np.random.default_rng(60 + side + uplo + order)
+    M, N = 5, 4
+    n = M if side == ref.Left else N
+    S = rnd(rng, n, n)
+    S = (S + S.T) / 2.0                       # the symmetric matrix the stored triangle stands for
+    P = S.copy()
+    for r in range(n):
+        for c in range(n):
+            if (r < c) if uplo == ref.Lower else (r > c):
+                P[r, c] = np.nan                # never read
+    B, C = rnd(rng, M, N), rnd(rng, M, N)
+    alpha, beta = -1.1, 0.6
+    Cs = store(C, order, 2)
+    ref.symm(order, side, uplo, alpha, store(P, order, 1), store(B, order), beta, Cs)
+    Se, Be = exact.frac(S), exact.frac(B)
+    W = exact.matmul(Se, Be) if side == ref.Left else exact.matmul(Be, Se)
+    Wabs = exact.abs_matmul(Se, Be) if side == ref.Left else exact.abs_matmul(Be, Se)
+    for i in range(M):
+        for j in range(N):
+            want = Fraction(alpha) * W[i][j] + Fraction(beta) * Fraction(float(C[i, j]))
+            bound = (n + 4) * U * float(abs(Fraction(alpha)) * Wabs[i][j] + abs(beta * C[i, j]))
+            assert abs(Fraction(float(Cs[i, j])) - want) <= bound, (i, j)
+
+
+def test_symm_equals_gemm_with_the_full_symmetric_matrix():
+    M, N = 9, 6
+    S = np.asarray(synth.matrix(M, M, 61, 0, integers=True))
+    S = np.tril(S) + np.tril(S, -1).T
+    B = np.asarray(synth.matrix(M, N, 61, 1, integers=True))
+    Cg = np.zeros((M, N), order="F")
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.NoTrans, 1.0, store(S, ref.ColMajor), store(B, ref.ColMajor), 0.0, Cg)
+    Cs = np.zeros((M, N), order="F")
+    ref.symm(ref.ColMajor, ref.Left, ref.Lower, 1.0, store(np.tril(S) + np.triu(np.full((M, M), 77.0), 1), ref.ColMajor),
+             store(B, ref.ColMajor), 0.0, Cs)
+    assert np.array_equal(Cs, Cg)
