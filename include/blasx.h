@@ -70,6 +70,24 @@ int blasx_dsyrk(int Order, int Uplo, int Trans, int N, int K, double alpha,
 int blasx_ssyrk(int Order, int Uplo, int Trans, int N, int K, float alpha,
                 const float* A, int lda, float beta, float* C, int ldc);
 
+/* C <- alpha * (A * B^T + B * A^T) + beta * C (Trans = none, A and B are N x K) or
+ * C <- alpha * (A^T * B + B^T * A) + beta * C (Trans = transpose, A and B are K x N)   (paper Eq. 1e)
+ * Only the Uplo triangle of C (with its diagonal) is read or written; the other triangle of
+ * the host matrix is left bit-identical.  Arguments 1..13 in prototype order. */
+int blasx_dsyr2k(int Order, int Uplo, int Trans, int N, int K, double alpha,
+                 const double* A, int lda, const double* B, int ldb, double beta, double* C, int ldc);
+int blasx_ssyr2k(int Order, int Uplo, int Trans, int N, int K, float alpha,
+                 const float* A, int lda, const float* B, int ldb, float beta, float* C, int ldc);
+
+/* C <- alpha * A * B + beta * C (Side = left, A is M x M) or
+ * C <- alpha * B * A + beta * C (Side = right, A is N x N), A symmetric, B and C M x N  (paper Eq. 1f)
+ * Only the Uplo triangle of A (with its diagonal) is read; the other triangle may hold anything.
+ * Diagonal tiles of A are completed by reflection on the device, in a cache slot of their own. */
+int blasx_dsymm(int Order, int Side, int Uplo, int M, int N, double alpha,
+                const double* A, int lda, const double* B, int ldb, double beta, double* C, int ldc);
+int blasx_ssymm(int Order, int Side, int Uplo, int M, int N, float alpha,
+                const float* A, int lda, const float* B, int ldb, float beta, float* C, int ldc);
+
 /* Solve op(A) * X = alpha * B (Side = left, A is M x M) or X * op(A) = alpha * B (right,
  * A is N x N); X overwrites B (M x N).                                  (paper Eq. 1c, with
  * alpha placed as in the BLAS standard).  Only the Uplo triangle of A is read; with

@@ -65,6 +65,10 @@ class Library:
         lib.blasx_sgemm.argtypes = [ci, ci, ci, ci, ci, ci, cf, vp, ci, vp, ci, cf, vp, ci]
         lib.blasx_dsyrk.argtypes = [ci, ci, ci, ci, ci, cd, vp, ci, cd, vp, ci]
         lib.blasx_ssyrk.argtypes = [ci, ci, ci, ci, ci, cf, vp, ci, cf, vp, ci]
+        lib.blasx_dsyr2k.argtypes = [ci, ci, ci, ci, ci, cd, vp, ci, vp, ci, cd, vp, ci]
+        lib.blasx_ssyr2k.argtypes = [ci, ci, ci, ci, ci, cf, vp, ci, vp, ci, cf, vp, ci]
+        lib.blasx_dsymm.argtypes = [ci, ci, ci, ci, ci, cd, vp, ci, vp, ci, cd, vp, ci]
+        lib.blasx_ssymm.argtypes = [ci, ci, ci, ci, ci, cf, vp, ci, vp, ci, cf, vp, ci]
         lib.blasx_dtrsm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci]
         lib.blasx_strsm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cf, vp, ci, vp, ci]
         lib.blasx_dtrmm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci]
@@ -180,6 +184,30 @@ class Library:
         if check:
             self._check("blasx_ssyrk", rc)
         return rc
+
+    def _syr2k(self, name, Order, Uplo, Trans_, N, K, alpha, A, lda, B, ldb, beta, C, ldc, check):
+        rc = getattr(self._lib, name)(Order, Uplo, Trans_, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc)
+        if check:
+            self._check(name, rc)
+        return rc
+
+    def dsyr2k(self, Order, Uplo, Trans_, N, K, alpha, A, lda, B, ldb, beta, C, ldc, check=True):
+        return self._syr2k("blasx_dsyr2k", Order, Uplo, Trans_, N, K, alpha, A, lda, B, ldb, beta, C, ldc, check)
+
+    def ssyr2k(self, Order, Uplo, Trans_, N, K, alpha, A, lda, B, ldb, beta, C, ldc, check=True):
+        return self._syr2k("blasx_ssyr2k", Order, Uplo, Trans_, N, K, alpha, A, lda, B, ldb, beta, C, ldc, check)
+
+    def _symm(self, name, Order, Side, Uplo, M, N, alpha, A, lda, B, ldb, beta, C, ldc, check):
+        rc = getattr(self._lib, name)(Order, Side, Uplo, M, N, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc)
+        if check:
+            self._check(name, rc)
+        return rc
+
+    def dsymm(self, Order, Side, Uplo, M, N, alpha, A, lda, B, ldb, beta, C, ldc, check=True):
+        return self._symm("blasx_dsymm", Order, Side, Uplo, M, N, alpha, A, lda, B, ldb, beta, C, ldc, check)
+
+    def ssymm(self, Order, Side, Uplo, M, N, alpha, A, lda, B, ldb, beta, C, ldc, check=True):
+        return self._symm("blasx_ssymm", Order, Side, Uplo, M, N, alpha, A, lda, B, ldb, beta, C, ldc, check)
 
     def strsm(self, Order, Side, Uplo, TransA, Diag, M, N, alpha, A, lda, B, ldb, check=True):
         rc = self._lib.blasx_strsm(Order, Side, Uplo, TransA, Diag, M, N, alpha, _ptr(A), lda, _ptr(B), ldb)

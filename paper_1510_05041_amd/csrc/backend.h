@@ -31,6 +31,10 @@ public:
     // major); flags: TS_TRI_LOWER / TS_TRI_UNIT of the source.  Used by the TRSM diagonal step.
     virtual int launch_trtri_blocks(int dtype, const void* tri, int ld_tri, void* inv, int ld_inv, int n, int nb,
                                     uint32_t flags, int stream) = 0;
+    // dst <- the n x n symmetric tile whose `lower` (or upper) triangle src stores (device pointers,
+    // column-major); the other triangle of src is never read.  Used by the SYMM diagonal step.
+    virtual int launch_symmetrize(int dtype, const void* src, int ld_src, void* dst, int ld_dst, int n, bool lower,
+                                  int stream) = 0;
     // Events are small integers; event_destroy() hands one back for reuse.
     virtual int  event_create() = 0;
     virtual void event_destroy(int ev) = 0;

@@ -129,6 +129,56 @@ int syrk_impl(int dtype, int Order, int Uplo, int Trans, int N, int K, double al
     return run_problem(p);
 }
 
+int syr2k_impl(int dtype, int Order, int Uplo, int Trans, int N, int K, double alpha, const void* A, int lda, const void* B,
+               int ldb, double beta, void* C, int ldc) {
+    if (Order != BLASX_ROW_MAJOR && Order != BLASX_COL_MAJOR) return -1;
+    if (Uplo != BLASX_UPPER && Uplo != BLASX_LOWER) return -2;
+    if (!ok_trans(Trans)) return -3;
+    if (N < 0) return -4;
+    if (K < 0) return -5;
+    const bool col = Order == BLASX_COL_MAJOR;
+    const int ab_lead = col ? (is_trans(Trans) ? K : N) : (is_trans(Trans) ? N : K);
+    if (lda < std::max(1, ab_lead)) return -8;
+    if (ldb < std::max(1, ab_lead)) return -10;
+    if (ldc < std::max(1, N)) return -13;
+    if (N == 0) return 0;
+    if ((alpha == 0.0 || K == 0) && beta == 1.0) return 0;
+    if (!lib().be) return BLASX_ERR_NOT_INITIALIZED;
+    if ((!A || !B) && alpha != 0.0 && K > 0) return A ? -9 : -7;
+    if (!C) return -12;
+    Problem p;
+    const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
+    const bool trans = col ? is_trans(Trans) : !is_trans(Trans);
+    build_syr2k(p, dtype, lib().T, lower, trans, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+    return run_problem(p);
+}
+
+int symm_impl(int dtype, int Order, int Side, int Uplo, int M, int N, double alpha, const void* A, int lda, const void* B,
+              int ldb, double beta, void* C, int ldc) {
+    if (Order != BLASX_ROW_MAJOR && Order != BLASX_COL_MAJOR) return -1;
+    if (Side != BLASX_LEFT && Side != BLASX_RIGHT) return -2;
+    if (Uplo != BLASX_UPPER && Uplo != BLASX_LOWER) return -3;
+    if (M < 0) return -4;
+    if (N < 0) return -5;
+    const bool col = Order == BLASX_COL_MAJOR;
+    const int na = Side == BLASX_LEFT ? M : N;
+    const int bc_lead = col ? M : N;
+    if (lda < std::max(1, na)) return -8;
+    if (ldb < std::max(1, bc_lead)) return -10;
+    if (ldc < std::max(1, bc_lead)) return -13;
+    if (M == 0 || N == 0) return 0;
+    if (alpha == 0.0 && beta == 1.0) return 0;
+    if (!lib().be) return BLASX_ERR_NOT_INITIALIZED;
+    if ((!A || !B) && alpha != 0.0) return A ? -9 : -7;
+    if (!C) return -12;
+    Problem p;
+    // row-major: C^T = alpha (A B)^T = alpha B^T A: side and triangle flip, M and N swap
+    const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
+    const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
+    build_symm(p, dtype, lib().T, left, lower, col ? M : N, col ? N : M, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+    return run_problem(p);
+}
+
 int trmm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const void* A,
               int lda, void* B, int ldb) {
     const int chk = tri_check(Order, Side, Uplo, TransA, Diag, M, N, A, lda, B, ldb);
@@ -187,6 +237,24 @@ int blasx_dsyrk(int Order, int Uplo, int Trans, int N, int K, double alpha, cons
 int blasx_ssyrk(int Order, int Uplo, int Trans, int N, int K, float alpha, const float* A, int lda, float beta,
                 float* C, int ldc) {
     return syrk_impl(1, Order, Uplo, Trans, N, K, (double)alpha, A, lda, (double)beta, C, ldc);
+}
+
+int blasx_dsyr2k(int Order, int Uplo, int Trans, int N, int K, double alpha, const double* A, int lda, const double* B,
+                 int ldb, double beta, double* C, int ldc) {
+    return syr2k_impl(0, Order, Uplo, Trans, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+int blasx_ssyr2k(int Order, int Uplo, int Trans, int N, int K, float alpha, const float* A, int lda, const float* B, int ldb,
+                 float beta, float* C, int ldc) {
+    return syr2k_impl(1, Order, Uplo, Trans, N, K, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc);
+}
+
+int blasx_dsymm(int Order, int Side, int Uplo, int M, int N, double alpha, const double* A, int lda, const double* B, int ldb,
+                double beta, double* C, int ldc) {
+    return symm_impl(0, Order, Side, Uplo, M, N, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+int blasx_ssymm(int Order, int Side, int Uplo, int M, int N, float alpha, const float* A, int lda, const float* B, int ldb,
+                float beta, float* C, int ldc) {
+    return symm_impl(1, Order, Side, Uplo, M, N, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc);
 }
 
 int blasx_dtrmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, double alpha, const double* A, int lda,

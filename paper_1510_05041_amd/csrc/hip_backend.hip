@@ -50,6 +50,43 @@ __global__ void trtri_blocks_kernel(const T* __restrict__ tri, int ld_tri, T* __
     }
 }
 
+// The full symmetric tile from its stored triangle (SYMM diagonal tiles, paper Eq. 1f): element
+// (r, c) outside the stored triangle is the stored element (c, r).  32 x 32 blocks through LDS so
+// that both the reads and the writes are coalesced.
+template <typename T>
+__global__ void symmetrize_kernel(const T* __restrict__ src, int ld_src, T* __restrict__ dst, int ld_dst, int n, int lower) {
+    __shared__ T blk[32][33];
+    const int br = blockIdx.x * 32, bc = blockIdx.y * 32;
+    // block (br, bc) of dst comes from block (br, bc) of src when that block is in the stored
+    // triangle, else from block (bc, br) transposed; diagonal blocks mix both element by element
+    const bool block_stored = lower ? (br >= bc) : (br <= bc);
+    const int sr = block_stored ? br : bc, sc = block_stored ? bc : br;
+    for (int c = threadIdx.y; c < 32; c += blockDim.y) {
+        const int r = threadIdx.x;
+        T v = T(0);
+        if (sr + r < n && sc + c < n) {
+            const int gr = sr + r, gc = sc + c;
+            const bool elem_stored = lower ? (gr >= gc) : (gr <= gc);
+            if (elem_stored) v = src[(size_t)gr + (size_t)gc * ld_src];
+        }
+        blk[c][r] = v;          // blk[c][r] = stored (sr + r, sc + c), zero where not stored
+    }
+    __syncthreads();
+    for (int c = threadIdx.y; c < 32; c += blockDim.y) {
+        const int r = threadIdx.x;
+        const int gr = br + r, gc = bc + c;
+        if (gr >= n || gc >= n) continue;
+        T v;
+        if (br != bc) {
+            v = block_stored ? blk[c][r] : blk[r][c];
+        } else {
+            const bool elem_stored = lower ? (gr >= gc) : (gr <= gc);
+            v = elem_stored ? blk[c][r] : blk[r][c];
+        }
+        dst[(size_t)gr + (size_t)gc * ld_dst] = v;
+    }
+}
+
 #define HB_CHECK(call)                                   \
     do {                                                 \
         hipError_t e_ = (call);                          \
@@ -134,6 +171,19 @@ public:
         else
             hipLaunchKernelGGL(trtri_blocks_kernel<float>, dim3(grid), dim3(64), 0, stream(s), static_cast<const float*>(tri),
                                ld_tri, static_cast<float*>(inv), ld_inv, n, nb, lower, unit);
+        HB_CHECK(hipGetLastError());
+        return 0;
+    }
+
+    int launch_symmetrize(int dtype, const void* src, int ld_src, void* dst, int ld_dst, int n, bool lower, int s) override {
+        if (n <= 0) return 0;
+        const dim3 grid((n + 31) / 32, (n + 31) / 32), block(32, 8);
+        if (dtype == 0)
+            hipLaunchKernelGGL(symmetrize_kernel<double>, grid, block, 0, stream(s), static_cast<const double*>(src), ld_src,
+                               static_cast<double*>(dst), ld_dst, n, lower ? 1 : 0);
+        else
+            hipLaunchKernelGGL(symmetrize_kernel<float>, grid, block, 0, stream(s), static_cast<const float*>(src), ld_src,
+                               static_cast<float*>(dst), ld_dst, n, lower ? 1 : 0);
         HB_CHECK(hipGetLastError());
         return 0;
     }

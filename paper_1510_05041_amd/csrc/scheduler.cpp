@@ -30,7 +30,9 @@ Scheduler::Scheduler(Backend& be, int nslots, size_t slot_bytes, const SchedConf
     cfg_.group = std::max(1, cfg_.group);
     cfg_.depth = std::max(1, cfg_.depth);
     cfg_.rs = std::max(cfg_.rs, cfg_.group);
-    for (int q = 0; q < 3; ++q) packs_[q].mode = q;
+    for (int q = 0; q < 3; ++q)
+        for (int a = 0; a < 2; ++a)
+            for (int b = 0; b < 2; ++b) packs_[q][a][b].mode = q;
 }
 
 Scheduler::~Scheduler() {
@@ -313,7 +315,9 @@ int Scheduler::flush(OpenPack& op) {
 }
 
 int Scheduler::flush_all() {
-    for (int q = 0; q < 3; ++q) BX_TRY(flush(packs_[q]));
+    for (int q = 0; q < 3; ++q)
+        for (int a = 0; a < 2; ++a)
+            for (int b = 0; b < 2; ++b) BX_TRY(flush(packs_[q][a][b]));
     return 0;
 }
 
@@ -400,17 +404,28 @@ int Scheduler::build_chain(int ri) {
     Block* held[2 * kMaxChain];
     int nheld = 0, nseg = 0;
     double flops = 0;
+    bool ta = p_->ta, tb = p_->tb;
     while (nseg < cfg_.kchain && r.next_step + nseg < nsteps) {
         const StepSpec& s = t.steps[r.next_step + nseg];
+        {
+            // all k-steps of one launch entry go through one kernel instantiation
+            const bool sta = s.ta >= 0 ? s.ta != 0 : p_->ta, stb = s.tb >= 0 ? s.tb != 0 : p_->tb;
+            if (nseg == 0) {
+                ta = sta;
+                tb = stb;
+            } else if (sta != ta || stb != tb) {
+                break;
+            }
+        }
         if (s.dep >= 0) {
             if (task_final_pack_[s.dep] == 0) break;          // producer's last launch not built yet
             if (task_final_pack_[s.dep] > flushed_pack_id_) BX_TRY(flush_all());
         }
         Block *ba = nullptr, *bb = nullptr;
-        int rc = fetch(s.a, &ba);
+        int rc = s.a_sym ? fetch_symmetric(s.a, s.sym_lower, &ba) : fetch(s.a, &ba);
         if (rc == 0) {
             cache_.acquire(ba);
-            rc = fetch(s.b, &bb);
+            rc = s.b_sym ? fetch_symmetric(s.b, s.sym_lower, &bb) : fetch(s.b, &bb);
             if (rc == 0) cache_.acquire(bb);
             else cache_.release(ba);
         }
@@ -440,11 +455,11 @@ int Scheduler::build_chain(int ri) {
     st.lda = st.ldb = st.ldc = T_;
     st.m = t.m;
     st.n = t.n;
-    st.flags = (p_->ta ? TS_TRANS_A : 0u) | (p_->tb ? TS_TRANS_B : 0u) | t.c_flags;
+    st.flags = (ta ? TS_TRANS_A : 0u) | (tb ? TS_TRANS_B : 0u) | t.c_flags;
     st.alpha = t.alpha_step;
     st.beta = r.first ? t.beta_first : 1.0;
-    OpenPack& op = packs_[step_mode(st, p_->dtype)];
-    BX_TRY(add_step(op, p_->ta, p_->tb, st, flops, (uint64_t)nseg));
+    OpenPack& op = pack_for(step_mode(st, p_->dtype), ta, tb);
+    BX_TRY(add_step(op, ta, tb, st, flops, (uint64_t)nseg));
     for (int q = 0; q < nheld; ++q) {
         op.blocks.push_back(held[q]);
         op.wait_slots.push_back(held[q]->slot);
@@ -545,7 +560,7 @@ int Scheduler::get_inverse(const Task& t, Block** out) {
                     }
                 }
                 st.beta = 0.0;
-                BX_TRY(add_step(packs_[step_mode(st, p_->dtype)], false, false, st, 1.0 * st.m * st.n * st.seg[0].k, 0));
+                BX_TRY(add_step(pack_for(step_mode(st, p_->dtype), false, false), false, false, st, 1.0 * st.m * st.n * st.seg[0].k, 0));
             }
             BX_TRY(flush_all());
         }
@@ -564,6 +579,44 @@ int Scheduler::get_inverse(const Task& t, Block** out) {
         inflight_.push_back(std::move(f));
     }
     *out = inv;
+    return 0;
+}
+
+// SYMM: device copy of a diagonal tile of the symmetric matrix with both triangles filled in,
+// cached under the tile's host address with a tag (5: upper stored, 6: lower stored).  The copy
+// is made on the compute stream, so every launch issued afterwards sees it.  Return values as fetch().
+int Scheduler::fetch_symmetric(const TileRef& t, bool lower, Block** out) {
+    const TileKey key = key_of(t, lower ? 6 : 5);
+    bool hit = false;
+    if (cache_.find(key)) {
+        *out = cache_.translate(key, &hit);
+        return 0;
+    }
+    Block* src = nullptr;
+    const int rc = fetch(t, &src);
+    if (rc) return rc;
+    cache_.acquire(src);
+    Block* sym = cache_.translate(key, &hit);
+    if (!sym) {
+        cache_.release(src);
+        return -1;
+    }
+    // the stored tile must have arrived, and a stale inbound copy into the new slot must be over
+    for (int slot : {src->slot, sym->slot}) {
+        if (fill_seq_[slot] > compute_waited_[fill_stream_[slot]]) {
+            if (be_.stream_wait_event(STREAM_COMPUTE, fill_ev_[slot])) return BLASX_ERR_DEVICE;
+            compute_waited_[fill_stream_[slot]] = fill_seq_[slot];
+        }
+    }
+    if (be_.launch_symmetrize(p_->dtype, slot_ptr(src->slot), T_, slot_ptr(sym->slot), T_, (int)t.rows, lower, STREAM_COMPUTE))
+        return BLASX_ERR_DEVICE;
+    // the stored tile keeps its reader until the copy has run
+    InFlight f;
+    f.done_ev = new_event();
+    if (be_.event_record(f.done_ev, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
+    f.blocks.push_back(src);
+    inflight_.push_back(std::move(f));
+    *out = sym;
     return 0;
 }
 
@@ -601,7 +654,7 @@ int Scheduler::build_solve(int ri) {
     }
     st.alpha = r.first ? t.beta_first : 1.0;   // a task without update steps still owes the alpha
     st.beta = 0.0;
-    OpenPack& op = packs_[step_mode(st, p_->dtype)];
+    OpenPack& op = pack_for(step_mode(st, p_->dtype), p_->ta, p_->tb);
     BX_TRY(add_step(op, p_->ta, p_->tb, st, 1.0 * t.m * t.n * st.seg[0].k, 1));
     op.blocks.push_back(inv);
     op.wait_slots.push_back(r.c_slot);

@@ -108,6 +108,8 @@ private:
     int  build_chain(int ri);
     int  build_solve(int ri);
     int  get_inverse(const Task& t, Block** out);
+    int  fetch_symmetric(const TileRef& t, bool lower, Block** out);
+    OpenPack& pack_for(int mode, bool ta, bool tb) { return packs_[mode][ta ? 1 : 0][tb ? 1 : 0]; }
     int  add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, double flops, uint64_t nsteps);
     int  flush(OpenPack& op);
     int  flush_all();
@@ -143,7 +145,7 @@ private:
     std::vector<char> task_started_, task_issued_;   // per task
     std::vector<uint64_t> task_final_pack_;          // pack id of the launch that finishes it
     std::vector<PanelState> panels_;
-    OpenPack packs_[3];                 // open launch packs, one per kernel mode
+    OpenPack packs_[3][2][2];           // open launch packs, one per kernel instantiation (mode, transA, transB)
     uint64_t next_pack_id_ = 1, flushed_pack_id_ = 0;
     std::deque<InFlight> inflight_;
     std::deque<WriteBack> writebacks_;

@@ -141,6 +141,95 @@ void build_syrk(Problem& p, int dtype, int T, bool lower, bool trans, int N, int
     }
 }
 
+// Eq. 1e: C_ij = alpha * sum_k A_ik B_jk^T + alpha * sum_k B_ik A_jk^T + beta * C_ij over one triangle:
+// two k-steps per k tile, both through the same kernel variant.
+void build_syr2k(Problem& p, int dtype, int T, bool lower, bool trans, int N, int K, double alpha,
+                 const void* A, int64_t lda, const void* B, int64_t ldb, double beta, void* C, int64_t ldc,
+                 const OrderOpts& oo) {
+    init_problem(p, dtype, T, trans, !trans, ldc);
+    const int nt = cdiv(N, T), ntk = (alpha == 0.0) ? 0 : cdiv(K, T);
+    const int64_t rows = trans ? K : N, cols = trans ? N : K;
+    auto keep = [lower](int i, int j) { return lower ? i >= j : i <= j; };
+    auto tile_of = [&](const void* X, int64_t ldx, int t, int kt) {
+        return trans ? stored_tile(X, ldx, p.esize, T, kt, t, rows, cols) : stored_tile(X, ldx, p.esize, T, t, kt, rows, cols);
+    };
+    for (auto ij : superblock_order(nt, nt, oo, keep)) {
+        const int i = ij.first, j = ij.second;
+        Task t;
+        t.ti = i;
+        t.tj = j;
+        const TileRef c = stored_tile(C, ldc, p.esize, T, i, j, N, N);
+        t.m = c.rows;
+        t.n = c.cols;
+        t.c_host = const_cast<char*>(c.host);
+        t.load_c = (beta != 0.0) || (i == j);
+        t.alpha_step = alpha;
+        t.beta_first = beta;
+        if (i == j) t.c_flags = lower ? TS_C_LOWER : TS_C_UPPER;
+        for (int kt = 0; kt < ntk; ++kt)
+            for (int half = 0; half < 2; ++half) {
+                StepSpec s;
+                s.a = tile_of(half ? B : A, half ? ldb : lda, i, kt);
+                s.b = tile_of(half ? A : B, half ? lda : ldb, j, kt);
+                s.k = trans ? s.a.rows : s.a.cols;
+                t.steps.push_back(s);
+                t.flops += (i == j ? 1.0 : 2.0) * t.m * t.n * s.k;
+            }
+        p.flops += t.flops;
+        p.tasks.push_back(std::move(t));
+    }
+}
+
+// Eq. 1f: C_ij = alpha * sum_k S_ik B_kj + beta * C_ij (left) with S the symmetric matrix whose
+// `lower` (or upper) triangle A stores: a tile of S outside the stored triangle is the mirrored
+// stored tile, transposed in the kernel; the diagonal tile is completed by reflection on the device.
+void build_symm(Problem& p, int dtype, int T, bool left, bool lower, int M, int N, double alpha,
+                const void* A, int64_t lda, const void* B, int64_t ldb, double beta, void* C, int64_t ldc,
+                const OrderOpts& oo) {
+    init_problem(p, dtype, T, false, false, ldc);
+    const int ntm = cdiv(M, T), ntn = cdiv(N, T);
+    const int na = left ? M : N, nta = (alpha == 0.0) ? 0 : cdiv(na, T);
+    for (auto ij : superblock_order(ntm, ntn, oo, [](int, int) { return true; })) {
+        const int i = ij.first, j = ij.second;
+        Task t;
+        t.ti = i;
+        t.tj = j;
+        const TileRef c = stored_tile(C, ldc, p.esize, T, i, j, M, N);
+        t.m = c.rows;
+        t.n = c.cols;
+        t.c_host = const_cast<char*>(c.host);
+        t.load_c = (beta != 0.0);
+        t.alpha_step = alpha;
+        t.beta_first = beta;
+        for (int kt = 0; kt < nta; ++kt) {
+            StepSpec s;
+            // tile (r, cidx) of S as the product needs it
+            const int r = left ? i : kt, cidx = left ? kt : j;
+            const bool stored = lower ? (r >= cidx) : (r <= cidx);
+            const TileRef st = stored ? stored_tile(A, lda, p.esize, T, r, cidx, na, na) : stored_tile(A, lda, p.esize, T, cidx, r, na, na);
+            if (left) {
+                s.a = st;
+                s.ta = stored ? 0 : 1;
+                s.tb = 0;
+                s.b = stored_tile(B, ldb, p.esize, T, kt, j, M, N);
+                s.k = s.b.rows;
+                if (r == cidx) { s.a_sym = true; s.sym_lower = lower; }
+            } else {
+                s.a = stored_tile(B, ldb, p.esize, T, i, kt, M, N);
+                s.b = st;
+                s.ta = 0;
+                s.tb = stored ? 0 : 1;
+                s.k = s.a.cols;
+                if (r == cidx) { s.b_sym = true; s.sym_lower = lower; }
+            }
+            t.steps.push_back(s);
+            t.flops += 2.0 * t.m * t.n * s.k;
+        }
+        p.flops += t.flops;
+        p.tasks.push_back(std::move(t));
+    }
+}
+
 // Eq. 1d with alpha on every term: B_ij = alpha * sum_k op(A)_ik B_kj (left) or
 // alpha * sum_k B_ik op(A)_kj (right); the sum covers the tiles where op(A) is non-zero and
 // the diagonal tile of A is masked to its triangle inside the kernel.

@@ -29,6 +29,11 @@ struct StepSpec {
     uint32_t seg_flags = 0;  // TS_TRI_* when one operand is a diagonal tile of a triangular matrix
     int32_t dep = -1;    // index of the task whose *result* one operand is (TRSM), or -1
     bool a_is_dep = false, b_is_dep = false;
+    int8_t ta = -1, tb = -1;   // per-step transposition of the left / right operand (-1: the problem's)
+    // SYMM: the operand is a diagonal tile of a symmetric matrix of which only one triangle is
+    // stored; the kernel gets a device copy with the other triangle filled in by reflection.
+    bool a_sym = false, b_sym = false;
+    bool sym_lower = false;
 };
 
 struct Task {
@@ -82,6 +87,15 @@ void build_gemm(Problem& p, int dtype, int T, bool ta, bool tb, int M, int N, in
 // Triangle `lower` of C (N x N) <- alpha A A^T + beta C (trans = false, A N x K) or alpha A^T A + beta C.
 void build_syrk(Problem& p, int dtype, int T, bool lower, bool trans, int N, int K, double alpha,
                 const void* A, int64_t lda, double beta, void* C, int64_t ldc, const OrderOpts& oo);
+// Triangle `lower` of C (N x N) <- alpha (A B^T + B A^T) + beta C (trans = false) or alpha (A^T B + B^T A) + beta C.
+void build_syr2k(Problem& p, int dtype, int T, bool lower, bool trans, int N, int K, double alpha,
+                 const void* A, int64_t lda, const void* B, int64_t ldb, double beta, void* C, int64_t ldc,
+                 const OrderOpts& oo);
+// C (M x N) <- alpha A B + beta C (left, A M x M symmetric) or alpha B A + beta C (right, A N x N symmetric);
+// only the `lower` (or upper) triangle of A is stored.
+void build_symm(Problem& p, int dtype, int T, bool left, bool lower, int M, int N, double alpha,
+                const void* A, int64_t lda, const void* B, int64_t ldb, double beta, void* C, int64_t ldc,
+                const OrderOpts& oo);
 // B (M x N) <- alpha op(A) B (left) or alpha B op(A) (right).
 void build_trmm(Problem& p, int dtype, int T, bool left, bool lower, bool trans, bool unit, int M, int N,
                 double alpha, const void* A, int64_t lda, void* B, int64_t ldb, const OrderOpts& oo);

@@ -22,7 +22,7 @@ namespace blasx {
 namespace {
 
 struct Op {
-    enum Kind { COPY, LAUNCH, TRTRI, RECORD, WAIT } kind = COPY;
+    enum Kind { COPY, LAUNCH, TRTRI, SYMMETRIZE, RECORD, WAIT } kind = COPY;
     // COPY (both directions are plain strided memcpy on the host)
     char* dst = nullptr;
     const char* src = nullptr;
@@ -120,6 +120,18 @@ void run_trtri(const Op& op) {
     }
 }
 
+template <typename T>
+void run_symmetrize(const Op& op) {
+    const T* src = static_cast<const T*>(op.tri);
+    T* dst = static_cast<T*>(op.inv);
+    const bool lower = op.flags & TS_TRI_LOWER;
+    for (int c = 0; c < op.n; ++c)
+        for (int r = 0; r < op.n; ++r) {
+            const bool stored = lower ? r >= c : r <= c;
+            dst[(size_t)r + (size_t)c * op.ld_inv] = stored ? src[(size_t)r + (size_t)c * op.ld_tri] : src[(size_t)c + (size_t)r * op.ld_tri];
+        }
+}
+
 class SimBackend : public Backend {
 public:
     SimBackend(size_t bytes, int nstreams) : mem_(bytes, (char)0xA5), queues_(nstreams), rng_(g_seed) {}
@@ -163,6 +175,19 @@ public:
         op.n = n;
         op.nb = nb;
         op.flags = flags;
+        push(s, op);
+        return 0;
+    }
+    int launch_symmetrize(int dtype, const void* src, int ld_src, void* dst, int ld_dst, int n, bool lower, int s) override {
+        Op op;
+        op.kind = Op::SYMMETRIZE;
+        op.dtype = dtype;
+        op.tri = src;
+        op.inv = dst;
+        op.ld_tri = ld_src;
+        op.ld_inv = ld_dst;
+        op.n = n;
+        op.flags = lower ? TS_TRI_LOWER : 0u;
         push(s, op);
         return 0;
     }
@@ -281,6 +306,10 @@ private:
             case Op::TRTRI:
                 if (op.dtype == 0) run_trtri<double>(op);
                 else run_trtri<float>(op);
+                break;
+            case Op::SYMMETRIZE:
+                if (op.dtype == 0) run_symmetrize<double>(op);
+                else run_symmetrize<float>(op);
                 break;
             case Op::RECORD:
                 if (events_[op.ev].done < op.gen) events_[op.ev].done = op.gen;

@@ -204,6 +204,50 @@ def test_dsyrk_small_full_compare(lib, uplo, trans):
     assert relerr(C, want) < TOL64
 
 
+@pytest.mark.parametrize("uplo", [blasx.Upper, blasx.Lower])
+@pytest.mark.parametrize("trans", TRANS)
+def test_dsyr2k_small_full_compare(lib, uplo, trans):
+    N, K = 650, 410
+    configure(lib, T=128, arena_gb=0.25, group=6)
+    shape = (N, K) if trans == blasx.NoTrans else (K, N)
+    A, ka = pinned(*shape, 14, 0)
+    B, kb = pinned(*shape, 14, 1)
+    C, kc = pinned(N, N, 14, 2)
+    other = np.triu_indices(N, 1) if uplo == blasx.Lower else np.tril_indices(N, -1)
+    C[other] = -8765.25
+    want = np.array(C, order="F")
+    lib.dsyr2k(blasx.ColMajor, uplo, trans, N, K, 0.6, A, A.shape[0], B, B.shape[0], -1.0, C, N)
+    ref.syr2k(ref.ColMajor, uplo, trans, 0.6, np.asarray(A), np.asarray(B), -1.0, want)
+    assert np.all(np.asarray(C)[other] == -8765.25)
+    assert relerr(C, want) < TOL64
+
+
+@pytest.mark.parametrize("order", [blasx.ColMajor, blasx.RowMajor])
+@pytest.mark.parametrize("side", [blasx.Left, blasx.Right])
+@pytest.mark.parametrize("uplo", [blasx.Upper, blasx.Lower])
+def test_dsymm_small_full_compare(lib, order, side, uplo):
+    M, N = 530, 390
+    configure(lib, T=128, arena_gb=0.25, group=6)
+    na = M if side == blasx.Left else N
+    A, ka = pinned(na, na, 15, 0)
+    # the triangle that is not stored, in terms of the logical matrix
+    logical_other = np.triu_indices(na, 1) if uplo == blasx.Lower else np.tril_indices(na, -1)
+    r, c = (M, N) if order == blasx.ColMajor else (N, M)   # array extents as column-major storage
+    B, kb = pinned(r, c, 15, 1)
+    C, kc = pinned(r, c, 15, 2)
+    if order == blasx.ColMajor:
+        A[logical_other] = np.nan
+        Ar, Br, want = np.asarray(A), np.asarray(B), np.array(C, order="F")
+    else:
+        A[logical_other[1], logical_other[0]] = np.nan     # the column-major array is the transpose
+        Ar, Br, want = np.asarray(A).T, np.asarray(B).T, np.array(np.asarray(C).T, order="C")
+    lib.dsymm(order, side, uplo, M, N, 1.3, A, na, B, r, 0.5, C, r)
+    ref.symm(order, side, uplo, 1.3, Ar, Br, 0.5, want)
+    got = np.asarray(C) if order == blasx.ColMajor else np.asarray(C).T
+    assert np.all(np.isfinite(got))
+    assert relerr(got, want) < TOL64
+
+
 FLAGS = list(itertools.product([blasx.Left, blasx.Right], [blasx.Upper, blasx.Lower], TRANS, [blasx.NonUnit, blasx.Unit]))
 
 
@@ -425,6 +469,84 @@ def test_config5b_sgemm_notrans_trans_sampled(lib):
     before = lambda gi, gj: np.array([[np.float32(synth.element(7, synth.MAT_C, int(i), int(j), n)) for j in gj] for i in gi],
                                      dtype=np.float32)
     check_gemm_sampled(blasx.NoTrans, blasx.Trans, n, n, n, 1.0, A, B, 1.0, before, C, T, 7, TOL32, dtype=np.float32)
+
+def test_dsyr2k_lower_notrans_16384_sampled(lib):
+    """DSYR2K Lower/NoTrans N=16384 K=8192, alpha=1, beta=1 at the SYRK workload's shape."""
+    N, K, T = 16384, 8192, 1024
+    configure(lib, T=T, nstreams=4, arena_gb=8.0)
+    A, ka = pinned(N, K, 16, synth.MAT_A)
+    B, kb = pinned(N, K, 16, synth.MAT_B)
+    C, kc = pinned(N, N, 16, synth.MAT_C)
+    dt = timed(lambda: lib.dsyr2k(blasx.ColMajor, blasx.Lower, blasx.NoTrans, N, K, 1.0, A, N, B, N, 1.0, C, N))
+    st = report("DSYR2K L/N N=16384 K=8192", lib, 2.0 * N * (N + 1) * K, dt)
+    nt = N // T
+    assert st["tasks"] == nt * (nt + 1) // 2 and st["bytes_d2h"] == 8 * T * T * st["tasks"]
+    rng = np.random.default_rng(16)
+    before = c_before(16, synth.MAT_C, N)
+    worst, seen = 0.0, 0
+    for (ti, tj) in synth.sample_tiles(nt, nt, 48, 16):
+        rows, cols = sampled_positions(T, T, T, rng)
+        gi, gj = np.array(rows) + ti * T, np.array(cols) + tj * T
+        got = np.asarray(C)[np.ix_(gi, gj)]
+        c0 = before(gi, gj)
+        if ti < tj:                                    # upper triangle: must be bit-identical
+            assert np.array_equal(got, c0)
+            continue
+        want = np.asfortranarray(c0)
+        ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, np.asfortranarray(A[gi, :]), np.asfortranarray(B[gj, :]), 1.0, want)
+        ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, np.asfortranarray(B[gi, :]), np.asfortranarray(A[gj, :]), 1.0, want)
+        mask = (gi[:, None] >= gj[None, :])
+        assert np.array_equal(got[~mask], c0[~mask])
+        worst = max(worst, relerr(got[mask], want[mask]))
+        seen += 1
+    assert seen > 10 and worst < TOL64, worst
+
+
+@pytest.mark.parametrize("side,uplo", [(blasx.Left, blasx.Lower), (blasx.Right, blasx.Upper)])
+def test_dsymm_16384_sampled(lib, side, uplo):
+    """DSYMM M=N=16384, alpha=1, beta=1; the triangle of A that is not stored holds NaN."""
+    n, T = 16384, 1024
+    configure(lib, T=T, nstreams=4, arena_gb=12.0)
+    A, ka = pinned(n, n, 17, synth.MAT_A)
+    B, kb = pinned(n, n, 17, synth.MAT_B)
+    C, kc = pinned(n, n, 17, synth.MAT_C)
+    for j in range(n):                                    # poison the other triangle column by column
+        if uplo == blasx.Lower:
+            A[:j, j] = np.nan
+        else:
+            A[j + 1:, j] = np.nan
+    dt = timed(lambda: lib.dsymm(blasx.ColMajor, side, uplo, n, n, 1.0, A, n, B, n, 1.0, C, n))
+    st = report("DSYMM %s N=16384" % ("L/L" if side == blasx.Left else "R/U"), lib, 2.0 * n ** 3, dt)
+    nt = n // T
+    assert st["tasks"] == nt * nt and st["tile_steps"] == nt ** 3
+    assert st["evictions"] == 0 and st["bytes_d2h"] == 8 * n * n
+    assert st["bytes_h2d"] == 8 * T * T * (nt * (nt + 1) // 2 + 2 * nt * nt)     # every stored tile exactly once
+    rng = np.random.default_rng(17)
+    before = c_before(17, synth.MAT_C, n)
+
+    def sym_rows(idx):            # rows idx of the full symmetric matrix (which are also its columns)
+        out = np.empty((len(idx), n))
+        for q, i in enumerate(idx):
+            if uplo == blasx.Lower:
+                out[q, :i + 1] = A[i, :i + 1]
+                out[q, i + 1:] = A[i + 1:, i]
+            else:
+                out[q, :i] = A[:i, i]
+                out[q, i:] = A[i, i:]
+        return out
+
+    worst = 0.0
+    for (ti, tj) in synth.sample_tiles(nt, nt, 32, 17):
+        rows, cols = sampled_positions(T, T, T, rng)
+        gi, gj = np.array(rows) + ti * T, np.array(cols) + tj * T
+        got = np.asarray(C)[np.ix_(gi, gj)]
+        want = np.asfortranarray(before(gi, gj))
+        if side == blasx.Left:
+            ref.gemm(ref.ColMajor, ref.NoTrans, ref.NoTrans, 1.0, np.asfortranarray(sym_rows(gi)), np.asfortranarray(B[:, gj]), 1.0, want)
+        else:
+            ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, np.asfortranarray(B[gi, :]), np.asfortranarray(sym_rows(gj)), 1.0, want)
+        worst = max(worst, relerr(got, want))
+    assert worst < TOL64, worst
 
 
 # ------------------------------------------------------------------ single-precision variants --

@@ -184,6 +184,19 @@ def test_argument_errors_follow_the_prototype_positions(sim):
     assert sim.dsyrk(CM, 0, NT, 8, 8, 1.0, a, 8, 0.0, a, 8, check=False) == -2
     assert sim.dtrsm(CM, blasx.Left, blasx.Lower, NT, 0, 8, 8, 1.0, a, 8, a, 8, check=False) == -5
     assert sim.dtrmm(CM, blasx.Left, blasx.Lower, NT, blasx.Unit, 8, 8, 1.0, a, 4, a, 8, check=False) == -10
+    k2 = lambda *args: sim.dsyr2k(*args, check=False)
+    UP = blasx.Upper
+    assert k2(CM, 0, NT, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 8) == -2
+    assert k2(CM, UP, NT, 8, 8, 1.0, a, 7, a, 8, 0.0, a, 8) == -8
+    assert k2(CM, UP, NT, 8, 8, 1.0, a, 8, a, 7, 0.0, a, 8) == -10
+    assert k2(CM, UP, NT, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 7) == -13
+    sm = lambda *args: sim.dsymm(*args, check=False)
+    assert sm(CM, 0, UP, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 8) == -2
+    assert sm(CM, blasx.Left, 0, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 8) == -3
+    assert sm(CM, blasx.Left, UP, 8, -2, 1.0, a, 8, a, 8, 0.0, a, 8) == -5
+    assert sm(CM, blasx.Right, UP, 4, 8, 1.0, a, 7, a, 8, 0.0, a, 8) == -8
+    assert sm(CM, blasx.Left, UP, 8, 8, 1.0, a, 8, a, 7, 0.0, a, 8) == -10
+    assert sm(CM, blasx.Left, UP, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 7) == -13
     assert sim.set_option.__self__._lib.blasx_set_tile(20) == 4
 
 
@@ -208,6 +221,86 @@ def test_syrk_matches_oracle_and_leaves_other_triangle(sim, order, uplo, trans, 
     assert relerr(Cs, np.asarray(Cr)) < 1e-14
     nt = -(-N // 16)
     assert sim.get_stats()["tasks"] == nt * (nt + 1) // 2
+
+
+# ------------------------------------------------------------------ SYR2K / SYMM ---
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("uplo", [blasx.Upper, blasx.Lower])
+@pytest.mark.parametrize("trans", TRANS)
+@pytest.mark.parametrize("beta", [0.0, -0.4])
+def test_syr2k_matches_oracle_and_leaves_other_triangle(sim, order, uplo, trans, beta):
+    setup(sim, T=16, seed=3 * uplo + trans + order, group=4)
+    rng = np.random.default_rng(8)
+    N, K = 53, 41
+    shape = (N, K) if trans == blasx.NoTrans else (K, N)
+    A, B = rng.uniform(-1, 1, shape), rng.uniform(-1, 1, shape)
+    C = rng.uniform(-1, 1, (N, N))
+    other = np.triu_indices(N, 1) if uplo == blasx.Lower else np.tril_indices(N, -1)
+    C[other] = -55.5
+    As, Bs, Cs, Cr = store(A, order, 1), store(B, order, 3), store(C, order, 2), store(C, order, 2)
+    sim.dsyr2k(order, uplo, trans, N, K, 0.75, As, ld_of(As, order), Bs, ld_of(Bs, order), beta, Cs, ld_of(Cs, order))
+    ref.syr2k(order, uplo, trans, 0.75, As, Bs, beta, Cr)
+    assert np.all(np.asarray(Cs)[other] == -55.5)
+    assert relerr(Cs, np.asarray(Cr)) < 1e-14
+    nt = -(-N // 16)
+    st = sim.get_stats()
+    assert st["tasks"] == nt * (nt + 1) // 2
+    assert st["tile_steps"] == 2 * -(-K // 16) * st["tasks"]
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("side", [blasx.Left, blasx.Right])
+@pytest.mark.parametrize("uplo", [blasx.Upper, blasx.Lower])
+@pytest.mark.parametrize("beta", [0.0, 1.25])
+def test_symm_matches_oracle_and_never_reads_the_other_triangle(sim, order, side, uplo, beta):
+    setup(sim, T=16, seed=side + uplo + order, group=6)
+    rng = np.random.default_rng(9)
+    M, N = 55, 38
+    na = M if side == blasx.Left else N
+    A = rng.uniform(-1, 1, (na, na))
+    other = np.triu_indices(na, 1) if uplo == blasx.Lower else np.tril_indices(na, -1)
+    A[other] = np.nan
+    B, C = rng.uniform(-1, 1, (M, N)), rng.uniform(-1, 1, (M, N))
+    As, Bs, Cs, Cr = store(A, order, 2), store(B, order, 1), store(C, order, 3), store(C, order, 3)
+    sim.dsymm(order, side, uplo, M, N, -1.5, As, ld_of(As, order), Bs, ld_of(Bs, order), beta, Cs, ld_of(Cs, order))
+    ref.symm(order, side, uplo, -1.5, As, Bs, beta, Cr)
+    assert np.all(np.isfinite(np.asarray(Cs)))
+    assert relerr(Cs, np.asarray(Cr)) < 1e-14
+    st = sim.get_stats()
+    assert st["tasks"] == -(-M // 16) * -(-N // 16)
+    assert st["tile_steps"] == st["tasks"] * -(-na // 16)
+
+
+def test_symm_under_slot_pressure_and_single_precision(sim):
+    # few slots: symmetrised diagonal tiles get evicted and rebuilt
+    setup(sim, T=16, seed=5, arena_tiles=14, group=3)
+    rng = np.random.default_rng(10)
+    M, N = 80, 64
+    A = np.tril(rng.integers(-2, 3, (M, M)).astype(np.float64))
+    B = rng.integers(-2, 3, (M, N)).astype(np.float64)
+    C = np.zeros((M, N))
+    As, Bs, Cs = store(A, blasx.ColMajor), store(B, blasx.ColMajor), store(C, blasx.ColMajor)
+    sim.dsymm(blasx.ColMajor, blasx.Left, blasx.Lower, M, N, 1.0, As, M, Bs, M, 0.0, Cs, M)
+    S = A + np.tril(A, -1).T
+    assert np.array_equal(np.asarray(Cs), S @ B)          # small integers: exact in any order
+    assert sim.get_stats()["evictions"] > 0
+
+    setup(sim, T=32, seed=6, esize=4)
+    A32 = rng.uniform(-1, 1, (N, N)).astype(np.float32)
+    B32, C32 = rng.uniform(-1, 1, (M, N)).astype(np.float32), rng.uniform(-1, 1, (M, N)).astype(np.float32)
+    As, Bs = store(A32, blasx.RowMajor, 1, np.float32), store(B32, blasx.RowMajor, 0, np.float32)
+    Cs, Cr = store(C32, blasx.RowMajor, 2, np.float32), store(C32, blasx.RowMajor, 2, np.float32)
+    sim.ssymm(blasx.RowMajor, blasx.Right, blasx.Upper, M, N, 0.5, As, ld_of(As, blasx.RowMajor), Bs, ld_of(Bs, blasx.RowMajor),
+              2.0, Cs, ld_of(Cs, blasx.RowMajor))
+    ref.symm(blasx.RowMajor, blasx.Right, blasx.Upper, 0.5, As, Bs, 2.0, Cr)
+    assert relerr(Cs, np.asarray(Cr)) < 1e-6
+    Cs, Cr = store(C32[:N, :N], blasx.ColMajor, 0, np.float32), store(C32[:N, :N], blasx.ColMajor, 0, np.float32)
+    Ak = store(B32.T.copy(), blasx.ColMajor, 0, np.float32)   # N x M
+    Bk = store(A32[:, :1].repeat(M, 1), blasx.ColMajor, 0, np.float32)
+    sim.ssyr2k(blasx.ColMajor, blasx.Upper, blasx.NoTrans, N, M, 1.0, Ak, N, Bk, N, 1.0, Cs, N)
+    ref.syr2k(blasx.ColMajor, blasx.Upper, blasx.NoTrans, 1.0, Ak, Bk, 1.0, Cr)
+    assert relerr(Cs, np.asarray(Cr)) < 1e-6
 
 
 # ------------------------------------------------------------------ TRMM / TRSM ---
