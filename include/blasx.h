@@ -133,9 +133,40 @@ int blasx_set_cache_bytes(size_t cap);
  *   "sb_rows", "sb_cols"  super-block shape used to order the task queue
  *   "shells"   1: super-blocks are visited in growing square shells, 0: block row by block row
  *   "profile"  1: time every launch with events (adds two event records per launch)
+ *   "persist"  1: the tile cache outlives the call (see below); 0 (default): it is dropped
+ *              when a call returns
  * Returns BLASX_ERR_CONFIG for an unknown name or an out-of-range value. */
 int blasx_set_option(const char* name, long value);
-long blasx_get_option(const char* name);   /* -1 for an unknown name */
+/* Reads a knob back; also "tile" and "cached_tiles" (blocks now held by the persistent cache).
+ * -1 for an unknown name. */
+long blasx_get_option(const char* name);
+
+/* Persistent tile cache (the paper's applications multiply by the same matrices call after
+ * call, Section V.C; the paper does not say what happens to cached tiles between calls).
+ * With "persist" = 1 operand tiles, and tiles derived from them (inverted or completed
+ * diagonal tiles), stay in HBM after a call returns and are hits for later calls that name the
+ * same host tile (address, leading dimension, extent, element size), least recently used
+ * ones making room as usual.  The contract:
+ *   - the library forgets by itself every cached tile that shares an element with a matrix it
+ *     writes (the output of any call, before and after the call; results of a triangular
+ *     solve stay cached, they equal the host copy);
+ *   - the caller must tell the library before the next call when it has changed, freed or
+ *     re-used the memory of a matrix that was an operand of an earlier call, by one of:
+ *       blasx_invalidate(ptr, bytes)       every cached tile touching [ptr, ptr + bytes)
+ *       blasx_invalidate_matrix(A, ld, rows, cols, elem_size)
+ *                                          every cached tile sharing an element with the
+ *                                          rows x cols column-major matrix at A (for a
+ *                                          row-major matrix pass its columns as rows); exact
+ *                                          for views of one parent matrix with the same ld
+ *       blasx_invalidate_all()             everything
+ *     A stale tile is not detected: results are then computed from the old values.
+ *   - changing the tile size, the cache cap or the element size of the calls empties the
+ *     cache; blasx_init / blasx_shutdown / "persist" = 0 drop it.
+ * The three calls return 0, or -k for a bad k-th argument; they are cheap no-ops when nothing
+ * is cached.  Not thread-safe, like the rest of the library. */
+int blasx_invalidate(const void* ptr, size_t bytes);
+int blasx_invalidate_matrix(const void* A, int ld, int rows, int cols, int elem_size);
+int blasx_invalidate_all(void);
 
 /* Page-locked host memory for matrices (hipHostMalloc).  Returns NULL on failure. */
 void* blasx_host_alloc(size_t bytes);
@@ -159,6 +190,7 @@ typedef struct blasx_stats {
     double   t_total_s;      /* wall time inside level-3 calls */
     double   t_issue_s;      /* of which: host scheduling/issue time (not waiting) */
     double   t_kernel_s;     /* sum of event-timed launch durations ("profile" = 1) */
+    uint64_t invalidations;  /* cached tiles forgotten because their host copy changed (persistent cache) */
 } blasx_stats;
 
 int blasx_get_stats(blasx_stats* out);

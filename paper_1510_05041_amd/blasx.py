@@ -25,7 +25,8 @@ class Stats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint64) for n in (
         "calls", "tasks", "tile_steps", "launches", "hits", "misses", "evictions", "refetches",
         "copies_h2d", "copies_d2h", "bytes_h2d", "bytes_d2h", "slot_waits", "peak_slots",
-        "profiled_launches")] + [(n, ctypes.c_double) for n in ("flops", "t_total_s", "t_issue_s", "t_kernel_s")]
+        "profiled_launches")] + [(n, ctypes.c_double) for n in ("flops", "t_total_s", "t_issue_s", "t_kernel_s")] + [
+        ("invalidations", ctypes.c_uint64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -79,6 +80,8 @@ class Library:
         lib.blasx_set_option.argtypes = [ctypes.c_char_p, ctypes.c_long]
         lib.blasx_get_option.argtypes = [ctypes.c_char_p]
         lib.blasx_get_option.restype = ctypes.c_long
+        lib.blasx_invalidate.argtypes = [vp, sz]
+        lib.blasx_invalidate_matrix.argtypes = [vp, ci, ci, ci, ci]
         lib.blasx_host_alloc.argtypes = [sz]
         lib.blasx_host_alloc.restype = vp
         lib.blasx_host_free.argtypes = [vp]
@@ -136,6 +139,18 @@ class Library:
 
     def get_option(self, name):
         return self._lib.blasx_get_option(name.encode())
+
+    def invalidate(self, a):
+        """Forget cached tiles of the numpy array `a` (its whole address range)."""
+        lo = a.ctypes.data
+        self._check("blasx_invalidate", self._lib.blasx_invalidate(lo, int(a.nbytes if a.flags.contiguous else
+                    sum((n - 1) * abs(st) for n, st in zip(a.shape, a.strides)) + a.itemsize)))
+
+    def invalidate_matrix(self, A, ld, rows, cols, elem_size):
+        self._check("blasx_invalidate_matrix", self._lib.blasx_invalidate_matrix(_ptr(A), ld, rows, cols, elem_size))
+
+    def invalidate_all(self):
+        self._check("blasx_invalidate_all", self._lib.blasx_invalidate_all())
 
     def host_alloc(self, nbytes):
         p = self._lib.blasx_host_alloc(int(nbytes))

@@ -2,6 +2,32 @@
 
 namespace blasx {
 
+bool TileKey::overlaps(const void* base, int64_t ld_r, int64_t rows_r, int64_t cols_r, int esize_r) const {
+    if (rows <= 0 || cols <= 0 || rows_r <= 0 || cols_r <= 0) return false;
+    const char* t0 = static_cast<const char*>(host);
+    const char* t1 = t0 + ((int64_t)(cols - 1) * ld + rows) * esize;
+    const char* r0 = static_cast<const char*>(base);
+    const char* r1 = r0 + ((cols_r - 1) * ld_r + rows_r) * esize_r;
+    if (t1 <= r0 || r1 <= t0) return false;
+    const int64_t d = t0 - r0;
+    if (ld != ld_r || esize != esize_r || d % esize != 0 || rows > ld || rows_r > ld) return true;
+    // position of the tile's first element on the region's column grid (floor division)
+    const int64_t e = d / esize;
+    int64_t c0 = e / ld;
+    int64_t q0 = e - c0 * ld;
+    if (q0 < 0) {
+        q0 += ld;
+        --c0;
+    }
+    auto rect_hits = [&](int64_t row_lo, int64_t row_hi, int64_t col_lo, int64_t col_hi) {
+        return row_lo < rows_r && row_hi > 0 && col_lo < cols_r && col_hi > 0 && row_lo < row_hi;
+    };
+    // rows [q0, q0 + rows) of columns [c0, c0 + cols); a tile that crosses the bottom of the grid
+    // continues at the top of the next column
+    if (q0 + rows <= ld) return rect_hits(q0, q0 + rows, c0, c0 + cols);
+    return rect_hits(q0, ld, c0, c0 + cols) || rect_hits(0, q0 + rows - ld, c0 + 1, c0 + 1 + cols);
+}
+
 Alru::Alru(int nslots) : nslots_(nslots) {
     free_.reserve(nslots);
     for (int s = nslots - 1; s >= 0; --s) free_.push_back(s);   // slot 0 is handed out first
@@ -128,6 +154,44 @@ bool Alru::drop(const TileKey& key) {
     give_slot(b->slot);
     delete b;
     return true;
+}
+
+size_t Alru::invalidate_region(const void* base, int64_t ld, int64_t rows, int64_t cols, int esize, size_t* busy) {
+    std::vector<Block*> hit;
+    for (auto& kv : map_)
+        if (kv.first.overlaps(base, ld, rows, cols, esize)) hit.push_back(kv.second);
+    size_t dropped = 0;
+    for (Block* b : hit) {
+        if (b->readers > 0) {
+            if (busy) ++*busy;
+            continue;
+        }
+        unlink(b);
+        map_.erase(b->key);
+        give_slot(b->slot);
+        delete b;
+        ++dropped;
+    }
+    return dropped;
+}
+
+size_t Alru::invalidate_all(size_t* busy) {
+    std::vector<Block*> all;
+    for (auto& kv : map_) all.push_back(kv.second);
+    size_t dropped = 0;
+    for (Block* b : all) {
+        if (b->readers > 0) {
+            if (busy) ++*busy;
+            continue;
+        }
+        unlink(b);
+        map_.erase(b->key);
+        give_slot(b->slot);
+        delete b;
+        ++dropped;
+    }
+    evicted_.clear();
+    return dropped;
 }
 
 std::vector<int> Alru::lru_order() const {

@@ -25,6 +25,10 @@ struct TileKey {
     int32_t rows, cols; // stored extent of the tile
     int32_t esize;      // element size in bytes
     int32_t tag;        // 0 = the tile itself; other values name data derived from it
+    // Does this tile share an element with the column-major region (base, ld, rows, cols, esize)?
+    // Exact when both have the same leading dimension and element size (two views of one parent
+    // matrix); otherwise decided on the address intervals, which can only err towards "yes".
+    bool overlaps(const void* base, int64_t ld, int64_t rows, int64_t cols, int esize) const;
     bool operator==(const TileKey& o) const {
         return host == o.host && ld == o.ld && rows == o.rows && cols == o.cols && esize == o.esize && tag == o.tag;
     }
@@ -73,6 +77,16 @@ public:
     Block* adopt(const TileKey& key, int slot);
     // Forget a cached tile (its host copy is about to change).  Returns false if it has readers.
     bool drop(const TileKey& key);
+
+    // Forget every cached tile (derived ones included) that shares an element with the column-major
+    // host region (base, ld, rows, cols, esize); blocks with readers are kept and counted in *busy.
+    // Returns the number of blocks dropped.
+    size_t invalidate_region(const void* base, int64_t ld, int64_t rows, int64_t cols, int esize, size_t* busy = nullptr);
+    // Forget everything without readers.
+    size_t invalidate_all(size_t* busy = nullptr);
+    // Statistics of misses on evicted tiles are per call: forget which tiles were evicted.
+    void forget_evictions() { evicted_.clear(); }
+    size_t blocks() const { return map_.size(); }
 
     // Front-to-back list of slots, for tests.
     std::vector<int> lru_order() const;

@@ -23,6 +23,11 @@ struct Library {
     OrderOpts order;
     Stats stats;
     std::string last_error;
+    // "persist" = 1: one scheduler, and with it the tile cache, lives across calls
+    bool persist = false;
+    std::unique_ptr<Scheduler> sched;
+    size_t sched_slot_bytes = 0, sched_nslots = 0;
+    int sched_T = 0;
 };
 
 Library& lib() {
@@ -48,8 +53,23 @@ int run_problem(Problem& p) {
     // the running set and its operands must fit: each running task owns an accumulator slot
     cfg.group = (int)std::max<size_t>(1, std::min<size_t>((size_t)cfg.group, nslots / 4));
     ++L.stats.calls;
-    Scheduler sched(*L.be, (int)std::min<size_t>(nslots, 1u << 30), slot_bytes, cfg, L.stats);
-    const int rc = sched.run(p);
+    int rc;
+    const size_t ns = std::min<size_t>(nslots, 1u << 30);
+    if (L.persist) {
+        // the cached tiles survive as long as the slot geometry does
+        if (!L.sched || L.sched_slot_bytes != slot_bytes || L.sched_nslots != ns || L.sched_T != L.T) {
+            L.sched.reset(new Scheduler(*L.be, (int)ns, slot_bytes, cfg, L.stats));
+            L.sched_slot_bytes = slot_bytes;
+            L.sched_nslots = ns;
+            L.sched_T = L.T;
+        }
+        L.sched->set_config(cfg);
+        rc = L.sched->run(p);
+    } else {
+        L.sched.reset();
+        Scheduler sched(*L.be, (int)ns, slot_bytes, cfg, L.stats);
+        rc = sched.run(p);
+    }
     if (rc == BLASX_ERR_DEVICE) L.last_error = L.be->last_error();
     if (rc == BLASX_ERR_ARENA_TOO_SMALL) L.last_error = "tile cache too small for the working set of this call";
     return rc;
@@ -277,6 +297,7 @@ int blasx_strsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int 
 
 int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int nstreams) {
     Library& L = lib();
+    L.sched.reset();
     L.be.reset();
     if (nstreams < 2 || nstreams > 4 || arena_bytes == 0) return BLASX_ERR_CONFIG;
     std::string err;
@@ -290,6 +311,7 @@ int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int ns
 }
 
 int blasx_shutdown(void) {
+    lib().sched.reset();
     lib().be.reset();
     return 0;
 }
@@ -317,6 +339,11 @@ int blasx_set_option(const char* name, long value) {
     else if (n == "sb_cols") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_cols = (int)value; }
     else if (n == "shells") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.order.shells = (int)value; }
     else if (n == "profile") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.profile = value != 0; }
+    else if (n == "persist") {
+        if (value < 0 || value > 1) return BLASX_ERR_CONFIG;
+        L.persist = value != 0;
+        if (!L.persist) L.sched.reset();
+    }
     else return BLASX_ERR_CONFIG;
     return 0;
 }
@@ -333,8 +360,34 @@ long blasx_get_option(const char* name) {
     if (n == "sb_cols") return L.order.sb_cols;
     if (n == "shells") return L.order.shells;
     if (n == "profile") return L.cfg.profile ? 1 : 0;
+    if (n == "persist") return L.persist ? 1 : 0;
+    if (n == "cached_tiles") return L.sched ? (long)L.sched->cached_blocks() : 0;
     if (n == "tile") return L.T;
     return -1;
+}
+
+int blasx_invalidate(const void* ptr, size_t bytes) {
+    if (!ptr && bytes) return -1;
+    Library& L = lib();
+    if (L.sched && bytes) L.sched->invalidate_region(ptr, (int64_t)bytes, (int64_t)bytes, 1, 1);
+    return 0;
+}
+
+int blasx_invalidate_matrix(const void* A, int ld, int rows, int cols, int elem_size) {
+    if (rows < 0) return -3;
+    if (cols < 0) return -4;
+    if (elem_size != 4 && elem_size != 8) return -5;
+    if (ld < std::max(1, rows)) return -2;
+    if (!A && rows && cols) return -1;
+    Library& L = lib();
+    if (L.sched && rows && cols) L.sched->invalidate_region(A, ld, rows, cols, elem_size);
+    return 0;
+}
+
+int blasx_invalidate_all(void) {
+    Library& L = lib();
+    if (L.sched) L.sched->invalidate_all();
+    return 0;
 }
 
 void* blasx_host_alloc(size_t bytes) { return backend_host_alloc(bytes); }
@@ -347,7 +400,7 @@ int blasx_get_stats(blasx_stats* out) {
     out->calls = s.calls; out->tasks = s.tasks; out->tile_steps = s.tile_steps; out->launches = s.launches;
     out->hits = s.hits; out->misses = s.misses; out->evictions = s.evictions; out->refetches = s.refetches;
     out->copies_h2d = s.copies_h2d; out->copies_d2h = s.copies_d2h; out->bytes_h2d = s.bytes_h2d; out->bytes_d2h = s.bytes_d2h;
-    out->slot_waits = s.slot_waits; out->peak_slots = s.peak_slots; out->profiled_launches = s.profiled_launches;
+    out->slot_waits = s.slot_waits; out->peak_slots = s.peak_slots; out->profiled_launches = s.profiled_launches; out->invalidations = s.invalidations;
     out->flops = s.flops; out->t_total_s = s.t_total_s; out->t_issue_s = s.t_issue_s; out->t_kernel_s = s.t_kernel_s;
     return 0;
 }

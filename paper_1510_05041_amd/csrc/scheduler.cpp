@@ -26,13 +26,30 @@ Scheduler::Scheduler(Backend& be, int nslots, size_t slot_bytes, const SchedConf
     fill_ev_.assign(nslots, -1);
     fill_seq_.assign(nslots, 0);
     fill_stream_.assign(nslots, STREAM_H2D);
+    set_config(cfg);
+    for (int q = 0; q < 3; ++q)
+        for (int a = 0; a < 2; ++a)
+            for (int b = 0; b < 2; ++b) packs_[q][a][b].mode = q;
+}
+
+void Scheduler::set_config(const SchedConfig& cfg) {
+    cfg_ = cfg;
     cfg_.kchain = std::max(1, std::min(cfg_.kchain, kMaxChain));
     cfg_.group = std::max(1, cfg_.group);
     cfg_.depth = std::max(1, cfg_.depth);
     cfg_.rs = std::max(cfg_.rs, cfg_.group);
-    for (int q = 0; q < 3; ++q)
-        for (int a = 0; a < 2; ++a)
-            for (int b = 0; b < 2; ++b) packs_[q][a][b].mode = q;
+}
+
+size_t Scheduler::invalidate_region(const void* base, int64_t ld, int64_t rows, int64_t cols, int esize) {
+    const size_t n = cache_.invalidate_region(base, ld, rows, cols, esize);
+    stats_.invalidations += n;
+    return n;
+}
+
+size_t Scheduler::invalidate_all() {
+    const size_t n = cache_.invalidate_all();
+    stats_.invalidations += n;
+    return n;
 }
 
 Scheduler::~Scheduler() {
@@ -687,6 +704,10 @@ int Scheduler::run(Problem& p) {
     panels_.assign(p.panels.size(), PanelState());
     for (size_t q = 0; q < p.panels.size(); ++q) panels_[q].remaining = p.panels[q].ntasks;
     int rc = 0;
+    // Tiles kept from earlier calls: whatever overlaps the matrix this call writes is stale from
+    // now on (and must not collide with result tiles adopted under the same host address).
+    cache_.forget_evictions();
+    if (cache_.blocks()) invalidate_region(p.c_host, p.ldc, p.c_rows, p.c_cols, (int)p.esize);
 
     for (;;) {
         retire(false);
@@ -759,6 +780,11 @@ int Scheduler::run(Problem& p) {
         if (!r.done && r.c_slot >= 0) cache_.give_slot(r.c_slot);
     running_.clear();
     pending_wb_.clear();
+    // What stays cached must equal the host matrices as this call leaves them: operand tiles do,
+    // TRSM result tiles do (they were written back from these very slots); original tiles of a
+    // matrix updated in place (TRMM) do not.  After an error nothing is trusted.
+    if (rc != 0) invalidate_all();
+    else if (!p.results_are_operands && cache_.blocks()) invalidate_region(p.c_host, p.ldc, p.c_rows, p.c_cols, (int)p.esize);
 
     stats_.hits += cache_.hits;
     stats_.misses += cache_.misses;

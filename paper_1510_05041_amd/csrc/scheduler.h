@@ -40,7 +40,7 @@ struct Stats {
     uint64_t calls = 0, tasks = 0, tile_steps = 0, launches = 0;
     uint64_t hits = 0, misses = 0, evictions = 0, refetches = 0;
     uint64_t copies_h2d = 0, copies_d2h = 0, bytes_h2d = 0, bytes_d2h = 0;
-    uint64_t slot_waits = 0, peak_slots = 0, profiled_launches = 0;
+    uint64_t slot_waits = 0, peak_slots = 0, profiled_launches = 0, invalidations = 0;
     double flops = 0, t_total_s = 0, t_issue_s = 0, t_kernel_s = 0;
 };
 
@@ -52,6 +52,13 @@ public:
     // Runs the whole problem and returns after every result tile is in host memory.
     // 0 on success, else a BLASX_ERR_* value.
     int run(Problem& p);
+    // The tile cache outlives run(): a later run() on the same object finds the operand tiles
+    // (and tiles derived from them) of earlier ones.  The two calls below forget cached tiles
+    // whose host copy has changed; both return the number of blocks dropped.
+    size_t invalidate_region(const void* base, int64_t ld, int64_t rows, int64_t cols, int esize);
+    size_t invalidate_all();
+    void set_config(const SchedConfig& cfg);
+    size_t cached_blocks() const { return cache_.blocks(); }
 
 private:
     struct Running {

@@ -52,8 +52,11 @@ std::vector<std::pair<int, int>> superblock_order(int nti, int ntj, const OrderO
     return out;
 }
 
-void init_problem(Problem& p, int dtype, int T, bool ta, bool tb, int64_t ldc) {
+void init_problem(Problem& p, int dtype, int T, bool ta, bool tb, const void* C, int64_t ldc, int64_t rows, int64_t cols) {
     p = Problem();
+    p.c_host = C;
+    p.c_rows = rows;
+    p.c_cols = cols;
     p.dtype = dtype;
     p.esize = dtype == 0 ? 8 : 4;
     p.ta = ta;
@@ -75,7 +78,7 @@ void tile_counts(int64_t rows, int64_t cols, int T, int64_t* square, int64_t* no
 void build_gemm(Problem& p, int dtype, int T, bool ta, bool tb, int M, int N, int K, double alpha,
                 const void* A, int64_t lda, const void* B, int64_t ldb, double beta, void* C, int64_t ldc,
                 const OrderOpts& oo) {
-    init_problem(p, dtype, T, ta, tb, ldc);
+    init_problem(p, dtype, T, ta, tb, C, ldc, M, N);
     const int ntm = cdiv(M, T), ntn = cdiv(N, T), ntk = (alpha == 0.0) ? 0 : cdiv(K, T);
     const int64_t a_rows = ta ? K : M, a_cols = ta ? M : K;   // stored shapes
     const int64_t b_rows = tb ? N : K, b_cols = tb ? K : N;
@@ -109,7 +112,7 @@ void build_syrk(Problem& p, int dtype, int T, bool lower, bool trans, int N, int
                 const void* A, int64_t lda, double beta, void* C, int64_t ldc, const OrderOpts& oo) {
     // trans = false: op(A) = A (N x K): left operand A_ik as stored, right operand A_jk transposed.
     // trans = true : A is K x N: left operand A_ki transposed, right operand A_kj as stored.
-    init_problem(p, dtype, T, trans, !trans, ldc);
+    init_problem(p, dtype, T, trans, !trans, C, ldc, N, N);
     const int nt = cdiv(N, T), ntk = (alpha == 0.0) ? 0 : cdiv(K, T);
     const int64_t a_rows = trans ? K : N, a_cols = trans ? N : K;
     auto keep = [lower](int i, int j) { return lower ? i >= j : i <= j; };
@@ -146,7 +149,7 @@ void build_syrk(Problem& p, int dtype, int T, bool lower, bool trans, int N, int
 void build_syr2k(Problem& p, int dtype, int T, bool lower, bool trans, int N, int K, double alpha,
                  const void* A, int64_t lda, const void* B, int64_t ldb, double beta, void* C, int64_t ldc,
                  const OrderOpts& oo) {
-    init_problem(p, dtype, T, trans, !trans, ldc);
+    init_problem(p, dtype, T, trans, !trans, C, ldc, N, N);
     const int nt = cdiv(N, T), ntk = (alpha == 0.0) ? 0 : cdiv(K, T);
     const int64_t rows = trans ? K : N, cols = trans ? N : K;
     auto keep = [lower](int i, int j) { return lower ? i >= j : i <= j; };
@@ -186,7 +189,7 @@ void build_syr2k(Problem& p, int dtype, int T, bool lower, bool trans, int N, in
 void build_symm(Problem& p, int dtype, int T, bool left, bool lower, int M, int N, double alpha,
                 const void* A, int64_t lda, const void* B, int64_t ldb, double beta, void* C, int64_t ldc,
                 const OrderOpts& oo) {
-    init_problem(p, dtype, T, false, false, ldc);
+    init_problem(p, dtype, T, false, false, C, ldc, M, N);
     const int ntm = cdiv(M, T), ntn = cdiv(N, T);
     const int na = left ? M : N, nta = (alpha == 0.0) ? 0 : cdiv(na, T);
     for (auto ij : superblock_order(ntm, ntn, oo, [](int, int) { return true; })) {
@@ -235,7 +238,7 @@ void build_symm(Problem& p, int dtype, int T, bool left, bool lower, int M, int 
 // the diagonal tile of A is masked to its triangle inside the kernel.
 void build_trmm(Problem& p, int dtype, int T, bool left, bool lower, bool trans, bool unit, int M, int N,
                 double alpha, const void* A, int64_t lda, void* B, int64_t ldb, const OrderOpts& oo) {
-    init_problem(p, dtype, T, left ? trans : false, left ? false : trans, ldb);
+    init_problem(p, dtype, T, left ? trans : false, left ? false : trans, B, ldb, M, N);
     const int ntm = cdiv(M, T), ntn = cdiv(N, T);
     const int na = left ? M : N;                 // order of A
     const bool eff_lower = lower != trans;       // op(A) is lower triangular
@@ -297,7 +300,7 @@ void build_trmm(Problem& p, int dtype, int T, bool left, bool lower, bool trans,
 // queue is ordered by dependency level so that every task's producers precede it.
 void build_trsm(Problem& p, int dtype, int T, bool left, bool lower, bool trans, bool unit, int M, int N,
                 double alpha, const void* A, int64_t lda, void* B, int64_t ldb, const OrderOpts& oo) {
-    init_problem(p, dtype, T, left ? trans : false, left ? false : trans, ldb);
+    init_problem(p, dtype, T, left ? trans : false, left ? false : trans, B, ldb, M, N);
     p.results_are_operands = true;
     (void)oo;
     const int ntm = cdiv(M, T), ntn = cdiv(N, T);

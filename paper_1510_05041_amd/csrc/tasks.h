@@ -68,6 +68,8 @@ struct Problem {
     size_t esize = 8;
     bool ta = false, tb = false;   // kernel transposes its left / right operand
     int64_t ldc = 0;         // host leading dimension of the output matrix
+    const void* c_host = nullptr;      // the output matrix as stored (column-major): first element,
+    int64_t c_rows = 0, c_cols = 0;    // and extent
     int T = 0;
     bool results_are_operands = false;  // TRSM: finished tiles stay cached under their host address
     std::vector<Task> tasks; // in queue order

@@ -33,7 +33,7 @@ def configure(L, T, nstreams=4, arena_gb=2.0, cap_bytes=0, **opts):
     L.init(int(arena_gb * 2 ** 30), nstreams=nstreams)
     L.set_tile(T)
     L.set_cache_bytes(cap_bytes)
-    defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, profile=0)
+    defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, profile=0, persist=0)
     defaults.update(opts)
     for k, v in defaults.items():
         L.set_option(k, v)
@@ -547,6 +547,38 @@ def test_dsymm_16384_sampled(lib, side, uplo):
             ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, np.asfortranarray(B[gi, :]), np.asfortranarray(sym_rows(gj)), 1.0, want)
         worst = max(worst, relerr(got, want))
     assert worst < TOL64, worst
+
+
+# ------------------------------------------------------------------ persistent tile cache --
+
+def test_persistent_cache_repeated_products_with_resident_weights(lib):
+    """The application pattern of Section V.C: one weight matrix W (16384^2), a stream of activation batches X_b
+    (16384 x 4096).  With the persistent cache W crosses the link once; every later call copies its batch only."""
+    n, nb, T = 16384, 4096, 1024
+    configure(lib, T=T, nstreams=4, arena_gb=8.0, persist=1)
+    W, kw = pinned(n, n, 18, synth.MAT_A)
+    X = [pinned(n, nb, 18 + b, synth.MAT_B) for b in range(3)]
+    Y, ky = blasx.pinned_matrix(n, nb)
+    times, stats = [], []
+    for b in range(3):
+        lib.reset_stats()
+        times.append(timed(lambda: lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, nb, n, 1.0, W, n, X[b][0], n, 0.0, Y, n)))
+        stats.append(report("persistent W: batch %d, DGEMM 16384x4096x16384" % b, lib, 2.0 * n * nb * n, times[-1]))
+        check_gemm_sampled(blasx.NoTrans, blasx.NoTrans, n, nb, n, 1.0, W, X[b][0], 0.0, lambda gi, gj: np.zeros((len(gi), len(gj))),
+                           Y, T, 18 + b, TOL64)
+    assert stats[0]["bytes_h2d"] == 8 * (n * n + n * nb)
+    assert stats[1]["bytes_h2d"] == 8 * n * nb and stats[2]["bytes_h2d"] == 8 * n * nb
+    assert stats[1]["misses"] == (n // T) * (nb // T)
+    # the host changes W: after the invalidation the new values are used
+    W[:, :1] = 0.0
+    lib.reset_stats()
+    lib.invalidate_matrix(W, n, n, 1, 8)            # first column only: one block column of tiles is dropped
+    lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, nb, n, 1.0, W, n, X[0][0], n, 0.0, Y, n)
+    st = lib.get_stats()
+    assert st["invalidations"] == n // T and st["bytes_h2d"] == 8 * n * T      # batch 0 is still cached as well
+    check_gemm_sampled(blasx.NoTrans, blasx.NoTrans, n, nb, n, 1.0, W, X[0][0], 0.0, lambda gi, gj: np.zeros((len(gi), len(gj))),
+                       Y, T, 21, TOL64)
+    lib.set_option("persist", 0)
 
 
 # ------------------------------------------------------------------ single-precision variants --

@@ -30,7 +30,7 @@ def setup(sim, T, nstreams=4, arena_tiles=64, cap_tiles=0, seed=1, esize=8, **op
     sim.init_raw(arena_tiles * T * T * esize, nstreams)
     sim.set_tile(T)
     sim.set_cache_bytes(cap_tiles * T * T * esize)
-    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, profile=0)
+    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, profile=0, persist=0)
     defaults.update(opts)
     for k, v in defaults.items():
         sim.set_option(k, v)
@@ -421,6 +421,162 @@ def test_run_to_run_reproducible_and_interleaving_independent(sim):
     C = np.zeros((n, n), order="F")
     sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 0.0, C, n)
     assert relerr(C, outs[0]) < 1e-15
+
+
+# ------------------------------------------------------------------ persistent cache ------
+
+CM, NT, TR = blasx.ColMajor, blasx.NoTrans, blasx.Trans
+
+
+def fmat(rng, r, c):
+    return np.asfortranarray(rng.integers(-3, 4, (r, c)).astype(np.float64))   # small integers: exact products
+
+
+def test_persistent_cache_serves_later_calls_and_forgets_on_request(sim):
+    setup(sim, T=16, arena_tiles=96, persist=1)
+    rng = np.random.default_rng(20)
+    n = 64
+    A, B, B2 = fmat(rng, n, n), fmat(rng, n, n), fmat(rng, n, n)
+    C = np.zeros((n, n), order="F")
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, A, n, B, n, 0.0, C, n)
+    first = sim.get_stats()
+    assert first["misses"] == 32 and np.array_equal(C, A @ B)
+    assert sim.get_option("cached_tiles") == 32              # A and B tiles stay, C tiles never do
+    # same A, new right-hand side: A is not copied again
+    sim.reset_stats()
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, A, n, B2, n, 0.0, C, n)
+    st = sim.get_stats()
+    assert st["misses"] == 16 and st["bytes_h2d"] == 16 * 16 * 16 * 8 and np.array_equal(C, A @ B2)
+    # the host changes A without telling: the stale tiles are used (documented), until invalidated
+    A_old = A.copy()
+    A[...] = fmat(rng, n, n)
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, A, n, B2, n, 0.0, C, n)
+    assert np.array_equal(C, A_old @ B2)
+    sim.reset_stats()
+    sim.invalidate(A)
+    assert sim.get_stats()["invalidations"] == 16
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, A, n, B2, n, 0.0, C, n)
+    assert np.array_equal(C, A @ B2) and sim.get_stats()["misses"] == 16
+    sim.invalidate_all()
+    assert sim.get_option("cached_tiles") == 0
+    # persist off: nothing survives a call
+    sim.set_option("persist", 0)
+    sim.reset_stats()
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, A, n, B2, n, 0.0, C, n)
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, A, n, B2, n, 0.0, C, n)
+    assert sim.get_stats()["misses"] == 64 and sim.get_option("cached_tiles") == 0
+
+
+def test_persistent_cache_forgets_what_the_library_itself_overwrites(sim):
+    setup(sim, T=16, arena_tiles=128, persist=1, group=5)
+    rng = np.random.default_rng(21)
+    n = 48
+    A, A2, B = fmat(rng, n, n), fmat(rng, n, n), fmat(rng, n, n)
+    D, E = np.zeros((n, n), order="F"), np.zeros((n, n), order="F")
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, A, n, B, n, 0.0, D, n)        # D = A B
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, D, n, B, n, 0.0, E, n)        # D is now a cached operand
+    assert np.array_equal(E, A @ B @ B)
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, A2, n, B, n, 0.0, D, n)       # D overwritten by the library
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, D, n, B, n, 0.0, E, n)
+    assert np.array_equal(E, A2 @ B @ B)
+    # in-place triangular multiply: the original tiles of B2 were cached as operands of the call
+    L = np.asfortranarray(np.tril(fmat(rng, n, n)))
+    B2 = fmat(rng, n, n)
+    want = L @ B2
+    sim.dtrmm(CM, blasx.Left, blasx.Lower, NT, blasx.NonUnit, n, n, 1.0, L, n, B2, n)
+    assert np.array_equal(B2, want)
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, B2, n, B, n, 0.0, E, n)
+    assert np.array_equal(E, want @ B)
+    # SYMM keeps the completed diagonal tiles; a change of the symmetric matrix must drop them too
+    S = fmat(rng, n, n)
+    sim.dsymm(CM, blasx.Left, blasx.Lower, n, n, 1.0, S, n, B, n, 0.0, E, n)
+    full = np.tril(S) + np.tril(S, -1).T
+    assert np.array_equal(E, full @ B)
+    S[np.diag_indices(n)] += 1.0
+    sim.invalidate_matrix(S, n, n, n, 8)
+    sim.dsymm(CM, blasx.Left, blasx.Lower, n, n, 1.0, S, n, B, n, 0.0, E, n)
+    assert np.array_equal(E, (full + np.eye(n)) @ B)
+
+
+def test_persistent_cache_triangular_solve_results_and_inverses_are_reused(sim):
+    setup(sim, T=16, arena_tiles=128, persist=1, group=4)
+    rng = np.random.default_rng(22)
+    n, m = 64, 48
+    L = np.asfortranarray(np.tril(rng.uniform(-1, 1, (n, n))) + n * np.eye(n))
+    X = rng.uniform(-1, 1, (n, m))
+    B = np.asfortranarray(L @ X)
+    sim.dtrsm(CM, blasx.Left, blasx.Lower, NT, blasx.NonUnit, n, m, 1.0, L, n, B, n)
+    assert relerr(B, X) < 1e-13
+    nt = n // 16
+    assert sim.get_stats()["misses"] == nt * (nt + 1) // 2 + nt     # L's tiles and one inverse per diagonal tile
+    # the solution tiles are cached under B's address: a product with B copies nothing but C... and W
+    sim.reset_stats()
+    W, E = fmat(rng, m, 32), np.zeros((n, 32), order="F")
+    sim.dgemm(CM, NT, NT, n, 32, m, 1.0, B, n, W, m, 0.0, E, n)
+    assert relerr(E, X @ W) < 1e-13
+    assert sim.get_stats()["misses"] == (m // 16) * 2            # only W's tiles
+    # a second solve with the same triangular matrix: neither its tiles nor the inverses are redone
+    sim.reset_stats()
+    B2 = np.asfortranarray(L @ X)
+    sim.dtrsm(CM, blasx.Left, blasx.Lower, NT, blasx.NonUnit, n, m, 1.0, L, n, B2, n)
+    st = sim.get_stats()
+    assert relerr(B2, X) < 1e-13 and st["misses"] == 0
+    assert st["bytes_h2d"] == n * m * 8                          # the right-hand sides only
+
+
+def test_persistent_cache_overlap_test_is_exact_for_views_of_one_matrix(sim):
+    setup(sim, T=16, arena_tiles=128, persist=1)
+    rng = np.random.default_rng(23)
+    P = fmat(rng, 96, 64)                       # parent; ld = 96
+    A = P[0:32, 0:32]                           # operand view
+    C = P[32:64, 0:32]                          # output view: same columns, other rows
+    B = fmat(rng, 32, 32)
+    want = A @ B
+    sim.dgemm(CM, NT, NT, 32, 32, 32, 1.0, A, 96, B, 32, 0.0, C, 96)
+    assert np.array_equal(C, want)
+    assert sim.get_stats()["invalidations"] == 0 and sim.get_option("cached_tiles") == 8
+    # an output view that does share elements with cached tiles of A
+    C2 = P[16:48, 16:48]
+    sim.dgemm(CM, NT, NT, 32, 32, 32, 1.0, B, 32, B, 32, 0.0, C2, 96)
+    assert sim.get_stats()["invalidations"] == 1   # only A's tile (1,1) = P[16:32, 16:32] lies inside the new output
+    assert np.array_equal(P[16:48, 16:48], B @ B)
+    E = np.zeros((32, 32), order="F")
+    sim.dgemm(CM, NT, NT, 32, 32, 32, 1.0, A, 96, B, 32, 0.0, E, 32)
+    assert np.array_equal(E, P[0:32, 0:32] @ B)
+    # a changed tile size empties the cache
+    sim.set_tile(32)
+    sim.dgemm(CM, NT, NT, 32, 32, 32, 1.0, A, 96, B, 32, 0.0, E, 32)
+    assert sim.get_option("cached_tiles") == 2
+
+
+def test_persistent_cache_blocked_cholesky_on_views(sim):
+    """Right-looking Cholesky of a matrix in host memory built from the library's TRSM / SYRK / GEMM on views of it,
+    the diagonal blocks factored on the host: every matrix is operand in one call and output in another."""
+    setup(sim, T=16, arena_tiles=160, persist=1, group=4)
+    rng = np.random.default_rng(24)
+    n, nb = 160, 48                              # block size is not a multiple of the tile: ragged views
+    Aw = np.zeros((n, n), order="F")
+    for attempt in range(2):                     # the second factorisation reuses the memory of the first
+        G = rng.uniform(-1, 1, (n, n))
+        S = G @ G.T + n * np.eye(n)
+        want = np.linalg.cholesky(S)
+        Aw[...] = S                              # the host rewrites an operand of earlier calls: tell the library
+        sim.invalidate(Aw)
+        for k in range(0, n, nb):
+            b = min(nb, n - k)
+            Akk = Aw[k:k + b, k:k + b]
+            Akk[...] = np.linalg.cholesky(Akk)
+            sim.invalidate_matrix(Akk, n, b, b, 8)
+            r = n - k - b
+            if r == 0:
+                break
+            panel = Aw[k + b:, k:k + b]
+            sim.dtrsm(CM, blasx.Right, blasx.Lower, TR, blasx.NonUnit, r, b, 1.0, Akk, n, panel, n)
+            trail = Aw[k + b:, k + b:]
+            sim.dsyrk(CM, blasx.Lower, NT, r, b, -1.0, panel, n, 1.0, trail, n)
+        assert relerr(np.tril(Aw), want) < 1e-13
+    st = sim.get_stats()
+    assert st["invalidations"] > 0 and st["hits"] > 0
 
 
 # ------------------------------------------------------------------ single precision ------
