@@ -113,13 +113,18 @@ int blasx_strmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int 
  *   hip_streams  HOST array of nstreams hipStream_t handles (e.g. torch streams), used in
  *                this order: compute, host-to-device, device-to-host, second host-to-device.
  *                NULL: the library creates nstreams streams.  All at default priority.
- *   nstreams     2..4.  With 2, both copy directions share one stream; with 3 each direction
+ *   nstreams     2..4, or 0 for the measured best (4; hip_streams must then be NULL or hold
+ *                4 handles).  With 2, both copy directions share one stream; with 3 each direction
  *                has its own; with 4 inbound copies alternate between two streams.
  * Must be called with the target device current.  Calling it again re-initialises. */
 int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int nstreams);
 int blasx_shutdown(void);
 
-/* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192. */
+/* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192, or
+ * 0: chosen per call from the extent of the output matrix, the element type and the room in
+ * the tile cache (2048 from 32768 rows/columns up, 1024 from 8192, 512 from 4096 in double
+ * precision, one tile per matrix below; halved until 64 tiles fit in the cache).  The choice
+ * of the latest call is blasx_get_option("last_tile").  The default is 1024. */
 int blasx_set_tile(int T);
 /* Cap on the bytes of the arena that the tile cache may use (0 = all of it); lowers the
  * number of tile slots so that eviction (Alg. 2, Dequeue) can be exercised. */

@@ -52,10 +52,20 @@ def _ptr(x):
     raise TypeError("unsupported matrix argument: %r" % type(x))
 
 
+_stream_cache = []
+
+
 class Library:
     """One loaded copy of the C library (the product ``libblasx.so`` unless a path is given)."""
 
     def __init__(self, path=None):
+        if path is None:
+            # PyTorch owns the device memory and the streams and ships its own HIP runtime: load it
+            # first so that this library binds to the same runtime instead of bringing a second one
+            try:
+                import torch  # noqa: F401
+            except ImportError:
+                pass
         path = path or _build.LIB_PATH
         if not os.path.exists(path):
             raise OSError("%s is not built: run __graft_entry__.build() (hipcc, gfx950) first" % path)
@@ -112,7 +122,13 @@ class Library:
                 keep.append(arena)
                 arena_ptr = arena.data_ptr()
             if stream_ptrs is None:
-                streams = [torch.cuda.Stream() for _ in range(nstreams)]
+                # the same streams for every init of the process: which hardware queue a new
+                # stream lands on depends on what was created before it, and two roles that end
+                # up sharing a queue serialise (measured: 68 -> 42 TFLOP/s); the first streams a
+                # process creates get queues of their own
+                while len(_stream_cache) < nstreams:
+                    _stream_cache.append(torch.cuda.Stream())
+                streams = _stream_cache[:nstreams]
                 keep.append(streams)
                 stream_ptrs = [s.cuda_stream for s in streams]
         arr = (ctypes.c_void_p * nstreams)(*stream_ptrs)

@@ -28,6 +28,7 @@ struct Library {
     std::unique_ptr<Scheduler> sched;
     size_t sched_slot_bytes = 0, sched_nslots = 0;
     int sched_T = 0;
+    int last_T = 0;   // tile edge of the most recent call
 };
 
 Library& lib() {
@@ -35,12 +36,37 @@ Library& lib() {
     return L;
 }
 
+// Tile edge for one call: the configured one, or (tile = 0) chosen from the extent of the output
+// matrix, the element type and the room in the tile cache.  The table behind it was measured
+// with the sweep in paper_1510_05041_amd/tune.py on an MI355X (end to end, host-resident
+// operands): a tile must be large enough that the fixed cost of one strided copy (~10 us on the
+// copy engine) is small beside its transfer time, and small enough that there are at least 8-16
+// tiles per dimension to overlap copies with kernels; below ~4096 nothing overlaps usefully and
+// one tile per matrix is as good as anything.
+int pick_tile(int dtype, int64_t rows, int64_t cols) {
+    Library& L = lib();
+    if (L.T > 0) return L.T;
+    const int64_t n = std::max<int64_t>(1, std::max(rows, cols));
+    const size_t es = dtype == 0 ? 8 : 4;
+    int T;
+    if (n >= 16 * 2048) T = 2048;
+    else if (n >= 8 * 1024) T = 1024;
+    else if (n >= 8 * 512 && dtype == 0) T = 512;
+    else T = (int)std::min<int64_t>(dtype == 0 ? 2048 : 4096, (n + 15) / 16 * 16);
+    // at least 64 tiles must fit in the cache (running set + operands), else eviction thrashes
+    size_t usable = L.be ? L.be->arena_bytes() : 0;
+    if (L.cache_cap && L.cache_cap < usable) usable = L.cache_cap;
+    while (usable && T > 256 && usable / ((size_t)T * T * es) < 64) T = std::max(256, (T / 2 + 15) / 16 * 16);
+    return T;
+}
+
 bool is_trans(int t) { return t == BLASX_TRANS || t == BLASX_CONJ_TRANS; }
 bool ok_trans(int t) { return t == BLASX_NO_TRANS || is_trans(t); }
 
 int run_problem(Problem& p) {
     Library& L = lib();
-    const size_t tile_bytes = (size_t)L.T * (size_t)L.T * p.esize;
+    const size_t tile_bytes = (size_t)p.T * (size_t)p.T * p.esize;
+    L.last_T = p.T;
     const size_t slot_bytes = (tile_bytes + 255) / 256 * 256;
     size_t usable = L.be->arena_bytes();
     if (L.cache_cap && L.cache_cap < usable) usable = L.cache_cap;
@@ -57,11 +83,11 @@ int run_problem(Problem& p) {
     const size_t ns = std::min<size_t>(nslots, 1u << 30);
     if (L.persist) {
         // the cached tiles survive as long as the slot geometry does
-        if (!L.sched || L.sched_slot_bytes != slot_bytes || L.sched_nslots != ns || L.sched_T != L.T) {
+        if (!L.sched || L.sched_slot_bytes != slot_bytes || L.sched_nslots != ns || L.sched_T != p.T) {
             L.sched.reset(new Scheduler(*L.be, (int)ns, slot_bytes, cfg, L.stats));
             L.sched_slot_bytes = slot_bytes;
             L.sched_nslots = ns;
-            L.sched_T = L.T;
+            L.sched_T = p.T;
         }
         L.sched->set_config(cfg);
         rc = L.sched->run(p);
@@ -99,9 +125,9 @@ int gemm_impl(int dtype, int Order, int TransA, int TransB, int M, int N, int K,
     if (!C) return -13;
     Problem p;
     if (col)
-        build_gemm(p, dtype, lib().T, is_trans(TransA), is_trans(TransB), M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+        build_gemm(p, dtype, pick_tile(dtype, M, N), is_trans(TransA), is_trans(TransB), M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
     else   // C^T = op(B)^T op(A)^T: the row-major arrays are the column-major transposes
-        build_gemm(p, dtype, lib().T, is_trans(TransB), is_trans(TransA), N, M, K, alpha, B, ldb, A, lda, beta, C, ldc, lib().order);
+        build_gemm(p, dtype, pick_tile(dtype, M, N), is_trans(TransB), is_trans(TransA), N, M, K, alpha, B, ldb, A, lda, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
@@ -145,7 +171,7 @@ int syrk_impl(int dtype, int Order, int Uplo, int Trans, int N, int K, double al
     // transposition flag both flip
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     const bool trans = col ? is_trans(Trans) : !is_trans(Trans);
-    build_syrk(p, dtype, lib().T, lower, trans, N, K, alpha, A, lda, beta, C, ldc, lib().order);
+    build_syrk(p, dtype, pick_tile(dtype, N, N), lower, trans, N, K, alpha, A, lda, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
@@ -169,7 +195,7 @@ int syr2k_impl(int dtype, int Order, int Uplo, int Trans, int N, int K, double a
     Problem p;
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     const bool trans = col ? is_trans(Trans) : !is_trans(Trans);
-    build_syr2k(p, dtype, lib().T, lower, trans, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+    build_syr2k(p, dtype, pick_tile(dtype, N, N), lower, trans, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
@@ -195,7 +221,7 @@ int symm_impl(int dtype, int Order, int Side, int Uplo, int M, int N, double alp
     // row-major: C^T = alpha (A B)^T = alpha B^T A: side and triangle flip, M and N swap
     const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
-    build_symm(p, dtype, lib().T, left, lower, col ? M : N, col ? N : M, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+    build_symm(p, dtype, pick_tile(dtype, M, N), left, lower, col ? M : N, col ? N : M, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
@@ -210,7 +236,7 @@ int trmm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, in
     const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     Problem p;
-    build_trmm(p, dtype, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+    build_trmm(p, dtype, pick_tile(dtype, M, N), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
                ldb, lib().order);
     return run_problem(p);
 }
@@ -227,10 +253,10 @@ int trsm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, in
     Problem p;
     if (alpha == 0.0) {
         // X = 0 and A is not read: a TRMM with no steps writes zero tiles
-        build_trmm(p, dtype, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, 0.0, A, lda, B,
+        build_trmm(p, dtype, pick_tile(dtype, M, N), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, 0.0, A, lda, B,
                    ldb, lib().order);
     } else {
-        build_trsm(p, dtype, lib().T, left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+        build_trsm(p, dtype, pick_tile(dtype, M, N), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
                    ldb, lib().order);
     }
     return run_problem(p);
@@ -299,6 +325,7 @@ int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int ns
     Library& L = lib();
     L.sched.reset();
     L.be.reset();
+    if (nstreams == 0) nstreams = 4;   // measured best at every size (a second inbound stream hides per-copy latency)
     if (nstreams < 2 || nstreams > 4 || arena_bytes == 0) return BLASX_ERR_CONFIG;
     std::string err;
     Backend* b = make_backend(arena, arena_bytes, hip_streams, nstreams, &err);
@@ -317,7 +344,7 @@ int blasx_shutdown(void) {
 }
 
 int blasx_set_tile(int T) {
-    if (T < 16 || T > 8192 || T % 16) return BLASX_ERR_CONFIG;
+    if (T != 0 && (T < 16 || T > 8192 || T % 16)) return BLASX_ERR_CONFIG;
     lib().T = T;
     return 0;
 }
@@ -363,6 +390,7 @@ long blasx_get_option(const char* name) {
     if (n == "persist") return L.persist ? 1 : 0;
     if (n == "cached_tiles") return L.sched ? (long)L.sched->cached_blocks() : 0;
     if (n == "tile") return L.T;
+    if (n == "last_tile") return L.last_T;
     return -1;
 }
 

@@ -2,6 +2,7 @@
 // (hipMemcpy2DAsync on page-locked memory), grouped tile-step launches, events.
 #include <hip/hip_runtime.h>
 
+#include <map>
 #include <string>
 #include <vector>
 
@@ -125,13 +126,28 @@ public:
             if (streams && streams[s]) {
                 st = static_cast<hipStream_t>(streams[s]);
             } else {
-                HB_CHECK(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
-                own = true;
+                // Streams the library makes itself live as long as the process and are reused by
+                // every later init on the device: which hardware queue a stream lands on depends
+                // on what was created before it, and two roles sharing one queue serialise.
+                int dev = 0;
+                HB_CHECK(hipGetDevice(&dev));
+                std::vector<hipStream_t>& made = own_streams()[dev];
+                while ((int)made.size() <= s) {
+                    hipStream_t fresh = nullptr;
+                    HB_CHECK(hipStreamCreateWithFlags(&fresh, hipStreamNonBlocking));
+                    made.push_back(fresh);
+                }
+                st = made[s];
             }
             streams_.push_back(st);
             own_stream_.push_back(own);
         }
         return 0;
+    }
+
+    static std::map<int, std::vector<hipStream_t>>& own_streams() {
+        static std::map<int, std::vector<hipStream_t>> m;
+        return m;
     }
 
     char* arena() override { return arena_; }

@@ -549,6 +549,22 @@ def test_dsymm_16384_sampled(lib, side, uplo):
     assert worst < TOL64, worst
 
 
+# ------------------------------------------------------------------ automatic tile size --
+
+@pytest.mark.parametrize("n,expect", [(1000, 1008), (4096, 512), (8192, 1024)])
+def test_auto_tile_dgemm_sampled(lib, n, expect):
+    """blasx_set_tile(0): the tile is chosen per call; same parity bar as a fixed tile."""
+    configure(lib, T=0, nstreams=4, arena_gb=4.0)
+    A, ka = pinned(n, n, 19, synth.MAT_A)
+    B, kb = pinned(n, n, 19, synth.MAT_B)
+    C, kc = pinned(n, n, 19, synth.MAT_C)
+    dt = timed(lambda: lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.Trans, n, n, n, 1.0, A, n, B, n, 1.0, C, n))
+    T = lib.get_option("last_tile")
+    report("auto tile DGEMM NT N=%d -> T=%d" % (n, T), lib, 2.0 * n ** 3, dt)
+    assert T == expect
+    check_gemm_sampled(blasx.NoTrans, blasx.Trans, n, n, n, 1.0, A, B, 1.0, c_before(19, synth.MAT_C, n), C, T, 19, TOL64)
+
+
 # ------------------------------------------------------------------ persistent tile cache --
 
 def test_persistent_cache_repeated_products_with_resident_weights(lib):

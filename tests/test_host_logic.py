@@ -423,6 +423,39 @@ def test_run_to_run_reproducible_and_interleaving_independent(sim):
     assert relerr(C, outs[0]) < 1e-15
 
 
+# ------------------------------------------------------------------ automatic tile size ---
+
+def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
+    def chosen(fn, M, N, dtype=np.float64):
+        A, B, C = np.ones((M, 1), dtype=dtype, order="F"), np.ones((1, N), dtype=dtype, order="F"), np.zeros((M, N), dtype=dtype, order="F")
+        fn(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, 1, 1.0, A, M, B, 1, 0.0, C, M)
+        assert np.all(C == 1.0)
+        return sim.get_option("last_tile")
+
+    sim._lib.blasx_sim_seed(1)
+    sim.init_raw(2 ** 31, 0)                     # 0 streams = the measured best
+    sim.set_cache_bytes(0)
+    sim.set_tile(0)
+    assert sim.get_option("tile") == 0
+    assert chosen(sim.dgemm, 32768, 16) == 2048
+    assert chosen(sim.dgemm, 16, 16384) == 1024
+    assert chosen(sim.dgemm, 8192, 16) == 1024
+    assert chosen(sim.dgemm, 4096, 16) == 512
+    assert chosen(sim.dgemm, 3000, 16) == 2048
+    assert chosen(sim.dgemm, 100, 50) == 112     # one tile, rounded up to the kernel's granule
+    assert chosen(sim.sgemm, 32768, 16, np.float32) == 2048
+    assert chosen(sim.sgemm, 8192, 16, np.float32) == 1024
+    assert chosen(sim.sgemm, 4096, 16, np.float32) == 2048    # 4096 by extent, halved: 64 tiles of 64 MB do not fit in 2 GB
+    assert chosen(sim.sgemm, 1500, 16, np.float32) == 1504
+    # a small cache: halve the tile until 64 tiles fit
+    sim.set_cache_bytes(64 * 2 ** 20)
+    assert chosen(sim.dgemm, 8192, 16) == 256
+    sim.set_cache_bytes(0)
+    sim.set_tile(1024)
+    assert chosen(sim.dgemm, 100, 50) == 1024 and sim.get_option("tile") == 1024
+    assert sim._lib.blasx_set_tile(8) == 4 and sim._lib.blasx_set_tile(1000) == 4
+
+
 # ------------------------------------------------------------------ persistent cache ------
 
 CM, NT, TR = blasx.ColMajor, blasx.NoTrans, blasx.Trans
