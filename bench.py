@@ -143,7 +143,7 @@ def main():
     # same counters on a plain 1 GiB device copy (profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md); they are
     # a property of the launch shape, so they are only quoted for the shape they were measured on.
     traffic = None
-    if (n, T, lib.get_option("group"), lib.get_option("kchain")) == (32768, 1024, 16, 4):
+    if (n, T, lib.get_option("last_group"), lib.get_option("kchain")) == (32768, 1024, 16, 4):
         traffic = {"hbm_bytes_per_launch": 1.869e9, "read": 1.735e9, "write": 0.1342e9, "algorithmic": 1.342e9,
                    "source": "profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md"}
     out = {
@@ -155,7 +155,7 @@ def main():
             "workload": "DGEMM NoTrans/NoTrans M=N=K=%d fp64 column-major page-locked host matrices, uniform[-1,1] seed 0, "
                         "alpha=1 beta=1, tile %d, %d streams; timed region = library call entry to return "
                         "(inbound tile copies, kernels, write-back)" % (n, T, args.streams),
-            "n": n, "tile": T, "streams": args.streams, "group": lib.get_option("group"), "kchain": lib.get_option("kchain"),
+            "n": n, "tile": T, "streams": args.streams, "group": lib.get_option("last_group"), "kchain": lib.get_option("kchain"),
             "depth": lib.get_option("depth"), "superblock": [lib.get_option("sb_rows"), lib.get_option("sb_cols")],
             "shells": lib.get_option("shells"),
             "arena_bytes": arena,

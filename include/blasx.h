@@ -82,7 +82,8 @@ int blasx_ssyr2k(int Order, int Uplo, int Trans, int N, int K, float alpha,
 /* C <- alpha * A * B + beta * C (Side = left, A is M x M) or
  * C <- alpha * B * A + beta * C (Side = right, A is N x N), A symmetric, B and C M x N  (paper Eq. 1f)
  * Only the Uplo triangle of A (with its diagonal) is read; the other triangle may hold anything.
- * Diagonal tiles of A are completed by reflection on the device, in a cache slot of their own. */
+ * Tiles of A outside the stored triangle are made on the device from the stored ones (diagonal
+ * tiles completed by reflection, the others transposed), in cache slots of their own. */
 int blasx_dsymm(int Order, int Side, int Uplo, int M, int N, double alpha,
                 const double* A, int lda, const double* B, int ldb, double beta, double* C, int ldc);
 int blasx_ssymm(int Order, int Side, int Uplo, int M, int N, float alpha,
@@ -122,15 +123,18 @@ int blasx_shutdown(void);
 
 /* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192, or
  * 0: chosen per call from the extent of the output matrix, the element type and the room in
- * the tile cache (2048 from 32768 rows/columns up, 1024 from 8192, 512 from 4096 in double
- * precision, one tile per matrix below; halved until 64 tiles fit in the cache).  The choice
+ * the tile cache (double precision: 2048 from 32768 rows/columns up, 1024 from 2048; single
+ * precision: 2048 from 4096; one tile per matrix below; halved until 64 tiles fit in the cache).  The choice
  * of the latest call is blasx_get_option("last_tile").  The default is 1024. */
 int blasx_set_tile(int T);
 /* Cap on the bytes of the arena that the tile cache may use (0 = all of it); lowers the
  * number of tile slots so that eviction (Alg. 2, Dequeue) can be exercised. */
 int blasx_set_cache_bytes(size_t cap);
 /* Scheduling knobs.  name is one of
- *   "group"    tile tasks that run together and advance k-step by k-step (>= 1)
+ *   "group"    tile tasks that run together and advance k-step by k-step; 0 (default): chosen
+ *              per call from the number of tasks (2 for a few tiles, where a short pipeline of
+ *              small launches keeps the link busy, up to 16 from 16 x 16 tiles; 16 for the
+ *              triangular routines); the choice of the latest call is "last_group"
  *   "kchain"   consecutive k-steps of a task fused into one launch (1..4; 1 = the paper's
  *              one kernel per (i,j,k))
  *   "depth"    launches the host may run ahead of the device (>= 1)

@@ -35,6 +35,8 @@ public:
     // column-major); the other triangle of src is never read.  Used by the SYMM diagonal step.
     virtual int launch_symmetrize(int dtype, const void* src, int ld_src, void* dst, int ld_dst, int n, bool lower,
                                   int stream) = 0;
+    // dst (cols x rows) <- transpose of src (rows x cols); device pointers, column-major.
+    virtual int launch_transpose(int dtype, const void* src, int ld_src, int rows, int cols, void* dst, int ld_dst, int stream) = 0;
     // Events are small integers; event_destroy() hands one back for reuse.
     virtual int  event_create() = 0;
     virtual void event_destroy(int ev) = 0;

@@ -29,6 +29,7 @@ struct Library {
     size_t sched_slot_bytes = 0, sched_nslots = 0;
     int sched_T = 0;
     int last_T = 0;   // tile edge of the most recent call
+    int last_group = 0;
 };
 
 Library& lib() {
@@ -39,25 +40,41 @@ Library& lib() {
 // Tile edge for one call: the configured one, or (tile = 0) chosen from the extent of the output
 // matrix, the element type and the room in the tile cache.  The table behind it was measured
 // with the sweep in paper_1510_05041_amd/tune.py on an MI355X (end to end, host-resident
-// operands): a tile must be large enough that the fixed cost of one strided copy (~10 us on the
-// copy engine) is small beside its transfer time, and small enough that there are at least 8-16
-// tiles per dimension to overlap copies with kernels; below ~4096 nothing overlaps usefully and
-// one tile per matrix is as good as anything.
+// operands, running-set size chosen by pick_group): a tile must be large enough that the fixed
+// cost of one strided copy (~10 us on the copy engine) is small beside its transfer time; 1024
+// (8 MB in double precision) is, and stays best down to 2 x 2 tiles; 2048 wins once there are
+// 16 x 16 of them (and from 4096 up in single precision, where it is the same 16 MB).
 int pick_tile(int dtype, int64_t rows, int64_t cols) {
     Library& L = lib();
     if (L.T > 0) return L.T;
     const int64_t n = std::max<int64_t>(1, std::max(rows, cols));
     const size_t es = dtype == 0 ? 8 : 4;
+    const int64_t one_tile = (n + 15) / 16 * 16;
     int T;
-    if (n >= 16 * 2048) T = 2048;
-    else if (n >= 8 * 1024) T = 1024;
-    else if (n >= 8 * 512 && dtype == 0) T = 512;
-    else T = (int)std::min<int64_t>(dtype == 0 ? 2048 : 4096, (n + 15) / 16 * 16);
+    if (dtype == 0) T = n >= 32768 ? 2048 : n >= 2048 ? 1024 : (int)one_tile;
+    else T = n >= 4096 ? 2048 : (int)std::min<int64_t>(2048, one_tile);
     // at least 64 tiles must fit in the cache (running set + operands), else eviction thrashes
     size_t usable = L.be ? L.be->arena_bytes() : 0;
     if (L.cache_cap && L.cache_cap < usable) usable = L.cache_cap;
     while (usable && T > 256 && usable / ((size_t)T * T * es) < 64) T = std::max(256, (T / 2 + 15) / 16 * 16);
     return T;
+}
+
+// Number of tile tasks that run together.  Many tasks in lockstep fill the chip with one
+// launch but also finish together: their write-backs bunch up at the end and the first launch
+// waits for the first tiles of all of them.  When the call is bound by the link (few tiles per
+// dimension) a small running set pipelines better: measured best 2 up to 5 x 5 tiles, 4 at
+// 6 x 6 to 8 x 8, 8 around 12 x 12, 16 from 16 x 16 tiles up (T = 1024, double precision);
+// one eighth of the task count, as a power of two in 2..16, follows that within a few percent
+// for the rectangular and the triangular task sets alike.
+int pick_group(const Problem& p) {
+    Library& L = lib();
+    if (L.cfg.group > 0) return L.cfg.group;
+    if (!p.panels.empty() || p.results_are_operands) return 16;   // TRMM / TRSM: parallelism is per dependency level
+    const size_t want = std::min<size_t>(16, std::max<size_t>(2, p.tasks.size() / 8));
+    int g = 2;
+    while ((size_t)g * 2 <= want) g *= 2;
+    return g;
 }
 
 bool is_trans(int t) { return t == BLASX_TRANS || t == BLASX_CONJ_TRANS; }
@@ -76,8 +93,11 @@ int run_problem(Problem& p) {
         return BLASX_ERR_ARENA_TOO_SMALL;
     }
     SchedConfig cfg = L.cfg;
+    cfg.group = pick_group(p);
+    cfg.rs = std::max(cfg.rs, 2 * cfg.group);
     // the running set and its operands must fit: each running task owns an accumulator slot
     cfg.group = (int)std::max<size_t>(1, std::min<size_t>((size_t)cfg.group, nslots / 4));
+    L.last_group = cfg.group;
     ++L.stats.calls;
     int rc;
     const size_t ns = std::min<size_t>(nslots, 1u << 30);
@@ -358,7 +378,7 @@ int blasx_set_option(const char* name, long value) {
     if (!name) return BLASX_ERR_CONFIG;
     Library& L = lib();
     const std::string n(name);
-    if (n == "group") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.group = (int)value; }
+    if (n == "group") { if (value < 0 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.group = (int)value; }
     else if (n == "kchain") { if (value < 1 || value > kMaxChain) return BLASX_ERR_CONFIG; L.cfg.kchain = (int)value; }
     else if (n == "depth") { if (value < 1 || value > 1024) return BLASX_ERR_CONFIG; L.cfg.depth = (int)value; }
     else if (n == "rs") { if (value < 1 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.rs = (int)value; }
@@ -391,6 +411,7 @@ long blasx_get_option(const char* name) {
     if (n == "cached_tiles") return L.sched ? (long)L.sched->cached_blocks() : 0;
     if (n == "tile") return L.T;
     if (n == "last_tile") return L.last_T;
+    if (n == "last_group") return L.last_group;
     return -1;
 }
 

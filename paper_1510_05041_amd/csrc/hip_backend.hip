@@ -88,6 +88,22 @@ __global__ void symmetrize_kernel(const T* __restrict__ src, int ld_src, T* __re
     }
 }
 
+// dst = src^T through 32 x 32 LDS blocks (reads and writes both coalesced).
+template <typename T>
+__global__ void transpose_kernel(const T* __restrict__ src, int ld_src, int rows, int cols, T* __restrict__ dst, int ld_dst) {
+    __shared__ T blk[32][33];
+    const int br = blockIdx.x * 32, bc = blockIdx.y * 32;     // block origin in src
+    for (int c = threadIdx.y; c < 32; c += blockDim.y) {
+        const int r = threadIdx.x;
+        if (br + r < rows && bc + c < cols) blk[c][r] = src[(size_t)(br + r) + (size_t)(bc + c) * ld_src];
+    }
+    __syncthreads();
+    for (int c = threadIdx.y; c < 32; c += blockDim.y) {
+        const int r = threadIdx.x;                             // dst row = src column bc + r, dst column = src row br + c
+        if (bc + r < cols && br + c < rows) dst[(size_t)(bc + r) + (size_t)(br + c) * ld_dst] = blk[r][c];
+    }
+}
+
 #define HB_CHECK(call)                                   \
     do {                                                 \
         hipError_t e_ = (call);                          \
@@ -200,6 +216,19 @@ public:
         else
             hipLaunchKernelGGL(symmetrize_kernel<float>, grid, block, 0, stream(s), static_cast<const float*>(src), ld_src,
                                static_cast<float*>(dst), ld_dst, n, lower ? 1 : 0);
+        HB_CHECK(hipGetLastError());
+        return 0;
+    }
+
+    int launch_transpose(int dtype, const void* src, int ld_src, int rows, int cols, void* dst, int ld_dst, int s) override {
+        if (rows <= 0 || cols <= 0) return 0;
+        const dim3 grid((rows + 31) / 32, (cols + 31) / 32), block(32, 8);
+        if (dtype == 0)
+            hipLaunchKernelGGL(transpose_kernel<double>, grid, block, 0, stream(s), static_cast<const double*>(src), ld_src, rows,
+                               cols, static_cast<double*>(dst), ld_dst);
+        else
+            hipLaunchKernelGGL(transpose_kernel<float>, grid, block, 0, stream(s), static_cast<const float*>(src), ld_src, rows,
+                               cols, static_cast<float*>(dst), ld_dst);
         HB_CHECK(hipGetLastError());
         return 0;
     }

@@ -13,6 +13,8 @@ double now_s() {
     return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
 constexpr int kTrtriBlock = 32;   // order of the diagonal blocks inverted directly
+// cache-key tags of tiles derived on the device (1..4 are the inverses of triangular diagonal tiles)
+constexpr int kDerivedSymUpper = 5, kDerivedSymLower = 6, kDerivedTranspose = 7;
 }  // namespace
 
 #define BX_TRY(expr)                      \
@@ -421,28 +423,19 @@ int Scheduler::build_chain(int ri) {
     Block* held[2 * kMaxChain];
     int nheld = 0, nseg = 0;
     double flops = 0;
-    bool ta = p_->ta, tb = p_->tb;
+    const bool ta = p_->ta, tb = p_->tb;
     while (nseg < cfg_.kchain && r.next_step + nseg < nsteps) {
         const StepSpec& s = t.steps[r.next_step + nseg];
-        {
-            // all k-steps of one launch entry go through one kernel instantiation
-            const bool sta = s.ta >= 0 ? s.ta != 0 : p_->ta, stb = s.tb >= 0 ? s.tb != 0 : p_->tb;
-            if (nseg == 0) {
-                ta = sta;
-                tb = stb;
-            } else if (sta != ta || stb != tb) {
-                break;
-            }
-        }
         if (s.dep >= 0) {
             if (task_final_pack_[s.dep] == 0) break;          // producer's last launch not built yet
             if (task_final_pack_[s.dep] > flushed_pack_id_) BX_TRY(flush_all());
         }
         Block *ba = nullptr, *bb = nullptr;
-        int rc = s.a_sym ? fetch_symmetric(s.a, s.sym_lower, &ba) : fetch(s.a, &ba);
+        const int sym_kind = s.sym_lower ? kDerivedSymLower : kDerivedSymUpper;
+        int rc = s.a_sym ? fetch_derived(s.a, sym_kind, &ba) : s.a_mirror ? fetch_derived(s.a, kDerivedTranspose, &ba) : fetch(s.a, &ba);
         if (rc == 0) {
             cache_.acquire(ba);
-            rc = s.b_sym ? fetch_symmetric(s.b, s.sym_lower, &bb) : fetch(s.b, &bb);
+            rc = s.b_sym ? fetch_derived(s.b, sym_kind, &bb) : s.b_mirror ? fetch_derived(s.b, kDerivedTranspose, &bb) : fetch(s.b, &bb);
             if (rc == 0) cache_.acquire(bb);
             else cache_.release(ba);
         }
@@ -599,11 +592,13 @@ int Scheduler::get_inverse(const Task& t, Block** out) {
     return 0;
 }
 
-// SYMM: device copy of a diagonal tile of the symmetric matrix with both triangles filled in,
-// cached under the tile's host address with a tag (5: upper stored, 6: lower stored).  The copy
-// is made on the compute stream, so every launch issued afterwards sees it.  Return values as fetch().
-int Scheduler::fetch_symmetric(const TileRef& t, bool lower, Block** out) {
-    const TileKey key = key_of(t, lower ? 6 : 5);
+// SYMM: a tile made on the device from a stored tile of the symmetric matrix and cached under the
+// stored tile's host address with a tag -- the diagonal tile with both triangles filled in
+// (kDerivedSymUpper / kDerivedSymLower: which triangle is stored) or the transpose of an
+// off-diagonal tile (kDerivedTranspose).  It is made on the compute stream, so every launch
+// issued afterwards sees it.  Return values as fetch().
+int Scheduler::fetch_derived(const TileRef& t, int kind, Block** out) {
+    const TileKey key = key_of(t, kind);
     bool hit = false;
     if (cache_.find(key)) {
         *out = cache_.translate(key, &hit);
@@ -625,13 +620,21 @@ int Scheduler::fetch_symmetric(const TileRef& t, bool lower, Block** out) {
             compute_waited_[fill_stream_[slot]] = fill_seq_[slot];
         }
     }
-    if (be_.launch_symmetrize(p_->dtype, slot_ptr(src->slot), T_, slot_ptr(sym->slot), T_, (int)t.rows, lower, STREAM_COMPUTE))
-        return BLASX_ERR_DEVICE;
-    // the stored tile keeps its reader until the copy has run
+    const int lrc = kind == kDerivedTranspose
+                        ? be_.launch_transpose(p_->dtype, slot_ptr(src->slot), T_, (int)t.rows, (int)t.cols, slot_ptr(sym->slot), T_,
+                                               STREAM_COMPUTE)
+                        : be_.launch_symmetrize(p_->dtype, slot_ptr(src->slot), T_, slot_ptr(sym->slot), T_, (int)t.rows,
+                                                kind == kDerivedSymLower, STREAM_COMPUTE);
+    if (lrc) return BLASX_ERR_DEVICE;
+    // Both tiles keep a reader until the kernel has run: the stored one because it is read, the
+    // new one because a block without readers may be evicted at once and its slot handed to an
+    // inbound copy, which is not ordered against work on the compute stream.
+    cache_.acquire(sym);
     InFlight f;
     f.done_ev = new_event();
     if (be_.event_record(f.done_ev, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
     f.blocks.push_back(src);
+    f.blocks.push_back(sym);
     inflight_.push_back(std::move(f));
     *out = sym;
     return 0;

@@ -29,7 +29,7 @@
 namespace blasx {
 
 struct SchedConfig {
-    int group = 16;     // tasks that run together
+    int group = 0;      // tasks that run together (0 in the library's settings: chosen per call)
     int kchain = 4;     // k-steps fused per launch (1..kMaxChain)
     int depth = 6;      // launches in flight before the host waits
     int rs = 32;        // reservation-station size
@@ -115,7 +115,7 @@ private:
     int  build_chain(int ri);
     int  build_solve(int ri);
     int  get_inverse(const Task& t, Block** out);
-    int  fetch_symmetric(const TileRef& t, bool lower, Block** out);
+    int  fetch_derived(const TileRef& t, int kind, Block** out);
     OpenPack& pack_for(int mode, bool ta, bool tb) { return packs_[mode][ta ? 1 : 0][tb ? 1 : 0]; }
     int  add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, double flops, uint64_t nsteps);
     int  flush(OpenPack& op);

@@ -185,7 +185,8 @@ void build_syr2k(Problem& p, int dtype, int T, bool lower, bool trans, int N, in
 
 // Eq. 1f: C_ij = alpha * sum_k S_ik B_kj + beta * C_ij (left) with S the symmetric matrix whose
 // `lower` (or upper) triangle A stores: a tile of S outside the stored triangle is the mirrored
-// stored tile, transposed in the kernel; the diagonal tile is completed by reflection on the device.
+// stored tile transposed, the diagonal tile is the stored one completed by reflection; both are
+// made on the device, once, from the stored tile, so every k-step is a plain product.
 void build_symm(Problem& p, int dtype, int T, bool left, bool lower, int M, int N, double alpha,
                 const void* A, int64_t lda, const void* B, int64_t ldb, double beta, void* C, int64_t ldc,
                 const OrderOpts& oo) {
@@ -212,16 +213,14 @@ void build_symm(Problem& p, int dtype, int T, bool left, bool lower, int M, int 
             const TileRef st = stored ? stored_tile(A, lda, p.esize, T, r, cidx, na, na) : stored_tile(A, lda, p.esize, T, cidx, r, na, na);
             if (left) {
                 s.a = st;
-                s.ta = stored ? 0 : 1;
-                s.tb = 0;
+                s.a_mirror = !stored;
                 s.b = stored_tile(B, ldb, p.esize, T, kt, j, M, N);
                 s.k = s.b.rows;
                 if (r == cidx) { s.a_sym = true; s.sym_lower = lower; }
             } else {
                 s.a = stored_tile(B, ldb, p.esize, T, i, kt, M, N);
                 s.b = st;
-                s.ta = 0;
-                s.tb = stored ? 0 : 1;
+                s.b_mirror = !stored;
                 s.k = s.a.cols;
                 if (r == cidx) { s.b_sym = true; s.sym_lower = lower; }
             }

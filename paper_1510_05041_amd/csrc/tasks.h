@@ -29,11 +29,13 @@ struct StepSpec {
     uint32_t seg_flags = 0;  // TS_TRI_* when one operand is a diagonal tile of a triangular matrix
     int32_t dep = -1;    // index of the task whose *result* one operand is (TRSM), or -1
     bool a_is_dep = false, b_is_dep = false;
-    int8_t ta = -1, tb = -1;   // per-step transposition of the left / right operand (-1: the problem's)
     // SYMM: the operand is a diagonal tile of a symmetric matrix of which only one triangle is
     // stored; the kernel gets a device copy with the other triangle filled in by reflection.
     bool a_sym = false, b_sym = false;
     bool sym_lower = false;
+    // SYMM: the operand is the transpose of the stored tile (a tile of the symmetric matrix that
+    // lies outside the stored triangle); the kernel gets a transposed device copy.
+    bool a_mirror = false, b_mirror = false;
 };
 
 struct Task {

@@ -6,8 +6,9 @@ one tuning parameter, and Section IV.D: the number of streams).
 For every problem size the host matrices are page-locked once; every (tile, streams, group)
 combination is then timed end to end (call entry to return, best of --reps calls after one
 warm-up call) and one table per stream count is printed: rows = N, columns = T, entries =
-TFLOP/s, with the best tile per row marked.  The measurements behind the automatic tile choice
-of blasx_set_tile(0) were taken with this tool.
+TFLOP/s, with the best tile per row marked.  A tile or group of 0 means the library's automatic
+choice (blasx_set_tile(0), option "group" = 0); the measurements behind those choices were taken
+with this tool.
 """
 import argparse
 import json
@@ -78,7 +79,7 @@ def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None
                     lib.init(int(arena_gb * 2 ** 30), nstreams=ns)
                     lib.set_tile(T)
                     lib.set_cache_bytes(0)
-                    for name, v in dict(group=g, rs=2 * g, kchain=4, depth=6, sb_rows=4, sb_cols=4, shells=1,
+                    for name, v in dict(group=g, rs=max(32, 2 * g), kchain=4, depth=6, sb_rows=4, sb_cols=4, shells=1,
                                         profile=0, persist=0).items():
                         lib.set_option(name, v)
                     times = []
@@ -91,6 +92,8 @@ def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None
                     best = min(times[1:])
                     rec = dict(routine=routine, n=n, k=k, T=T, streams=ns, group=g, ms=best * 1e3,
                                tflops=flop / best / 1e12)
+                    if T == 0 or g == 0:      # automatic choices: say what was chosen
+                        rec["chosen_T"], rec["chosen_group"] = lib.get_option("last_tile"), lib.get_option("last_group")
                     results.append(rec)
                     print(json.dumps(rec), flush=True)
                     if out:

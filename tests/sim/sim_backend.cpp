@@ -22,7 +22,7 @@ namespace blasx {
 namespace {
 
 struct Op {
-    enum Kind { COPY, LAUNCH, TRTRI, SYMMETRIZE, RECORD, WAIT } kind = COPY;
+    enum Kind { COPY, LAUNCH, TRTRI, SYMMETRIZE, TRANSPOSE, RECORD, WAIT } kind = COPY;
     // COPY (both directions are plain strided memcpy on the host)
     char* dst = nullptr;
     const char* src = nullptr;
@@ -132,6 +132,14 @@ void run_symmetrize(const Op& op) {
         }
 }
 
+template <typename T>
+void run_transpose(const Op& op) {
+    const T* src = static_cast<const T*>(op.tri);
+    T* dst = static_cast<T*>(op.inv);
+    for (int c = 0; c < op.nb; ++c)
+        for (int r = 0; r < op.n; ++r) dst[(size_t)c + (size_t)r * op.ld_inv] = src[(size_t)r + (size_t)c * op.ld_tri];
+}
+
 class SimBackend : public Backend {
 public:
     SimBackend(size_t bytes, int nstreams) : mem_(bytes, (char)0xA5), queues_(nstreams), rng_(g_seed) {}
@@ -188,6 +196,19 @@ public:
         op.ld_inv = ld_dst;
         op.n = n;
         op.flags = lower ? TS_TRI_LOWER : 0u;
+        push(s, op);
+        return 0;
+    }
+    int launch_transpose(int dtype, const void* src, int ld_src, int rows, int cols, void* dst, int ld_dst, int s) override {
+        Op op;
+        op.kind = Op::TRANSPOSE;
+        op.dtype = dtype;
+        op.tri = src;
+        op.inv = dst;
+        op.ld_tri = ld_src;
+        op.ld_inv = ld_dst;
+        op.n = rows;
+        op.nb = cols;
         push(s, op);
         return 0;
     }
@@ -310,6 +331,10 @@ private:
             case Op::SYMMETRIZE:
                 if (op.dtype == 0) run_symmetrize<double>(op);
                 else run_symmetrize<float>(op);
+                break;
+            case Op::TRANSPOSE:
+                if (op.dtype == 0) run_transpose<double>(op);
+                else run_transpose<float>(op);
                 break;
             case Op::RECORD:
                 if (events_[op.ev].done < op.gen) events_[op.ev].done = op.gen;

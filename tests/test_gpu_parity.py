@@ -551,17 +551,17 @@ def test_dsymm_16384_sampled(lib, side, uplo):
 
 # ------------------------------------------------------------------ automatic tile size --
 
-@pytest.mark.parametrize("n,expect", [(1000, 1008), (4096, 512), (8192, 1024)])
-def test_auto_tile_dgemm_sampled(lib, n, expect):
-    """blasx_set_tile(0): the tile is chosen per call; same parity bar as a fixed tile."""
-    configure(lib, T=0, nstreams=4, arena_gb=4.0)
+@pytest.mark.parametrize("n,expect,group", [(1000, 1008, 2), (4096, 1024, 2), (8192, 1024, 8)])
+def test_auto_tile_dgemm_sampled(lib, n, expect, group):
+    """blasx_set_tile(0) and group 0: tile and running set are chosen per call; same parity bar as fixed ones."""
+    configure(lib, T=0, nstreams=4, arena_gb=4.0, group=0)
     A, ka = pinned(n, n, 19, synth.MAT_A)
     B, kb = pinned(n, n, 19, synth.MAT_B)
     C, kc = pinned(n, n, 19, synth.MAT_C)
     dt = timed(lambda: lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.Trans, n, n, n, 1.0, A, n, B, n, 1.0, C, n))
     T = lib.get_option("last_tile")
     report("auto tile DGEMM NT N=%d -> T=%d" % (n, T), lib, 2.0 * n ** 3, dt)
-    assert T == expect
+    assert T == expect and lib.get_option("last_group") == group
     check_gemm_sampled(blasx.NoTrans, blasx.Trans, n, n, n, 1.0, A, B, 1.0, c_before(19, synth.MAT_C, n), C, T, 19, TOL64)
 
 

@@ -272,6 +272,25 @@ def test_symm_matches_oracle_and_never_reads_the_other_triangle(sim, order, side
     assert st["tile_steps"] == st["tasks"] * -(-na // 16)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_symm_capped_cache_many_interleavings(sim, seed):
+    """Derived tiles (completed diagonal tiles, transposed mirror tiles) are written by kernels on the compute stream:
+    under slot pressure they are evicted and rebuilt while copies and launches interleave at random."""
+    side, uplo = [(blasx.Left, blasx.Lower), (blasx.Right, blasx.Upper), (blasx.Left, blasx.Upper), (blasx.Right, blasx.Lower)][seed % 4]
+    setup(sim, T=16, seed=100 + seed, arena_tiles=12 + seed, group=2 + seed % 3, kchain=1 + seed % 3)
+    rng = np.random.default_rng(seed)
+    M, N = 96, 80
+    na = M if side == blasx.Left else N
+    A = rng.integers(-2, 3, (na, na)).astype(np.float64)
+    full = np.tril(A) + np.tril(A, -1).T if uplo == blasx.Lower else np.triu(A) + np.triu(A, 1).T
+    B = rng.integers(-2, 3, (M, N)).astype(np.float64)
+    As, Bs, Cs = store(A, blasx.ColMajor), store(B, blasx.ColMajor), store(np.zeros((M, N)), blasx.ColMajor)
+    sim.dsymm(blasx.ColMajor, side, uplo, M, N, 1.0, As, na, Bs, M, 0.0, Cs, M)
+    assert np.array_equal(np.asarray(Cs), full @ B if side == blasx.Left else B @ full)
+    st = sim.get_stats()
+    assert st["evictions"] > 0
+
+
 def test_symm_under_slot_pressure_and_single_precision(sim):
     # few slots: symmetrised diagonal tiles get evicted and rebuilt
     setup(sim, T=16, seed=5, arena_tiles=14, group=3)
@@ -439,18 +458,29 @@ def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
     assert sim.get_option("tile") == 0
     assert chosen(sim.dgemm, 32768, 16) == 2048
     assert chosen(sim.dgemm, 16, 16384) == 1024
-    assert chosen(sim.dgemm, 8192, 16) == 1024
-    assert chosen(sim.dgemm, 4096, 16) == 512
-    assert chosen(sim.dgemm, 3000, 16) == 2048
+    assert chosen(sim.dgemm, 4096, 16) == 1024
+    assert chosen(sim.dgemm, 2048, 2048) == 1024
+    assert chosen(sim.dgemm, 2000, 16) == 2000
     assert chosen(sim.dgemm, 100, 50) == 112     # one tile, rounded up to the kernel's granule
     assert chosen(sim.sgemm, 32768, 16, np.float32) == 2048
-    assert chosen(sim.sgemm, 8192, 16, np.float32) == 1024
-    assert chosen(sim.sgemm, 4096, 16, np.float32) == 2048    # 4096 by extent, halved: 64 tiles of 64 MB do not fit in 2 GB
+    assert chosen(sim.sgemm, 4096, 16, np.float32) == 2048
+    assert chosen(sim.sgemm, 3000, 16, np.float32) == 2048
     assert chosen(sim.sgemm, 1500, 16, np.float32) == 1504
     # a small cache: halve the tile until 64 tiles fit
     sim.set_cache_bytes(64 * 2 ** 20)
     assert chosen(sim.dgemm, 8192, 16) == 256
     sim.set_cache_bytes(0)
+    # the running set: 2 for a few tiles, 16 from 16 x 16 tiles, 16 for the triangular routines
+    sim.set_option("group", 0)
+    sim.set_tile(16)
+    for n, g in ((32, 2), (64, 2), (96, 4), (128, 8), (192, 16), (400, 16)):
+        assert chosen(sim.dgemm, n, n) == 16 and sim.get_option("last_group") == g, n
+    L = np.asfortranarray(np.tril(np.ones((64, 64))) + 63 * np.eye(64))
+    B = np.ones((64, 32), order="F")
+    sim.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, 64, 32, 1.0, L, 64, B, 64)
+    assert sim.get_option("last_group") == 16
+    sim.set_option("group", 5)
+    assert chosen(sim.dgemm, 256, 256) == 16 and sim.get_option("last_group") == 5
     sim.set_tile(1024)
     assert chosen(sim.dgemm, 100, 50) == 1024 and sim.get_option("tile") == 1024
     assert sim._lib.blasx_set_tile(8) == 4 and sim._lib.blasx_set_tile(1000) == 4
