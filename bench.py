@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--sb", type=int, nargs=2, default=None)
     ap.add_argument("--shells", type=int, default=None)
     ap.add_argument("--rs", type=int, default=None)
+    ap.add_argument("--prefetch", type=int, default=None)
+    ap.add_argument("--wide", type=int, default=None, help="least k-steps per task for which all tasks advance together when the cache has room (default 12); 0: grouped")
     ap.add_argument("--arena-gb", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check", action="store_true", help="also compare sampled outputs with the oracle")
@@ -94,12 +96,12 @@ def main():
         n //= 2
         need = 3 * 8 * n * n
     tile_bytes = T * T * 8
-    arena = int(args.arena_gb * 2 ** 30) if args.arena_gb else 2 * 8 * n * n + 160 * tile_bytes
+    arena = int(args.arena_gb * 2 ** 30) if args.arena_gb else 3 * 8 * n * n + 512 * tile_bytes
     lib.init(arena, nstreams=args.streams)
     lib.set_tile(T)
     lib.set_cache_bytes(0)
     for name, val in (("group", args.group), ("kchain", args.kchain), ("depth", args.depth), ("shells", args.shells),
-                      ("rs", args.rs)):
+                      ("rs", args.rs), ("wide", args.wide), ("prefetch", args.prefetch)):
         if val is not None:
             lib.set_option(name, val)
     if args.sb:
@@ -143,7 +145,7 @@ def main():
     # same counters on a plain 1 GiB device copy (profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md); they are
     # a property of the launch shape, so they are only quoted for the shape they were measured on.
     traffic = None
-    if (n, T, lib.get_option("last_group"), lib.get_option("kchain")) == (32768, 1024, 16, 4):
+    if (n, T, lib.get_option("last_group"), lib.get_option("last_kchain"), lib.get_option("last_wide")) == (32768, 1024, 16, 4, 0):
         traffic = {"hbm_bytes_per_launch": 1.869e9, "read": 1.735e9, "write": 0.1342e9, "algorithmic": 1.342e9,
                    "source": "profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md"}
     out = {
@@ -155,9 +157,9 @@ def main():
             "workload": "DGEMM NoTrans/NoTrans M=N=K=%d fp64 column-major page-locked host matrices, uniform[-1,1] seed 0, "
                         "alpha=1 beta=1, tile %d, %d streams; timed region = library call entry to return "
                         "(inbound tile copies, kernels, write-back)" % (n, T, args.streams),
-            "n": n, "tile": T, "streams": args.streams, "group": lib.get_option("last_group"), "kchain": lib.get_option("kchain"),
+            "n": n, "tile": T, "streams": args.streams, "group": lib.get_option("last_group"), "kchain": lib.get_option("last_kchain"),
             "depth": lib.get_option("depth"), "superblock": [lib.get_option("sb_rows"), lib.get_option("sb_cols")],
-            "shells": lib.get_option("shells"),
+            "shells": lib.get_option("shells"), "wide": lib.get_option("last_wide"),
             "arena_bytes": arena,
         },
         "roofline": {

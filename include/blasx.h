@@ -123,8 +123,8 @@ int blasx_shutdown(void);
 
 /* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192, or
  * 0: chosen per call from the extent of the output matrix, the element type and the room in
- * the tile cache (double precision: 2048 from 32768 rows/columns up, 1024 from 2048; single
- * precision: 2048 from 4096; one tile per matrix below; halved until 64 tiles fit in the cache).  The choice
+ * the tile cache (double precision: 1024 from 2048 rows/columns up; single precision: 2048
+ * from 4096; one tile per matrix below; halved until 64 tiles fit in the cache).  The choice
  * of the latest call is blasx_get_option("last_tile").  The default is 1024. */
 int blasx_set_tile(int T);
 /* Cap on the bytes of the arena that the tile cache may use (0 = all of it); lowers the
@@ -135,8 +135,15 @@ int blasx_set_cache_bytes(size_t cap);
  *              per call from the number of tasks (2 for a few tiles, where a short pipeline of
  *              small launches keeps the link busy, up to 16 from 16 x 16 tiles; 16 for the
  *              triangular routines); the choice of the latest call is "last_group"
- *   "kchain"   consecutive k-steps of a task fused into one launch (1..4; 1 = the paper's
- *              one kernel per (i,j,k))
+ *   "kchain"   consecutive k-steps of a task fused into one launch (1..8; 1 = the paper's
+ *              one kernel per (i,j,k)); 0 (default): 8 in the wide schedule, else 4
+ *   "wide"     least number of k-steps per task from which ALL tasks of a call run together and
+ *              advance k-chunk by k-chunk (an outer-product order: enough products per tile
+ *              copied from the first launch on, C tiles fetched only for a task's last launch,
+ *              results leaving during the whole last round), provided the cache has room for
+ *              an accumulator tile per output tile; 0: never (tasks run to completion in
+ *              groups, the paper's scheme).  Default 12.  Never used by TRSM / TRMM.
+ *   "prefetch" wide schedule: inbound copies are started this many launches ahead (default 24)
  *   "depth"    launches the host may run ahead of the device (>= 1)
  *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)
  *   "sb_rows", "sb_cols"  super-block shape used to order the task queue

@@ -30,6 +30,8 @@ struct Library {
     int sched_T = 0;
     int last_T = 0;   // tile edge of the most recent call
     int last_group = 0;
+    bool last_wide = false;
+    int last_kchain = 0;
 };
 
 Library& lib() {
@@ -42,8 +44,8 @@ Library& lib() {
 // with the sweep in paper_1510_05041_amd/tune.py on an MI355X (end to end, host-resident
 // operands, running-set size chosen by pick_group): a tile must be large enough that the fixed
 // cost of one strided copy (~10 us on the copy engine) is small beside its transfer time; 1024
-// (8 MB in double precision) is, and stays best down to 2 x 2 tiles; 2048 wins once there are
-// 16 x 16 of them (and from 4096 up in single precision, where it is the same 16 MB).
+// (8 MB in double precision) is, and stays best down to 2 x 2 tiles; larger tiles only shorten
+// the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 4096 up.
 int pick_tile(int dtype, int64_t rows, int64_t cols) {
     Library& L = lib();
     if (L.T > 0) return L.T;
@@ -51,7 +53,7 @@ int pick_tile(int dtype, int64_t rows, int64_t cols) {
     const size_t es = dtype == 0 ? 8 : 4;
     const int64_t one_tile = (n + 15) / 16 * 16;
     int T;
-    if (dtype == 0) T = n >= 32768 ? 2048 : n >= 2048 ? 1024 : (int)one_tile;
+    if (dtype == 0) T = n >= 2048 ? 1024 : (int)one_tile;
     else T = n >= 4096 ? 2048 : (int)std::min<int64_t>(2048, one_tile);
     // at least 64 tiles must fit in the cache (running set + operands), else eviction thrashes
     size_t usable = L.be ? L.be->arena_bytes() : 0;
@@ -111,10 +113,14 @@ int run_problem(Problem& p) {
         }
         L.sched->set_config(cfg);
         rc = L.sched->run(p);
+        L.last_wide = L.sched->last_run_was_wide();
+        L.last_kchain = L.sched->last_run_kchain();
     } else {
         L.sched.reset();
         Scheduler sched(*L.be, (int)ns, slot_bytes, cfg, L.stats);
         rc = sched.run(p);
+        L.last_wide = sched.last_run_was_wide();
+        L.last_kchain = sched.last_run_kchain();
     }
     if (rc == BLASX_ERR_DEVICE) L.last_error = L.be->last_error();
     if (rc == BLASX_ERR_ARENA_TOO_SMALL) L.last_error = "tile cache too small for the working set of this call";
@@ -379,12 +385,15 @@ int blasx_set_option(const char* name, long value) {
     Library& L = lib();
     const std::string n(name);
     if (n == "group") { if (value < 0 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.group = (int)value; }
-    else if (n == "kchain") { if (value < 1 || value > kMaxChain) return BLASX_ERR_CONFIG; L.cfg.kchain = (int)value; }
+    else if (n == "kchain") { if (value < 0 || value > kMaxChain) return BLASX_ERR_CONFIG; L.cfg.kchain = (int)value; }
     else if (n == "depth") { if (value < 1 || value > 1024) return BLASX_ERR_CONFIG; L.cfg.depth = (int)value; }
     else if (n == "rs") { if (value < 1 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.rs = (int)value; }
     else if (n == "sb_rows") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_rows = (int)value; }
     else if (n == "sb_cols") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_cols = (int)value; }
     else if (n == "shells") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.order.shells = (int)value; }
+    else if (n == "wide") { if (value < 0 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.wide = (int)value; }
+    else if (n == "prefetch") { if (value < 0 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.prefetch = (int)value; }
+    else if (n == "wide") { if (value < 0 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.wide = (int)value; }
     else if (n == "profile") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.profile = value != 0; }
     else if (n == "persist") {
         if (value < 0 || value > 1) return BLASX_ERR_CONFIG;
@@ -406,12 +415,16 @@ long blasx_get_option(const char* name) {
     if (n == "sb_rows") return L.order.sb_rows;
     if (n == "sb_cols") return L.order.sb_cols;
     if (n == "shells") return L.order.shells;
+    if (n == "wide") return L.cfg.wide;
+    if (n == "prefetch") return L.cfg.prefetch;
     if (n == "profile") return L.cfg.profile ? 1 : 0;
     if (n == "persist") return L.persist ? 1 : 0;
     if (n == "cached_tiles") return L.sched ? (long)L.sched->cached_blocks() : 0;
     if (n == "tile") return L.T;
     if (n == "last_tile") return L.last_T;
     if (n == "last_group") return L.last_group;
+    if (n == "last_wide") return L.last_wide ? 1 : 0;
+    if (n == "last_kchain") return L.last_kchain;
     return -1;
 }
 

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cstring>
+#include <unordered_set>
 
 #include "../../include/blasx.h"
 
@@ -36,7 +37,8 @@ Scheduler::Scheduler(Backend& be, int nslots, size_t slot_bytes, const SchedConf
 
 void Scheduler::set_config(const SchedConfig& cfg) {
     cfg_ = cfg;
-    cfg_.kchain = std::max(1, std::min(cfg_.kchain, kMaxChain));
+    cfg_.kchain = std::max(0, std::min(cfg_.kchain, kMaxChain));   // 0: chosen per run
+    kchain_ = cfg_.kchain ? cfg_.kchain : 4;
     cfg_.group = std::max(1, cfg_.group);
     cfg_.depth = std::max(1, cfg_.depth);
     cfg_.rs = std::max(cfg_.rs, cfg_.group);
@@ -330,6 +332,8 @@ int Scheduler::flush(OpenPack& op) {
     op.flops = 0;
     op.steps = 0;
     for (int ri : finishing) BX_TRY(finish_task(ri, done_ev));
+    // bound the host's run-ahead: at most `depth` launches in flight
+    while ((int)inflight_.size() > cfg_.depth) retire(true);
     return 0;
 }
 
@@ -395,7 +399,7 @@ int Scheduler::start_task(int task_index, Running* r) {
     *r = Running();
     r->task = task_index;
     r->c_slot = slot;
-    if (t.load_c) {
+    if (t.load_c && !wide_) {
         TileRef c;
         c.host = t.c_host;
         c.ld = p_->ldc;
@@ -405,6 +409,83 @@ int Scheduler::start_task(int task_index, Running* r) {
     }
     task_started_[task_index] = 1;
     return 0;
+}
+
+// Wide mode: start the inbound copy of a task's host C tile into a slot of its own (the
+// accumulator slot holds partial sums by then).  Without may_wait nothing is evicted-by-waiting:
+// if no slot is free right now the copy is simply started later.
+int Scheduler::prefetch_c(Running& r, const Task& t, bool may_wait) {
+    if (r.h_slot >= 0) return 0;
+    int slot = -1;
+    if (may_wait) BX_TRY(take_slot_blocking(&slot));
+    else slot = cache_.take_slot();
+    if (slot < 0) return 0;
+    TileRef c;
+    c.host = t.c_host;
+    c.ld = p_->ldc;
+    c.rows = t.m;
+    c.cols = t.n;
+    BX_TRY(issue_h2d(c, slot));
+    r.h_slot = slot;
+    return 0;
+}
+
+// Wide mode: start the inbound copies of the launches that will be built next, in the order in
+// which they will be needed (round by round, task by task), up to `prefetch` launches ahead.  The
+// host may only run `depth` launches ahead of the device, which is a few milliseconds of copies;
+// the copy queue has to be fed further ahead than that or the link idles at every round boundary,
+// where a whole new panel of B is needed at once.  Only a hint: build_chain() fetches whatever is
+// still missing.
+void Scheduler::prefetch_ahead(size_t build_pos) {
+    const size_t ntasks = p_->tasks.size();
+    const size_t target = build_pos + (size_t)cfg_.prefetch * kMaxStepsPerLaunch;
+    if (pf_pos_ <= build_pos) pf_pos_ = build_pos + 1;
+    while (pf_pos_ <= target) {
+        const size_t round = pf_pos_ / ntasks, ri = pf_pos_ % ntasks;
+        if (ri >= running_.size()) return;
+        Running& r = running_[ri];
+        if (r.task < 0 || r.done) {
+            ++pf_pos_;
+            continue;
+        }
+        const Task& t = p_->tasks[r.task];
+        const size_t nsteps = t.steps.size();
+        const size_t s0 = round * (size_t)kchain_, s1 = std::min(nsteps, s0 + (size_t)kchain_);
+        if (round > pf_last_round_) return;       // nothing left in any task
+        for (size_t q = s0; q < s1; ++q) {
+            for (const TileRef* ref : {&t.steps[q].a, &t.steps[q].b}) {
+                if (cache_.find(key_of(*ref))) continue;
+                Block* b = nullptr;
+                if (fetch(*ref, &b) != 0) return;     // no slot right now: try again after the next launch
+            }
+        }
+        if (s0 < nsteps && s1 >= nsteps && s0 > 0 && t.load_c) {
+            if (prefetch_c(r, t, false) != 0 || r.h_slot < 0) return;
+        }
+        ++pf_pos_;
+    }
+}
+
+// Wide mode needs an accumulator slot per task plus the operand tiles of two rounds (the round
+// being computed and the one being copied in) plus some slots for late C tiles.
+bool Scheduler::wide_fits(const Problem& p) const {
+    std::unordered_set<TileKey, TileKeyHash> uniq;
+    size_t max_steps = 0, with_c = 0;
+    for (const Task& t : p.tasks) {
+        max_steps = std::max(max_steps, t.steps.size());
+        with_c += t.load_c ? 1 : 0;
+        for (const StepSpec& s : t.steps) {
+            uniq.insert(key_of(s.a));
+            uniq.insert(key_of(s.b));
+        }
+    }
+    const size_t rounds = std::max<size_t>(1, (max_steps + kchain_ - 1) / kchain_);
+    // one launch per task leaves nothing to pipeline, and with barely more than one round the
+    // grouped schedule (whose tasks finish one after the other) measures better
+    if (rounds < 2 || max_steps < (size_t)cfg_.wide) return false;
+    const size_t per_round = (uniq.size() + rounds - 1) / rounds;
+    const size_t late_c = with_c ? std::min<size_t>(with_c, (size_t)kMaxStepsPerLaunch * (cfg_.prefetch + cfg_.depth + 2)) : 0;
+    return (size_t)cache_.nslots() >= p.tasks.size() + 2 * per_round + late_c + kMaxStepsPerLaunch;
 }
 
 // Next launch of one running task: up to kchain consecutive k-steps (Alg. 1 lines 19-25 for one
@@ -424,7 +505,7 @@ int Scheduler::build_chain(int ri) {
     int nheld = 0, nseg = 0;
     double flops = 0;
     const bool ta = p_->ta, tb = p_->tb;
-    while (nseg < cfg_.kchain && r.next_step + nseg < nsteps) {
+    while (nseg < kchain_ && r.next_step + nseg < nsteps) {
         const StepSpec& s = t.steps[r.next_step + nseg];
         if (s.dep >= 0) {
             if (task_final_pack_[s.dep] == 0) break;          // producer's last launch not built yet
@@ -460,14 +541,40 @@ int Scheduler::build_chain(int ri) {
         ++nseg;
     }
     if (nseg == 0 && nsteps > 0 && r.next_step < nsteps) return 1;   // blocked on a producer
+    const bool last = r.next_step + nseg >= nsteps && !t.solve;
+    int acc_slot = -1;          // wide mode: accumulator that the last launch only reads
     st.C = slot_ptr(r.c_slot);
-    st.nseg = nseg;
-    st.lda = st.ldb = st.ldc = T_;
-    st.m = t.m;
-    st.n = t.n;
+    st.beta = r.first ? t.beta_first : 1.0;
+    if (wide_) {
+        // The host C tile is not needed before the task's last launch: earlier launches build
+        // alpha * sum(A B) in the accumulator slot, the last one computes
+        // alpha * (its products) + beta * C_host + accumulator  into the slot holding C_host.
+        if (!last) {
+            st.beta = r.first ? 0.0 : 1.0;
+        } else if (t.load_c) {
+            if (r.first) {
+                // single launch: the tile goes straight into the accumulator slot
+                TileRef c;
+                c.host = t.c_host;
+                c.ld = p_->ldc;
+                c.rows = t.m;
+                c.cols = t.n;
+                BX_TRY(issue_h2d(c, r.c_slot));
+            } else {
+                BX_TRY(prefetch_c(r, t, true));
+                acc_slot = r.c_slot;
+                st.D = slot_ptr(acc_slot);
+                st.C = slot_ptr(r.h_slot);
+                st.beta = t.beta_first;
+            }
+        }
+    }
+    st.nseg = (uint16_t)nseg;
+    st.lda = st.ldb = st.ldc = (uint16_t)T_;
+    st.m = (uint16_t)t.m;
+    st.n = (uint16_t)t.n;
     st.flags = (ta ? TS_TRANS_A : 0u) | (tb ? TS_TRANS_B : 0u) | t.c_flags;
     st.alpha = t.alpha_step;
-    st.beta = r.first ? t.beta_first : 1.0;
     OpenPack& op = pack_for(step_mode(st, p_->dtype), ta, tb);
     BX_TRY(add_step(op, ta, tb, st, flops, (uint64_t)nseg));
     for (int q = 0; q < nheld; ++q) {
@@ -475,6 +582,13 @@ int Scheduler::build_chain(int ri) {
         op.wait_slots.push_back(held[q]->slot);
     }
     op.wait_slots.push_back(r.c_slot);
+    if (acc_slot >= 0) {
+        // the result now lives in the slot of the host tile; the accumulator is free once this launch is done
+        op.wait_slots.push_back(r.h_slot);
+        op.free_slots.push_back(acc_slot);
+        r.c_slot = r.h_slot;
+        r.h_slot = -1;
+    }
     r.next_step += nseg;
     r.first = false;
     r.last_pack = op.id;
@@ -482,6 +596,7 @@ int Scheduler::build_chain(int ri) {
         op.finishing.push_back(ri);
         task_final_pack_[r.task] = op.id;
     }
+    if (wide_) prefetch_ahead(round_ * p_->tasks.size() + (size_t)ri);
     return 0;
 }
 
@@ -707,6 +822,27 @@ int Scheduler::run(Problem& p) {
     panels_.assign(p.panels.size(), PanelState());
     for (size_t q = 0; q < p.panels.size(); ++q) panels_[q].remaining = p.panels[q].ntasks;
     int rc = 0;
+    // Wide mode: every task of the call runs at once and all advance k-chunk by k-chunk (an
+    // outer-product order).  A launch then shares its operand tiles with many others, so the
+    // device has enough products per tile copied from the first launches on, instead of starving
+    // while the first few output tiles wait for whole rows of A and columns of B; and result
+    // tiles leave during the whole last round instead of in bursts.  The price is an
+    // accumulator slot per output tile, so it is used only when the cache has that room, and
+    // never for the routines whose tasks depend on each other or update their input in place.
+    // Chains: 8 k-tiles per launch in wide mode (fewer, longer launches; fewer rounds), 4 otherwise
+    // (shorter pipeline stages for the link-bound sizes), unless the caller fixed the number.
+    kchain_ = cfg_.kchain ? cfg_.kchain : kMaxChain;
+    wide_ = cfg_.wide > 0 && p.panels.empty() && !p.results_are_operands && (int)ntasks > cfg_.group && wide_fits(p);
+    if (!wide_ && !cfg_.kchain) kchain_ = 4;
+    const int group = wide_ ? (int)ntasks : cfg_.group;
+    round_ = 0;
+    pf_pos_ = 0;
+    pf_last_round_ = 0;
+    if (wide_) {
+        size_t max_steps = 0;
+        for (const Task& t : p.tasks) max_steps = std::max(max_steps, t.steps.size());
+        pf_last_round_ = max_steps ? (max_steps - 1) / (size_t)kchain_ : 0;
+    }
     // Tiles kept from earlier calls: whatever overlaps the matrix this call writes is stale from
     // now on (and must not collide with result tiles adopted under the same host address).
     cache_.forget_evictions();
@@ -716,11 +852,16 @@ int Scheduler::run(Problem& p) {
         retire(false);
         poll_writebacks(false);
         // keep `group` tasks running: top-priority tasks of the reservation station
-        refill_rs();
+        if (!wide_) refill_rs();
         size_t active = 0;
         for (const Running& r : running_) active += r.done ? 0 : 1;
-        while ((int)active < cfg_.group) {
-            const int task = pick_from_rs();
+        while ((int)active < group) {
+            int task = -1;
+            if (wide_) {                     // everything starts at once, in queue order
+                if (next_task_ < ntasks) task = (int)next_task_++;
+            } else {
+                task = pick_from_rs();
+            }
             if (task < 0) break;
             Running r;
             rc = start_task(task, &r);
@@ -734,7 +875,7 @@ int Scheduler::run(Problem& p) {
                 }
             if (!placed) running_.push_back(r);
             ++active;
-            refill_rs();
+            if (!wide_) refill_rs();
         }
         if (rc) break;
         if (active == 0) {
@@ -753,6 +894,7 @@ int Scheduler::run(Problem& p) {
         if (rc) break;
         rc = flush_all();
         if (rc) break;
+        ++round_;
         if (!progressed) {
             // every running task waits for a producer that is itself not running: cannot happen
             // with a dependency-ordered queue, but never spin
@@ -779,8 +921,10 @@ int Scheduler::run(Problem& p) {
         for (Block* b : ps.blocks) cache_.release(b);
         ps.blocks.clear();
     }
-    for (Running& r : running_)
+    for (Running& r : running_) {
         if (!r.done && r.c_slot >= 0) cache_.give_slot(r.c_slot);
+        if (!r.done && r.h_slot >= 0) cache_.give_slot(r.h_slot);
+    }
     running_.clear();
     pending_wb_.clear();
     // What stays cached must equal the host matrices as this call leaves them: operand tiles do,

@@ -30,9 +30,12 @@ namespace blasx {
 
 struct SchedConfig {
     int group = 0;      // tasks that run together (0 in the library's settings: chosen per call)
-    int kchain = 4;     // k-steps fused per launch (1..kMaxChain)
+    int kchain = 0;     // k-steps fused per launch (1..kMaxChain; 0: chosen per run)
     int depth = 6;      // launches in flight before the host waits
     int rs = 32;        // reservation-station size
+    int wide = 12;      // let every task of a call advance together when the cache has room and every
+                        // task has at least this many k-steps (see run()); 0: never
+    int prefetch = 24;  // wide mode: inbound copies are started this many launches ahead of the launch being built
     bool profile = false;
 };
 
@@ -59,12 +62,15 @@ public:
     size_t invalidate_all();
     void set_config(const SchedConfig& cfg);
     size_t cached_blocks() const { return cache_.blocks(); }
+    bool last_run_was_wide() const { return wide_; }
+    int last_run_kchain() const { return kchain_; }
 
 private:
     struct Running {
         int task = -1;
         int next_step = 0;
-        int c_slot = -1;
+        int c_slot = -1;            // slot of the accumulator (of the result once the last launch is built)
+        int h_slot = -1;            // wide mode: slot the host C tile is (being) copied into, or -1
         bool first = true;          // no launch issued yet (beta_first applies)
         bool solved = false;
         uint64_t last_pack = 0;     // id of the pack holding this task's latest chain
@@ -113,6 +119,9 @@ private:
     int  start_task(int task_index, Running* r);
     int  ensure_panel(int panel);
     int  build_chain(int ri);
+    int  prefetch_c(Running& r, const Task& t, bool may_wait);
+    void prefetch_ahead(size_t build_pos);
+    bool wide_fits(const Problem& p) const;
     int  build_solve(int ri);
     int  get_inverse(const Task& t, Block** out);
     int  fetch_derived(const TileRef& t, int kind, Block** out);
@@ -136,6 +145,11 @@ private:
     Stats& stats_;
     Problem* p_ = nullptr;
     int T_ = 0;
+    int kchain_ = 4;                    // this run: k-steps fused per launch
+    bool wide_ = false;                 // this run: all tasks advance together, C tiles arrive late
+    size_t round_ = 0;                  // wide mode: index of the round being built
+    size_t pf_last_round_ = 0;          // wide mode: last round in which any task still has steps
+    size_t pf_pos_ = 0;                 // wide mode: next (round * ntasks + task) whose tiles get prefetched
 
     std::vector<int> fill_ev_;          // per slot: event of its latest inbound copy
     std::vector<uint64_t> fill_seq_;    // per slot: sequence number of that copy on its stream

@@ -229,6 +229,7 @@ __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j
     const uint32_t flags = st.flags;
     const T alpha = (T)st.alpha, beta = (T)st.beta;
     const bool use_c = (st.beta != 0.0);
+    const T* __restrict__ D = static_cast<const T*>(st.D);
     const int ldc = st.ldc;
 #pragma unroll
     for (int bj = 0; bj < 4; ++bj)
@@ -244,6 +245,7 @@ __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j
                 T* p = C + (size_t)i + (size_t)j * ldc;
                 T v = alpha * acc[bi][bj][r];
                 if (use_c) v += beta * (*p);
+                if (D) v += D[(size_t)i + (size_t)j * ldc];
                 *p = v;
             }
         }
@@ -468,37 +470,40 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     }
 
     T* __restrict__ C = static_cast<T*>(st.C);
+    const T* __restrict__ D = static_cast<const T*>(st.D);
     const T alpha = (T)st.alpha, beta = (T)st.beta;
     const bool use_c = (st.beta != 0.0);
     const int ldc = st.ldc;
     // Output-triangle mask (diagonal tiles of SYRK): +1 keeps i >= j, -1 keeps i <= j, 0 keeps all.
     const int tri = (st.flags & TS_C_LOWER) ? 1 : ((st.flags & TS_C_UPPER) ? -1 : 0);
 #pragma unroll
-    for (int bj = 0; bj < 2; ++bj) {
-        // one 16-column block at a time keeps the C values in flight to 16 elements per lane
-        T cv[4][4];
-        if (use_c) {
+    for (int bj = 0; bj < 2; ++bj)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
+        for (int rh = 0; rh < 4; rh += 2) {
+            // half a 16-column block at a time: 8 values of C and 8 of the addend D in flight per lane
+            T cv[2][4], dv[2][4];
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
 #pragma unroll
                 for (int bi = 0; bi < 4; ++bi) {
                     const int i = i_base + wm * 64 + bi * 16 + r16;
-                    const int j = j_base + wn * 32 + bj * 16 + Mfma<T>::drow(r, g);
-                    cv[r][bi] = (tri * (i - j) >= 0) ? C[(size_t)i + (size_t)j * ldc] : T(0);
+                    const int j = j_base + wn * 32 + bj * 16 + Mfma<T>::drow(rh + r, g);
+                    const bool keep = tri * (i - j) >= 0;
+                    cv[r][bi] = (use_c && keep) ? C[(size_t)i + (size_t)j * ldc] : T(0);
+                    dv[r][bi] = (D && keep) ? D[(size_t)i + (size_t)j * ldc] : T(0);
                 }
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int bi = 0; bi < 4; ++bi) {
+                    const int i = i_base + wm * 64 + bi * 16 + r16;
+                    const int j = j_base + wn * 32 + bj * 16 + Mfma<T>::drow(rh + r, g);
+                    T v = alpha * acc[bi][bj][rh + r] + dv[r][bi];
+                    if (use_c) v += beta * cv[r][bi];
+                    if (tri * (i - j) >= 0) C[(size_t)i + (size_t)j * ldc] = v;
+                }
+            __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int bi = 0; bi < 4; ++bi) {
-                const int i = i_base + wm * 64 + bi * 16 + r16;
-                const int j = j_base + wn * 32 + bj * 16 + Mfma<T>::drow(r, g);
-                T v = alpha * acc[bi][bj][r];
-                if (use_c) v += beta * cv[r][bi];
-                if (tri * (i - j) >= 0) C[(size_t)i + (size_t)j * ldc] = v;
-            }
-        __builtin_amdgcn_sched_barrier(0);
-    }
 }
 
 // MODE 0: fast path (the host has checked with step_is_fast() that every step of the pack is made

@@ -2,7 +2,7 @@
 //
 // A tile step is the unit of work of the tile algorithms (Section III.B, Eq. 1a-1d):
 //     C <- alpha * op(A) * op(B) + beta * C
-// on one m x n output tile with one k-deep pair of operand tiles.  All three tiles
+// (plus, optionally, a second addend tile D) on one m x n output tile with one k-deep pair of operand tiles.  All three tiles
 // live in HBM, column-major.  A and B are stored as they are in the host matrix; a
 // transposed operand is transposed while it is staged into LDS (Section III.C), never
 // in memory.
@@ -35,23 +35,28 @@ struct TileSeg {
     uint32_t flags;          // TS_TRI_* of this pair only
 };
 
-constexpr int kMaxChain = 4;
+constexpr int kMaxChain = 8;
 
-// C <- alpha * sum_s op(A_s) op(B_s) + beta * C for one output tile.
+// C <- alpha * sum_s op(A_s) op(B_s) + beta * C (+ D) for one output tile.  Extents and leading
+// dimensions are at most 8192 (the largest tile edge), so 16 bits hold them and 16 steps with 8
+// pairs each fit the kernel-argument segment.
 struct TileStep {
-    void*    C;
+    void*       C;
+    const void* D;           // optional addend tile (shape and leading dimension of C), or null:
+                             // partial sums of earlier launches when C itself arrives late
     TileSeg  seg[kMaxChain];
-    int32_t  nseg;           // 0: C <- beta * C only
-    int32_t  lda, ldb, ldc;  // leading dimensions in elements (same for every pair)
-    int32_t  m, n;           // C is m x n
+    double   alpha, beta;    // beta == 0: C is not read
     uint32_t flags;          // TS_TRANS_*, TS_C_*
     uint32_t wg_begin;       // first workgroup (virtual index) of this step within its launch
-    double   alpha, beta;    // beta == 0: C is not read
+    uint16_t lda, ldb, ldc;  // leading dimensions in elements (same for every pair)
+    uint16_t m, n;           // C is m x n
+    uint16_t nseg;           // 0: C <- beta * C (+ D) only
 };
+static_assert(sizeof(TileStep) == 248, "tile step layout");
 
 // Up to this many tile steps travel by value in the kernel arguments of one launch
 // (the whole pack must stay below the 4 KB kernel-argument limit).
-constexpr int kMaxStepsPerLaunch = 26;
+constexpr int kMaxStepsPerLaunch = 16;
 
 struct LaunchPack {
     int32_t  nsteps;

@@ -18,7 +18,7 @@ import numpy as np
 
 from . import blasx
 
-ROUTINES = ("dgemm", "sgemm", "dsyrk", "dtrsm", "dsymm")
+ROUTINES = ("dgemm", "sgemm", "dsyrk", "dsyr2k", "dtrsm", "dsymm")
 
 
 def _fill(a, seed):
@@ -51,6 +51,10 @@ def _problem(lib, routine, n, k):
         A, C = mat(n, k, 1), mat(n, n, 3)
         f = getattr(lib, routine)
         return (lambda: f(CM, blasx.Lower, NT, n, k, 1.0, A, n, 1.0, C, n)), 1.0 * n * (n + 1) * k, None, owners
+    if kind == "syr2k":
+        A, B, C = mat(n, k, 1), mat(n, k, 2), mat(n, n, 3)
+        f = getattr(lib, routine)
+        return (lambda: f(CM, blasx.Lower, NT, n, k, 1.0, A, n, B, n, 1.0, C, n)), 2.0 * n * (n + 1) * k, None, owners
     if kind == "symm":
         A, B, C = mat(n, n, 1), mat(n, n, 2), mat(n, n, 3)
         f = getattr(lib, routine)
@@ -67,7 +71,7 @@ def _problem(lib, routine, n, k):
     raise ValueError(routine)
 
 
-def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None):
+def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=12):
     lib = blasx.default()
     results = []
     for n in sizes:
@@ -79,8 +83,8 @@ def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None
                     lib.init(int(arena_gb * 2 ** 30), nstreams=ns)
                     lib.set_tile(T)
                     lib.set_cache_bytes(0)
-                    for name, v in dict(group=g, rs=max(32, 2 * g), kchain=4, depth=6, sb_rows=4, sb_cols=4, shells=1,
-                                        profile=0, persist=0).items():
+                    for name, v in dict(group=g, rs=max(32, 2 * g), kchain=0, depth=6, sb_rows=4, sb_cols=4, shells=1,
+                                        profile=0, persist=0, wide=wide).items():
                         lib.set_option(name, v)
                     times = []
                     for rep in range(reps + 1):
@@ -92,6 +96,7 @@ def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None
                     best = min(times[1:])
                     rec = dict(routine=routine, n=n, k=k, T=T, streams=ns, group=g, ms=best * 1e3,
                                tflops=flop / best / 1e12)
+                    rec["wide"] = lib.get_option("last_wide")
                     if T == 0 or g == 0:      # automatic choices: say what was chosen
                         rec["chosen_T"], rec["chosen_group"] = lib.get_option("last_tile"), lib.get_option("last_group")
                     results.append(rec)
@@ -133,12 +138,13 @@ def main(argv=None):
     ap.add_argument("--groups", default="16")
     ap.add_argument("--reps", type=int, default=3)
     ap.add_argument("--arena-gb", type=float, default=24.0)
+    ap.add_argument("--wide", type=int, default=12, help="option \"wide\": least k-steps per task for which all tasks advance together; 0: never")
     ap.add_argument("--out", default="", help="also append the JSON records to this file")
     a = ap.parse_args(argv)
     ints = lambda s: [int(x) for x in s.split(",") if x]
     sizes, tiles, streams, groups = ints(a.sizes), ints(a.tiles), ints(a.streams), ints(a.groups)
     out = open(a.out, "a") if a.out else None
-    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out)
+    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out, a.wide)
     print()
     print(tables(res, tiles, streams))
 

@@ -85,6 +85,7 @@ void run_step(const TileStep& st) {
             T* p = C + (size_t)i + (size_t)j * st.ldc;
             double v = st.alpha * acc[(size_t)i + (size_t)j * st.m];
             if (st.beta != 0.0) v += st.beta * (double)*p;
+            if (st.D) v += (double)static_cast<const T*>(st.D)[(size_t)i + (size_t)j * st.ldc];
             *p = (T)v;
         }
 }

@@ -33,7 +33,7 @@ def configure(L, T, nstreams=4, arena_gb=2.0, cap_bytes=0, **opts):
     L.init(int(arena_gb * 2 ** 30), nstreams=nstreams)
     L.set_tile(T)
     L.set_cache_bytes(cap_bytes)
-    defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, profile=0, persist=0)
+    defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, profile=0, persist=0, wide=0)
     defaults.update(opts)
     for k, v in defaults.items():
         L.set_option(k, v)
@@ -360,17 +360,71 @@ def c_before(seed, mat, rows):
     return lambda gi, gj: np.array([[synth.element(seed, mat, int(i), int(j), rows) for j in gj] for i in gi])
 
 
+AUTO = dict(group=0, kchain=0, wide=12)      # the library's own choices: what bench.py times
+
+
+@pytest.mark.parametrize("schedule", ["grouped", "auto"])
 @pytest.mark.parametrize("n", [16384, 32768])
-def test_config2_dgemm_large_sampled(lib, n):
-    """The benchmark workload itself (N=32768) and the size below it, in the launch configuration bench.py times."""
-    configure(lib, T=1024, nstreams=4, arena_gb=(2 * 8 * n * n + 160 * 8 * 2 ** 20) / 2 ** 30)
+def test_config2_dgemm_large_sampled(lib, n, schedule):
+    """The benchmark workload itself (N=32768) and the size below it: in the launch configuration bench.py times
+    (all tasks advance together, C tiles arrive late) and in the grouped schedule (16 tasks run to completion)."""
+    tiles = 512 if schedule == "auto" else 160
+    opts = AUTO if schedule == "auto" else {}
+    configure(lib, T=1024, nstreams=4, arena_gb=((3 if schedule == "auto" else 2) * 8 * n * n + tiles * 8 * 2 ** 20) / 2 ** 30, **opts)
     A, ka = pinned(n, n, 0, synth.MAT_A)
     B, kb = pinned(n, n, 0, synth.MAT_B)
     C, kc = pinned(n, n, 0, synth.MAT_C)
     dt = timed(lambda: lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 1.0, C, n))
-    st = report("cfg2 DGEMM NN N=%d T=1024" % n, lib, 2.0 * n ** 3, dt)
+    st = report("cfg2 DGEMM NN N=%d T=1024 %s" % (n, schedule), lib, 2.0 * n ** 3, dt)
     check_gemm_sampled(blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, B, 1.0, c_before(0, synth.MAT_C, n), C, 1024, n, TOL64)
-    assert st["bytes_h2d"] == 3 * 8 * n * n and st["bytes_d2h"] == 8 * n * n and st["evictions"] == 0
+    assert st["bytes_h2d"] == 3 * 8 * n * n and st["bytes_d2h"] == 8 * n * n and st["refetches"] == 0
+    assert lib.get_option("last_wide") == (1 if schedule == "auto" else 0)
+
+
+@pytest.mark.parametrize("ta,tb", list(itertools.product(TRANS, TRANS)))
+def test_wide_schedule_dgemm_ragged_full_compare(lib, ta, tb):
+    """The wide schedule on ragged tiles with 17 k-tiles: three rounds of 8, 8 and 1 k-steps, late C tiles."""
+    M, N, K = 650, 530, 2100
+    configure(lib, T=128, arena_gb=0.5, **AUTO)
+    A, ka = pinned(*((M, K) if ta == blasx.NoTrans else (K, M)), 30, 0)
+    B, kb = pinned(*((K, N) if tb == blasx.NoTrans else (N, K)), 30, 1)
+    C, kc = pinned(M, N, 30, 2)
+    want = np.array(C, order="F")
+    lib.dgemm(blasx.ColMajor, ta, tb, M, N, K, -1.25, A, A.shape[0], B, B.shape[0], 0.75, C, M)
+    assert lib.get_option("last_wide") == 1 and lib.get_option("last_kchain") == 8
+    ref.gemm(ref.ColMajor, ta, tb, -1.25, np.asarray(A), np.asarray(B), 0.75, want)
+    assert relerr(C, want) < TOL64
+    st = lib.get_stats()
+    assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N) and st["copies_d2h"] == 6 * 5
+
+
+def test_wide_schedule_symmetric_routines_full_compare(lib):
+    N, K = 650, 1700
+    configure(lib, T=128, arena_gb=0.5, **AUTO)
+    A, ka = pinned(N, K, 31, 0)
+    B, kb = pinned(N, K, 31, 1)
+    C, kc = pinned(N, N, 31, 2)
+    other = np.triu_indices(N, 1)
+    C[other] = 1234.5
+    want = np.array(C, order="F")
+    lib.dsyrk(blasx.ColMajor, blasx.Lower, blasx.NoTrans, N, K, 1.0, A, N, 0.0, C, N)     # beta = 0: diagonal tiles still need C
+    assert lib.get_option("last_wide") == 1
+    ref.syrk(ref.ColMajor, ref.Lower, ref.NoTrans, 1.0, np.asarray(A), 0.0, want)
+    assert np.all(np.asarray(C)[other] == 1234.5) and relerr(C, want) < TOL64
+    lib.dsyr2k(blasx.ColMajor, blasx.Lower, blasx.NoTrans, N, K, 0.5, A, N, B, N, 1.0, C, N)
+    assert lib.get_option("last_wide") == 1
+    ref.syr2k(ref.ColMajor, ref.Lower, ref.NoTrans, 0.5, np.asarray(A), np.asarray(B), 1.0, want)
+    assert np.all(np.asarray(C)[other] == 1234.5) and relerr(C, want) < TOL64
+    M = 1700
+    S, ks = pinned(M, M, 32, 0)
+    S[np.tril_indices(M, -1)] = np.nan                       # upper triangle stored
+    X, kx = pinned(M, 390, 32, 1)
+    Y, ky = pinned(M, 390, 32, 2)
+    want = np.array(Y, order="F")
+    lib.dsymm(blasx.ColMajor, blasx.Left, blasx.Upper, M, 390, 1.0, S, M, X, M, -1.0, Y, M)
+    assert lib.get_option("last_wide") == 1
+    ref.symm(ref.ColMajor, ref.Left, ref.Upper, 1.0, np.asarray(S), np.asarray(X), -1.0, want)
+    assert relerr(Y, want) < TOL64
 
 
 def test_config3_out_of_core_dgemm_capped_cache(lib):
@@ -473,7 +527,7 @@ def test_config5b_sgemm_notrans_trans_sampled(lib):
 def test_dsyr2k_lower_notrans_16384_sampled(lib):
     """DSYR2K Lower/NoTrans N=16384 K=8192, alpha=1, beta=1 at the SYRK workload's shape."""
     N, K, T = 16384, 8192, 1024
-    configure(lib, T=T, nstreams=4, arena_gb=8.0)
+    configure(lib, T=T, nstreams=4, arena_gb=8.0, **AUTO)
     A, ka = pinned(N, K, 16, synth.MAT_A)
     B, kb = pinned(N, K, 16, synth.MAT_B)
     C, kc = pinned(N, N, 16, synth.MAT_C)
@@ -506,7 +560,7 @@ def test_dsyr2k_lower_notrans_16384_sampled(lib):
 def test_dsymm_16384_sampled(lib, side, uplo):
     """DSYMM M=N=16384, alpha=1, beta=1; the triangle of A that is not stored holds NaN."""
     n, T = 16384, 1024
-    configure(lib, T=T, nstreams=4, arena_gb=12.0)
+    configure(lib, T=T, nstreams=4, arena_gb=12.0, **AUTO)
     A, ka = pinned(n, n, 17, synth.MAT_A)
     B, kb = pinned(n, n, 17, synth.MAT_B)
     C, kc = pinned(n, n, 17, synth.MAT_C)
@@ -551,7 +605,7 @@ def test_dsymm_16384_sampled(lib, side, uplo):
 
 # ------------------------------------------------------------------ automatic tile size --
 
-@pytest.mark.parametrize("n,expect,group", [(1000, 1008, 2), (4096, 1024, 2), (8192, 1024, 8)])
+@pytest.mark.parametrize("n,expect,group", [(1000, 1008, 2), (4096, 1024, 2), (8192, 1024, 8)])  # all below the wide threshold
 def test_auto_tile_dgemm_sampled(lib, n, expect, group):
     """blasx_set_tile(0) and group 0: tile and running set are chosen per call; same parity bar as fixed ones."""
     configure(lib, T=0, nstreams=4, arena_gb=4.0, group=0)

@@ -30,7 +30,7 @@ def setup(sim, T, nstreams=4, arena_tiles=64, cap_tiles=0, seed=1, esize=8, **op
     sim.init_raw(arena_tiles * T * T * esize, nstreams)
     sim.set_tile(T)
     sim.set_cache_bytes(cap_tiles * T * T * esize)
-    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, profile=0, persist=0)
+    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, profile=0, persist=0, wide=0)
     defaults.update(opts)
     for k, v in defaults.items():
         sim.set_option(k, v)
@@ -442,6 +442,98 @@ def test_run_to_run_reproducible_and_interleaving_independent(sim):
     assert relerr(C, outs[0]) < 1e-15
 
 
+# ------------------------------------------------------------------ wide mode --------------
+# All tasks of a call advance together, k-chunk by k-chunk; the host C tile arrives late, in a slot
+# of its own, and the last launch of a task adds the accumulated partial sums to it.
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("ta,tb", list(itertools.product(TRANS, TRANS)))
+@pytest.mark.parametrize("M,N,K,kchain", [(64, 80, 96, 2), (37, 53, 41, 1), (50, 50, 100, 3), (48, 48, 16, 4)])
+def test_wide_mode_gemm_matches_oracle(sim, order, ta, tb, M, N, K, kchain):
+    setup(sim, T=16, arena_tiles=400, seed=M + ta + 3 * tb + order, wide=2, group=2, kchain=kchain)
+    rng = np.random.default_rng(M * K + ta)
+    A = rng.uniform(-1, 1, (M, K) if ta == blasx.NoTrans else (K, M))
+    B = rng.uniform(-1, 1, (K, N) if tb == blasx.NoTrans else (N, K))
+    C = rng.uniform(-1, 1, (M, N))
+    As, Bs, Cs, Cr = store(A, order, 1), store(B, order, 2), store(C, order, 3), store(C, order, 3)
+    sim.dgemm(order, ta, tb, M, N, K, 0.75, As, ld_of(As, order), Bs, ld_of(Bs, order), -0.5, Cs, ld_of(Cs, order))
+    # one launch per task leaves nothing to pipeline: such calls keep the grouped schedule
+    assert sim.get_option("last_wide") == (1 if -(-K // 16) > kchain else 0)
+    ref.gemm(order, ta, tb, 0.75, As, Bs, -0.5, Cr)
+    assert relerr(Cs, np.asarray(Cr)) < 1e-14
+    st = sim.get_stats()
+    nt = -(-M // 16) * -(-N // 16)
+    assert st["tasks"] == nt and st["copies_d2h"] == nt
+    assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N)        # every tile exactly once, C included
+
+
+def test_wide_mode_special_cases(sim):
+    rng = np.random.default_rng(31)
+    n = 64
+    A, B = fmat(rng, n, n), fmat(rng, n, n)
+    # beta = 0: C is never read (NaN in, exact integers out); no C tile crosses the link
+    setup(sim, T=16, arena_tiles=400, wide=2, group=2, kchain=2)
+    C = np.full((n, n), np.nan, order="F")
+    sim.dgemm(CM, NT, NT, n, n, n, 2.0, A, n, B, n, 0.0, C, n)
+    assert sim.get_option("last_wide") == 1 and np.array_equal(C, 2.0 * (A @ B))
+    assert sim.get_stats()["bytes_h2d"] == 2 * 8 * n * n
+    # alpha = 0: A and B are never read; C <- beta C
+    C0 = fmat(rng, n, n)
+    C = C0.copy(order="F")
+    sim.dgemm(CM, NT, NT, n, n, n, 0.0, np.full((n, n), np.nan, order="F"), n, np.full((n, n), np.nan, order="F"), n, 3.0, C, n)
+    assert np.array_equal(C, 3.0 * C0)
+    # integer data: bit-exact whatever the order of the partial sums, also with one launch per task (kchain >= k tiles)
+    for kchain in (1, 2, 4):
+        setup(sim, T=16, arena_tiles=400, wide=2, group=2, kchain=kchain, seed=kchain)
+        C = C0.copy(order="F")
+        sim.dgemm(CM, NT, blasx.Trans, n, n, n, 1.0, A, n, B, n, -1.0, C, n)
+        assert sim.get_option("last_wide") == (1 if kchain < 4 else 0) and np.array_equal(C, A @ B.T - C0)
+    # not enough room for an accumulator per task: the call falls back to the grouped schedule
+    setup(sim, T=16, arena_tiles=40, wide=2, group=2, kchain=2)
+    C = C0.copy(order="F")
+    sim.dgemm(CM, NT, NT, n, n, n, 1.0, A, n, B, n, 1.0, C, n)
+    assert sim.get_option("last_wide") == 0 and np.array_equal(C, A @ B + C0)
+    # the triangular routines never run wide
+    setup(sim, T=16, arena_tiles=400, wide=2, group=2)
+    L = np.asfortranarray(np.tril(fmat(rng, n, n)) + 9 * np.eye(n))
+    X = B.copy(order="F")
+    sim.dtrmm(CM, blasx.Left, blasx.Lower, NT, blasx.NonUnit, n, n, 1.0, L, n, X, n)
+    assert sim.get_option("last_wide") == 0 and np.array_equal(X, L @ B)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_wide_mode_symmetric_routines_and_tight_cache(sim, seed):
+    """SYRK / SYR2K (output-triangle mask: the C tile of a diagonal task is needed even for beta = 0) and SYMM
+    (derived tiles) in wide mode, with barely enough slots so that operand tiles of finished rounds are evicted."""
+    rng = np.random.default_rng(40 + seed)
+    n, k = 80, 256
+    uplo = blasx.Lower if seed % 2 else blasx.Upper
+    other = np.triu_indices(n, 1) if uplo == blasx.Lower else np.tril_indices(n, -1)
+    A, B = fmat(rng, n, k), fmat(rng, n, k)
+    C0 = fmat(rng, n, n)
+    C0[other] = 99.0
+    beta = 0.0 if seed % 3 == 0 else 2.0
+    setup(sim, T=16, arena_tiles=72 + 4 * seed, wide=2, group=2, kchain=1 + seed % 3, seed=seed)
+    C = C0.copy(order="F")
+    sim.dsyrk(CM, uplo, NT, n, k, 1.0, A, n, beta, C, n)
+    assert sim.get_option("last_wide") == 1 and sim.get_stats()["evictions"] > 0
+    want = np.where(np.isin(np.arange(n * n).reshape(n, n), np.ravel_multi_index(other, (n, n))), 99.0, A @ A.T + beta * C0)
+    assert np.array_equal(C, want)
+    C = C0.copy(order="F")
+    sim.dsyr2k(CM, uplo, NT, n, k, 1.0, A, n, B, n, beta, C, n)
+    assert sim.get_option("last_wide") == 1
+    want = np.where(np.isin(np.arange(n * n).reshape(n, n), np.ravel_multi_index(other, (n, n))), 99.0, A @ B.T + B @ A.T + beta * C0)
+    assert np.array_equal(C, want)
+    S = fmat(rng, n, n)
+    full = np.tril(S) + np.tril(S, -1).T if uplo == blasx.Lower else np.triu(S) + np.triu(S, 1).T
+    Bm, Cm = fmat(rng, n, 48), fmat(rng, n, 48)
+    Cs = Cm.copy(order="F")
+    setup(sim, T=16, arena_tiles=72 + 4 * seed, wide=2, group=2, kchain=1 + seed % 3, seed=seed)
+    sim.dsymm(CM, blasx.Left, uplo, n, 48, 1.0, S, n, Bm, n, beta, Cs, n)
+    assert sim.get_option("last_wide") == 1
+    assert np.array_equal(Cs, full @ Bm + beta * Cm)
+
+
 # ------------------------------------------------------------------ automatic tile size ---
 
 def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
@@ -456,7 +548,7 @@ def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
     sim.set_cache_bytes(0)
     sim.set_tile(0)
     assert sim.get_option("tile") == 0
-    assert chosen(sim.dgemm, 32768, 16) == 2048
+    assert chosen(sim.dgemm, 32768, 16) == 1024
     assert chosen(sim.dgemm, 16, 16384) == 1024
     assert chosen(sim.dgemm, 4096, 16) == 1024
     assert chosen(sim.dgemm, 2048, 2048) == 1024
