@@ -62,6 +62,12 @@ Scheduler::~Scheduler() {
     for (int ev : free_events_) be_.event_destroy(ev);
 }
 
+// Event whose completion implies that the latest inbound copy into `slot` has landed.  Every
+// copy gets an event of its own (re-recorded when the slot is filled again): measured on the
+// copy engines an event record costs under 1 us next to a 150 us tile copy, while an event shared
+// by several copies would make a launch wait for copies that were only prefetched for later ones.
+int Scheduler::fill_event(int slot) const { return fill_ev_[slot]; }
+
 TileKey Scheduler::key_of(const TileRef& t, int tag) const {
     TileKey k;
     k.host = t.host;
@@ -126,7 +132,7 @@ void Scheduler::poll_writebacks(bool block) {
         } else {
             cache_.give_slot(w.slot);
         }
-        put_event(w.ev);
+        if (w.owns_ev) put_event(w.ev);
         writebacks_.pop_front();
     }
 }
@@ -135,7 +141,7 @@ int Scheduler::take_slot_blocking(int* slot) {
     for (;;) {
         const int s = cache_.take_slot();
         if (s >= 0) {
-            // fill_seq_/fill_ev_ of the slot are kept: an inbound copy issued for its previous
+            // fill_seq_ / fill_stream_ of the slot are kept: an inbound copy issued for its previous
             // owner may still be in flight, and whoever writes the slot next must be ordered after it
             *slot = s;
             return 0;
@@ -164,7 +170,7 @@ int Scheduler::issue_h2d(const TileRef& t, int slot) {
     // A slot can change owner while a copy for its previous owner is still queued on the other
     // inbound stream (a block that was evicted before any launch read it): order the two copies.
     if (fill_seq_[slot] != 0 && fill_stream_[slot] != stream) {
-        if (be_.stream_wait_event(stream, fill_ev_[slot])) return BLASX_ERR_DEVICE;
+        if (be_.stream_wait_event(stream, fill_event(slot))) return BLASX_ERR_DEVICE;
     }
     if (be_.copy_h2d(slot_ptr(slot), (size_t)T_ * es, t.host, (size_t)t.ld * es, (size_t)t.rows * es, (size_t)t.cols, stream))
         return BLASX_ERR_DEVICE;
@@ -303,7 +309,7 @@ int Scheduler::flush(OpenPack& op) {
                 (best < 0 || fill_seq_[s] > fill_seq_[best]))
                 best = s;
         if (best >= 0) {
-            if (be_.stream_wait_event(STREAM_COMPUTE, fill_ev_[best])) return BLASX_ERR_DEVICE;
+            if (be_.stream_wait_event(STREAM_COMPUTE, fill_event(best))) return BLASX_ERR_DEVICE;
             compute_waited_[stream] = fill_seq_[best];
         }
     }
@@ -331,7 +337,20 @@ int Scheduler::flush(OpenPack& op) {
     op.wait_slots.clear();
     op.flops = 0;
     op.steps = 0;
-    for (int ri : finishing) BX_TRY(finish_task(ri, done_ev));
+    if (!finishing.empty()) {
+        // the write-backs of one launch: one wait before them, one event after them
+        const int d2h = be_.num_streams() >= 3 ? STREAM_D2H : STREAM_H2D;
+        if (be_.stream_wait_event(d2h, done_ev)) return BLASX_ERR_DEVICE;
+        const size_t first = writebacks_.size();
+        for (int ri : finishing) BX_TRY(finish_task(ri));
+        const int ev = new_event();
+        if (be_.event_record(ev, d2h)) return BLASX_ERR_DEVICE;
+        for (size_t q = first; q < writebacks_.size(); ++q) {
+            writebacks_[q].ev = ev;
+            if (writebacks_[q].block) pending_wb_[writebacks_[q].key] = ev;
+        }
+        writebacks_.back().owns_ev = true;
+    }
     // bound the host's run-ahead: at most `depth` launches in flight
     while ((int)inflight_.size() > cfg_.depth) retire(true);
     return 0;
@@ -346,23 +365,20 @@ int Scheduler::flush_all() {
 
 // The last launch of a task has been issued: write the tile back to the host matrix once that
 // launch is done, and let go of it (the paper's ephemeral M state: written back, then invalid).
-int Scheduler::finish_task(int ri, int done_ev) {
+int Scheduler::finish_task(int ri) {
     Running& r = running_[ri];
     const Task& t = p_->tasks[r.task];
     const size_t es = p_->esize;
     const int d2h = be_.num_streams() >= 3 ? STREAM_D2H : STREAM_H2D;
-    if (be_.stream_wait_event(d2h, done_ev)) return BLASX_ERR_DEVICE;
     if (t.panel >= 0) {
         // the panel's original tiles must have been read from the host before it is overwritten
         for (Block* b : panels_[t.panel].blocks)
-            if (fill_seq_[b->slot] > 0) be_.stream_wait_event(d2h, fill_ev_[b->slot]);
+            if (fill_seq_[b->slot] > 0 && be_.stream_wait_event(d2h, fill_event(b->slot))) return BLASX_ERR_DEVICE;
     }
     if (be_.copy_d2h(t.c_host, (size_t)p_->ldc * es, slot_ptr(r.c_slot), (size_t)T_ * es, (size_t)t.m * es, (size_t)t.n, d2h))
         return BLASX_ERR_DEVICE;
-    WriteBack w;
-    w.ev = new_event();
+    WriteBack w;            // the caller records the event that covers this copy
     w.slot = r.c_slot;
-    if (be_.event_record(w.ev, d2h)) return BLASX_ERR_DEVICE;
     ++stats_.copies_d2h;
     stats_.bytes_d2h += (uint64_t)t.m * t.n * es;
     if (p_->results_are_operands) {
@@ -375,7 +391,6 @@ int Scheduler::finish_task(int ri, int done_ev) {
         w.block = cache_.adopt(w.key, r.c_slot);
         if (!w.block) return BLASX_ERR_DEVICE;
         cache_.acquire(w.block);
-        pending_wb_[w.key] = w.ev;
     }
     writebacks_.push_back(w);
     task_issued_[r.task] = 1;
@@ -442,7 +457,7 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
     if (pf_pos_ <= build_pos) pf_pos_ = build_pos + 1;
     while (pf_pos_ <= target) {
         const size_t round = pf_pos_ / ntasks, ri = pf_pos_ % ntasks;
-        if (ri >= running_.size()) return;
+        if (round > pf_last_round_ || ri >= running_.size()) break;       // nothing left in any task
         Running& r = running_[ri];
         if (r.task < 0 || r.done) {
             ++pf_pos_;
@@ -450,25 +465,50 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
         }
         const Task& t = p_->tasks[r.task];
         const size_t nsteps = t.steps.size();
-        const size_t s0 = round * (size_t)kchain_, s1 = std::min(nsteps, s0 + (size_t)kchain_);
-        if (round > pf_last_round_) return;       // nothing left in any task
-        for (size_t q = s0; q < s1; ++q) {
+        const size_t s0 = std::min(nsteps, round_begin(round)), s1 = std::min(nsteps, round_begin(round + 1));
+        bool stalled = false;
+        for (size_t q = s0; q < s1 && !stalled; ++q) {
             for (const TileRef* ref : {&t.steps[q].a, &t.steps[q].b}) {
                 if (cache_.find(key_of(*ref))) continue;
                 Block* b = nullptr;
-                if (fetch(*ref, &b) != 0) return;     // no slot right now: try again after the next launch
+                if (fetch(*ref, &b) != 0) {       // no slot right now: try again after the next launch
+                    stalled = true;
+                    break;
+                }
             }
         }
+        if (stalled) break;
         if (s0 < nsteps && s1 >= nsteps && s0 > 0 && t.load_c) {
-            if (prefetch_c(r, t, false) != 0 || r.h_slot < 0) return;
+            if (prefetch_c(r, t, false) != 0 || r.h_slot < 0) break;
         }
         ++pf_pos_;
+    }
+    // Host C tiles are wanted by the last launch of each task only, and the last round is the one
+    // in which the link is busiest (its operand tiles in, every result tile out).  They are
+    // therefore fetched up to a whole round early, into slots that are free anyway: never at
+    // the price of evicting an operand tile.
+    const size_t c_target = build_pos + ntasks;
+    if (pfc_pos_ <= build_pos) pfc_pos_ = build_pos + 1;
+    while (pfc_pos_ <= c_target) {
+        const size_t round = pfc_pos_ / ntasks, ri = pfc_pos_ % ntasks;
+        if (round > pf_last_round_ || ri >= running_.size()) break;
+        Running& r = running_[ri];
+        if (r.task >= 0 && !r.done && r.h_slot < 0) {
+            const Task& t = p_->tasks[r.task];
+            const size_t nsteps = t.steps.size();
+            const size_t s0 = std::min(nsteps, round_begin(round)), s1 = std::min(nsteps, round_begin(round + 1));
+            if (s0 < nsteps && s1 >= nsteps && s0 > 0 && t.load_c) {
+                if ((size_t)(cache_.nslots() - cache_.used_slots()) <= pf_reserve_) break;
+                if (prefetch_c(r, t, false) != 0 || r.h_slot < 0) break;
+            }
+        }
+        ++pfc_pos_;
     }
 }
 
 // Wide mode needs an accumulator slot per task plus the operand tiles of two rounds (the round
 // being computed and the one being copied in) plus some slots for late C tiles.
-bool Scheduler::wide_fits(const Problem& p) const {
+bool Scheduler::wide_fits(const Problem& p) {
     std::unordered_set<TileKey, TileKeyHash> uniq;
     size_t max_steps = 0, with_c = 0;
     for (const Task& t : p.tasks) {
@@ -479,12 +519,13 @@ bool Scheduler::wide_fits(const Problem& p) const {
             uniq.insert(key_of(s.b));
         }
     }
-    const size_t rounds = std::max<size_t>(1, (max_steps + kchain_ - 1) / kchain_);
     // one launch per task leaves nothing to pipeline, and with barely more than one round the
     // grouped schedule (whose tasks finish one after the other) measures better
-    if (rounds < 2 || max_steps < (size_t)cfg_.wide) return false;
+    if (max_steps <= (size_t)kchain_ || max_steps < (size_t)cfg_.wide) return false;
+    const size_t rounds = (max_steps + kchain_ - 1) / kchain_;
     const size_t per_round = (uniq.size() + rounds - 1) / rounds;
     const size_t late_c = with_c ? std::min<size_t>(with_c, (size_t)kMaxStepsPerLaunch * (cfg_.prefetch + cfg_.depth + 2)) : 0;
+    pf_reserve_ = per_round + kMaxStepsPerLaunch;
     return (size_t)cache_.nslots() >= p.tasks.size() + 2 * per_round + late_c + kMaxStepsPerLaunch;
 }
 
@@ -642,7 +683,7 @@ int Scheduler::get_inverse(const Task& t, Block** out) {
     // queued into the two slots that are about to be written
     for (int slot : {src->slot, inv->slot, tmp}) {
         if (fill_seq_[slot] > compute_waited_[fill_stream_[slot]]) {
-            if (be_.stream_wait_event(STREAM_COMPUTE, fill_ev_[slot])) return BLASX_ERR_DEVICE;
+            if (be_.stream_wait_event(STREAM_COMPUTE, fill_event(slot))) return BLASX_ERR_DEVICE;
             compute_waited_[fill_stream_[slot]] = fill_seq_[slot];
         }
     }
@@ -731,7 +772,7 @@ int Scheduler::fetch_derived(const TileRef& t, int kind, Block** out) {
     // the stored tile must have arrived, and a stale inbound copy into the new slot must be over
     for (int slot : {src->slot, sym->slot}) {
         if (fill_seq_[slot] > compute_waited_[fill_stream_[slot]]) {
-            if (be_.stream_wait_event(STREAM_COMPUTE, fill_ev_[slot])) return BLASX_ERR_DEVICE;
+            if (be_.stream_wait_event(STREAM_COMPUTE, fill_event(slot))) return BLASX_ERR_DEVICE;
             compute_waited_[fill_stream_[slot]] = fill_seq_[slot];
         }
     }
@@ -836,12 +877,12 @@ int Scheduler::run(Problem& p) {
     if (!wide_ && !cfg_.kchain) kchain_ = 4;
     const int group = wide_ ? (int)ntasks : cfg_.group;
     round_ = 0;
-    pf_pos_ = 0;
+    pf_pos_ = pfc_pos_ = 0;
     pf_last_round_ = 0;
     if (wide_) {
         size_t max_steps = 0;
         for (const Task& t : p.tasks) max_steps = std::max(max_steps, t.steps.size());
-        pf_last_round_ = max_steps ? (max_steps - 1) / (size_t)kchain_ : 0;
+        while (round_begin(pf_last_round_ + 1) < max_steps) ++pf_last_round_;
     }
     // Tiles kept from earlier calls: whatever overlaps the matrix this call writes is stale from
     // now on (and must not collide with result tiles adopted under the same host address).

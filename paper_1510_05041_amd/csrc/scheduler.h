@@ -96,14 +96,14 @@ private:
         uint64_t id = 0;
     };
     struct WriteBack {
-        int ev = -1;
+        int ev = -1;              // event after the last outbound copy of the launch this one belongs to
+        bool owns_ev = false;     // the last entry of that launch hands the event back
         int slot = -1;
         Block* block = nullptr;   // adopted result (TRSM): drop the reader instead of freeing
         TileKey key;
     };
     struct PanelState {
         std::vector<Block*> blocks;
-        int fill_ev = -1, fill_ev_b = -1;   // last inbound copy of the snapshot per stream
         int remaining = 0;
         bool loaded = false;
     };
@@ -121,7 +121,9 @@ private:
     int  build_chain(int ri);
     int  prefetch_c(Running& r, const Task& t, bool may_wait);
     void prefetch_ahead(size_t build_pos);
-    bool wide_fits(const Problem& p) const;
+    bool wide_fits(const Problem& p);
+    // wide mode: first k-step of round r
+    size_t round_begin(size_t r) const { return r * (size_t)kchain_; }
     int  build_solve(int ri);
     int  get_inverse(const Task& t, Block** out);
     int  fetch_derived(const TileRef& t, int kind, Block** out);
@@ -129,7 +131,8 @@ private:
     int  add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, double flops, uint64_t nsteps);
     int  flush(OpenPack& op);
     int  flush_all();
-    int  finish_task(int ri, int done_ev);
+    int  finish_task(int ri);
+    int  fill_event(int slot) const;
     bool retire(bool block_on_oldest);
     void poll_writebacks(bool block);
     void refill_rs();
@@ -149,10 +152,12 @@ private:
     bool wide_ = false;                 // this run: all tasks advance together, C tiles arrive late
     size_t round_ = 0;                  // wide mode: index of the round being built
     size_t pf_last_round_ = 0;          // wide mode: last round in which any task still has steps
+    size_t pfc_pos_ = 0;                // wide mode: same for the host C tiles, which run further ahead
+    size_t pf_reserve_ = 0;             // free slots that early C tiles must leave for operand tiles
     size_t pf_pos_ = 0;                 // wide mode: next (round * ntasks + task) whose tiles get prefetched
 
     std::vector<int> fill_ev_;          // per slot: event of its latest inbound copy
-    std::vector<uint64_t> fill_seq_;    // per slot: sequence number of that copy on its stream
+    std::vector<uint64_t> fill_seq_;    // per slot: number of its latest inbound copy on its stream (0: none yet)
     std::vector<int> fill_stream_;
     uint64_t h2d_issued_[4] = {0, 0, 0, 0};      // per stream role
     uint64_t compute_waited_[4] = {0, 0, 0, 0};
