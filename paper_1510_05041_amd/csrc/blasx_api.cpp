@@ -45,8 +45,10 @@ Library& lib() {
 // operands, running-set size chosen by pick_group): a tile must be large enough that the fixed
 // cost of one strided copy (~10 us on the copy engine) is small beside its transfer time; 1024
 // (8 MB in double precision) is, and stays best down to 2 x 2 tiles; larger tiles only shorten
-// the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 4096 up.
-int pick_tile(int dtype, int64_t rows, int64_t cols) {
+// the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 4096 up, but
+// 1024 where the wide schedule applies (large output and inner dimension: measured 117 against
+// 104 TFLOP/s at 16384, 131 against 130 at 32768).  `inner` is 0 for the triangular routines.
+int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner) {
     Library& L = lib();
     if (L.T > 0) return L.T;
     const int64_t n = std::max<int64_t>(1, std::max(rows, cols));
@@ -54,7 +56,7 @@ int pick_tile(int dtype, int64_t rows, int64_t cols) {
     const int64_t one_tile = (n + 15) / 16 * 16;
     int T;
     if (dtype == 0) T = n >= 2048 ? 1024 : (int)one_tile;
-    else T = n >= 4096 ? 2048 : (int)std::min<int64_t>(2048, one_tile);
+    else T = (n >= 12288 && inner >= 12288) ? 1024 : n >= 4096 ? 2048 : (int)std::min<int64_t>(2048, one_tile);
     // at least 64 tiles must fit in the cache (running set + operands), else eviction thrashes
     size_t usable = L.be ? L.be->arena_bytes() : 0;
     if (L.cache_cap && L.cache_cap < usable) usable = L.cache_cap;
@@ -151,9 +153,9 @@ int gemm_impl(int dtype, int Order, int TransA, int TransB, int M, int N, int K,
     if (!C) return -13;
     Problem p;
     if (col)
-        build_gemm(p, dtype, pick_tile(dtype, M, N), is_trans(TransA), is_trans(TransB), M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+        build_gemm(p, dtype, pick_tile(dtype, M, N, K), is_trans(TransA), is_trans(TransB), M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
     else   // C^T = op(B)^T op(A)^T: the row-major arrays are the column-major transposes
-        build_gemm(p, dtype, pick_tile(dtype, M, N), is_trans(TransB), is_trans(TransA), N, M, K, alpha, B, ldb, A, lda, beta, C, ldc, lib().order);
+        build_gemm(p, dtype, pick_tile(dtype, M, N, K), is_trans(TransB), is_trans(TransA), N, M, K, alpha, B, ldb, A, lda, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
@@ -197,7 +199,7 @@ int syrk_impl(int dtype, int Order, int Uplo, int Trans, int N, int K, double al
     // transposition flag both flip
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     const bool trans = col ? is_trans(Trans) : !is_trans(Trans);
-    build_syrk(p, dtype, pick_tile(dtype, N, N), lower, trans, N, K, alpha, A, lda, beta, C, ldc, lib().order);
+    build_syrk(p, dtype, pick_tile(dtype, N, N, K), lower, trans, N, K, alpha, A, lda, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
@@ -221,7 +223,7 @@ int syr2k_impl(int dtype, int Order, int Uplo, int Trans, int N, int K, double a
     Problem p;
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     const bool trans = col ? is_trans(Trans) : !is_trans(Trans);
-    build_syr2k(p, dtype, pick_tile(dtype, N, N), lower, trans, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+    build_syr2k(p, dtype, pick_tile(dtype, N, N, K), lower, trans, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
@@ -247,7 +249,7 @@ int symm_impl(int dtype, int Order, int Side, int Uplo, int M, int N, double alp
     // row-major: C^T = alpha (A B)^T = alpha B^T A: side and triangle flip, M and N swap
     const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
-    build_symm(p, dtype, pick_tile(dtype, M, N), left, lower, col ? M : N, col ? N : M, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+    build_symm(p, dtype, pick_tile(dtype, M, N, Side == BLASX_LEFT ? M : N), left, lower, col ? M : N, col ? N : M, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
@@ -262,7 +264,7 @@ int trmm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, in
     const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     Problem p;
-    build_trmm(p, dtype, pick_tile(dtype, M, N), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+    build_trmm(p, dtype, pick_tile(dtype, M, N, 0), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
                ldb, lib().order);
     return run_problem(p);
 }
@@ -279,10 +281,10 @@ int trsm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, in
     Problem p;
     if (alpha == 0.0) {
         // X = 0 and A is not read: a TRMM with no steps writes zero tiles
-        build_trmm(p, dtype, pick_tile(dtype, M, N), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, 0.0, A, lda, B,
+        build_trmm(p, dtype, pick_tile(dtype, M, N, 0), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, 0.0, A, lda, B,
                    ldb, lib().order);
     } else {
-        build_trsm(p, dtype, pick_tile(dtype, M, N), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+        build_trsm(p, dtype, pick_tile(dtype, M, N, 0), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
                    ldb, lib().order);
     }
     return run_problem(p);

@@ -502,7 +502,7 @@ def test_config5a_dgemm_trans_notrans_long_k_sampled(lib):
     """DGEMM Trans/NoTrans M=N=8192 K=65536 (A stored 65536 x 8192), alpha=beta=1, T=1024."""
     M = N = 8192
     K, T = 65536, 1024
-    configure(lib, T=T, nstreams=4, arena_gb=10.0)
+    configure(lib, T=T, nstreams=4, arena_gb=12.0, **AUTO)        # 64 tasks x 64 k-steps: the wide schedule
     A, ka = pinned(K, M, 6, synth.MAT_A)
     B, kb = pinned(K, N, 6, synth.MAT_B)
     C, kc = pinned(M, N, 6, synth.MAT_C)
@@ -514,7 +514,7 @@ def test_config5a_dgemm_trans_notrans_long_k_sampled(lib):
 def test_config5b_sgemm_notrans_trans_sampled(lib):
     """SGEMM NoTrans/Trans M=N=K=32768 fp32, alpha=beta=1, T=2048."""
     n, T = 32768, 2048
-    configure(lib, T=T, nstreams=4, arena_gb=(2 * 4 * n * n + 64 * 4 * T * T) / 2 ** 30)
+    configure(lib, T=T, nstreams=4, arena_gb=(4 * 4 * n * n + 128 * 4 * T * T) / 2 ** 30, **AUTO)
     A, ka = pinned(n, n, 7, synth.MAT_A, dtype=np.float32)
     B, kb = pinned(n, n, 7, synth.MAT_B, dtype=np.float32)
     C, kc = pinned(n, n, 7, synth.MAT_C, dtype=np.float32)
