@@ -292,7 +292,12 @@ __device__ __forceinline__ const T* dma_origin(const T* p, int ld, int mn_base, 
     typedef FastShape<T> S;
     if (!KCONTIG) {
         const int row = wave * DMA_PER_WAVE * S::ROWS_PER_COPY + lane / S::LANES_PER_ROW;
-        return p + (size_t)(mn_base + (lane % S::LANES_PER_ROW) * S::EPC) + (size_t)row * ld;
+        // fp32: a 4-byte fragment read serves 32 lanes per pass = two lane groups g, whose rows are
+        // 4 apart and would start at the same bank; every other group of 4 rows is therefore stored
+        // with its columns shifted by half the banks (col ^ 16).  All rows of one wave's copies
+        // fall in the same group of 4, so the shift is the same for the whole wave.
+        const int chunk = (lane % S::LANES_PER_ROW) ^ (sizeof(T) == 4 ? 4 * ((row >> 2) & 1) : 0);
+        return p + (size_t)(mn_base + chunk * S::EPC) + (size_t)row * ld;
     }
     const int m = lane >> 3, q = (lane & 7) ^ m;
     return p + (size_t)(S::EPC * q) + (size_t)(mn_base + wave * DMA_PER_WAVE * 8 + m) * ld;
@@ -317,7 +322,8 @@ __device__ __forceinline__ void frag_read(T (&f)[NB], const T* stage, int c, int
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (!KCONTIG) {
-            f[b] = stage[(4 * S::EPC * c + S::EPC * g + h) * 128 + base + b * 16 + r16];
+            const int swz = sizeof(T) == 4 ? 16 * (g & 1) : 0;      // see dma_origin
+            f[b] = stage[(4 * S::EPC * c + S::EPC * g + h) * 128 + ((base + b * 16 + r16) ^ swz)];
         } else {
             const int mn = base + b * 16 + r16;
             f[b] = stage[(mn * 8 + ((4 * c + g) ^ (r16 & 7))) * S::EPC + h];
@@ -364,6 +370,68 @@ __device__ __forceinline__ void compute_stage(typename Mfma<T>::acc_t (&acc)[4][
             }
         }
     };
+    if constexpr (sizeof(T) == 4) {
+        // fp32: the four MFMA groups h = 0..3 of one c share their 16-byte chunks, so a k-contiguous
+        // operand is read one whole chunk per lane (conflict-free for 16-byte reads thanks to the
+        // XOR in the layout; four separate 4-byte reads of it would collide four ways).
+        auto load_c = [&](T (&va)[4][4], T (&vb)[2][4], int c) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (TA) {
+                    const int mn = wm * 64 + b * 16 + r16;
+                    const float4 v = reinterpret_cast<const float4*>(sa)[mn * 8 + ((4 * c + g) ^ (r16 & 7))];
+                    va[b][0] = v.x; va[b][1] = v.y; va[b][2] = v.z; va[b][3] = v.w;
+                } else {
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) va[b][h] = sa[(16 * c + 4 * g + h) * 128 + ((wm * 64 + b * 16 + r16) ^ (16 * (g & 1)))];
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                if (!TB) {
+                    const int mn = wn * 32 + b * 16 + r16;
+                    const float4 v = reinterpret_cast<const float4*>(sb)[mn * 8 + ((4 * c + g) ^ (r16 & 7))];
+                    vb[b][0] = v.x; vb[b][1] = v.y; vb[b][2] = v.z; vb[b][3] = v.w;
+                } else {
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) vb[b][h] = sb[(16 * c + 4 * g + h) * 128 + ((wn * 32 + b * 16 + r16) ^ (16 * (g & 1)))];
+                }
+            }
+            if (MASK) {
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    const int kg = k0 + 16 * c + 4 * g + h;
+                    if (sflags & TS_TRI_A) {
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const int i = i_base + wm * 64 + b * 16 + r16;
+                            va[b][h] = TA ? tri_select(va[b][h], kg, i, sflags) : tri_select(va[b][h], i, kg, sflags);
+                        }
+                    }
+                    if (sflags & TS_TRI_B) {
+#pragma unroll
+                        for (int b = 0; b < 2; ++b) {
+                            const int j = j_base + wn * 32 + b * 16 + r16;
+                            vb[b][h] = TB ? tri_select(vb[b][h], j, kg, sflags) : tri_select(vb[b][h], kg, j, sflags);
+                        }
+                    }
+                }
+            }
+        };
+        T va[2][4][4], vb[2][2][4];
+        load_c(va[0], vb[0], 0);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            if (c == 0) load_c(va[1], vb[1], 1);
+#pragma unroll
+            for (int h = 0; h < 4; ++h)
+#pragma unroll
+                for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+                    for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = Mfma<T>::run(vb[c][bj][h], va[c][bi][h], acc[bi][bj]);
+        }
+        return;
+    }
     // fragments are double buffered: those of group t+1 are requested before the MFMAs of group t
     T fa[2][4], fb[2][2];
     load_group(fa[0], fb[0], 0);
