@@ -521,7 +521,7 @@ bool Scheduler::wide_fits(const Problem& p) {
     }
     // one launch per task leaves nothing to pipeline, and with barely more than one round the
     // grouped schedule (whose tasks finish one after the other) measures better
-    if (max_steps <= (size_t)kchain_ || max_steps < (size_t)cfg_.wide) return false;
+    if (max_steps <= (size_t)kchain_ || max_steps < (size_t)cfg_.wide * (size_t)p.steps_per_k) return false;
     const size_t rounds = (max_steps + kchain_ - 1) / kchain_;
     const size_t per_round = (uniq.size() + rounds - 1) / rounds;
     const size_t late_c = with_c ? std::min<size_t>(with_c, (size_t)kMaxStepsPerLaunch * (cfg_.prefetch + cfg_.depth + 2)) : 0;

@@ -150,6 +150,7 @@ void build_syr2k(Problem& p, int dtype, int T, bool lower, bool trans, int N, in
                  const void* A, int64_t lda, const void* B, int64_t ldb, double beta, void* C, int64_t ldc,
                  const OrderOpts& oo) {
     init_problem(p, dtype, T, trans, !trans, C, ldc, N, N);
+    p.steps_per_k = 2;
     const int nt = cdiv(N, T), ntk = (alpha == 0.0) ? 0 : cdiv(K, T);
     const int64_t rows = trans ? K : N, cols = trans ? N : K;
     auto keep = [lower](int i, int j) { return lower ? i >= j : i <= j; };

@@ -74,6 +74,7 @@ struct Problem {
     int64_t c_rows = 0, c_cols = 0;    // and extent
     int T = 0;
     bool results_are_operands = false;  // TRSM: finished tiles stay cached under their host address
+    int steps_per_k = 1;     // k-steps a task makes per tile of the inner dimension (SYR2K: 2)
     std::vector<Task> tasks; // in queue order
     std::vector<Panel> panels;
     double flops = 0.0;
