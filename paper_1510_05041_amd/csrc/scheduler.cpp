@@ -469,6 +469,8 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
         bool stalled = false;
         for (size_t q = s0; q < s1 && !stalled; ++q) {
             for (const TileRef* ref : {&t.steps[q].a, &t.steps[q].b}) {
+                // an operand that another task produces is not on the host yet
+                if ((ref == &t.steps[q].a && t.steps[q].a_is_dep) || (ref == &t.steps[q].b && t.steps[q].b_is_dep)) continue;
                 if (cache_.find(key_of(*ref))) continue;
                 Block* b = nullptr;
                 if (fetch(*ref, &b) != 0) {       // no slot right now: try again after the next launch
@@ -521,7 +523,10 @@ bool Scheduler::wide_fits(const Problem& p) {
     }
     // one launch per task leaves nothing to pipeline, and with barely more than one round the
     // grouped schedule (whose tasks finish one after the other) measures better
-    if (max_steps <= (size_t)kchain_ || max_steps < (size_t)cfg_.wide * (size_t)p.steps_per_k) return false;
+    // (the triangular solve, one k-tile per round, pays from two thirds of that: measured equal at
+    // 8 x 8 tiles, +16 % at 10 x 10)
+    const size_t least = p.results_are_operands ? ((size_t)cfg_.wide * 2 + 2) / 3 : (size_t)cfg_.wide * (size_t)p.steps_per_k;
+    if (max_steps <= (size_t)kchain_ || max_steps < least) return false;
     const size_t rounds = (max_steps + kchain_ - 1) / kchain_;
     const size_t per_round = (uniq.size() + rounds - 1) / rounds;
     const size_t late_c = with_c ? std::min<size_t>(with_c, (size_t)kMaxStepsPerLaunch * (cfg_.prefetch + cfg_.depth + 2)) : 0;
@@ -582,7 +587,9 @@ int Scheduler::build_chain(int ri) {
         ++nseg;
     }
     if (nseg == 0 && nsteps > 0 && r.next_step < nsteps) return 1;   // blocked on a producer
-    const bool last = r.next_step + nseg >= nsteps && !t.solve;
+    // last launch of the task's k loop (a solve task still has its diagonal step to come, which then
+    // finds the combined tile alpha * B - sum(A X) in the task's slot)
+    const bool last = r.next_step + nseg >= nsteps;
     int acc_slot = -1;          // wide mode: accumulator that the last launch only reads
     st.C = slot_ptr(r.c_slot);
     st.beta = r.first ? t.beta_first : 1.0;
@@ -802,6 +809,15 @@ int Scheduler::build_solve(int ri) {
     Running& r = running_[ri];
     const Task& t = p_->tasks[r.task];
     if (r.last_pack > flushed_pack_id_) BX_TRY(flush_all());
+    if (wide_ && r.first) {
+        // no update step came before: the right-hand-side tile has not been fetched yet
+        TileRef c;
+        c.host = t.c_host;
+        c.ld = p_->ldc;
+        c.rows = t.m;
+        c.cols = t.n;
+        BX_TRY(issue_h2d(c, r.c_slot));
+    }
     Block* inv = nullptr;
     BX_TRY(get_inverse(t, &inv));
     cache_.acquire(inv);
@@ -872,9 +888,11 @@ int Scheduler::run(Problem& p) {
     // never for the routines whose tasks depend on each other or update their input in place.
     // Chains: 8 k-tiles per launch in wide mode (fewer, longer launches; fewer rounds), 4 otherwise
     // (shorter pipeline stages for the link-bound sizes), unless the caller fixed the number.
-    kchain_ = cfg_.kchain ? cfg_.kchain : kMaxChain;
-    wide_ = cfg_.wide > 0 && p.panels.empty() && !p.results_are_operands && (int)ntasks > cfg_.group && wide_fits(p);
-    if (!wide_ && !cfg_.kchain) kchain_ = 4;
+    // A triangular solve runs wide one k-step at a time (a right-looking solve): step k of every
+    // task below block row k needs the results of block row k, which are solved in the same round.
+    kchain_ = p.results_are_operands ? 1 : cfg_.kchain ? cfg_.kchain : kMaxChain;
+    wide_ = cfg_.wide > 0 && p.panels.empty() && (int)ntasks > cfg_.group && wide_fits(p);
+    if (!wide_) kchain_ = cfg_.kchain ? cfg_.kchain : 4;
     const int group = wide_ ? (int)ntasks : cfg_.group;
     round_ = 0;
     pf_pos_ = pfc_pos_ = 0;

@@ -477,16 +477,19 @@ def test_config4_dsyrk_lower_notrans_sampled(lib):
     assert seen > 10 and worst < TOL64, worst
 
 
-def test_config4_dtrsm_left_lower_notrans_nonunit_residual(lib):
-    """DTRSM Left/Lower/NoTrans/NonUnit M=N=16384, A with diag = N + uniform[0,1], alpha=1; residual on sampled columns."""
+@pytest.mark.parametrize("schedule", ["grouped", "auto"])
+def test_config4_dtrsm_left_lower_notrans_nonunit_residual(lib, schedule):
+    """DTRSM Left/Lower/NoTrans/NonUnit M=N=16384, A with diag = N + uniform[0,1], alpha=1; residual on sampled columns.
+    grouped: tasks queued by dependency level, 16 at a time; auto: the wide (right-looking) schedule."""
     M = N = 16384
     T = 1024
-    configure(lib, T=T, nstreams=4, arena_gb=12.0)
+    configure(lib, T=T, nstreams=4, arena_gb=12.0, **(AUTO if schedule == "auto" else {}))
     A, ka = pinned(M, M, 5, synth.MAT_A)
     synth.dominant_diag(A, 5, synth.MAT_A)
     B, kb = pinned(M, N, 5, synth.MAT_B)
     dt = timed(lambda: lib.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, M, N, 1.0, A, M, B, M))
-    report("cfg4 DTRSM L/L/N/N M=N=16384", lib, 1.0 * M * M * N, dt)
+    report("cfg4 DTRSM L/L/N/N M=N=16384 %s" % schedule, lib, 1.0 * M * M * N, dt)
+    assert lib.get_option("last_wide") == (1 if schedule == "auto" else 0)
     cols = np.random.default_rng(5).choice(N, 16, replace=False)
     X = np.asfortranarray(np.asarray(B)[:, cols])
     assert np.all(np.isfinite(X))
@@ -601,6 +604,28 @@ def test_dsymm_16384_sampled(lib, side, uplo):
             ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, np.asfortranarray(B[gi, :]), np.asfortranarray(sym_rows(gj)), 1.0, want)
         worst = max(worst, relerr(got, want))
     assert worst < TOL64, worst
+
+
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS[1::3])
+def test_wide_schedule_dtrsm_full_compare_and_residual(lib, side, uplo, trans, diag):
+    """The triangular solve in the wide schedule (14 x 11 ragged tiles), compared element by element and by residual."""
+    M, N = 1700, 1330
+    configure(lib, T=128, arena_gb=0.5, **AUTO)
+    n = M if side == blasx.Left else N
+    A, ka = triangular(n, 33, uplo, diag)
+    B, kb = pinned(M, N, 33, 1)
+    B0 = np.array(B, order="F")
+    want = np.array(B, order="F")
+    lib.dtrsm(blasx.ColMajor, side, uplo, trans, diag, M, N, -1.3, A, n, B, M)
+    assert lib.get_option("last_wide") == 1
+    ref.trsm(ref.ColMajor, side, uplo, trans, diag, -1.3, np.asarray(A), want)
+    X = np.array(B, order="F")
+    assert np.all(np.isfinite(X))
+    assert relerr(X, want) < TOL64
+    R = X.copy(order="F")
+    ref.trmm(ref.ColMajor, side, uplo, trans, diag, 1.0, np.asarray(A), R)
+    norm_a = np.linalg.norm(np.nan_to_num(np.asarray(A))) + (np.sqrt(n) if diag == blasx.Unit else 0.0)
+    assert np.linalg.norm(R + 1.3 * B0) / (norm_a * np.linalg.norm(X)) < TOL64
 
 
 # ------------------------------------------------------------------ automatic tile size --

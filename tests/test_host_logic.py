@@ -534,6 +534,52 @@ def test_wide_mode_symmetric_routines_and_tight_cache(sim, seed):
     assert np.array_equal(Cs, full @ Bm + beta * Cm)
 
 
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS)
+def test_wide_mode_trsm_all_flags(sim, order, side, uplo, trans, diag):
+    """The triangular solve in the wide schedule: right-looking, one k-step per round, the right-hand-side tile
+    fetched late and combined with the accumulated updates by the task's last update launch."""
+    setup(sim, T=16, arena_tiles=300, seed=side + uplo + trans + diag + order, wide=2, group=3)
+    rng = np.random.default_rng(50 + side + uplo)
+    M, N = 84, 70
+    n = M if side == blasx.Left else N
+    P = poisoned(rng, n, uplo, diag, dominant=True)
+    if diag == blasx.Unit:
+        P = np.where(np.isnan(P), P, P / n)
+    B = rng.uniform(-1, 1, (M, N))
+    Ps, Bs, Br = store(P, order, 2), store(B, order, 1), store(B, order, 1)
+    sim.dtrsm(order, side, uplo, trans, diag, M, N, 0.7, Ps, ld_of(Ps, order), Bs, ld_of(Bs, order))
+    assert sim.get_option("last_wide") == 1
+    ref.trsm(order, side, uplo, trans, diag, 0.7, Ps, Br)
+    assert np.all(np.isfinite(np.asarray(Bs)))
+    assert relerr(Bs, np.asarray(Br)) < 1e-13
+    st = sim.get_stats()
+    ntm, ntn = -(-M // 16), -(-N // 16)
+    assert st["tasks"] == ntm * ntn
+    nta = ntm if side == blasx.Left else ntn
+    assert st["bytes_h2d"] >= 8 * M * N and st["copies_d2h"] == ntm * ntn
+    assert st["misses"] >= nta * (nta + 1) // 2 + nta
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_wide_mode_trsm_tight_cache_many_interleavings(sim, seed):
+    rng = np.random.default_rng(60 + seed)
+    n, m = 96, 80
+    side = blasx.Left if seed % 2 else blasx.Right
+    uplo = blasx.Lower if seed % 3 else blasx.Upper
+    na = n if side == blasx.Left else m
+    L = np.tril(rng.integers(-2, 3, (na, na)).astype(np.float64), -1) + np.eye(na)      # unit triangular, integers
+    if uplo == blasx.Upper:
+        L = L.T.copy()
+    X = rng.integers(-2, 3, (n, m)).astype(np.float64)
+    B = L @ X if side == blasx.Left else X @ L
+    setup(sim, T=16, arena_tiles=98 + 3 * seed, wide=2, group=2, seed=200 + seed)
+    Ls, Bs = store(L, blasx.ColMajor), store(B, blasx.ColMajor)
+    sim.dtrsm(blasx.ColMajor, side, uplo, blasx.NoTrans, blasx.Unit, n, m, 1.0, Ls, na, Bs, n)
+    assert sim.get_option("last_wide") == 1
+    assert np.array_equal(np.asarray(Bs), X)          # small integers and a unit diagonal: the solve is exact
+
+
 # ------------------------------------------------------------------ automatic tile size ---
 
 def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
