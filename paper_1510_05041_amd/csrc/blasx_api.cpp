@@ -117,6 +117,7 @@ int run_problem(Problem& p) {
         rc = L.sched->run(p);
         L.last_wide = L.sched->last_run_was_wide();
         L.last_kchain = L.sched->last_run_kchain();
+        if (rc != 0) L.sched.reset();      // after a failed call nothing cached is trusted: start afresh
     } else {
         L.sched.reset();
         Scheduler sched(*L.be, (int)ns, slot_bytes, cfg, L.stats);

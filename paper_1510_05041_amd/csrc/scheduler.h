@@ -13,7 +13,15 @@
 //   - the paper's per-round StreamsSynch + ReaderUpdate is replaced by an event per launch:
 //     readers are released when that event has completed, the host never drains the device;
 //   - up to `kchain` consecutive k-steps of a task are fused into one launch so the
-//     accumulators stay in registers.
+//     accumulators stay in registers;
+//   - when the tile cache has room for an accumulator per output tile, ALL tasks of a call run
+//     at once and advance k-chunk by k-chunk (the "wide" schedule, an outer-product order):
+//     a task needs a whole block row and block column of operand tiles, so a small running set
+//     starves the device while those arrive, whereas the whole task set offers about ten times
+//     more products per tile copied.  The host tile of C then arrives late, in a slot of its
+//     own, and the task's last launch adds the accumulated partial sums to it; inbound copies
+//     are issued by a cursor that runs ahead of the launch being built.  The triangular solve
+//     runs the same way one k-tile per round (right-looking).
 #pragma once
 #include <stdint.h>
 
