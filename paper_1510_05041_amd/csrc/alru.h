@@ -47,6 +47,7 @@ struct Block {
     TileKey key;
     int slot = -1;
     int readers = 0;
+    bool pending = false;    // the slot is reserved but the tile's inbound copy has not been started yet
     Block* prev = nullptr;   // towards the front (most recently used)
     Block* next = nullptr;   // towards the end (least recently used)
 };

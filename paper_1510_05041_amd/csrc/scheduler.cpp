@@ -190,7 +190,8 @@ int Scheduler::fetch(const TileRef& t, Block** out) {
     bool hit = false;
     Block* b = cache_.translate(key, &hit);
     if (!b) return -1;
-    if (!hit) {
+    if (!hit || b->pending) {
+        b->pending = false;
         auto it = pending_wb_.find(key);
         if (it != pending_wb_.end()) {
             // the host copy of this tile is still being written by an outbound copy
@@ -212,7 +213,18 @@ int Scheduler::ensure_panel(int panel) {
     for (const TileRef& t : pn.tiles) {
         Block* b = nullptr;
         for (;;) {
-            const int rc = fetch(t, &b);
+            // Wide schedule: every panel is entered at once, so the tiles are only given their
+            // slots here (they must never be evicted and fetched again once results overwrite the
+            // host matrix); each is copied in when its first reader, or the prefetch cursor, gets to it.
+            int rc = 0;
+            if (wide_) {
+                bool hit = false;
+                b = cache_.translate(key_of(t), &hit);
+                if (!b) rc = -1;
+                else if (!hit) b->pending = true;
+            } else {
+                rc = fetch(t, &b);
+            }
             if (rc == 0) break;
             if (rc > 0) return rc;
             ++stats_.slot_waits;
@@ -371,9 +383,17 @@ int Scheduler::finish_task(int ri) {
     const size_t es = p_->esize;
     const int d2h = be_.num_streams() >= 3 ? STREAM_D2H : STREAM_H2D;
     if (t.panel >= 0) {
-        // the panel's original tiles must have been read from the host before it is overwritten
-        for (Block* b : panels_[t.panel].blocks)
-            if (fill_seq_[b->slot] > 0 && be_.stream_wait_event(d2h, fill_event(b->slot))) return BLASX_ERR_DEVICE;
+        // In-place update: the original of the tile this result overwrites is an operand of other
+        // tasks of the panel.  It is pinned in the cache; it must have been read from the host
+        // before the outbound copy lands there.
+        TileRef own;
+        own.host = t.c_host;
+        own.ld = p_->ldc;
+        own.rows = t.m;
+        own.cols = t.n;
+        Block* b = nullptr;
+        BX_TRY(fetch(own, &b));            // pinned with the panel: always there, copied in now if it was only reserved
+        if (fill_seq_[b->slot] > 0 && be_.stream_wait_event(d2h, fill_event(b->slot))) return BLASX_ERR_DEVICE;
     }
     if (be_.copy_d2h(t.c_host, (size_t)p_->ldc * es, slot_ptr(r.c_slot), (size_t)T_ * es, (size_t)t.m * es, (size_t)t.n, d2h))
         return BLASX_ERR_DEVICE;
@@ -471,7 +491,8 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
             for (const TileRef* ref : {&t.steps[q].a, &t.steps[q].b}) {
                 // an operand that another task produces is not on the host yet
                 if ((ref == &t.steps[q].a && t.steps[q].a_is_dep) || (ref == &t.steps[q].b && t.steps[q].b_is_dep)) continue;
-                if (cache_.find(key_of(*ref))) continue;
+                const Block* have = cache_.find(key_of(*ref));
+                if (have && !have->pending) continue;
                 Block* b = nullptr;
                 if (fetch(*ref, &b) != 0) {       // no slot right now: try again after the next launch
                     stalled = true;
@@ -531,7 +552,9 @@ bool Scheduler::wide_fits(const Problem& p) {
     const size_t per_round = (uniq.size() + rounds - 1) / rounds;
     const size_t late_c = with_c ? std::min<size_t>(with_c, (size_t)kMaxStepsPerLaunch * (cfg_.prefetch + cfg_.depth + 2)) : 0;
     pf_reserve_ = per_round + kMaxStepsPerLaunch;
-    return (size_t)cache_.nslots() >= p.tasks.size() + 2 * per_round + late_c + kMaxStepsPerLaunch;
+    size_t pinned = 0;      // TRMM: the original tiles of the matrix updated in place stay for the whole call
+    for (const Panel& pn : p.panels) pinned += pn.tiles.size();
+    return (size_t)cache_.nslots() >= p.tasks.size() + pinned + 2 * per_round + late_c + kMaxStepsPerLaunch;
 }
 
 // Next launch of one running task: up to kchain consecutive k-steps (Alg. 1 lines 19-25 for one
@@ -891,7 +914,7 @@ int Scheduler::run(Problem& p) {
     // A triangular solve runs wide one k-step at a time (a right-looking solve): step k of every
     // task below block row k needs the results of block row k, which are solved in the same round.
     kchain_ = p.results_are_operands ? 1 : cfg_.kchain ? cfg_.kchain : kMaxChain;
-    wide_ = cfg_.wide > 0 && p.panels.empty() && (int)ntasks > cfg_.group && wide_fits(p);
+    wide_ = cfg_.wide > 0 && (int)ntasks > cfg_.group && wide_fits(p);
     if (!wide_) kchain_ = cfg_.kchain ? cfg_.kchain : 4;
     const int group = wide_ ? (int)ntasks : cfg_.group;
     round_ = 0;

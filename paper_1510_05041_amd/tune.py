@@ -18,7 +18,7 @@ import numpy as np
 
 from . import blasx
 
-ROUTINES = ("dgemm", "sgemm", "dsyrk", "dsyr2k", "dtrsm", "dsymm")
+ROUTINES = ("dgemm", "sgemm", "dsyrk", "dsyr2k", "dtrsm", "dtrmm", "dsymm")
 
 
 def _fill(a, seed):
@@ -59,6 +59,11 @@ def _problem(lib, routine, n, k):
         A, B, C = mat(n, n, 1), mat(n, n, 2), mat(n, n, 3)
         f = getattr(lib, routine)
         return (lambda: f(CM, blasx.Left, blasx.Lower, n, n, 1.0, A, n, B, n, 1.0, C, n)), 2.0 * n * n * n, None, owners
+    if kind == "trmm":
+        A, B = mat(n, n, 1), mat(n, n, 2)
+        A *= 1.0 / n                                  # keeps repeated in-place products bounded
+        f = getattr(lib, routine)
+        return (lambda: f(CM, blasx.Left, blasx.Lower, NT, blasx.NonUnit, n, n, 1.0, A, n, B, n)), 1.0 * n * n * n, None, owners
     if kind == "trsm":
         A, B = mat(n, n, 1), mat(n, n, 2)
         A[np.diag_indices(n)] = n + 0.5

@@ -628,6 +628,22 @@ def test_wide_schedule_dtrsm_full_compare_and_residual(lib, side, uplo, trans, d
     assert np.linalg.norm(R + 1.3 * B0) / (norm_a * np.linalg.norm(X)) < TOL64
 
 
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS[2::3])
+def test_wide_schedule_dtrmm_full_compare(lib, side, uplo, trans, diag):
+    """The in-place triangular product in the wide schedule (14 x 13 ragged tiles): all panels pinned at once."""
+    M, N = 1700, 1600
+    configure(lib, T=128, arena_gb=0.5, **AUTO)
+    A, ka = triangular(M if side == blasx.Left else N, 34, uplo, diag)
+    B, kb = pinned(M, N, 34, 1)
+    want = np.array(B, order="F")
+    lib.dtrmm(blasx.ColMajor, side, uplo, trans, diag, M, N, 0.9, A, A.shape[0], B, M)
+    assert lib.get_option("last_wide") == 1
+    ref.trmm(ref.ColMajor, side, uplo, trans, diag, 0.9, np.asarray(A), want)
+    assert np.all(np.isfinite(np.asarray(B)))
+    assert relerr(B, want) < TOL64
+    assert lib.get_stats()["bytes_h2d"] >= 8 * M * N
+
+
 # ------------------------------------------------------------------ automatic tile size --
 
 @pytest.mark.parametrize("n,expect,group", [(1000, 1008, 2), (4096, 1024, 2), (8192, 1024, 8)])  # all below the wide threshold

@@ -493,12 +493,12 @@ def test_wide_mode_special_cases(sim):
     C = C0.copy(order="F")
     sim.dgemm(CM, NT, NT, n, n, n, 1.0, A, n, B, n, 1.0, C, n)
     assert sim.get_option("last_wide") == 0 and np.array_equal(C, A @ B + C0)
-    # the triangular routines never run wide
+    # the in-place triangular product runs wide too, exact on integers
     setup(sim, T=16, arena_tiles=400, wide=2, group=2)
     L = np.asfortranarray(np.tril(fmat(rng, n, n)) + 9 * np.eye(n))
     X = B.copy(order="F")
     sim.dtrmm(CM, blasx.Left, blasx.Lower, NT, blasx.NonUnit, n, n, 1.0, L, n, X, n)
-    assert sim.get_option("last_wide") == 0 and np.array_equal(X, L @ B)
+    assert sim.get_option("last_wide") == 1 and np.array_equal(X, L @ B)
 
 
 @pytest.mark.parametrize("seed", range(6))
@@ -559,6 +559,45 @@ def test_wide_mode_trsm_all_flags(sim, order, side, uplo, trans, diag):
     nta = ntm if side == blasx.Left else ntn
     assert st["bytes_h2d"] >= 8 * M * N and st["copies_d2h"] == ntm * ntn
     assert st["misses"] >= nta * (nta + 1) // 2 + nta
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS)
+def test_wide_mode_trmm_all_flags(sim, order, side, uplo, trans, diag):
+    """The in-place triangular product in the wide schedule: every panel of B is pinned at once, its tiles copied in
+    when first needed, and a result may only overwrite the host tile whose original has been read."""
+    setup(sim, T=16, arena_tiles=300, seed=3 * side + uplo + trans + diag + order, wide=2, group=3, kchain=1 + (side + uplo) % 3)
+    rng = np.random.default_rng(70 + side + trans)
+    M, N = 84, 70
+    P = poisoned(rng, M if side == blasx.Left else N, uplo, diag)
+    B = rng.uniform(-1, 1, (M, N))
+    Ps, Bs, Br = store(P, order, 2), store(B, order, 1), store(B, order, 1)
+    sim.dtrmm(order, side, uplo, trans, diag, M, N, -0.8, Ps, ld_of(Ps, order), Bs, ld_of(Bs, order))
+    assert sim.get_option("last_wide") == 1
+    ref.trmm(order, side, uplo, trans, diag, -0.8, Ps, Br)
+    assert np.all(np.isfinite(np.asarray(Bs)))
+    assert relerr(Bs, np.asarray(Br)) < 1e-14
+    st = sim.get_stats()
+    assert st["copies_d2h"] == -(-M // 16) * -(-N // 16)
+    nta = -(-(M if side == blasx.Left else N) // 16)
+    assert st["bytes_h2d"] >= 8 * M * N           # every tile of B once (its original), plus the triangle of A
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_wide_mode_trmm_tight_cache_many_interleavings(sim, seed):
+    rng = np.random.default_rng(80 + seed)
+    n, m = 96, 80
+    side = blasx.Left if seed % 2 else blasx.Right
+    uplo = blasx.Lower if seed % 3 else blasx.Upper
+    na = n if side == blasx.Left else m
+    A = rng.integers(-2, 3, (na, na)).astype(np.float64)
+    Tm = np.tril(A) if uplo == blasx.Lower else np.triu(A)
+    B = rng.integers(-2, 3, (n, m)).astype(np.float64)
+    setup(sim, T=16, arena_tiles=150 + 3 * seed, wide=2, group=2, kchain=1 + seed % 3, seed=300 + seed)
+    As, Bs = store(A, blasx.ColMajor), store(B, blasx.ColMajor)
+    sim.dtrmm(blasx.ColMajor, side, uplo, blasx.NoTrans, blasx.NonUnit, n, m, 1.0, As, na, Bs, n)
+    assert sim.get_option("last_wide") == 1
+    assert np.array_equal(np.asarray(Bs), Tm @ B if side == blasx.Left else B @ Tm)
 
 
 @pytest.mark.parametrize("seed", range(6))
