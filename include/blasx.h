@@ -144,7 +144,8 @@ int blasx_set_cache_bytes(size_t cap);
  *              results leaving during the whole last round), provided the cache has room for
  *              an accumulator tile per output tile; 0: never (tasks run to completion in
  *              groups, the paper's scheme).  Default 12.  TRSM uses it from two thirds of the
- *              value, one k-tile per round (a right-looking solve); TRMM never does.
+ *              value, one k-tile per round (a right-looking solve); TRMM pins every original
+ *              tile of B at once and copies each in when it is first needed.
  *   "prefetch" wide schedule: inbound copies are started this many launches ahead (default 24)
  *   "depth"    launches the host may run ahead of the device (>= 1)
  *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)
