@@ -1,6 +1,7 @@
-// Tile-step kernels for CDNA4 (gfx950): C <- alpha * sum_s op(A_s) * op(B_s) + beta * C on
-// HBM-resident tiles (Section III.B, Eq. 1a-1d; the call the paper's Alg. 1 makes once per
-// (i, j, k), here with up to four chained k-steps per call).
+// Tile-step kernels for CDNA4 (gfx950): C <- alpha * sum_s op(A_s) * op(B_s) + beta * C (+ D) on
+// HBM-resident tiles (Section III.B, Eq. 1a-1f; the call the paper's Alg. 1 makes once per
+// (i, j, k), here with up to eight chained k-steps per call; D is an optional second addend
+// tile, the partial sums of earlier launches when the host tile of C itself arrives late).
 //
 // One launch executes a *pack* of tile steps (different output tiles), so that a launch fills
 // the 256 CUs even though a single 1024^3 step only has 64 macro-tiles.  The paper shares the
