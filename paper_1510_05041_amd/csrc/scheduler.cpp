@@ -907,8 +907,7 @@ int Scheduler::run(Problem& p) {
     // device has enough products per tile copied from the first launches on, instead of starving
     // while the first few output tiles wait for whole rows of A and columns of B; and result
     // tiles leave during the whole last round instead of in bursts.  The price is an
-    // accumulator slot per output tile, so it is used only when the cache has that room, and
-    // never for the routines whose tasks depend on each other or update their input in place.
+    // accumulator slot per output tile, so it is used only when the cache has that room.
     // Chains: 8 k-tiles per launch in wide mode (fewer, longer launches; fewer rounds), 4 otherwise
     // (shorter pipeline stages for the link-bound sizes), unless the caller fixed the number.
     // A triangular solve runs wide one k-step at a time (a right-looking solve): step k of every
