@@ -340,6 +340,16 @@ __device__ __forceinline__ T tri_select(T v, int r, int c, uint32_t flags) {
     return inside ? v : T(0);
 }
 
+// Waits for this wave's outstanding LDS reads and pins the wait in place.  The software pipelines
+// below request the fragments of step t+1, issue the MFMAs of step t, and only then wait: left
+// alone, the compiler sinks every LDS read to just before its first use, or waits for all reads
+// right after requesting the next ones, and the wave sits out the LDS latency once per step.
+__device__ __forceinline__ void lds_fence() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), other counters untouched
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // MFMAs of one slab.  MASK: one operand of this chained pair is a diagonal tile of a triangular
 // matrix (sflags says which and how); its fragments are masked on their way out of LDS, so what
 // the other triangle holds in memory never reaches an MFMA.  k0 = k offset of the slab in the pair.
@@ -374,19 +384,30 @@ __device__ __forceinline__ void compute_stage(typename Mfma<T>::acc_t (&acc)[4][
     if constexpr (sizeof(T) == 4) {
         // fp32: the four MFMA groups h = 0..3 of one c share their 16-byte chunks, so a k-contiguous
         // operand is read one whole chunk per lane (conflict-free for 16-byte reads thanks to the
-        // XOR in the layout; four separate 4-byte reads of it would collide four ways).
-        auto load_c = [&](T (&va)[4][4], T (&vb)[2][4], int c) {
+        // XOR in the layout; four separate 4-byte reads of it would collide four ways).  The unit
+        // of the software pipeline is therefore (c, block row bi): 8 MFMAs (4 h x 2 bj) on the A
+        // values of one block and the B values of c; the A values of the next unit are requested
+        // before the MFMAs of this one, the B values of c = 1 during the first units of c = 0, so
+        // that only three chunks per lane stand between the barrier and a wave's first MFMA.
+        auto load_a = [&](T (&va)[4], int c, int bi) {
+            if (TA) {
+                const int mn = wm * 64 + bi * 16 + r16;
+                const float4 v = reinterpret_cast<const float4*>(sa)[mn * 8 + ((4 * c + g) ^ (r16 & 7))];
+                va[0] = v.x; va[1] = v.y; va[2] = v.z; va[3] = v.w;
+            } else {
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (TA) {
-                    const int mn = wm * 64 + b * 16 + r16;
-                    const float4 v = reinterpret_cast<const float4*>(sa)[mn * 8 + ((4 * c + g) ^ (r16 & 7))];
-                    va[b][0] = v.x; va[b][1] = v.y; va[b][2] = v.z; va[b][3] = v.w;
-                } else {
+                for (int h = 0; h < 4; ++h) va[h] = sa[(16 * c + 4 * g + h) * 128 + ((wm * 64 + bi * 16 + r16) ^ (16 * (g & 1)))];
+            }
+            if (MASK && (sflags & TS_TRI_A)) {
+                const int i = i_base + wm * 64 + bi * 16 + r16;
 #pragma unroll
-                    for (int h = 0; h < 4; ++h) va[b][h] = sa[(16 * c + 4 * g + h) * 128 + ((wm * 64 + b * 16 + r16) ^ (16 * (g & 1)))];
+                for (int h = 0; h < 4; ++h) {
+                    const int kg = k0 + 16 * c + 4 * g + h;
+                    va[h] = TA ? tri_select(va[h], kg, i, sflags) : tri_select(va[h], i, kg, sflags);
                 }
             }
+        };
+        auto load_b = [&](T (&vb)[2][4], int c) {
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 if (!TB) {
@@ -397,39 +418,31 @@ __device__ __forceinline__ void compute_stage(typename Mfma<T>::acc_t (&acc)[4][
 #pragma unroll
                     for (int h = 0; h < 4; ++h) vb[b][h] = sb[(16 * c + 4 * g + h) * 128 + ((wn * 32 + b * 16 + r16) ^ (16 * (g & 1)))];
                 }
-            }
-            if (MASK) {
+                if (MASK && (sflags & TS_TRI_B)) {
+                    const int j = j_base + wn * 32 + b * 16 + r16;
 #pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    const int kg = k0 + 16 * c + 4 * g + h;
-                    if (sflags & TS_TRI_A) {
-#pragma unroll
-                        for (int b = 0; b < 4; ++b) {
-                            const int i = i_base + wm * 64 + b * 16 + r16;
-                            va[b][h] = TA ? tri_select(va[b][h], kg, i, sflags) : tri_select(va[b][h], i, kg, sflags);
-                        }
-                    }
-                    if (sflags & TS_TRI_B) {
-#pragma unroll
-                        for (int b = 0; b < 2; ++b) {
-                            const int j = j_base + wn * 32 + b * 16 + r16;
-                            vb[b][h] = TB ? tri_select(vb[b][h], j, kg, sflags) : tri_select(vb[b][h], kg, j, sflags);
-                        }
+                    for (int h = 0; h < 4; ++h) {
+                        const int kg = k0 + 16 * c + 4 * g + h;
+                        vb[b][h] = TB ? tri_select(vb[b][h], j, kg, sflags) : tri_select(vb[b][h], kg, j, sflags);
                     }
                 }
             }
         };
-        T va[2][4][4], vb[2][2][4];
-        load_c(va[0], vb[0], 0);
+        T va[2][4], vb[2][2][4];
+        load_b(vb[0], 0);
+        load_a(va[0], 0, 0);
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            if (c == 0) load_c(va[1], vb[1], 1);
+        for (int u = 0; u < 8; ++u) {
+            const int c = u >> 2, bi = u & 3, cur = u & 1;
+            lds_fence();      // the values of this unit, requested one unit earlier, have arrived
+            if (u + 1 < 8) load_a(va[cur ^ 1], (u + 1) >> 2, (u + 1) & 3);
+            if (u == 1) load_b(vb[1], 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int h = 0; h < 4; ++h)
 #pragma unroll
-                for (int bi = 0; bi < 4; ++bi)
-#pragma unroll
-                    for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = Mfma<T>::run(vb[c][bj][h], va[c][bi][h], acc[bi][bj]);
+                for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = Mfma<T>::run(vb[c][bj][h], va[cur][h], acc[bi][bj]);
+            __builtin_amdgcn_sched_barrier(0);
         }
         return;
     }
