@@ -916,6 +916,15 @@ int Scheduler::run(Problem& p) {
     wide_ = cfg_.wide > 0 && (int)ntasks > cfg_.group && wide_fits(p);
     if (!wide_) kchain_ = cfg_.kchain ? cfg_.kchain : 4;
     const int group = wide_ ? (int)ntasks : cfg_.group;
+    // A launch lasts as long as its longest chain.  Where the tasks differ in length (TRMM: task
+    // (i, j) has as many k-steps as block row i has tiles in the triangle), tasks of equal length
+    // are therefore put next to each other: the chains of a round then come out sorted and every
+    // launch holds chains of (nearly) one length.  Shortest first: the first launches need the
+    // fewest tiles, so the device starts early, and the short tasks' results leave during the
+    // call instead of queueing behind its end.
+    if (wide_ && !p.results_are_operands)
+        std::stable_sort(p.tasks.begin(), p.tasks.end(),
+                         [](const Task& a, const Task& b) { return a.steps.size() < b.steps.size(); });
     round_ = 0;
     pf_pos_ = pfc_pos_ = 0;
     pf_last_round_ = 0;
