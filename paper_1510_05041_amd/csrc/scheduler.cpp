@@ -471,13 +471,47 @@ int Scheduler::prefetch_c(Running& r, const Task& t, bool may_wait) {
 // the copy queue has to be fed further ahead than that or the link idles at every round boundary,
 // where a whole new panel of B is needed at once.  Only a hint: build_chain() fetches whatever is
 // still missing.
+// Wide mode: the order in which the running tasks (running_[i] is task i) get their chain of
+// `round`.  Queue order, except for the triangular solve (one k-step per round): there the tasks
+// solved in this round come first (everyone else's step needs their results), the tasks that
+// take their last update in this round -- the launch that also needs the task's own tile of B
+// from the host -- come last, and the tasks in between need one tile of A per block row.  The
+// copies are prefetched in the same order, so the first update launches of a round wait for a
+// handful of tiles instead of a whole block row of B (which is first used a round later).
+const std::vector<uint32_t>& Scheduler::round_order(size_t round) {
+    const size_t key = p_->results_are_operands ? round : 0;
+    int q = 0;                           // an unused entry, else the earliest round
+    for (int i = 0; i < kOrders; ++i) {
+        if (order_round_[i] == key) return order_[i];
+        if (order_round_[q] != SIZE_MAX && (order_round_[i] == SIZE_MAX || order_round_[i] < order_round_[q])) q = i;
+    }
+    std::vector<uint32_t>& o = order_[q];
+    o.clear();
+    const size_t n = p_->tasks.size();
+    if (!p_->results_are_operands) {
+        for (size_t i = 0; i < n; ++i) o.push_back((uint32_t)i);
+    } else {
+        auto cls = [&](size_t i) {
+            const size_t ns = p_->tasks[i].steps.size();
+            return ns == round ? 0 : ns > round + 1 ? 1 : ns == round + 1 ? 2 : 3;
+        };
+        for (int c = 0; c < 4; ++c)
+            for (size_t i = 0; i < n; ++i)
+                if (cls(i) == c) o.push_back((uint32_t)i);
+    }
+    order_round_[q] = key;
+    return o;
+}
+
 void Scheduler::prefetch_ahead(size_t build_pos) {
     const size_t ntasks = p_->tasks.size();
     const size_t target = build_pos + (size_t)cfg_.prefetch * kMaxStepsPerLaunch;
     if (pf_pos_ <= build_pos) pf_pos_ = build_pos + 1;
     while (pf_pos_ <= target) {
-        const size_t round = pf_pos_ / ntasks, ri = pf_pos_ % ntasks;
-        if (round > pf_last_round_ || ri >= running_.size()) break;       // nothing left in any task
+        const size_t round = pf_pos_ / ntasks;
+        if (round > pf_last_round_) break;                                // nothing left in any task
+        const size_t ri = round_order(round)[pf_pos_ % ntasks];
+        if (ri >= running_.size()) break;
         Running& r = running_[ri];
         if (r.task < 0 || r.done) {
             ++pf_pos_;
@@ -513,8 +547,10 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
     const size_t c_target = build_pos + ntasks;
     if (pfc_pos_ <= build_pos) pfc_pos_ = build_pos + 1;
     while (pfc_pos_ <= c_target) {
-        const size_t round = pfc_pos_ / ntasks, ri = pfc_pos_ % ntasks;
-        if (round > pf_last_round_ || ri >= running_.size()) break;
+        const size_t round = pfc_pos_ / ntasks;
+        if (round > pf_last_round_) break;
+        const size_t ri = round_order(round)[pfc_pos_ % ntasks];
+        if (ri >= running_.size()) break;
         Running& r = running_[ri];
         if (r.task >= 0 && !r.done && r.h_slot < 0) {
             const Task& t = p_->tasks[r.task];
@@ -545,8 +581,10 @@ bool Scheduler::wide_fits(const Problem& p) {
     // one launch per task leaves nothing to pipeline, and with barely more than one round the
     // grouped schedule (whose tasks finish one after the other) measures better
     // (the triangular solve, one k-tile per round, pays from two thirds of that: measured equal at
-    // 8 x 8 tiles, +16 % at 10 x 10)
-    const size_t least = p.results_are_operands ? ((size_t)cfg_.wide * 2 + 2) / 3 : (size_t)cfg_.wide * (size_t)p.steps_per_k;
+    // 8 x 8 tiles, +16 % at 10 x 10; so does the triangular product, whose tasks the wide schedule
+    // sorts by length: +10 % at 10 x 10)
+    const bool triangular = p.results_are_operands || !p.panels.empty();
+    const size_t least = triangular ? ((size_t)cfg_.wide * 2 + 2) / 3 : (size_t)cfg_.wide * (size_t)p.steps_per_k;
     if (max_steps <= (size_t)kchain_ || max_steps < least) return false;
     const size_t rounds = (max_steps + kchain_ - 1) / kchain_;
     const size_t per_round = (uniq.size() + rounds - 1) / rounds;
@@ -667,7 +705,7 @@ int Scheduler::build_chain(int ri) {
         op.finishing.push_back(ri);
         task_final_pack_[r.task] = op.id;
     }
-    if (wide_) prefetch_ahead(round_ * p_->tasks.size() + (size_t)ri);
+    if (wide_) prefetch_ahead(build_pos_);
     return 0;
 }
 
@@ -926,6 +964,7 @@ int Scheduler::run(Problem& p) {
         std::stable_sort(p.tasks.begin(), p.tasks.end(),
                          [](const Task& a, const Task& b) { return a.steps.size() < b.steps.size(); });
     round_ = 0;
+    for (size_t& key : order_round_) key = SIZE_MAX;
     pf_pos_ = pfc_pos_ = 0;
     pf_last_round_ = 0;
     if (wide_) {
@@ -975,11 +1014,23 @@ int Scheduler::run(Problem& p) {
         }
         // one round: the next chain of every running task (step k of all tasks before k+1)
         bool progressed = false;
-        for (size_t ri = 0; ri < running_.size() && !rc; ++ri) {
-            if (running_[ri].done) continue;
-            const int brc = build_chain((int)ri);
-            if (brc == 0) progressed = true;
-            else if (brc != 1) rc = brc;
+        if (wide_) {
+            const std::vector<uint32_t> order = round_order(round_);     // a copy: prefetching asks for other rounds
+            for (size_t pos = 0; pos < order.size() && !rc; ++pos) {
+                const size_t ri = order[pos];
+                if (ri >= running_.size() || running_[ri].done) continue;
+                build_pos_ = round_ * ntasks + pos;
+                const int brc = build_chain((int)ri);
+                if (brc == 0) progressed = true;
+                else if (brc != 1) rc = brc;
+            }
+        } else {
+            for (size_t ri = 0; ri < running_.size() && !rc; ++ri) {
+                if (running_[ri].done) continue;
+                const int brc = build_chain((int)ri);
+                if (brc == 0) progressed = true;
+                else if (brc != 1) rc = brc;
+            }
         }
         if (rc) break;
         rc = flush_all();

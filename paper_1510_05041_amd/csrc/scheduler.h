@@ -23,6 +23,7 @@
 //     are issued by a cursor that runs ahead of the launch being built.  The triangular solve
 //     runs the same way one k-tile per round (right-looking).
 #pragma once
+#include <cstdint>
 #include <stdint.h>
 
 #include <cstring>
@@ -127,6 +128,7 @@ private:
     int  start_task(int task_index, Running* r);
     int  ensure_panel(int panel);
     int  build_chain(int ri);
+    const std::vector<uint32_t>& round_order(size_t round);
     int  prefetch_c(Running& r, const Task& t, bool may_wait);
     void prefetch_ahead(size_t build_pos);
     bool wide_fits(const Problem& p);
@@ -162,6 +164,10 @@ private:
     size_t pf_last_round_ = 0;          // wide mode: last round in which any task still has steps
     size_t pfc_pos_ = 0;                // wide mode: same for the host C tiles, which run further ahead
     size_t pf_reserve_ = 0;             // free slots that early C tiles must leave for operand tiles
+    size_t build_pos_ = 0;              // wide mode: (round * ntasks + position in the round's order) of the chain being built
+    static constexpr int kOrders = 4;   // the round being built and those the two prefetch cursors are in
+    std::vector<uint32_t> order_[kOrders];   // wide mode: round_order() of the latest rounds asked for
+    size_t order_round_[kOrders] = {SIZE_MAX, SIZE_MAX, SIZE_MAX, SIZE_MAX};
     size_t pf_pos_ = 0;                 // wide mode: next (round * ntasks + task) whose tiles get prefetched
 
     std::vector<int> fill_ev_;          // per slot: event of its latest inbound copy

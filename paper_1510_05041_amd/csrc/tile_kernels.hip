@@ -460,6 +460,53 @@ __device__ __forceinline__ void compute_stage(typename Mfma<T>::acc_t (&acc)[4][
     }
 }
 
+// The k range [kb, ke) of a chained pair in which the macro-tile at (i_base, j_base) can meet the
+// stored triangle of the pair's triangular operand; outside it every product is zero, so those
+// slabs are neither copied nor multiplied (half the work of a diagonal tile on average).  Macro-
+// tile origins and extents are multiples of two slabs, so the range is a whole number of slab
+// pairs.  Element (r, c) of the stored tile is inside a lower triangle when r >= c.
+template <bool TA, bool TB>
+__device__ __forceinline__ void masked_k_range(uint32_t sflags, int k, int i_base, int j_base, int& kb, int& ke) {
+    kb = 0;
+    ke = k;
+    const bool lower = sflags & TS_TRI_LOWER;
+    if (sflags & TS_TRI_A) {
+        // op(A)(i, kk) is stored at (kk, i) when transposed, else at (i, kk)
+        if (lower != TA) ke = min(ke, i_base + BM);      // needs kk <= i
+        else kb = max(kb, i_base);                       // needs kk >= i
+    }
+    if (sflags & TS_TRI_B) {
+        // op(B)(kk, j) is stored at (j, kk) when transposed, else at (kk, j)
+        if (lower != TB) kb = max(kb, j_base);           // needs kk >= j
+        else ke = min(ke, j_base + BN);                  // needs kk <= j
+    }
+    if (ke < kb) ke = kb;
+}
+
+// Whether the slab k0 .. k0 + slab_k - 1 of a masked pair lies wholly inside the stored triangle
+// (diagonal excluded) for every row and column of the macro-tile: such a slab needs no masking.
+template <bool TA, bool TB>
+__device__ __forceinline__ bool slab_inside_triangle(uint32_t sflags, int k0, int slab_k, int i_base, int j_base) {
+    const bool lower = sflags & TS_TRI_LOWER;
+    bool inside = true;
+    if (sflags & TS_TRI_A) inside = inside && ((lower != TA) ? k0 + slab_k <= i_base : k0 >= i_base + BM);
+    if (sflags & TS_TRI_B) inside = inside && ((lower != TB) ? k0 >= j_base + BN : k0 + slab_k <= j_base);
+    return inside;
+}
+
+// Whether the work of a step's macro-tiles grows with the tile index (the triangle cuts the k
+// range from above): such a step hands out its macro-tiles last to first, longest first.
+template <bool TA, bool TB>
+__device__ __forceinline__ bool work_grows_with_index(const TileStep& st) {
+    for (int q = 0; q < st.nseg; ++q) {
+        const uint32_t f = st.seg[q].flags;
+        const bool lower = f & TS_TRI_LOWER;
+        if (f & TS_TRI_A) return lower != TA;
+        if (f & TS_TRI_B) return lower == TB;
+    }
+    return false;
+}
+
 // MASK: the pack holds steps with triangular operands (separate kernel instantiation, so that
 // the plain one carries no trace of the masking code).
 template <typename T, bool TA, bool TB, bool MASK>
@@ -487,47 +534,70 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     const size_t step_a = TA ? (size_t)S::SLAB_K : (size_t)S::SLAB_K * lda;
     const size_t step_b = !TB ? (size_t)S::SLAB_K : (size_t)S::SLAB_K * ldb;
 
-    int pseg = 0, pslab = 0;
-    int pk = nseg > 0 ? st.seg[0].k : 0;
+    // Copy cursor: slab `pslab` of the k range [pkb, pke) of pair `pseg` is the next one to fetch.
+    int pseg = -1, pslab = 0, pkb = 0, pke = 0;
     const T* pa = nullptr;
     const T* pb = nullptr;
-    if (nseg > 0) {
-        pa = dma_origin<T, TA>(static_cast<const T*>(st.seg[0].A), lda, i_base, wave, lane);
-        pb = dma_origin<T, !TB>(static_cast<const T*>(st.seg[0].B), ldb, j_base, wave, lane);
-        dma_slab<T, TA>(pa, lda, sA0, wave);
-        dma_slab<T, !TB>(pb, ldb, sB0, wave);
-    }
+    // first slab of the next pair that has any (a masked pair may have none for this macro-tile)
+    auto next_pair = [&]() -> bool {
+        if constexpr (MASK) {
+            for (++pseg; pseg < nseg; ++pseg) {
+                masked_k_range<TA, TB>(st.seg[pseg].flags, st.seg[pseg].k, i_base, j_base, pkb, pke);
+                if (pke > pkb) break;
+            }
+            if (pseg >= nseg) return false;
+            pa = dma_origin<T, TA>(static_cast<const T*>(st.seg[pseg].A), lda, i_base, wave, lane) + (size_t)(pkb / S::SLAB_K) * step_a;
+            pb = dma_origin<T, !TB>(static_cast<const T*>(st.seg[pseg].B), ldb, j_base, wave, lane) + (size_t)(pkb / S::SLAB_K) * step_b;
+        } else {
+            if (++pseg >= nseg) return false;
+            pke = st.seg[pseg].k;
+            pa = dma_origin<T, TA>(static_cast<const T*>(st.seg[pseg].A), lda, i_base, wave, lane);
+            pb = dma_origin<T, !TB>(static_cast<const T*>(st.seg[pseg].B), ldb, j_base, wave, lane);
+        }
+        pslab = 0;
+        return true;
+    };
     // advance the copy cursor to the next slab of the chain; false when the chain is exhausted
     auto advance = [&]() -> bool {
         ++pslab;
-        if (pslab * S::SLAB_K >= pk) {
-            ++pseg;
-            pslab = 0;
-            if (pseg >= nseg) return false;
-            pk = st.seg[pseg].k;
-            pa = dma_origin<T, TA>(static_cast<const T*>(st.seg[pseg].A), lda, i_base, wave, lane);
-            pb = dma_origin<T, !TB>(static_cast<const T*>(st.seg[pseg].B), ldb, j_base, wave, lane);
-        } else {
-            pa += step_a;
-            pb += step_b;
-        }
+        if ((MASK ? pkb : 0) + pslab * S::SLAB_K >= pke) return next_pair();
+        pa += step_a;
+        pb += step_b;
         return true;
     };
     int total = 0;
-    for (int q = 0; q < nseg; ++q) total += st.seg[q].k / S::SLAB_K;
-    // Compute cursor: the slab now being multiplied (one behind the copy cursor).
-    int cseg = 0, cslab = 0;
-    int ck = pk;
-    uint32_t cflags = nseg > 0 ? st.seg[0].flags : 0;
+    for (int q = 0; q < nseg; ++q) {
+        int kb = 0, ke = st.seg[q].k;
+        if (MASK) masked_k_range<TA, TB>(st.seg[q].flags, st.seg[q].k, i_base, j_base, kb, ke);
+        total += (ke - kb) / S::SLAB_K;
+    }
+    if (next_pair()) {
+        dma_slab<T, TA>(pa, lda, sA0, wave);
+        dma_slab<T, !TB>(pb, ldb, sB0, wave);
+    }
+    // Compute cursor: the slab now being multiplied (one behind the copy cursor); only the masks
+    // need to know where in its pair a slab lies.
+    int cseg = pseg, cslab = 0, ckb = pkb, cke = pke;
+    uint32_t cflags = MASK && cseg < nseg ? st.seg[cseg].flags : 0;
     auto multiply = [&](const T* sa, const T* sb) {
-        compute_stage<T, TA, TB, MASK>(acc, sa, sb, wm, wn, g, r16, cflags, cslab * S::SLAB_K, i_base, j_base);
+        if constexpr (!MASK) {
+            compute_stage<T, TA, TB, false>(acc, sa, sb, wm, wn, g, r16, 0u, 0, i_base, j_base);
+            return;
+        }
+        const int k0 = ckb + cslab * S::SLAB_K;
+        const uint32_t mflags = slab_inside_triangle<TA, TB>(cflags, k0, S::SLAB_K, i_base, j_base) ? 0u : cflags;
+        compute_stage<T, TA, TB, MASK>(acc, sa, sb, wm, wn, g, r16, mflags, k0, i_base, j_base);
         if (MASK) {
             ++cslab;
-            if (cslab * S::SLAB_K >= ck && cseg + 1 < nseg) {
-                ++cseg;
+            if (ckb + cslab * S::SLAB_K >= cke) {
+                for (++cseg; cseg < nseg; ++cseg) {
+                    ckb = 0;
+                    cke = st.seg[cseg].k;
+                    masked_k_range<TA, TB>(st.seg[cseg].flags, st.seg[cseg].k, i_base, j_base, ckb, cke);
+                    if (cke > ckb) break;
+                }
                 cslab = 0;
-                ck = st.seg[cseg].k;
-                cflags = st.seg[cseg].flags;
+                cflags = cseg < nseg ? st.seg[cseg].flags : 0;
             }
         }
     };
@@ -609,8 +679,10 @@ void tile_steps_kernel(const LaunchPack pack) {
     while (s + 1 < pack.nsteps && pack.step[s + 1].wg_begin <= v) ++s;
     const TileStep& st = pack.step[s];
 
-    const uint32_t local = v - st.wg_begin;
+    uint32_t local = v - st.wg_begin;
     const uint32_t tiles_m = (uint32_t)(st.m + BM - 1) / BM;
+    if (MODE == MODE_FAST_MASKED && work_grows_with_index<TA, TB>(st))
+        local = tiles_m * ((uint32_t)(st.n + BN - 1) / BN) - 1 - local;
     const int i_base = (int)(local % tiles_m) * BM;
     const int j_base = (int)(local / tiles_m) * BN;
     if (MODE == MODE_GENERAL)

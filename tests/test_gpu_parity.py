@@ -296,6 +296,48 @@ def test_dtrsm_small_full_compare_and_residual(lib, side, uplo, trans, diag):
     assert np.linalg.norm(R - 0.7 * B0) / (norm_a * np.linalg.norm(X)) < TOL64
 
 
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS)
+def test_dtrmm_dtrsm_tiles_of_several_macro_tiles(lib, side, uplo, trans, diag):
+    """Tile-aligned 1024 x 1024 with T = 512: a triangular tile spans 4 x 4 macro-tiles, so the kernel
+    that masks triangular operands skips the slabs outside the triangle (a different k range per
+    macro-tile), masks only the slabs that cross the diagonal, and hands its macro-tiles out longest
+    first.  NaN outside the stored triangle must never be read."""
+    M = N = 1024
+    configure(lib, T=512, arena_gb=0.25, group=4)
+    A, ka = triangular(M, 41, uplo, diag)
+    B, kb = pinned(M, N, 41, 1)
+    B0 = np.array(B, order="F")
+    want = np.array(B, order="F")
+    lib.dtrmm(blasx.ColMajor, side, uplo, trans, diag, M, N, 0.8, A, M, B, M)
+    ref.trmm(ref.ColMajor, side, uplo, trans, diag, 0.8, np.asarray(A), want)
+    assert np.all(np.isfinite(np.asarray(B)))
+    assert relerr(B, want) < TOL64
+    B[...] = B0
+    lib.dtrsm(blasx.ColMajor, side, uplo, trans, diag, M, N, 0.8, A, M, B, M)
+    X = np.array(B, order="F")
+    assert np.all(np.isfinite(X))
+    R = X.copy(order="F")
+    ref.trmm(ref.ColMajor, side, uplo, trans, diag, 1.0, np.asarray(A), R)
+    norm_a = np.linalg.norm(np.nan_to_num(np.asarray(A))) + (np.sqrt(M) if diag == blasx.Unit else 0.0)
+    assert np.linalg.norm(R - 0.8 * B0) / (norm_a * np.linalg.norm(X)) < TOL64
+
+
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS[::5])
+def test_strmm_tiles_of_several_macro_tiles(lib, side, uplo, trans, diag):
+    """Same in single precision (slabs are 32 deep there)."""
+    M = N = 1024
+    configure(lib, T=512, arena_gb=0.25, group=4)
+    A64, ka = triangular(M, 42, uplo, diag)
+    A, k32 = blasx.pinned_matrix(M, M, dtype=np.float32)
+    A[...] = np.asarray(A64).astype(np.float32)
+    B, kb = pinned(M, N, 42, 1, dtype=np.float32)
+    want = np.array(B, order="F")
+    lib.strmm(blasx.ColMajor, side, uplo, trans, diag, M, N, 1.2, A, M, B, M)
+    ref.trmm(ref.ColMajor, side, uplo, trans, diag, 1.2, np.asarray(A), want)
+    assert np.all(np.isfinite(np.asarray(B)))
+    assert relerr(B, want) < TOL32
+
+
 # ------------------------------------------------------------------ benchmark sizes, sampled --
 
 def sampled_positions(T, rows, cols, rng, count=8):
