@@ -396,7 +396,6 @@ int blasx_set_option(const char* name, long value) {
     else if (n == "shells") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.order.shells = (int)value; }
     else if (n == "wide") { if (value < 0 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.wide = (int)value; }
     else if (n == "prefetch") { if (value < 0 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.prefetch = (int)value; }
-    else if (n == "wide") { if (value < 0 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.wide = (int)value; }
     else if (n == "profile") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.profile = value != 0; }
     else if (n == "persist") {
         if (value < 0 || value > 1) return BLASX_ERR_CONFIG;

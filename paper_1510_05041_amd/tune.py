@@ -76,7 +76,7 @@ def _problem(lib, routine, n, k):
     raise ValueError(routine)
 
 
-def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=12):
+def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=12, kchain=0):
     lib = blasx.default()
     results = []
     for n in sizes:
@@ -88,7 +88,7 @@ def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None
                     lib.init(int(arena_gb * 2 ** 30), nstreams=ns)
                     lib.set_tile(T)
                     lib.set_cache_bytes(0)
-                    for name, v in dict(group=g, rs=max(32, 2 * g), kchain=0, depth=6, sb_rows=4, sb_cols=4, shells=1,
+                    for name, v in dict(group=g, rs=max(32, 2 * g), kchain=kchain, depth=6, sb_rows=4, sb_cols=4, shells=1,
                                         profile=0, persist=0, wide=wide).items():
                         lib.set_option(name, v)
                     times = []
@@ -144,12 +144,13 @@ def main(argv=None):
     ap.add_argument("--reps", type=int, default=3)
     ap.add_argument("--arena-gb", type=float, default=24.0)
     ap.add_argument("--wide", type=int, default=12, help="option \"wide\": least k-steps per task for which all tasks advance together; 0: never")
+    ap.add_argument("--kchain", type=int, default=0, help="option \"kchain\": k-tiles per launch and task; 0: the library's choice")
     ap.add_argument("--out", default="", help="also append the JSON records to this file")
     a = ap.parse_args(argv)
     ints = lambda s: [int(x) for x in s.split(",") if x]
     sizes, tiles, streams, groups = ints(a.sizes), ints(a.tiles), ints(a.streams), ints(a.groups)
     out = open(a.out, "a") if a.out else None
-    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out, a.wide)
+    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out, a.wide, a.kchain)
     print()
     print(tables(res, tiles, streams))
 
