@@ -143,9 +143,11 @@ int blasx_set_cache_bytes(size_t cap);
  *              copied from the first launch on, C tiles fetched only for a task's last launch,
  *              results leaving during the whole last round), provided the cache has room for
  *              an accumulator tile per output tile; 0: never (tasks run to completion in
- *              groups, the paper's scheme).  Default 12.  TRSM uses it from two thirds of the
- *              value, one k-tile per round (a right-looking solve); TRMM pins every original
- *              tile of B at once and copies each in when it is first needed.
+ *              groups, the paper's scheme).  Default 12.  TRSM uses it from a third of the
+ *              value, one k-tile per round (a right-looking solve, every diagonal tile
+ *              inverted before the first round); TRMM from two thirds of the value: it pins
+ *              every original tile of B at once, copies each in when it is first needed, and
+ *              runs its tasks shortest first.
  *   "prefetch" wide schedule: inbound copies are started this many launches ahead (default 24)
  *   "depth"    launches the host may run ahead of the device (>= 1)
  *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)

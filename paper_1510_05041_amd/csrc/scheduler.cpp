@@ -465,12 +465,20 @@ int Scheduler::prefetch_c(Running& r, const Task& t, bool may_wait) {
     return 0;
 }
 
-// Wide mode: start the inbound copies of the launches that will be built next, in the order in
-// which they will be needed (round by round, task by task), up to `prefetch` launches ahead.  The
-// host may only run `depth` launches ahead of the device, which is a few milliseconds of copies;
-// the copy queue has to be fed further ahead than that or the link idles at every round boundary,
-// where a whole new panel of B is needed at once.  Only a hint: build_chain() fetches whatever is
-// still missing.
+// Wide mode, a task whose first launch is its last: the host C tile goes straight into the
+// task's own slot (nothing has been accumulated there yet).
+int Scheduler::load_c_direct(Running& r, const Task& t) {
+    if (r.c_direct) return 0;
+    TileRef c;
+    c.host = t.c_host;
+    c.ld = p_->ldc;
+    c.rows = t.m;
+    c.cols = t.n;
+    BX_TRY(issue_h2d(c, r.c_slot));
+    r.c_direct = true;
+    return 0;
+}
+
 // Wide mode: the order in which the running tasks (running_[i] is task i) get their chain of
 // `round`.  Queue order, except for the triangular solve (one k-step per round): there the tasks
 // solved in this round come first (everyone else's step needs their results), the tasks that
@@ -503,6 +511,12 @@ const std::vector<uint32_t>& Scheduler::round_order(size_t round) {
     return o;
 }
 
+// Wide mode: start the inbound copies of the launches that will be built next, in the order in
+// which they will be needed (round by round, in each round's order), up to `prefetch` launches
+// ahead.  The host may only run `depth` launches ahead of the device, which is a few milliseconds
+// of copies; the copy queue has to be fed further ahead than that or the link idles at every round
+// boundary, where a whole new panel of B is needed at once.  Only a hint: build_chain() fetches
+// whatever is still missing.
 void Scheduler::prefetch_ahead(size_t build_pos) {
     const size_t ntasks = p_->tasks.size();
     const size_t target = build_pos + (size_t)cfg_.prefetch * kMaxStepsPerLaunch;
@@ -535,8 +549,12 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
             }
         }
         if (stalled) break;
-        if (s0 < nsteps && s1 >= nsteps && s0 > 0 && t.load_c) {
-            if (prefetch_c(r, t, false) != 0 || r.h_slot < 0) break;
+        if (s0 < nsteps && s1 >= nsteps && t.load_c) {
+            if (s0 == 0) {
+                if (r.first && load_c_direct(r, t) != 0) break;
+            } else if (prefetch_c(r, t, false) != 0 || r.h_slot < 0) {
+                break;
+            }
         }
         ++pf_pos_;
     }
@@ -565,6 +583,15 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
     }
 }
 
+// One task per distinct diagonal tile that the solve tasks of a problem invert, in queue order.
+std::vector<const Task*> Scheduler::diag_tasks(const Problem& p) const {
+    std::vector<const Task*> out;
+    std::unordered_set<TileKey, TileKeyHash> seen;
+    for (const Task& t : p.tasks)
+        if (t.solve && seen.insert(key_of(t.diag, 1 + (int)((t.diag_flags >> 4) & 3u))).second) out.push_back(&t);
+    return out;
+}
+
 // Wide mode needs an accumulator slot per task plus the operand tiles of two rounds (the round
 // being computed and the one being copied in) plus some slots for late C tiles.
 bool Scheduler::wide_fits(const Problem& p) {
@@ -580,11 +607,12 @@ bool Scheduler::wide_fits(const Problem& p) {
     }
     // one launch per task leaves nothing to pipeline, and with barely more than one round the
     // grouped schedule (whose tasks finish one after the other) measures better
-    // (the triangular solve, one k-tile per round, pays from two thirds of that: measured equal at
-    // 8 x 8 tiles, +16 % at 10 x 10; so does the triangular product, whose tasks the wide schedule
-    // sorts by length: +10 % at 10 x 10)
-    const bool triangular = p.results_are_operands || !p.panels.empty();
-    const size_t least = triangular ? ((size_t)cfg_.wide * 2 + 2) / 3 : (size_t)cfg_.wide * (size_t)p.steps_per_k;
+    // (the triangular product, whose tasks the wide schedule sorts by length, pays from two thirds
+    // of that: +10 % at 10 x 10 tiles; the triangular solve, one k-tile per round with its
+    // inverses made up front, from a third: 5 x 5 tiles +10 %, 8 x 8 tiles +40 %)
+    const size_t least = p.results_are_operands ? ((size_t)cfg_.wide + 2) / 3
+                         : !p.panels.empty()    ? ((size_t)cfg_.wide * 2 + 2) / 3
+                                                : (size_t)cfg_.wide * (size_t)p.steps_per_k;
     if (max_steps <= (size_t)kchain_ || max_steps < least) return false;
     const size_t rounds = (max_steps + kchain_ - 1) / kchain_;
     const size_t per_round = (uniq.size() + rounds - 1) / rounds;
@@ -592,6 +620,8 @@ bool Scheduler::wide_fits(const Problem& p) {
     pf_reserve_ = per_round + kMaxStepsPerLaunch;
     size_t pinned = 0;      // TRMM: the original tiles of the matrix updated in place stay for the whole call
     for (const Panel& pn : p.panels) pinned += pn.tiles.size();
+    // TRSM: diagonal tile, inverse and a scratch tile per block row while the inverses are made up front
+    if (p.results_are_operands) pinned += 3 * diag_tasks(p).size();
     return (size_t)cache_.nslots() >= p.tasks.size() + pinned + 2 * per_round + late_c + kMaxStepsPerLaunch;
 }
 
@@ -662,13 +692,7 @@ int Scheduler::build_chain(int ri) {
             st.beta = r.first ? 0.0 : 1.0;
         } else if (t.load_c) {
             if (r.first) {
-                // single launch: the tile goes straight into the accumulator slot
-                TileRef c;
-                c.host = t.c_host;
-                c.ld = p_->ldc;
-                c.rows = t.m;
-                c.cols = t.n;
-                BX_TRY(issue_h2d(c, r.c_slot));
+                BX_TRY(load_c_direct(r, t));      // single launch: the tile goes straight into the accumulator slot
             } else {
                 BX_TRY(prefetch_c(r, t, true));
                 acc_slot = r.c_slot;
@@ -716,103 +740,132 @@ int Scheduler::build_chain(int ri) {
 int Scheduler::get_inverse(const Task& t, Block** out) {
     const int tag = 1 + (int)((t.diag_flags >> 4) & 3u);
     const TileKey key = key_of(t.diag, tag);
-    if (cache_.find(key)) {
-        bool hit;
-        *out = cache_.translate(key, &hit);
+    if (!cache_.find(key)) {
+        const Task* one = &t;
+        BX_TRY(make_inverses(&one, 1));
+    }
+    bool hit;
+    *out = cache_.translate(key, &hit);
+    return *out ? 0 : BLASX_ERR_ARENA_TOO_SMALL;
+}
+
+// Inverts the diagonal tiles of `count` tasks (those not cached yet) together: one base-block
+// launch per tile, then every merge level as one set of launches for all the tiles.  A level of
+// one 1024 x 1024 tile is a few small products, far too few to fill the device, and the ten
+// levels of a tile run one after the other; the levels of many tiles fill it better and cost
+// little more than those of one.
+int Scheduler::make_inverses(const Task* const* tasks, size_t count) {
+    struct Job {
+        Block *src, *inv;
+        int tmp, n;
+        uint32_t flags;
+    };
+    std::vector<Job> jobs;
+    auto wait_for_room = [&]() -> int {
+        BX_TRY(flush_all());
+        if (!inflight_.empty()) retire(true);
+        else if (!writebacks_.empty()) poll_writebacks(true);
+        else return BLASX_ERR_ARENA_TOO_SMALL;
         return 0;
-    }
-    const int n = t.diag.rows;
-    const bool lower = (t.diag_flags & TS_TRI_LOWER) != 0;
-    Block *src = nullptr, *inv = nullptr;
-    for (;;) {
-        int rc = fetch(t.diag, &src);
-        if (rc == 0) break;
-        if (rc > 0) return rc;
-        BX_TRY(flush_all());
-        if (!inflight_.empty()) retire(true);
-        else if (!writebacks_.empty()) poll_writebacks(true);
-        else return BLASX_ERR_ARENA_TOO_SMALL;
-    }
-    cache_.acquire(src);
-    for (;;) {
-        bool hit;
-        inv = cache_.translate(key, &hit);
-        if (inv) break;
-        BX_TRY(flush_all());
-        if (!inflight_.empty()) retire(true);
-        else if (!writebacks_.empty()) poll_writebacks(true);
-        else return BLASX_ERR_ARENA_TOO_SMALL;
-    }
-    cache_.acquire(inv);
-    int tmp = -1;
-    BX_TRY(take_slot_blocking(&tmp));
-    BX_TRY(flush_all());
-    // the source tile's inbound copy must have landed, and so must any stale copy still
-    // queued into the two slots that are about to be written
-    for (int slot : {src->slot, inv->slot, tmp}) {
-        if (fill_seq_[slot] > compute_waited_[fill_stream_[slot]]) {
-            if (be_.stream_wait_event(STREAM_COMPUTE, fill_event(slot))) return BLASX_ERR_DEVICE;
-            compute_waited_[fill_stream_[slot]] = fill_seq_[slot];
+    };
+    for (size_t q = 0; q < count; ++q) {
+        const Task& t = *tasks[q];
+        const int tag = 1 + (int)((t.diag_flags >> 4) & 3u);
+        const TileKey key = key_of(t.diag, tag);
+        if (cache_.find(key)) continue;
+        Job job{nullptr, nullptr, -1, (int)t.diag.rows, t.diag_flags};
+        for (;;) {
+            const int rc = fetch(t.diag, &job.src);
+            if (rc == 0) break;
+            if (rc > 0) return rc;
+            BX_TRY(wait_for_room());
         }
+        cache_.acquire(job.src);
+        for (;;) {
+            bool hit;
+            job.inv = cache_.translate(key, &hit);
+            if (job.inv) break;
+            BX_TRY(wait_for_room());
+        }
+        cache_.acquire(job.inv);
+        BX_TRY(take_slot_blocking(&job.tmp));
+        jobs.push_back(job);
     }
-    if (be_.launch_trtri_blocks(p_->dtype, slot_ptr(src->slot), T_, slot_ptr(inv->slot), T_, n, kTrtriBlock, t.diag_flags,
-                                STREAM_COMPUTE))
-        return BLASX_ERR_DEVICE;
+    if (jobs.empty()) return 0;
+    BX_TRY(flush_all());
     const size_t es = p_->esize;
     auto at = [&](int slot, int r, int c) { return slot_ptr(slot) + ((size_t)r + (size_t)c * T_) * es; };
-    for (int s = kTrtriBlock; s < n; s *= 2) {
+    int max_n = 0;
+    for (const Job& job : jobs) {
+        // the source tile's inbound copy must have landed, and so must any stale copy still
+        // queued into the two slots that are about to be written
+        for (int slot : {job.src->slot, job.inv->slot, job.tmp}) {
+            if (fill_seq_[slot] > compute_waited_[fill_stream_[slot]]) {
+                if (be_.stream_wait_event(STREAM_COMPUTE, fill_event(slot))) return BLASX_ERR_DEVICE;
+                compute_waited_[fill_stream_[slot]] = fill_seq_[slot];
+            }
+        }
+        if (be_.launch_trtri_blocks(p_->dtype, slot_ptr(job.src->slot), T_, slot_ptr(job.inv->slot), T_, job.n, kTrtriBlock,
+                                    job.flags, STREAM_COMPUTE))
+            return BLASX_ERR_DEVICE;
+        max_n = std::max(max_n, job.n);
+    }
+    for (int s = kTrtriBlock; s < max_n; s *= 2) {
         for (int phase = 0; phase < 2; ++phase) {
-            for (int o = 0; o + s < n; o += 2 * s) {
-                const int s2 = std::min(s, n - (o + s));   // order of the second block of the pair
-                TileStep st;
-                std::memset(&st, 0, sizeof(st));
-                st.nseg = 1;
-                st.lda = st.ldb = st.ldc = T_;
-                if (lower) {
-                    st.m = s2;
-                    st.n = s;
-                    if (phase == 0) {       // tmp = L21 * inv11
-                        st.C = at(tmp, o + s, o);
-                        st.seg[0] = TileSeg{at(src->slot, o + s, o), at(inv->slot, o, o), s, TS_TRI_B | TS_TRI_LOWER};
-                        st.alpha = 1.0;
-                    } else {                // inv21 = -inv22 * tmp
-                        st.C = at(inv->slot, o + s, o);
-                        st.seg[0] = TileSeg{at(inv->slot, o + s, o + s), at(tmp, o + s, o), s2, TS_TRI_A | TS_TRI_LOWER};
-                        st.alpha = -1.0;
+            for (const Job& job : jobs) {
+                const int n = job.n, src = job.src->slot, inv = job.inv->slot, tmp = job.tmp;
+                const bool lower = (job.flags & TS_TRI_LOWER) != 0;
+                for (int o = 0; o + s < n; o += 2 * s) {
+                    const int s2 = std::min(s, n - (o + s));   // order of the second block of the pair
+                    TileStep st;
+                    std::memset(&st, 0, sizeof(st));
+                    st.nseg = 1;
+                    st.lda = st.ldb = st.ldc = T_;
+                    if (lower) {
+                        st.m = s2;
+                        st.n = s;
+                        if (phase == 0) {       // tmp = L21 * inv11
+                            st.C = at(tmp, o + s, o);
+                            st.seg[0] = TileSeg{at(src, o + s, o), at(inv, o, o), s, TS_TRI_B | TS_TRI_LOWER};
+                            st.alpha = 1.0;
+                        } else {                // inv21 = -inv22 * tmp
+                            st.C = at(inv, o + s, o);
+                            st.seg[0] = TileSeg{at(inv, o + s, o + s), at(tmp, o + s, o), s2, TS_TRI_A | TS_TRI_LOWER};
+                            st.alpha = -1.0;
+                        }
+                    } else {
+                        st.m = s;
+                        st.n = s2;
+                        if (phase == 0) {       // tmp = U12 * inv22
+                            st.C = at(tmp, o, o + s);
+                            st.seg[0] = TileSeg{at(src, o, o + s), at(inv, o + s, o + s), s2, TS_TRI_B};
+                            st.alpha = 1.0;
+                        } else {                // inv12 = -inv11 * tmp
+                            st.C = at(inv, o, o + s);
+                            st.seg[0] = TileSeg{at(inv, o, o), at(tmp, o, o + s), s, TS_TRI_A};
+                            st.alpha = -1.0;
+                        }
                     }
-                } else {
-                    st.m = s;
-                    st.n = s2;
-                    if (phase == 0) {       // tmp = U12 * inv22
-                        st.C = at(tmp, o, o + s);
-                        st.seg[0] = TileSeg{at(src->slot, o, o + s), at(inv->slot, o + s, o + s), s2, TS_TRI_B};
-                        st.alpha = 1.0;
-                    } else {                // inv12 = -inv11 * tmp
-                        st.C = at(inv->slot, o, o + s);
-                        st.seg[0] = TileSeg{at(inv->slot, o, o), at(tmp, o, o + s), s, TS_TRI_A};
-                        st.alpha = -1.0;
-                    }
+                    st.beta = 0.0;
+                    BX_TRY(add_step(pack_for(step_mode(st, p_->dtype), false, false), false, false, st, 1.0 * st.m * st.n * st.seg[0].k, 0));
                 }
-                st.beta = 0.0;
-                BX_TRY(add_step(pack_for(step_mode(st, p_->dtype), false, false), false, false, st, 1.0 * st.m * st.n * st.seg[0].k, 0));
             }
             BX_TRY(flush_all());
         }
     }
-    // src, inv and tmp stay reserved until the last merge has run: a marker record that
-    // retires after everything issued so far on the compute stream
-    {
-        InFlight f;
-        f.id = next_pack_id_++;
-        f.done_ev = new_event();
-        if (be_.event_record(f.done_ev, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
-        f.blocks.push_back(src);
-        f.blocks.push_back(inv);
-        f.free_slots.push_back(tmp);
-        flushed_pack_id_ = std::max(flushed_pack_id_, f.id);
-        inflight_.push_back(std::move(f));
+    // sources, inverses and scratch tiles stay reserved until the last merge has run: a marker
+    // record that retires after everything issued so far on the compute stream
+    InFlight f;
+    f.id = next_pack_id_++;
+    f.done_ev = new_event();
+    if (be_.event_record(f.done_ev, STREAM_COMPUTE)) return BLASX_ERR_DEVICE;
+    for (const Job& job : jobs) {
+        f.blocks.push_back(job.src);
+        f.blocks.push_back(job.inv);
+        f.free_slots.push_back(job.tmp);
     }
-    *out = inv;
+    flushed_pack_id_ = std::max(flushed_pack_id_, f.id);
+    inflight_.push_back(std::move(f));
     return 0;
 }
 
@@ -870,15 +923,7 @@ int Scheduler::build_solve(int ri) {
     Running& r = running_[ri];
     const Task& t = p_->tasks[r.task];
     if (r.last_pack > flushed_pack_id_) BX_TRY(flush_all());
-    if (wide_ && r.first) {
-        // no update step came before: the right-hand-side tile has not been fetched yet
-        TileRef c;
-        c.host = t.c_host;
-        c.ld = p_->ldc;
-        c.rows = t.m;
-        c.cols = t.n;
-        BX_TRY(issue_h2d(c, r.c_slot));
-    }
+    if (wide_ && r.first) BX_TRY(load_c_direct(r, t));   // no update step came before: the right-hand-side tile has not been fetched yet
     Block* inv = nullptr;
     BX_TRY(get_inverse(t, &inv));
     cache_.acquire(inv);
@@ -977,7 +1022,16 @@ int Scheduler::run(Problem& p) {
     cache_.forget_evictions();
     if (cache_.blocks()) invalidate_region(p.c_host, p.ldc, p.c_rows, p.c_cols, (int)p.esize);
 
-    for (;;) {
+    // Wide triangular solve: every diagonal tile is fetched and inverted before anything else.
+    // Made on demand, the inverse of block row k stands between rounds k - 1 and k: its diagonal
+    // tile would be requested behind all the copies already queued, and its ten merge levels keep
+    // the device nearly idle for half a millisecond per round.
+    if (wide_ && p.results_are_operands) {
+        const std::vector<const Task*> diag = diag_tasks(p);
+        rc = make_inverses(diag.data(), diag.size());
+    }
+
+    for (; rc == 0;) {
         retire(false);
         poll_writebacks(false);
         // keep `group` tasks running: top-priority tasks of the reservation station

@@ -81,6 +81,8 @@ private:
         int c_slot = -1;            // slot of the accumulator (of the result once the last launch is built)
         int h_slot = -1;            // wide mode: slot the host C tile is (being) copied into, or -1
         bool first = true;          // no launch issued yet (beta_first applies)
+        bool c_direct = false;      // wide mode: the host C tile is (being) copied straight into c_slot
+                                    // (tasks whose first launch is their last)
         bool solved = false;
         uint64_t last_pack = 0;     // id of the pack holding this task's latest chain
         bool done = false;
@@ -130,12 +132,15 @@ private:
     int  build_chain(int ri);
     const std::vector<uint32_t>& round_order(size_t round);
     int  prefetch_c(Running& r, const Task& t, bool may_wait);
+    int  load_c_direct(Running& r, const Task& t);
     void prefetch_ahead(size_t build_pos);
     bool wide_fits(const Problem& p);
     // wide mode: first k-step of round r
     size_t round_begin(size_t r) const { return r * (size_t)kchain_; }
     int  build_solve(int ri);
     int  get_inverse(const Task& t, Block** out);
+    int  make_inverses(const Task* const* tasks, size_t count);
+    std::vector<const Task*> diag_tasks(const Problem& p) const;
     int  fetch_derived(const TileRef& t, int kind, Block** out);
     OpenPack& pack_for(int mode, bool ta, bool tb) { return packs_[mode][ta ? 1 : 0][tb ? 1 : 0]; }
     int  add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, double flops, uint64_t nsteps);

@@ -612,7 +612,7 @@ def test_wide_mode_trsm_tight_cache_many_interleavings(sim, seed):
         L = L.T.copy()
     X = rng.integers(-2, 3, (n, m)).astype(np.float64)
     B = L @ X if side == blasx.Left else X @ L
-    setup(sim, T=16, arena_tiles=98 + 3 * seed, wide=2, group=2, seed=200 + seed)
+    setup(sim, T=16, arena_tiles=116 + 3 * seed, wide=2, group=2, seed=200 + seed)
     Ls, Bs = store(L, blasx.ColMajor), store(B, blasx.ColMajor)
     sim.dtrsm(blasx.ColMajor, side, uplo, blasx.NoTrans, blasx.Unit, n, m, 1.0, Ls, na, Bs, n)
     assert sim.get_option("last_wide") == 1
