@@ -494,17 +494,26 @@ __device__ __forceinline__ bool slab_inside_triangle(uint32_t sflags, int k0, in
     return inside;
 }
 
-// Whether the work of a step's macro-tiles grows with the tile index (the triangle cuts the k
-// range from above): such a step hands out its macro-tiles last to first, longest first.
+// How a step with a triangular operand hands out its macro-tiles.  Their work depends on the
+// row block (triangular A) or the column block (triangular B) only, so that index is made the
+// slow one: consecutive workgroups, which the hardware deals round-robin to the shader engines
+// of an XCD, are then equally long and every engine gets the same mix (with the row block as the
+// fast index one engine got all the longest macro-tiles: 584 us for a launch of 16 diagonal
+// steps instead of 300).  And where the work grows with the index (the triangle cuts the k range
+// from above) the macro-tiles go out last to first, longest first.
+struct MaskedOrder {
+    bool reversed;        // hand out last to first
+    bool rows_slow;       // row block = slow index (else the usual column-major order of macro-tiles)
+};
 template <bool TA, bool TB>
-__device__ __forceinline__ bool work_grows_with_index(const TileStep& st) {
+__device__ __forceinline__ MaskedOrder masked_order(const TileStep& st) {
     for (int q = 0; q < st.nseg; ++q) {
         const uint32_t f = st.seg[q].flags;
         const bool lower = f & TS_TRI_LOWER;
-        if (f & TS_TRI_A) return lower != TA;
-        if (f & TS_TRI_B) return lower == TB;
+        if (f & TS_TRI_A) return MaskedOrder{lower != TA, true};
+        if (f & TS_TRI_B) return MaskedOrder{lower == TB, false};
     }
-    return false;
+    return MaskedOrder{false, false};
 }
 
 // MASK: the pack holds steps with triangular operands (separate kernel instantiation, so that
@@ -681,10 +690,15 @@ void tile_steps_kernel(const LaunchPack pack) {
 
     uint32_t local = v - st.wg_begin;
     const uint32_t tiles_m = (uint32_t)(st.m + BM - 1) / BM;
-    if (MODE == MODE_FAST_MASKED && work_grows_with_index<TA, TB>(st))
-        local = tiles_m * ((uint32_t)(st.n + BN - 1) / BN) - 1 - local;
-    const int i_base = (int)(local % tiles_m) * BM;
-    const int j_base = (int)(local / tiles_m) * BN;
+    int i_base = (int)(local % tiles_m) * BM;
+    int j_base = (int)(local / tiles_m) * BN;
+    if (MODE == MODE_FAST_MASKED) {
+        const uint32_t tiles_n = (uint32_t)(st.n + BN - 1) / BN;
+        const MaskedOrder order = masked_order<TA, TB>(st);
+        if (order.reversed) local = tiles_m * tiles_n - 1 - local;
+        i_base = (int)(order.rows_slow ? local / tiles_n : local % tiles_m) * BM;
+        j_base = (int)(order.rows_slow ? local % tiles_n : local / tiles_m) * BN;
+    }
     if (MODE == MODE_GENERAL)
         macro_tile<T, TA, TB>(st, i_base, j_base);
     else
