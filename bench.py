@@ -159,7 +159,7 @@ def main():
                         "(inbound tile copies, kernels, write-back)" % (n, T, args.streams),
             "n": n, "tile": T, "streams": args.streams, "group": lib.get_option("last_group"), "kchain": lib.get_option("last_kchain"),
             "depth": lib.get_option("depth"), "superblock": [lib.get_option("sb_rows"), lib.get_option("sb_cols")],
-            "shells": lib.get_option("shells"), "wide": lib.get_option("last_wide"),
+            "shells": lib.get_option("shells"), "wide": lib.get_option("last_wide"), "first_round": lib.get_option("last_ramp"),
             "arena_bytes": arena,
         },
         "roofline": {

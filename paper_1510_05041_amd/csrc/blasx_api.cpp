@@ -31,6 +31,7 @@ struct Library {
     int last_T = 0;   // tile edge of the most recent call
     int last_group = 0;
     bool last_wide = false;
+    int last_ramp = 0;
     int last_kchain = 0;
 };
 
@@ -117,6 +118,7 @@ int run_problem(Problem& p) {
         rc = L.sched->run(p);
         L.last_wide = L.sched->last_run_was_wide();
         L.last_kchain = L.sched->last_run_kchain();
+        L.last_ramp = L.sched->last_run_first_chain();
         if (rc != 0) L.sched.reset();      // after a failed call nothing cached is trusted: start afresh
     } else {
         L.sched.reset();
@@ -124,6 +126,7 @@ int run_problem(Problem& p) {
         rc = sched.run(p);
         L.last_wide = sched.last_run_was_wide();
         L.last_kchain = sched.last_run_kchain();
+        L.last_ramp = sched.last_run_first_chain();
     }
     if (rc == BLASX_ERR_DEVICE) L.last_error = L.be->last_error();
     if (rc == BLASX_ERR_ARENA_TOO_SMALL) L.last_error = "tile cache too small for the working set of this call";
@@ -395,6 +398,7 @@ int blasx_set_option(const char* name, long value) {
     else if (n == "sb_cols") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_cols = (int)value; }
     else if (n == "shells") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.order.shells = (int)value; }
     else if (n == "wide") { if (value < 0 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.wide = (int)value; }
+    else if (n == "ramp") { if (value < 0 || value > kMaxChain) return BLASX_ERR_CONFIG; L.cfg.ramp = (int)value; }
     else if (n == "prefetch") { if (value < 0 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.prefetch = (int)value; }
     else if (n == "profile") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.profile = value != 0; }
     else if (n == "persist") {
@@ -419,6 +423,7 @@ long blasx_get_option(const char* name) {
     if (n == "shells") return L.order.shells;
     if (n == "wide") return L.cfg.wide;
     if (n == "prefetch") return L.cfg.prefetch;
+    if (n == "ramp") return L.cfg.ramp;
     if (n == "profile") return L.cfg.profile ? 1 : 0;
     if (n == "persist") return L.persist ? 1 : 0;
     if (n == "cached_tiles") return L.sched ? (long)L.sched->cached_blocks() : 0;
@@ -426,6 +431,7 @@ long blasx_get_option(const char* name) {
     if (n == "last_tile") return L.last_T;
     if (n == "last_group") return L.last_group;
     if (n == "last_wide") return L.last_wide ? 1 : 0;
+    if (n == "last_ramp") return L.last_ramp;
     if (n == "last_kchain") return L.last_kchain;
     return -1;
 }

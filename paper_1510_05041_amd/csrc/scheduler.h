@@ -45,6 +45,8 @@ struct SchedConfig {
     int wide = 12;      // let every task of a call advance together when the cache has room and every
                         // task has at least this many k-steps (see run()); 0: never
     int prefetch = 24;  // wide mode: inbound copies are started this many launches ahead of the launch being built
+    int ramp = 0;       // wide mode: k-steps per task in the first round (1..kMaxChain, cut to the chain length of
+                        // the run, i.e. kMaxChain = no shorter first round; 0: chosen per run, see run())
     bool profile = false;
 };
 
@@ -71,6 +73,7 @@ public:
     size_t invalidate_all();
     void set_config(const SchedConfig& cfg);
     size_t cached_blocks() const { return cache_.blocks(); }
+    int  last_run_first_chain() const { return first_chain_; }
     bool last_run_was_wide() const { return wide_; }
     int last_run_kchain() const { return kchain_; }
 
@@ -136,7 +139,8 @@ private:
     void prefetch_ahead(size_t build_pos);
     bool wide_fits(const Problem& p);
     // wide mode: first k-step of round r
-    size_t round_begin(size_t r) const { return r * (size_t)kchain_; }
+    // first k-step of round r: rounds are kchain_ steps long, except that the first may be shorter
+    size_t round_begin(size_t r) const { return r == 0 ? 0 : (size_t)first_chain_ + (r - 1) * (size_t)kchain_; }
     int  build_solve(int ri);
     int  get_inverse(const Task& t, Block** out);
     int  make_inverses(const Task* const* tasks, size_t count);
@@ -169,6 +173,7 @@ private:
     size_t pf_last_round_ = 0;          // wide mode: last round in which any task still has steps
     size_t pfc_pos_ = 0;                // wide mode: same for the host C tiles, which run further ahead
     size_t pf_reserve_ = 0;             // free slots that early C tiles must leave for operand tiles
+    int first_chain_ = 0;               // wide mode: k-steps per task in the first round (<= kchain_)
     size_t build_pos_ = 0;              // wide mode: (round * ntasks + position in the round's order) of the chain being built
     static constexpr int kOrders = 4;   // the round being built and those the two prefetch cursors are in
     std::vector<uint32_t> order_[kOrders];   // wide mode: round_order() of the latest rounds asked for

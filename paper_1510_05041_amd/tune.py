@@ -76,7 +76,7 @@ def _problem(lib, routine, n, k):
     raise ValueError(routine)
 
 
-def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=12, kchain=0):
+def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=12, kchain=0, ramp=0):
     lib = blasx.default()
     results = []
     for n in sizes:
@@ -91,6 +91,7 @@ def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None
                     for name, v in dict(group=g, rs=max(32, 2 * g), kchain=kchain, depth=6, sb_rows=4, sb_cols=4, shells=1,
                                         profile=0, persist=0, wide=wide).items():
                         lib.set_option(name, v)
+                    lib.set_option("ramp", ramp)
                     times = []
                     for rep in range(reps + 1):
                         if refresh:
@@ -145,12 +146,13 @@ def main(argv=None):
     ap.add_argument("--arena-gb", type=float, default=24.0)
     ap.add_argument("--wide", type=int, default=12, help="option \"wide\": least k-steps per task for which all tasks advance together; 0: never")
     ap.add_argument("--kchain", type=int, default=0, help="option \"kchain\": k-tiles per launch and task; 0: the library's choice")
+    ap.add_argument("--ramp", type=int, default=0, help="option \"ramp\": k-steps per task in the first round of the wide schedule (8: as in the others); 0: the library's choice")
     ap.add_argument("--out", default="", help="also append the JSON records to this file")
     a = ap.parse_args(argv)
     ints = lambda s: [int(x) for x in s.split(",") if x]
     sizes, tiles, streams, groups = ints(a.sizes), ints(a.tiles), ints(a.streams), ints(a.groups)
     out = open(a.out, "a") if a.out else None
-    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out, a.wide, a.kchain)
+    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out, a.wide, a.kchain, a.ramp)
     print()
     print(tables(res, tiles, streams))
 

@@ -30,7 +30,7 @@ def setup(sim, T, nstreams=4, arena_tiles=64, cap_tiles=0, seed=1, esize=8, **op
     sim.init_raw(arena_tiles * T * T * esize, nstreams)
     sim.set_tile(T)
     sim.set_cache_bytes(cap_tiles * T * T * esize)
-    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, profile=0, persist=0, wide=0)
+    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, profile=0, persist=0, wide=0, ramp=0)
     defaults.update(opts)
     for k, v in defaults.items():
         sim.set_option(k, v)
@@ -465,6 +465,25 @@ def test_wide_mode_gemm_matches_oracle(sim, order, ta, tb, M, N, K, kchain):
     nt = -(-M // 16) * -(-N // 16)
     assert st["tasks"] == nt and st["copies_d2h"] == nt
     assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N)        # every tile exactly once, C included
+
+
+@pytest.mark.parametrize("ktiles,ramp,expect", [(19, 0, 3), (16, 0, 2), (24, 0, 2), (13, 0, 8), (19, 8, 8), (19, 5, 5), (17, 0, 1)])
+def test_wide_mode_first_round_takes_the_odd_steps(sim, ktiles, ramp, expect):
+    """The k loop is cut into rounds of 8 steps; what is left over goes into the first round (or 2 steps when
+    nothing is left over), never the last; with fewer than two full rounds the first stays full."""
+    M, N, K = 48, 40, 16 * ktiles - 5
+    setup(sim, T=16, arena_tiles=800, seed=ktiles + ramp, wide=2, group=2, kchain=0, ramp=ramp)
+    rng = np.random.default_rng(ktiles)
+    A, B, C = fmat(rng, M, K), fmat(rng, K, N), fmat(rng, M, N)
+    want = A @ B - 2.0 * C
+    sim.dgemm(CM, NT, NT, M, N, K, 1.0, A, M, B, K, -2.0, C, M)
+    assert sim.get_option("last_wide") == 1 and sim.get_option("last_kchain") == 8
+    assert sim.get_option("last_ramp") == expect
+    assert np.array_equal(C, want)                       # small integers: exact in any order
+    st = sim.get_stats()
+    assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N)
+    first, rest = expect, ktiles - expect
+    assert st["launches"] == (1 if first else 0) + -(-rest // 8) if st["tasks"] <= 16 else True
 
 
 def test_wide_mode_special_cases(sim):
