@@ -145,8 +145,10 @@ def main():
     # same counters on a plain 1 GiB device copy (profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md); they are
     # a property of the launch shape, so they are only quoted for the shape they were measured on.
     traffic = None
-    if (n, T, lib.get_option("last_group"), lib.get_option("last_kchain"), lib.get_option("last_wide")) == (32768, 1024, 16, 8, 1):
-        traffic = {"hbm_bytes_per_launch": 3.483e9, "read": 3.348e9, "write": 0.1349e9, "algorithmic": 2.416e9,
+    shape = (n, T, lib.get_option("last_group"), lib.get_option("last_kchain"), lib.get_option("last_wide"), lib.get_option("last_ramp"))
+    if shape == (32768, 1024, 16, 8, 1, 2):
+        # means over the 320 launches of a call (rounds of 2, 6, 8, 8 and 8 k-tiles)
+        traffic = {"hbm_bytes_per_launch": 2.839e9, "read": 2.704e9, "write": 0.1345e9, "algorithmic": 1.986e9,
                    "source": "profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md"}
     out = {
         "metric": "host-resident DGEMM GFLOP/s on 1 MI355X", "value": round(gflops, 1), "unit": "GFLOP/s",

@@ -151,9 +151,10 @@ int blasx_set_cache_bytes(size_t cap);
  *   "ramp"     wide schedule: k-steps per task in the first round (1..8; 8 = as in every other
  *              round).  0 (default): the steps left over when the k loop is cut into rounds
  *              are taken in the first round rather than the last (a short last round cannot
- *              hide the result tiles leaving and the C tiles arriving), or 2 when nothing is
- *              left over (the device starts earlier); with fewer than two full rounds the
- *              first round stays full.  The choice of the latest call is "last_ramp".
+ *              hide the result tiles leaving and the C tiles arriving); when nothing is left
+ *              over the first full round is split into 2 steps and the rest (the device
+ *              starts earlier); with fewer than two full rounds the first round stays full.
+ *              The choice of the latest call is "last_ramp".
  *   "prefetch" wide schedule: inbound copies are started this many launches ahead (default 24)
  *   "depth"    launches the host may run ahead of the device (>= 1)
  *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)

@@ -1004,17 +1004,25 @@ int Scheduler::run(Problem& p) {
     // Length of the first round.  The last round is the one in which every result tile leaves and
     // every late C tile arrives: a short one cannot hide that traffic (measured at 8 k-steps per
     // round: a last round of 1 / 2 / 3 / 4 / 5 / 6 steps costs 20 / 18 / 14 / 8 / 4 / 1 % of the
-    // call).  So the odd steps are taken first, not last; and when there are none a first round
-    // of two steps still starts the device a few milliseconds earlier (+3 % at 16 k-tiles, +1 % at
-    // 32).  With only two rounds the remainder stays where it was (12 .. 15 k-tiles: measured 0 ..
-    // 4 % better that way).
-    first_chain_ = kchain_;
+    // call).  So the odd steps are taken first, not last; and when there are none the first full
+    // round is split into one of two steps and one of the rest, which starts the device a few
+    // milliseconds earlier (+3 % at 16 k-tiles, +1 % at 32) and still leaves a full last round.
+    // With only two rounds the remainder stays where it was (12 .. 15 k-tiles: measured 0 .. 4 %
+    // better that way).
+    first_chain_ = second_chain_ = kchain_;
     if (wide_ && !p.results_are_operands && kchain_ > 2) {
         size_t max_steps = 0;
         for (const Task& t : p.tasks) max_steps = std::max(max_steps, t.steps.size());
-        if (cfg_.ramp > 0) first_chain_ = std::min(cfg_.ramp, kchain_);
-        else if (max_steps >= 2 * (size_t)kchain_)
-            first_chain_ = max_steps % kchain_ ? (int)(max_steps % kchain_) : 2;
+        if (cfg_.ramp > 0) {
+            first_chain_ = std::min(cfg_.ramp, kchain_);
+        } else if (max_steps >= 2 * (size_t)kchain_) {
+            if (max_steps % kchain_) {
+                first_chain_ = (int)(max_steps % kchain_);
+            } else {
+                first_chain_ = 2;
+                second_chain_ = kchain_ - 2;
+            }
+        }
     }
     const int group = wide_ ? (int)ntasks : cfg_.group;
     // A launch lasts as long as its longest chain.  Where the tasks differ in length (TRMM: task

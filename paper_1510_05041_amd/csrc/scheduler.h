@@ -139,8 +139,10 @@ private:
     void prefetch_ahead(size_t build_pos);
     bool wide_fits(const Problem& p);
     // wide mode: first k-step of round r
-    // first k-step of round r: rounds are kchain_ steps long, except that the first may be shorter
-    size_t round_begin(size_t r) const { return r == 0 ? 0 : (size_t)first_chain_ + (r - 1) * (size_t)kchain_; }
+    // first k-step of round r: rounds are kchain_ steps long, except that the first two may be shorter
+    size_t round_begin(size_t r) const {
+        return r == 0 ? 0 : r == 1 ? (size_t)first_chain_ : (size_t)(first_chain_ + second_chain_) + (r - 2) * (size_t)kchain_;
+    }
     int  build_solve(int ri);
     int  get_inverse(const Task& t, Block** out);
     int  make_inverses(const Task* const* tasks, size_t count);
@@ -173,6 +175,7 @@ private:
     size_t pf_last_round_ = 0;          // wide mode: last round in which any task still has steps
     size_t pfc_pos_ = 0;                // wide mode: same for the host C tiles, which run further ahead
     size_t pf_reserve_ = 0;             // free slots that early C tiles must leave for operand tiles
+    int second_chain_ = 0;              // wide mode: k-steps per task in the second round (<= kchain_)
     int first_chain_ = 0;               // wide mode: k-steps per task in the first round (<= kchain_)
     size_t build_pos_ = 0;              // wide mode: (round * ntasks + position in the round's order) of the chain being built
     static constexpr int kOrders = 4;   // the round being built and those the two prefetch cursors are in

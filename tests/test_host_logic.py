@@ -482,8 +482,10 @@ def test_wide_mode_first_round_takes_the_odd_steps(sim, ktiles, ramp, expect):
     assert np.array_equal(C, want)                       # small integers: exact in any order
     st = sim.get_stats()
     assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N)
-    first, rest = expect, ktiles - expect
-    assert st["launches"] == (1 if first else 0) + -(-rest // 8) if st["tasks"] <= 16 else True
+    # 9 tasks = one launch per round: the odd steps first, then full rounds (nothing left over and no explicit
+    # request: the first full round is split into 2 + 6, the same number of rounds as 2 + 8 + ... + 6)
+    rounds = 1 + -(-(ktiles - expect) // 8) if expect < 8 else -(-ktiles // 8)
+    assert st["tasks"] == 9 and st["launches"] == rounds
 
 
 def test_wide_mode_special_cases(sim):
