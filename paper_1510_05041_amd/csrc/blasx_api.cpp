@@ -47,8 +47,9 @@ Library& lib() {
 // cost of one strided copy (~10 us on the copy engine) is small beside its transfer time; 1024
 // (8 MB in double precision) is, and stays best down to 2 x 2 tiles; larger tiles only shorten
 // the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 4096 up, but
-// 1024 where the wide schedule pays (output and inner dimension from 16384: measured 117 against
-// 104 TFLOP/s at 16384, 131 against 130 at 32768, but 64 against 86 at 12288).  `inner` is 0 for the triangular routines.
+// 1024 where the wide schedule applies (output and inner dimension from 12288 = 12 k-tiles: measured
+// 91.6 against 86.5 TFLOP/s at 12288, 110 against 101 at 14336, 123 against 105 at 16384, 131 against
+// 130 at 32768; below, 77 against 84 at 10240).  `inner` is 0 for the triangular routines.
 int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner) {
     Library& L = lib();
     if (L.T > 0) return L.T;
@@ -57,7 +58,7 @@ int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner) {
     const int64_t one_tile = (n + 15) / 16 * 16;
     int T;
     if (dtype == 0) T = n >= 2048 ? 1024 : (int)one_tile;
-    else T = (n >= 16384 && inner >= 16384) ? 1024 : n >= 4096 ? 2048 : (int)std::min<int64_t>(2048, one_tile);
+    else T = (n >= 12288 && inner >= 12288) ? 1024 : n >= 4096 ? 2048 : (int)std::min<int64_t>(2048, one_tile);
     // at least 64 tiles must fit in the cache (running set + operands), else eviction thrashes
     size_t usable = L.be ? L.be->arena_bytes() : 0;
     if (L.cache_cap && L.cache_cap < usable) usable = L.cache_cap;
