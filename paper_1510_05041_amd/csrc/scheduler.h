@@ -20,10 +20,13 @@
 //     starves the device while those arrive, whereas the whole task set offers about ten times
 //     more products per tile copied.  The host tile of C then arrives late, in a slot of its
 //     own, and the task's last launch adds the accumulated partial sums to it; inbound copies
-//     are issued by a cursor that runs ahead of the launch being built.  The triangular solve
-//     runs the same way one k-tile per round (right-looking).
+//     are issued by a cursor that runs ahead of the launch being built.  The k loop is cut into
+//     rounds of kchain steps with the left-over steps first (the last round carries every
+//     result tile out and must be a full one); tasks of unequal length (triangular product)
+//     are sorted by length, because a launch lasts as long as its longest chain.  The
+//     triangular solve runs the same way one k-tile per round (right-looking), with every
+//     diagonal tile inverted before the first round.
 #pragma once
-#include <cstdint>
 #include <stdint.h>
 
 #include <cstring>
