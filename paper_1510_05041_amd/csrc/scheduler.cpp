@@ -614,8 +614,8 @@ bool Scheduler::wide_fits(const Problem& p) {
                          : !p.panels.empty()    ? ((size_t)cfg_.wide * 2 + 2) / 3
                                                 : (size_t)cfg_.wide * (size_t)p.steps_per_k;
     if (max_steps <= (size_t)kchain_ || max_steps < least) return false;
-    const size_t rounds = (max_steps + kchain_ - 1) / kchain_;
-    const size_t per_round = (uniq.size() + rounds - 1) / rounds;
+    // operand tiles of one full round (the left-over steps make a shorter round of their own)
+    const size_t per_round = (uniq.size() * std::min<size_t>(kchain_, max_steps) + max_steps - 1) / max_steps;
     const size_t late_c = with_c ? std::min<size_t>(with_c, (size_t)kMaxStepsPerLaunch * (cfg_.prefetch + cfg_.depth + 2)) : 0;
     pf_reserve_ = per_round + kMaxStepsPerLaunch;
     size_t pinned = 0;      // TRMM: the original tiles of the matrix updated in place stay for the whole call

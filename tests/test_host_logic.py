@@ -549,7 +549,7 @@ def test_wide_mode_symmetric_routines_and_tight_cache(sim, seed):
     full = np.tril(S) + np.tril(S, -1).T if uplo == blasx.Lower else np.triu(S) + np.triu(S, 1).T
     Bm, Cm = fmat(rng, n, 48), fmat(rng, n, 48)
     Cs = Cm.copy(order="F")
-    setup(sim, T=16, arena_tiles=72 + 4 * seed, wide=2, group=2, kchain=1 + seed % 3, seed=seed)
+    setup(sim, T=16, arena_tiles=76 + 4 * seed, wide=2, group=2, kchain=1 + seed % 3, seed=seed)
     sim.dsymm(CM, blasx.Left, uplo, n, 48, 1.0, S, n, Bm, n, beta, Cs, n)
     assert sim.get_option("last_wide") == 1
     assert np.array_equal(Cs, full @ Bm + beta * Cm)
