@@ -33,7 +33,7 @@ def configure(L, T, nstreams=4, arena_gb=2.0, cap_bytes=0, **opts):
     L.init(int(arena_gb * 2 ** 30), nstreams=nstreams)
     L.set_tile(T)
     L.set_cache_bytes(cap_bytes)
-    defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, profile=0, persist=0, wide=0)
+    defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, profile=0, persist=0, wide=0, ramp=0)
     defaults.update(opts)
     for k, v in defaults.items():
         L.set_option(k, v)
@@ -760,3 +760,78 @@ def test_single_precision_syrk_trmm_trsm(lib):
     lib.strsm(blasx.ColMajor, blasx.Left, blasx.Upper, blasx.NoTrans, blasx.NonUnit, M, Nb, 1.0, T32, M, B, M)
     ref.trsm(ref.ColMajor, ref.Left, ref.Upper, ref.NoTrans, ref.NonUnit, 1.0, np.asarray(T32), want)
     assert relerr(B, want) < TOL32
+
+
+# ------------------------------------------------------------------ seeded random problems --
+
+@pytest.mark.parametrize("seed", range(36))
+def test_seeded_random_problems_every_routine_and_schedule(lib, seed):
+    """Routine, flags, ragged extents, tile size, schedule options and scalars drawn from a seeded generator; every
+    element compared with the oracle.  The k extents reach 30 tiles, so the wide schedule's rounds come out in every
+    shape (left-over steps first, a split first round, two rounds only)."""
+    rng = np.random.default_rng(1000 + seed)
+    routine = ("gemm", "syrk", "syr2k", "symm", "trmm", "trsm")[seed % 6]
+    T = int(rng.choice([128, 256]))
+    opts = dict(group=int(rng.choice([0, 4, 16])), kchain=int(rng.choice([0, 0, 3, 8])), wide=int(rng.choice([0, 2, 12])),
+                ramp=int(rng.choice([0, 0, 1, 8])))
+    configure(lib, T=T, arena_gb=1.5, **opts)
+    uplo = int(rng.choice([blasx.Lower, blasx.Upper]))
+    trans = int(rng.choice(TRANS))
+    side = int(rng.choice([blasx.Left, blasx.Right]))
+    diag = int(rng.choice([blasx.NonUnit, blasx.Unit]))
+    alpha = float(rng.choice([1.0, -0.6, 0.0, 1.7]))
+    beta = float(rng.choice([0.0, 1.0, -1.3]))
+    M, N = int(rng.integers(200, 1500)), int(rng.integers(200, 1500))
+    K = int(rng.integers(100, 30 * T))
+    tag = "%s T=%d %s M=%d N=%d K=%d uplo=%d trans=%d side=%d diag=%d alpha=%g beta=%g" % (routine, T, opts, M, N, K, uplo, trans, side, diag, alpha, beta)
+    print(tag, flush=True)
+    if routine == "gemm":
+        ta, tb = trans, int(rng.choice(TRANS))
+        A, ka = pinned(M if ta == blasx.NoTrans else K, K if ta == blasx.NoTrans else M, seed, 0)
+        B, kb = pinned(K if tb == blasx.NoTrans else N, N if tb == blasx.NoTrans else K, seed, 1)
+        C, kc = pinned(M, N, seed, 2)
+        want = np.array(C, order="F")
+        lib.dgemm(blasx.ColMajor, ta, tb, M, N, K, alpha, A, A.shape[0], B, B.shape[0], beta, C, M)
+        ref.gemm(ref.ColMajor, ta, tb, alpha, np.asarray(A), np.asarray(B), beta, want)
+        assert relerr(C, want) < TOL64, tag
+    elif routine in ("syrk", "syr2k"):
+        K = min(K, 12 * T)
+        A, ka = pinned(N if trans == blasx.NoTrans else K, K if trans == blasx.NoTrans else N, seed, 0)
+        B, kb = pinned(A.shape[0], A.shape[1], seed, 1)
+        C, kc = pinned(N, N, seed, 2)
+        want = np.array(C, order="F")
+        if routine == "syrk":
+            lib.dsyrk(blasx.ColMajor, uplo, trans, N, K, alpha, A, A.shape[0], beta, C, N)
+            ref.syrk(ref.ColMajor, uplo, trans, alpha, np.asarray(A), beta, want)
+        else:
+            lib.dsyr2k(blasx.ColMajor, uplo, trans, N, K, alpha, A, A.shape[0], B, B.shape[0], beta, C, N)
+            ref.syr2k(ref.ColMajor, uplo, trans, alpha, np.asarray(A), np.asarray(B), beta, want)
+        assert relerr(C, want) < TOL64, tag
+    elif routine == "symm":
+        n = M if side == blasx.Left else N
+        A, ka = pinned(n, n, seed, 0)
+        B, kb = pinned(M, N, seed, 1)
+        C, kc = pinned(M, N, seed, 2)
+        want = np.array(C, order="F")
+        lib.dsymm(blasx.ColMajor, side, uplo, M, N, alpha, A, n, B, M, beta, C, M)
+        ref.symm(ref.ColMajor, side, uplo, alpha, np.asarray(A), np.asarray(B), beta, want)
+        assert relerr(C, want) < TOL64, tag
+    else:
+        n = M if side == blasx.Left else N
+        A, ka = triangular(n, seed, uplo, diag)
+        B, kb = pinned(M, N, seed, 1)
+        B0 = np.array(B, order="F")
+        want = np.array(B, order="F")
+        alpha = alpha if alpha != 0.0 else 0.9
+        if routine == "trmm":
+            lib.dtrmm(blasx.ColMajor, side, uplo, trans, diag, M, N, alpha, A, n, B, M)
+            ref.trmm(ref.ColMajor, side, uplo, trans, diag, alpha, np.asarray(A), want)
+            assert np.all(np.isfinite(np.asarray(B))) and relerr(B, want) < TOL64, tag
+        else:
+            lib.dtrsm(blasx.ColMajor, side, uplo, trans, diag, M, N, alpha, A, n, B, M)
+            X = np.array(B, order="F")
+            assert np.all(np.isfinite(X)), tag
+            R = X.copy(order="F")
+            ref.trmm(ref.ColMajor, side, uplo, trans, diag, 1.0, np.asarray(A), R)
+            norm_a = np.linalg.norm(np.nan_to_num(np.asarray(A))) + (np.sqrt(n) if diag == blasx.Unit else 0.0)
+            assert np.linalg.norm(R - alpha * B0) / (norm_a * np.linalg.norm(X)) < TOL64, tag
