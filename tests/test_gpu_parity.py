@@ -835,3 +835,76 @@ def test_seeded_random_problems_every_routine_and_schedule(lib, seed):
             ref.trmm(ref.ColMajor, side, uplo, trans, diag, 1.0, np.asarray(A), R)
             norm_a = np.linalg.norm(np.nan_to_num(np.asarray(A))) + (np.sqrt(n) if diag == blasx.Unit else 0.0)
             assert np.linalg.norm(R - alpha * B0) / (norm_a * np.linalg.norm(X)) < TOL64, tag
+
+
+@pytest.mark.parametrize("seed", range(18))
+def test_seeded_random_problems_single_precision(lib, seed):
+    """The same in single precision (tile-aligned and ragged extents, so both the fast and the general kernel run)."""
+    rng = np.random.default_rng(2000 + seed)
+    routine = ("gemm", "syrk", "syr2k", "symm", "trmm", "trsm")[seed % 6]
+    T = int(rng.choice([256, 512]))
+    opts = dict(group=int(rng.choice([0, 4, 16])), kchain=int(rng.choice([0, 0, 3])), wide=int(rng.choice([0, 2, 12])))
+    configure(lib, T=T, arena_gb=1.5, **opts)
+    uplo = int(rng.choice([blasx.Lower, blasx.Upper]))
+    trans = int(rng.choice(TRANS))
+    side = int(rng.choice([blasx.Left, blasx.Right]))
+    diag = int(rng.choice([blasx.NonUnit, blasx.Unit]))
+    alpha = float(rng.choice([1.0, -0.6, 1.7]))
+    beta = float(rng.choice([0.0, 1.0, -1.3]))
+    aligned = bool(rng.integers(0, 2))
+    M = int(rng.integers(1, 5)) * T if aligned else int(rng.integers(200, 1500))
+    N = int(rng.integers(1, 5)) * T if aligned else int(rng.integers(200, 1500))
+    K = int(rng.integers(1, 20)) * T if aligned else int(rng.integers(100, 20 * T))
+    tag = "%s T=%d %s M=%d N=%d K=%d uplo=%d trans=%d side=%d diag=%d alpha=%g beta=%g" % (routine, T, opts, M, N, K, uplo, trans, side, diag, alpha, beta)
+    print(tag, flush=True)
+    f32 = np.float32
+
+    def single(a64):
+        a, owner = blasx.pinned_matrix(a64.shape[0], a64.shape[1], dtype=f32)
+        a[...] = np.asarray(a64).astype(f32)
+        return a, owner
+
+    if routine == "gemm":
+        ta, tb = trans, int(rng.choice(TRANS))
+        A, ka = pinned(M if ta == blasx.NoTrans else K, K if ta == blasx.NoTrans else M, seed, 0, dtype=f32)
+        B, kb = pinned(K if tb == blasx.NoTrans else N, N if tb == blasx.NoTrans else K, seed, 1, dtype=f32)
+        C, kc = pinned(M, N, seed, 2, dtype=f32)
+        want = np.array(C, order="F")
+        lib.sgemm(blasx.ColMajor, ta, tb, M, N, K, alpha, A, A.shape[0], B, B.shape[0], beta, C, M)
+        ref.gemm(ref.ColMajor, ta, tb, alpha, np.asarray(A), np.asarray(B), beta, want)
+        assert relerr(C, want) < TOL32, tag
+    elif routine in ("syrk", "syr2k"):
+        K = min(K, 12 * T)
+        A, ka = pinned(N if trans == blasx.NoTrans else K, K if trans == blasx.NoTrans else N, seed, 0, dtype=f32)
+        B, kb = pinned(A.shape[0], A.shape[1], seed, 1, dtype=f32)
+        C, kc = pinned(N, N, seed, 2, dtype=f32)
+        want = np.array(C, order="F")
+        if routine == "syrk":
+            lib.ssyrk(blasx.ColMajor, uplo, trans, N, K, alpha, A, A.shape[0], beta, C, N)
+            ref.syrk(ref.ColMajor, uplo, trans, alpha, np.asarray(A), beta, want)
+        else:
+            lib.ssyr2k(blasx.ColMajor, uplo, trans, N, K, alpha, A, A.shape[0], B, B.shape[0], beta, C, N)
+            ref.syr2k(ref.ColMajor, uplo, trans, alpha, np.asarray(A), np.asarray(B), beta, want)
+        assert relerr(C, want) < TOL32, tag
+    elif routine == "symm":
+        n = M if side == blasx.Left else N
+        A, ka = pinned(n, n, seed, 0, dtype=f32)
+        B, kb = pinned(M, N, seed, 1, dtype=f32)
+        C, kc = pinned(M, N, seed, 2, dtype=f32)
+        want = np.array(C, order="F")
+        lib.ssymm(blasx.ColMajor, side, uplo, M, N, alpha, A, n, B, M, beta, C, M)
+        ref.symm(ref.ColMajor, side, uplo, alpha, np.asarray(A), np.asarray(B), beta, want)
+        assert relerr(C, want) < TOL32, tag
+    else:
+        n = M if side == blasx.Left else N
+        A64, k64 = triangular(n, seed, uplo, diag)
+        A, ka = single(A64)
+        B, kb = pinned(M, N, seed, 1, dtype=f32)
+        want = np.array(B, order="F")
+        if routine == "trmm":
+            lib.strmm(blasx.ColMajor, side, uplo, trans, diag, M, N, alpha, A, n, B, M)
+            ref.trmm(ref.ColMajor, side, uplo, trans, diag, alpha, np.asarray(A), want)
+        else:
+            lib.strsm(blasx.ColMajor, side, uplo, trans, diag, M, N, alpha, A, n, B, M)
+            ref.trsm(ref.ColMajor, side, uplo, trans, diag, alpha, np.asarray(A), want)
+        assert np.all(np.isfinite(np.asarray(B))) and relerr(B, want) < TOL32, tag
