@@ -103,6 +103,11 @@ int run_problem(Problem& p) {
     cfg.rs = std::max(cfg.rs, 2 * cfg.group);
     // the running set and its operands must fit: each running task owns an accumulator slot
     cfg.group = (int)std::max<size_t>(1, std::min<size_t>((size_t)cfg.group, nslots / 4));
+    // TRMM pins the original tiles of the panel of every running task: in the worst case each running task
+    // belongs to a panel of its own, and they must all fit beside the tasks' own slots and operands
+    size_t panel_tiles = 0;
+    for (const Panel& pn : p.panels) panel_tiles = std::max(panel_tiles, pn.tiles.size());
+    if (panel_tiles) cfg.group = (int)std::max<size_t>(1, std::min<size_t>((size_t)cfg.group, nslots / (panel_tiles + 4)));
     L.last_group = cfg.group;
     ++L.stats.calls;
     int rc;

@@ -276,9 +276,20 @@ int Scheduler::pick_from_rs() {
         for (size_t q = 0; q < rs_.size(); ++q) rs_prio_[q] = priority(p_->tasks[rs_[q]]);
         rs_dirty_ = false;
     }
+    // TRMM: a panel's original tiles stay pinned until the last of its tasks has finished, so the
+    // number of panels entered and not yet finished is bounded by what half the cache holds; a
+    // task of a further panel waits until one is finished (tasks of open panels are preferred).
+    size_t open_panels = 0, panel_tiles = 1;
+    for (size_t q = 0; q < panels_.size(); ++q) {
+        open_panels += panels_[q].loaded && panels_[q].remaining > 0 ? 1 : 0;
+        panel_tiles = std::max(panel_tiles, p_->panels[q].tiles.size());
+    }
+    const bool may_open = force_open_ || open_panels == 0 || (open_panels + 1) * panel_tiles <= (size_t)cache_.nslots() / 2;
     int best = -1;
     for (size_t q = 0; q < rs_.size(); ++q) {
-        if (!deps_started(p_->tasks[rs_[q]])) continue;
+        const Task& t = p_->tasks[rs_[q]];
+        if (!deps_started(t)) continue;
+        if (t.panel >= 0 && !panels_[t.panel].loaded && !may_open) continue;
         if (best < 0 || rs_prio_[q] > rs_prio_[best]) best = (int)q;
     }
     if (best < 0) return -1;
@@ -292,8 +303,8 @@ int Scheduler::pick_from_rs() {
 
 int Scheduler::add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, double flops, uint64_t nsteps) {
     if (op.pack.nsteps > 0 && (op.ta != ta || op.tb != tb)) BX_TRY(flush(op));
-    // A launch is cut at 24 steps rather than at the 26 that fit: 8 whole-tile steps of 64 macro-tiles
-    // fill the 512 workgroup slots of the chip once, so multiples of 8 leave no partial wave of workgroups.
+    // A launch is cut at a multiple of 8 steps: 8 whole-tile steps of 64 macro-tiles fill the 512
+    // workgroup slots of the chip once, so multiples of 8 leave no partial wave of workgroups.
     if (op.pack.nsteps == (kMaxStepsPerLaunch / 8) * 8) BX_TRY(flush(op));
     if (op.pack.nsteps == 0) {
         op.ta = ta;
@@ -1070,6 +1081,13 @@ int Scheduler::run(Problem& p) {
                 if (next_task_ < ntasks) task = (int)next_task_++;
             } else {
                 task = pick_from_rs();
+                if (task < 0 && active == 0) {
+                    // nothing runs and the station only holds tasks of panels not entered yet (those of
+                    // the open panels are further down the queue): enter one more rather than stop
+                    force_open_ = true;
+                    task = pick_from_rs();
+                    force_open_ = false;
+                }
             }
             if (task < 0) break;
             Running r;

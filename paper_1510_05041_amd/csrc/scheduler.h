@@ -179,6 +179,7 @@ private:
     size_t pfc_pos_ = 0;                // wide mode: same for the host C tiles, which run further ahead
     size_t pf_reserve_ = 0;             // free slots that early C tiles must leave for operand tiles
     int second_chain_ = 0;              // wide mode: k-steps per task in the second round (<= kchain_)
+    bool force_open_ = false;           // pick_from_rs(): ignore the bound on open panels (nothing else can run)
     int first_chain_ = 0;               // wide mode: k-steps per task in the first round (<= kchain_)
     size_t build_pos_ = 0;              // wide mode: (round * ntasks + position in the round's order) of the chain being built
     static constexpr int kOrders = 4;   // the round being built and those the two prefetch cursors are in

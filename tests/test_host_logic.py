@@ -874,3 +874,69 @@ def test_ssyrk_matches_oracle(sim):
     ref.syrk(ref.ColMajor, ref.Upper, ref.Trans, 1.0, A, 0.5, Cr)
     assert relerr(Cs, Cr.astype(np.float64)) < 1e-6
     assert np.array_equal(np.tril(Cs, -1), np.tril(C, -1))
+
+
+# ------------------------------------------------------------------ seeded random problems ---
+
+@pytest.mark.parametrize("seed", range(60))
+def test_seeded_random_problems_every_routine_schedule_and_cache_size(sim, seed):
+    """Routine, flags, storage order, ragged extents, schedule options and the size of the tile cache drawn from
+    a seeded generator (k extents up to 30 tiles: every shape of the wide schedule's rounds), against the oracle."""
+    rng = np.random.default_rng(3000 + seed)
+    routine = ("gemm", "syrk", "syr2k", "symm", "trmm", "trsm")[seed % 6]
+    order = int(rng.choice(ORDERS))
+    uplo = int(rng.choice([blasx.Lower, blasx.Upper]))
+    trans, tb = int(rng.choice(TRANS)), int(rng.choice(TRANS))
+    side = int(rng.choice([blasx.Left, blasx.Right]))
+    diag = int(rng.choice([blasx.NonUnit, blasx.Unit]))
+    alpha = float(rng.choice([1.0, -0.5, 0.0, 2.0]))
+    beta = float(rng.choice([0.0, 1.0, -1.5]))
+    M, N, K = int(rng.integers(10, 130)), int(rng.integers(10, 130)), int(rng.integers(5, 480))
+    setup(sim, T=16, arena_tiles=int(rng.choice([64, 100, 200, 900])), seed=seed, group=int(rng.choice([0, 2, 5, 16])),
+          kchain=int(rng.choice([0, 0, 1, 3, 8])), wide=int(rng.choice([0, 2, 12])), ramp=int(rng.choice([0, 0, 1, 5, 8])),
+          depth=int(rng.choice([2, 6])), persist=int(rng.choice([0, 0, 1])))
+    tag = "%s order=%d M=%d N=%d K=%d uplo=%d trans=%d/%d side=%d diag=%d alpha=%g beta=%g" % (routine, order, M, N, K, uplo, trans, tb, side, diag, alpha, beta)
+    if routine == "gemm":
+        A = rng.uniform(-1, 1, (M, K) if trans == blasx.NoTrans else (K, M))
+        B = rng.uniform(-1, 1, (K, N) if tb == blasx.NoTrans else (N, K))
+        C = rng.uniform(-1, 1, (M, N))
+        As, Bs, Cs, Cr = store(A, order, 1), store(B, order, 2), store(C, order, 3), store(C, order, 3)
+        sim.dgemm(order, trans, tb, M, N, K, alpha, As, ld_of(As, order), Bs, ld_of(Bs, order), beta, Cs, ld_of(Cs, order))
+        ref.gemm(order, trans, tb, alpha, As, Bs, beta, Cr)
+        assert relerr(Cs, np.asarray(Cr)) < 1e-13, tag
+    elif routine in ("syrk", "syr2k"):
+        A = rng.uniform(-1, 1, (N, K) if trans == blasx.NoTrans else (K, N))
+        B = rng.uniform(-1, 1, A.shape)
+        C = rng.uniform(-1, 1, (N, N))
+        As, Bs, Cs, Cr = store(A, order, 1), store(B, order, 2), store(C, order, 3), store(C, order, 3)
+        if routine == "syrk":
+            sim.dsyrk(order, uplo, trans, N, K, alpha, As, ld_of(As, order), beta, Cs, ld_of(Cs, order))
+            ref.syrk(order, uplo, trans, alpha, As, beta, Cr)
+        else:
+            sim.dsyr2k(order, uplo, trans, N, K, alpha, As, ld_of(As, order), Bs, ld_of(Bs, order), beta, Cs, ld_of(Cs, order))
+            ref.syr2k(order, uplo, trans, alpha, As, Bs, beta, Cr)
+        assert relerr(Cs, np.asarray(Cr)) < 1e-13, tag
+    elif routine == "symm":
+        n = M if side == blasx.Left else N
+        A, B, C = rng.uniform(-1, 1, (n, n)), rng.uniform(-1, 1, (M, N)), rng.uniform(-1, 1, (M, N))
+        As, Bs, Cs, Cr = store(A, order, 1), store(B, order, 2), store(C, order, 3), store(C, order, 3)
+        sim.dsymm(order, side, uplo, M, N, alpha, As, ld_of(As, order), Bs, ld_of(Bs, order), beta, Cs, ld_of(Cs, order))
+        ref.symm(order, side, uplo, alpha, As, Bs, beta, Cr)
+        assert relerr(Cs, np.asarray(Cr)) < 1e-13, tag
+    else:
+        n = M if side == blasx.Left else N
+        P = poisoned(rng, n, uplo, diag, dominant=True)
+        if diag == blasx.Unit:
+            P = np.where(np.isnan(P), P, P / n)
+        B = rng.uniform(-1, 1, (M, N))
+        Ps, Bs, Br = store(P, order, 2), store(B, order, 1), store(B, order, 1)
+        alpha = alpha if alpha != 0.0 else 0.7
+        if routine == "trmm":
+            sim.dtrmm(order, side, uplo, trans, diag, M, N, alpha, Ps, ld_of(Ps, order), Bs, ld_of(Bs, order))
+            ref.trmm(order, side, uplo, trans, diag, alpha, Ps, Br)
+        else:
+            sim.dtrsm(order, side, uplo, trans, diag, M, N, alpha, Ps, ld_of(Ps, order), Bs, ld_of(Bs, order))
+            ref.trsm(order, side, uplo, trans, diag, alpha, Ps, Br)
+        assert np.all(np.isfinite(np.asarray(Bs))), tag
+        assert relerr(Bs, np.asarray(Br)) < 1e-12, tag
+    sim.set_option("persist", 0)
