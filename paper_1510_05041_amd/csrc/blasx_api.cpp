@@ -50,14 +50,18 @@ Library& lib() {
 // 1024 where the wide schedule applies (output and inner dimension from 12288 = 12 k-tiles: measured
 // 91.6 against 86.5 TFLOP/s at 12288, 110 against 101 at 14336, 123 against 105 at 16384, 131 against
 // 130 at 32768; below, 77 against 84 at 10240).  `inner` is 0 for the triangular routines.
-int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner) {
+// `solve_order` is the order of the triangular matrix of a TRSM (0 otherwise): the solve advances one
+// k-tile per round, so its update launches are one tile deep, and from 20 tiles of 1024 on the twice
+// as deep launches of 2048-tiles win (double precision, 1024 / 2048: 58.0 / 59.2 TFLOP/s at 20480,
+// 60.6 / 62.2 at 24576, 62.0 / 64.8 at 28672, 63.7 / 67.1 at 32768; 54.4 / 54.7 at 16384, 45.6 / 42.9 at 12288).
+int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solve_order = 0) {
     Library& L = lib();
     if (L.T > 0) return L.T;
     const int64_t n = std::max<int64_t>(1, std::max(rows, cols));
     const size_t es = dtype == 0 ? 8 : 4;
     const int64_t one_tile = (n + 15) / 16 * 16;
     int T;
-    if (dtype == 0) T = n >= 2048 ? 1024 : (int)one_tile;
+    if (dtype == 0) T = solve_order >= 20480 ? 2048 : n >= 2048 ? 1024 : (int)one_tile;
     else T = (n >= 12288 && inner >= 12288) ? 1024 : n >= 4096 ? 2048 : (int)std::min<int64_t>(2048, one_tile);
     // at least 64 tiles must fit in the cache (running set + operands), else eviction thrashes
     size_t usable = L.be ? L.be->arena_bytes() : 0;
@@ -294,7 +298,7 @@ int trsm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, in
         build_trmm(p, dtype, pick_tile(dtype, M, N, 0), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, 0.0, A, lda, B,
                    ldb, lib().order);
     } else {
-        build_trsm(p, dtype, pick_tile(dtype, M, N, 0), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+        build_trsm(p, dtype, pick_tile(dtype, M, N, 0, Side == BLASX_LEFT ? M : N), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
                    ldb, lib().order);
     }
     return run_problem(p);

@@ -543,6 +543,27 @@ def test_config4_dtrsm_left_lower_notrans_nonunit_residual(lib, schedule):
     assert res < TOL64, res
 
 
+def test_dtrsm_order_20480_takes_2048_tiles_residual(lib):
+    """A triangular matrix of order 20480: the automatic tile is 2048 (10 x 2 tiles, wide right-looking solve);
+    residual on sampled columns."""
+    M, N = 20480, 4096
+    configure(lib, T=0, nstreams=4, arena_gb=16.0, **AUTO)
+    A, ka = pinned(M, M, 6, synth.MAT_A)
+    synth.dominant_diag(A, 6, synth.MAT_A)
+    B, kb = pinned(M, N, 6, synth.MAT_B)
+    lib.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, M, N, 1.0, A, M, B, M)
+    assert lib.get_option("last_tile") == 2048 and lib.get_option("last_wide") == 1
+    cols = np.random.default_rng(6).choice(N, 8, replace=False)
+    X = np.asfortranarray(np.asarray(B)[:, cols])
+    assert np.all(np.isfinite(X))
+    R = X.copy(order="F")
+    ref.trmm(ref.ColMajor, ref.Left, ref.Lower, ref.NoTrans, ref.NonUnit, 1.0, np.asarray(A), R)
+    B0 = np.array([[synth.element(6, synth.MAT_B, i, int(j), M) for j in cols] for i in range(M)])
+    norm_a = np.sqrt(sum(float(np.dot(A[j:, j], A[j:, j])) for j in range(M)))
+    res = np.linalg.norm(R - B0) / (norm_a * np.linalg.norm(X))
+    assert res < TOL64, res
+
+
 def test_config5a_dgemm_trans_notrans_long_k_sampled(lib):
     """DGEMM Trans/NoTrans M=N=8192 K=65536 (A stored 65536 x 8192), alpha=beta=1, T=1024."""
     M = N = 8192
