@@ -18,7 +18,7 @@ import numpy as np
 
 from . import blasx
 
-ROUTINES = ("dgemm", "sgemm", "dsyrk", "dsyr2k", "dtrsm", "dtrmm", "dsymm")
+ROUTINES = ("dgemm", "sgemm", "dsyrk", "ssyrk", "dsyr2k", "ssyr2k", "dtrsm", "strsm", "dtrmm", "strmm", "dsymm", "ssymm")
 
 
 def _fill(a, seed):
