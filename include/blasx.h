@@ -124,7 +124,8 @@ int blasx_shutdown(void);
 /* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192, or
  * 0: chosen per call from the extent of the output matrix, the element type and the room in
  * the tile cache (double precision: 1024 from 2048 rows/columns up; single precision: 2048
- * from 4096, 1024 when output and inner dimensions are both at least 12288; double-precision
+ * from 4096, 1024 when output and inner dimensions (TRMM: the triangular matrix) are both at
+ * least 12288, TRSM always 2048; double-precision
  * TRSM with a triangular matrix of order 20480 or more: 2048; one tile per matrix
  * below; halved until 64 tiles fit in the cache).  The choice
  * of the latest call is blasx_get_option("last_tile").  The default is 1024. */

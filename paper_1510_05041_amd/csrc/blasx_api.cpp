@@ -49,7 +49,9 @@ Library& lib() {
 // the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 4096 up, but
 // 1024 where the wide schedule applies (output and inner dimension from 12288 = 12 k-tiles: measured
 // 91.6 against 86.5 TFLOP/s at 12288, 110 against 101 at 14336, 123 against 105 at 16384, 131 against
-// 130 at 32768; below, 77 against 84 at 10240).  `inner` is 0 for the triangular routines.
+// 130 at 32768; below, 77 against 84 at 10240; STRMM 1024 / 2048: 66.9 / 53.5 at 12288, 100.6 / 68.7 at 16384, 114.4 / 105.8
+// at 24576).  `inner` is 0 for the triangular solve, whose single-precision calls do better with 2048 throughout
+// (STRSM 1024 / 2048: 52.2 / 71.9 at 12288, 69.3 / 92.7 at 16384, 105.3 / 112.9 at 24576).
 // `solve_order` is the order of the triangular matrix of a TRSM (0 otherwise): the solve advances one
 // k-tile per round, so its update launches are one tile deep, and from 20 tiles of 1024 on the twice
 // as deep launches of 2048-tiles win (double precision, 1024 / 2048: 58.0 / 59.2 TFLOP/s at 20480,
@@ -278,7 +280,8 @@ int trmm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, in
     const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     Problem p;
-    build_trmm(p, dtype, pick_tile(dtype, M, N, 0), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+    // the k loop of the triangular product is as long as the triangular matrix is wide
+    build_trmm(p, dtype, pick_tile(dtype, M, N, Side == BLASX_LEFT ? M : N), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
                ldb, lib().order);
     return run_problem(p);
 }
