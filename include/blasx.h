@@ -139,7 +139,8 @@ int blasx_set_cache_bytes(size_t cap);
  *              small launches keeps the link busy, up to 16 from 16 x 16 tiles; 16 for the
  *              triangular routines); the choice of the latest call is "last_group"
  *   "kchain"   consecutive k-steps of a task fused into one launch (1..8; 1 = the paper's
- *              one kernel per (i,j,k)); 0 (default): 8 in the wide schedule, else 4
+ *              one kernel per (i,j,k)); 0 (default): 8 in the wide schedule, else 4 (the wide
+ *              triangular solve always takes one k-step per round)
  *   "wide"     least number of k-tiles per task from which ALL tasks of a call run together and
  *              advance k-chunk by k-chunk (an outer-product order: enough products per tile
  *              copied from the first launch on, C tiles fetched only for a task's last launch,
@@ -167,8 +168,9 @@ int blasx_set_cache_bytes(size_t cap);
  *              when a call returns
  * Returns BLASX_ERR_CONFIG for an unknown name or an out-of-range value. */
 int blasx_set_option(const char* name, long value);
-/* Reads a knob back; also "tile" and "cached_tiles" (blocks now held by the persistent cache).
- * -1 for an unknown name. */
+/* Reads a knob back; also "tile", "cached_tiles" (blocks now held by the persistent cache) and
+ * the choices of the latest call: "last_tile", "last_group", "last_kchain", "last_wide" (1: the
+ * wide schedule ran), "last_ramp".  -1 for an unknown name. */
 long blasx_get_option(const char* name);
 
 /* Persistent tile cache (the paper's applications multiply by the same matrices call after
