@@ -139,7 +139,9 @@ int blasx_set_cache_bytes(size_t cap);
  *              small launches keeps the link busy, up to 16 from 16 x 16 tiles; 16 for the
  *              triangular routines); the choice of the latest call is "last_group"
  *   "kchain"   consecutive k-steps of a task fused into one launch (1..8; 1 = the paper's
- *              one kernel per (i,j,k)); 0 (default): 8 in the wide schedule, else 4 (the wide
+ *              one kernel per (i,j,k)); 0 (default): 8 in the wide schedule (6 for 12 .. 15
+ *              k-tiles, which 8 would cut into two rounds only), else 4; TRMM: 1 up to 14 x 14
+ *              tiles in either schedule, 3 for 15 and 16, then as the others (the wide
  *              triangular solve always takes one k-step per round)
  *   "wide"     least number of k-tiles per task from which ALL tasks of a call run together and
  *              advance k-chunk by k-chunk (an outer-product order: enough products per tile
@@ -148,15 +150,16 @@ int blasx_set_cache_bytes(size_t cap);
  *              an accumulator tile per output tile; 0: never (tasks run to completion in
  *              groups, the paper's scheme).  Default 12.  TRSM uses it from a third of the
  *              value, one k-tile per round (a right-looking solve, every diagonal tile
- *              inverted before the first round); TRMM from two thirds of the value: it pins
- *              every original tile of B at once, copies each in when it is first needed, and
- *              runs its tasks shortest first.
+ *              inverted before the first round), and so does TRMM: it pins every original
+ *              tile of B at once, copies each in when it is first needed, and runs its tasks
+ *              shortest first.
  *   "ramp"     wide schedule: k-steps per task in the first round (1..8; 8 = as in every other
  *              round).  0 (default): the steps left over when the k loop is cut into rounds
  *              are taken in the first round rather than the last (a short last round cannot
  *              hide the result tiles leaving and the C tiles arriving); when nothing is left
  *              over the first full round is split into 2 steps and the rest (the device
- *              starts earlier); with fewer than two full rounds the first round stays full.
+ *              starts earlier); with fewer than two rounds' worth of steps the first round
+ *              stays full.
  *              The choice of the latest call is "last_ramp".
  *   "prefetch" wide schedule: inbound copies are started this many launches ahead (default 24)
  *   "depth"    launches the host may run ahead of the device (>= 1)

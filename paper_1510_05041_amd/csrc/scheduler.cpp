@@ -618,12 +618,11 @@ bool Scheduler::wide_fits(const Problem& p) {
     }
     // one launch per task leaves nothing to pipeline, and with barely more than one round the
     // grouped schedule (whose tasks finish one after the other) measures better
-    // (the triangular product, whose tasks the wide schedule sorts by length, pays from two thirds
-    // of that: +10 % at 10 x 10 tiles; the triangular solve, one k-tile per round with its
-    // inverses made up front, from a third: 5 x 5 tiles +10 %, 8 x 8 tiles +40 %)
-    const size_t least = p.results_are_operands ? ((size_t)cfg_.wide + 2) / 3
-                         : !p.panels.empty()    ? ((size_t)cfg_.wide * 2 + 2) / 3
-                                                : (size_t)cfg_.wide * (size_t)p.steps_per_k;
+    // (the triangular product, whose tasks the wide schedule sorts by length and advances one
+    // k-tile per round up to 14 tiles, and the triangular solve, one k-tile per round with its
+    // inverses made up front, pay from a third of that: 5 x 5 tiles +10 %, 8 x 8 tiles +40 .. +50 %)
+    const size_t least = p.results_are_operands || !p.panels.empty() ? ((size_t)cfg_.wide + 2) / 3
+                                                                     : (size_t)cfg_.wide * (size_t)p.steps_per_k;
     if (max_steps <= (size_t)kchain_ || max_steps < least) return false;
     // operand tiles of one full round (the left-over steps make a shorter round of their own)
     const size_t per_round = (uniq.size() * std::min<size_t>(kchain_, max_steps) + max_steps - 1) / max_steps;
@@ -1009,9 +1008,31 @@ int Scheduler::run(Problem& p) {
     // (shorter pipeline stages for the link-bound sizes), unless the caller fixed the number.
     // A triangular solve runs wide one k-step at a time (a right-looking solve): step k of every
     // task below block row k needs the results of block row k, which are solved in the same round.
-    kchain_ = p.results_are_operands ? 1 : cfg_.kchain ? cfg_.kchain : kMaxChain;
+    // Shorter chains where 8 would leave two rounds only: the device then waits for eight k-tiles
+    // of operands before its first launch and the results leave in two bursts, which the outbound
+    // link cannot absorb (one tile per 160 us).  12 .. 15 k-tiles: 6 per launch, which with the
+    // short first round below gives three rounds (DSYRK / DSYMM at 12 and 14 k-tiles: +7 .. +14 %;
+    // DGEMM, which is bound by its inbound bytes there: unchanged).
+    // The triangular product has half the products per byte of the others, so it is bound by the
+    // link up to twice the order, and its tasks differ in length: one k-tile per launch lets every
+    // launch start as soon as its own few tiles have landed and lets the short tasks' results
+    // leave from the first round on (grouped, single precision, 3 x 3 and 4 x 4 tiles of 2048:
+    // +30 / +44 % over chains of 4; wide, 5 .. 8 tiles: +10 .. +50 % over grouped; 9 .. 14 tiles:
+    // +15 .. +35 % over chains of 8).  15 and 16 tiles: 3 per launch (+1 .. +2 %); from there on 8
+    // is as good or better.
+    size_t longest = 0;
+    for (const Task& t : p.tasks) longest = std::max(longest, t.steps.size());
+    const bool tri_product = !p.panels.empty();
+    int wide_chain = kMaxChain, grouped_chain = 4;
+    if (tri_product) {
+        wide_chain = longest <= 14 ? 1 : longest <= 16 ? 3 : kMaxChain;
+        if (longest <= 14) grouped_chain = 1;
+    } else if (longest >= 12 && longest < 16) {
+        wide_chain = 6;
+    }
+    kchain_ = p.results_are_operands ? 1 : cfg_.kchain ? cfg_.kchain : wide_chain;
     wide_ = cfg_.wide > 0 && (int)ntasks > cfg_.group && wide_fits(p);
-    if (!wide_) kchain_ = cfg_.kchain ? cfg_.kchain : 4;
+    if (!wide_) kchain_ = cfg_.kchain ? cfg_.kchain : grouped_chain;
     // Length of the first round.  The last round is the one in which every result tile leaves and
     // every late C tile arrives: a short one cannot hide that traffic (measured at 8 k-steps per
     // round: a last round of 1 / 2 / 3 / 4 / 5 / 6 steps costs 20 / 18 / 14 / 8 / 4 / 1 % of the

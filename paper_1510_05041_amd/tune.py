@@ -76,12 +76,24 @@ def _problem(lib, routine, n, k):
     raise ValueError(routine)
 
 
-def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=12, kchain=0, ramp=0):
+def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=12, kchain=0, ramp=0, warmup_s=2.0):
     lib = blasx.default()
     results = []
+    warm = False
     for n in sizes:
         k = kdim or n
         call, flop, refresh, owners = _problem(lib, routine, n, k)
+        if not warm:
+            # The first calls of a process can run with inbound and outbound copies taking turns instead of
+            # overlapping (seen for up to eight calls, then never again in that process): keep them out of the table.
+            lib.init(int(arena_gb * 2 ** 30), nstreams=streams[0])
+            lib.set_tile(0)
+            t_end = time.perf_counter() + warmup_s
+            while time.perf_counter() < t_end:
+                if refresh:
+                    refresh()
+                call()
+            warm = True
         for ns in streams:
             for T in tiles:
                 for g in groups:
@@ -147,12 +159,13 @@ def main(argv=None):
     ap.add_argument("--wide", type=int, default=12, help="option \"wide\": least k-steps per task for which all tasks advance together; 0: never")
     ap.add_argument("--kchain", type=int, default=0, help="option \"kchain\": k-tiles per launch and task; 0: the library's choice")
     ap.add_argument("--ramp", type=int, default=0, help="option \"ramp\": k-steps per task in the first round of the wide schedule (8: as in the others); 0: the library's choice")
+    ap.add_argument("--warmup-s", type=float, default=2.0, help="seconds of untimed calls of the first problem before anything is timed")
     ap.add_argument("--out", default="", help="also append the JSON records to this file")
     a = ap.parse_args(argv)
     ints = lambda s: [int(x) for x in s.split(",") if x]
     sizes, tiles, streams, groups = ints(a.sizes), ints(a.tiles), ints(a.streams), ints(a.groups)
     out = open(a.out, "a") if a.out else None
-    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out, a.wide, a.kchain, a.ramp)
+    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out, a.wide, a.kchain, a.ramp, a.warmup_s)
     print()
     print(tables(res, tiles, streams))
 

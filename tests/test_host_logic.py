@@ -467,24 +467,25 @@ def test_wide_mode_gemm_matches_oracle(sim, order, ta, tb, M, N, K, kchain):
     assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N)        # every tile exactly once, C included
 
 
-@pytest.mark.parametrize("ktiles,ramp,expect", [(19, 0, 3), (16, 0, 2), (24, 0, 2), (13, 0, 8), (19, 8, 8), (19, 5, 5), (17, 0, 1)])
+@pytest.mark.parametrize("ktiles,ramp,expect", [(19, 0, 3), (16, 0, 2), (24, 0, 2), (13, 0, 1), (12, 0, 2), (15, 0, 3), (19, 8, 8), (19, 5, 5), (17, 0, 1)])
 def test_wide_mode_first_round_takes_the_odd_steps(sim, ktiles, ramp, expect):
-    """The k loop is cut into rounds of 8 steps; what is left over goes into the first round (or 2 steps when
-    nothing is left over), never the last; with fewer than two full rounds the first stays full."""
+    """The k loop is cut into rounds of 8 steps (6 for 12 .. 15 k-tiles, which would otherwise make two rounds only);
+    what is left over goes into the first round (or 2 steps when nothing is left over), never the last."""
     M, N, K = 48, 40, 16 * ktiles - 5
     setup(sim, T=16, arena_tiles=800, seed=ktiles + ramp, wide=2, group=2, kchain=0, ramp=ramp)
     rng = np.random.default_rng(ktiles)
     A, B, C = fmat(rng, M, K), fmat(rng, K, N), fmat(rng, M, N)
     want = A @ B - 2.0 * C
     sim.dgemm(CM, NT, NT, M, N, K, 1.0, A, M, B, K, -2.0, C, M)
-    assert sim.get_option("last_wide") == 1 and sim.get_option("last_kchain") == 8
+    kc = 6 if 12 <= ktiles < 16 else 8
+    assert sim.get_option("last_wide") == 1 and sim.get_option("last_kchain") == kc
     assert sim.get_option("last_ramp") == expect
     assert np.array_equal(C, want)                       # small integers: exact in any order
     st = sim.get_stats()
     assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N)
     # 9 tasks = one launch per round: the odd steps first, then full rounds (nothing left over and no explicit
     # request: the first full round is split into 2 + 6, the same number of rounds as 2 + 8 + ... + 6)
-    rounds = 1 + -(-(ktiles - expect) // 8) if expect < 8 else -(-ktiles // 8)
+    rounds = 1 + -(-(ktiles - expect) // kc) if expect < kc else -(-ktiles // kc)
     assert st["tasks"] == 9 and st["launches"] == rounds
 
 
