@@ -123,11 +123,12 @@ int blasx_shutdown(void);
 
 /* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192, or
  * 0: chosen per call from the extent of the output matrix, the element type and the room in
- * the tile cache (double precision: 1024 from 2048 rows/columns up; single precision: 2048
- * from 4096, 1024 when output and inner dimensions (TRMM: the triangular matrix) are both at
- * least 12288, TRSM always 2048; double-precision
- * TRSM with a triangular matrix of order 20480 or more: 2048; one tile per matrix
- * below; halved until 64 tiles fit in the cache).  The choice
+ * the tile cache (double precision: 1024 from 2048 rows/columns up, one tile per matrix below;
+ * single precision: 1024 above 2048 rows/columns, 2048 from 5120, 1024 again when output and
+ * inner dimensions are both at least 12288; STRMM: 1024 throughout.  By the order of the
+ * triangular matrix: TRSM and DTRMM 512 for 2560 .. 4096 (five block rows, from which all
+ * tasks advance together); STRSM 1024 for 4097 .. 12288, 2048 above; DTRSM 2048 from 20480.
+ * Halved until 64 tiles fit in the cache).  The choice
  * of the latest call is blasx_get_option("last_tile").  The default is 1024. */
 int blasx_set_tile(int T);
 /* Cap on the bytes of the arena that the tile cache may use (0 = all of it); lowers the

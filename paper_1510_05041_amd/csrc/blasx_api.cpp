@@ -46,25 +46,48 @@ Library& lib() {
 // operands, running-set size chosen by pick_group): a tile must be large enough that the fixed
 // cost of one strided copy (~10 us on the copy engine) is small beside its transfer time; 1024
 // (8 MB in double precision) is, and stays best down to 2 x 2 tiles; larger tiles only shorten
-// the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 4096 up, but
+// the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 5120 up, but
 // 1024 where the wide schedule applies (output and inner dimension from 12288 = 12 k-tiles: measured
 // 91.6 against 86.5 TFLOP/s at 12288, 110 against 101 at 14336, 123 against 105 at 16384, 131 against
 // 130 at 32768; below, 77 against 84 at 10240; STRMM 1024 / 2048: 66.9 / 53.5 at 12288, 100.6 / 68.7 at 16384, 114.4 / 105.8
-// at 24576).  `inner` is 0 for the triangular solve, whose single-precision calls do better with 2048 throughout
-// (STRSM 1024 / 2048: 52.2 / 71.9 at 12288, 69.3 / 92.7 at 16384, 105.3 / 112.9 at 24576).
+// at 24576).  `inner` is 0 for the triangular solve, whose large single-precision calls do better with 2048
+// (STRSM 1024 / 2048: 105.3 / 112.9 TFLOP/s at 24576).
 // `solve_order` is the order of the triangular matrix of a TRSM (0 otherwise): the solve advances one
 // k-tile per round, so its update launches are one tile deep, and from 20 tiles of 1024 on the twice
 // as deep launches of 2048-tiles win (double precision, 1024 / 2048: 58.0 / 59.2 TFLOP/s at 20480,
 // 60.6 / 62.2 at 24576, 62.0 / 64.8 at 28672, 63.7 / 67.1 at 32768; 54.4 / 54.7 at 16384, 45.6 / 42.9 at 12288).
-int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solve_order = 0) {
+// Small triangular calls take the tile that gives them the five block rows from which the wide schedule
+// runs.  Orders 2560 .. 4096, 512 / 1024: DTRSM 2.67 / 3.52 ms at 2560, 3.70 / 4.57 at 3072, 4.69 / 5.77 at 3584,
+// 6.06 / 6.98 at 4096 (7.42 / 7.01 at 4608, 3.08 / 2.64 at 2048); DTRMM 2.46 / 2.85 at 2560, 3.39 / 3.89 at 3072,
+// 5.70 / 6.50 at 4096 (7.09 / 6.50 at 4608); STRSM 1.73 / 2.25 at 2560, 2.33 / 2.82 at 3072, 3.97 / 4.32 at 4096
+// (4.73 / 4.02 at 4608); STRMM the same either way (1.57 / 1.61, 2.12 / 2.14, 3.65 / 3.52), so it keeps 1024.
+// Single-precision solves of orders 4097 .. 12288: 1024 (1024 / 2048: 4.62 / 6.08 ms at 5120, 6.34 / 8.58 at 6144,
+// 10.43 / 14.33 at 8192, 15.77 / 16.96 at 10240, 23.37 / 23.60 at 12288; 33.5 / 33.0 at 14336, 46.7 / 44.8 at 16384).
+// The single-precision triangular product: 1024 throughout (1024 / 2048: 4.25 / 5.76 ms at 5120, 5.82 / 7.85 at
+// 6144, 9.9 / 13.8 at 8192, 15.3 / 16.3 at 10240, 18.7 / 19.5 at 11264).  Single precision otherwise, below 5120:
+// 1024 (1024 / 2048 at 3072 and 4096: SGEMM 2.81 / 2.86 and 4.75 / 4.97 ms, SSYRK 1.79 / 2.22 and 2.87 / 3.42, SSYR2K
+// 2.82 / 3.35 and 4.66 / 5.25, SSYMM 2.58 / 2.86 and 4.49 / 4.66; at 5120: SGEMM 7.27 / 6.97, SSYMM 7.19 / 6.68,
+// SSYR2K 7.59 / 7.28, SSYRK 4.30 / 4.53; double precision 512 / 1024: DGEMM 3.27 / 2.57 at 2048, 10.5 / 8.8 at 4096).
+int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solve_order = 0, bool tri_product = false) {
     Library& L = lib();
     if (L.T > 0) return L.T;
     const int64_t n = std::max<int64_t>(1, std::max(rows, cols));
     const size_t es = dtype == 0 ? 8 : 4;
     const int64_t one_tile = (n + 15) / 16 * 16;
+    const bool five_rows_of_512 = solve_order >= 2560 && solve_order <= 4096;
     int T;
-    if (dtype == 0) T = solve_order >= 20480 ? 2048 : n >= 2048 ? 1024 : (int)one_tile;
-    else T = (n >= 12288 && inner >= 12288) ? 1024 : n >= 4096 ? 2048 : (int)std::min<int64_t>(2048, one_tile);
+    if (dtype == 0) {
+        if (solve_order >= 20480) T = 2048;
+        else if (five_rows_of_512 || (tri_product && inner >= 2560 && inner <= 4096)) T = 512;
+        else T = n >= 2048 ? 1024 : (int)one_tile;
+    } else {
+        if (solve_order > 12288) T = 2048;
+        else if (five_rows_of_512) T = 512;
+        else if (solve_order > 4096) T = 1024;
+        else if (n >= 12288 && inner >= 12288) T = 1024;
+        else if (n >= 5120 && !tri_product) T = 2048;
+        else T = n > 2048 ? 1024 : (int)std::min<int64_t>(2048, one_tile);
+    }
     // at least 64 tiles must fit in the cache (running set + operands), else eviction thrashes
     size_t usable = L.be ? L.be->arena_bytes() : 0;
     if (L.cache_cap && L.cache_cap < usable) usable = L.cache_cap;
@@ -281,7 +304,7 @@ int trmm_impl(int dtype, int Order, int Side, int Uplo, int TransA, int Diag, in
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
     Problem p;
     // the k loop of the triangular product is as long as the triangular matrix is wide
-    build_trmm(p, dtype, pick_tile(dtype, M, N, Side == BLASX_LEFT ? M : N), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
+    build_trmm(p, dtype, pick_tile(dtype, M, N, Side == BLASX_LEFT ? M : N, 0, true), left, lower, is_trans(TransA), Diag == BLASX_UNIT, col ? M : N, col ? N : M, alpha, A, lda, B,
                ldb, lib().order);
     return run_problem(p);
 }

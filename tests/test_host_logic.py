@@ -662,9 +662,29 @@ def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
     assert chosen(sim.dgemm, 2000, 16) == 2000
     assert chosen(sim.dgemm, 100, 50) == 112     # one tile, rounded up to the kernel's granule
     assert chosen(sim.sgemm, 32768, 16, np.float32) == 2048      # inner dimension 1: not the wide schedule's case
-    assert chosen(sim.sgemm, 4096, 16, np.float32) == 2048
-    assert chosen(sim.sgemm, 3000, 16, np.float32) == 2048
+    assert chosen(sim.sgemm, 5120, 16, np.float32) == 2048
+    assert chosen(sim.sgemm, 4096, 16, np.float32) == 1024       # single precision below 5120: 1024
+    assert chosen(sim.sgemm, 3000, 16, np.float32) == 1024
+    assert chosen(sim.sgemm, 2048, 16, np.float32) == 2048       # one tile
     assert chosen(sim.sgemm, 1500, 16, np.float32) == 1504
+
+    # the triangular solve: the tile that gives a small solve five block rows (the wide schedule's least)
+    def solve_tile(fn, n, dtype):
+        L = np.asfortranarray(np.eye(n, dtype=dtype))
+        B = np.ones((n, 16), dtype=dtype, order="F")
+        fn(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, n, 16, 1.0, L, n, B, n)
+        assert np.all(B == 1.0)
+        return sim.get_option("last_tile")
+
+    assert [solve_tile(sim.dtrsm, n, np.float64) for n in (2048, 2560, 4096)] == [1024, 512, 512]
+    assert solve_tile(sim.strsm, 5120, np.float32) == 1024
+    assert solve_tile(sim.strsm, 2560, np.float32) == 512
+    assert solve_tile(sim.dtrmm, 2560, np.float64) == 512 and solve_tile(sim.dtrmm, 2048, np.float64) == 1024
+    # the triangular product in single precision: 1024 whatever the order
+    Ltri = np.asfortranarray(np.eye(5120, dtype=np.float32))
+    Btri = np.ones((5120, 16), dtype=np.float32, order="F")
+    sim.strmm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, 5120, 16, 1.0, Ltri, 5120, Btri, 5120)
+    assert np.all(Btri == 1.0) and sim.get_option("last_tile") == 1024
     # a small cache: halve the tile until 64 tiles fit
     sim.set_cache_bytes(64 * 2 ** 20)
     assert chosen(sim.dgemm, 8192, 16) == 256
