@@ -106,7 +106,12 @@ int pick_group(const Problem& p) {
     Library& L = lib();
     if (L.cfg.group > 0) return L.cfg.group;
     if (!p.panels.empty() || p.results_are_operands) return 16;   // TRMM / TRSM: parallelism is per dependency level
-    const size_t want = std::min<size_t>(16, std::max<size_t>(2, p.tasks.size() / 8));
+    size_t want = std::min<size_t>(16, std::max<size_t>(2, p.tasks.size() / 8));
+    // From 5 x 5 tiles of up to 8 MB at least 4 (2 / 4 tasks, ms: DSYRK 11.0 / 12.2 at N = 6144, 17.3 / 14.7 at 7168;
+    // DSYR2K 14.1 / 12.3 at 5120, 31.7 / 25.2 at 7168; DGEMM 13.5 / 13.2 at 5120); not for tiles of 16 MB, whose
+    // copies take twice as long (SSYRK N = 10240, 5 x 5 tiles of 2048: 14.9 / 17.1; SGEMM 25.7 / 27.2).
+    const int64_t side = std::max((p.c_rows + p.T - 1) / p.T, (p.c_cols + p.T - 1) / p.T);
+    if (side >= 5 && (size_t)p.T * p.T * p.esize <= ((size_t)8 << 20)) want = std::max<size_t>(want, 4);
     int g = 2;
     while ((size_t)g * 2 <= want) g *= 2;
     return g;

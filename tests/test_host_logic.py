@@ -689,10 +689,10 @@ def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
     sim.set_cache_bytes(64 * 2 ** 20)
     assert chosen(sim.dgemm, 8192, 16) == 256
     sim.set_cache_bytes(0)
-    # the running set: 2 for a few tiles, 16 from 16 x 16 tiles, 16 for the triangular routines
+    # the running set: 2 for a few tiles, 4 from 5 x 5, 16 from 16 x 16 tiles, 16 for the triangular routines
     sim.set_option("group", 0)
     sim.set_tile(16)
-    for n, g in ((32, 2), (64, 2), (96, 4), (128, 8), (192, 16), (400, 16)):
+    for n, g in ((32, 2), (64, 2), (80, 4), (96, 4), (128, 8), (192, 16), (400, 16)):   # at least 4 from 5 x 5 tiles
         assert chosen(sim.dgemm, n, n) == 16 and sim.get_option("last_group") == g, n
     L = np.asfortranarray(np.tril(np.ones((64, 64))) + 63 * np.eye(64))
     B = np.ones((64, 32), order="F")
