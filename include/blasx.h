@@ -124,8 +124,8 @@ int blasx_shutdown(void);
 /* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192, or
  * 0: chosen per call from the extent of the output matrix, the element type and the room in
  * the tile cache (double precision: 1024 from 2048 rows/columns up, one tile per matrix below;
- * single precision: 1024 above 2048 rows/columns, 2048 from 5120, 1024 again when output and
- * inner dimensions are both at least 12288; STRMM: 1024 throughout.  By the order of the
+ * single precision: 1024 above 2048 rows/columns, 2048 from 6656, 1024 again when output and
+ * inner dimensions are both at least 11264; STRMM: 1024 throughout.  By the order of the
  * triangular matrix: TRSM and DTRMM 512 for 2560 .. 4096 (five block rows, from which all
  * tasks advance together); STRSM 1024 for 4097 .. 12288, 2048 above; DTRSM 2048 from 20480.
  * Halved until 64 tiles fit in the cache).  The choice

@@ -46,8 +46,8 @@ Library& lib() {
 // operands, running-set size chosen by pick_group): a tile must be large enough that the fixed
 // cost of one strided copy (~10 us on the copy engine) is small beside its transfer time; 1024
 // (8 MB in double precision) is, and stays best down to 2 x 2 tiles; larger tiles only shorten
-// the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 5120 up, but
-// 1024 where the wide schedule applies (output and inner dimension from 12288 = 12 k-tiles: measured
+// the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 6656 up, but
+// 1024 where the wide schedule applies or nearly (output and inner dimension from 11264; at 12288 = 12 k-tiles measured
 // 91.6 against 86.5 TFLOP/s at 12288, 110 against 101 at 14336, 123 against 105 at 16384, 131 against
 // 130 at 32768; below, 77 against 84 at 10240; STRMM 1024 / 2048: 66.9 / 53.5 at 12288, 100.6 / 68.7 at 16384, 114.4 / 105.8
 // at 24576).  `inner` is 0 for the triangular solve, whose large single-precision calls do better with 2048
@@ -63,6 +63,11 @@ Library& lib() {
 // (4.73 / 4.02 at 4608); STRMM the same either way (1.57 / 1.61, 2.12 / 2.14, 3.65 / 3.52), so it keeps 1024.
 // Single-precision solves of orders 4097 .. 12288: 1024 (1024 / 2048: 4.62 / 6.08 ms at 5120, 6.34 / 8.58 at 6144,
 // 10.43 / 14.33 at 8192, 15.77 / 16.96 at 10240, 23.37 / 23.60 at 12288; 33.5 / 33.0 at 14336, 46.7 / 44.8 at 16384).
+// Between 5120 and 11264 the other single-precision routines differ (1024 / 2048, ms, running set as chosen:
+// 5120: SGEMM 7.13 / 6.98, SSYRK 4.19 / 4.54, SSYMM 6.28 / 6.68, SSYR2K 6.60 / 7.28; 6144: 10.29 / 9.89, 5.91 / 6.40,
+// 8.91 / 9.25, 10.15 / 10.33; 8192: 18.83 / 17.16, 10.30 / 10.29, 16.30 / 16.51, 17.85 / 17.02; 10240: 27.81 / 25.61,
+// 15.91 / 14.95, 25.43 / 25.40, 28.42 / 26.63; 11264: 34.75 / 35.00, 19.24 / 19.76, 32.56 / 33.81, 34.45 / 35.92):
+// 1024 below 6656 and from 11264, 2048 between.
 // The single-precision triangular product: 1024 throughout (1024 / 2048: 4.25 / 5.76 ms at 5120, 5.82 / 7.85 at
 // 6144, 9.9 / 13.8 at 8192, 15.3 / 16.3 at 10240, 18.7 / 19.5 at 11264).  Single precision otherwise, below 5120:
 // 1024 (1024 / 2048 at 3072 and 4096: SGEMM 2.81 / 2.86 and 4.75 / 4.97 ms, SSYRK 1.79 / 2.22 and 2.87 / 3.42, SSYR2K
@@ -84,8 +89,8 @@ int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solv
         if (solve_order > 12288) T = 2048;
         else if (five_rows_of_512) T = 512;
         else if (solve_order > 4096) T = 1024;
-        else if (n >= 12288 && inner >= 12288) T = 1024;
-        else if (n >= 5120 && !tri_product) T = 2048;
+        else if (n >= 11264 && inner >= 11264) T = 1024;
+        else if (n >= 6656 && !tri_product) T = 2048;
         else T = n > 2048 ? 1024 : (int)std::min<int64_t>(2048, one_tile);
     }
     // at least 64 tiles must fit in the cache (running set + operands), else eviction thrashes

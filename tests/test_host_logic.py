@@ -662,7 +662,8 @@ def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
     assert chosen(sim.dgemm, 2000, 16) == 2000
     assert chosen(sim.dgemm, 100, 50) == 112     # one tile, rounded up to the kernel's granule
     assert chosen(sim.sgemm, 32768, 16, np.float32) == 2048      # inner dimension 1: not the wide schedule's case
-    assert chosen(sim.sgemm, 5120, 16, np.float32) == 2048
+    assert chosen(sim.sgemm, 6656, 16, np.float32) == 2048
+    assert chosen(sim.sgemm, 6144, 16, np.float32) == 1024
     assert chosen(sim.sgemm, 4096, 16, np.float32) == 1024       # single precision below 5120: 1024
     assert chosen(sim.sgemm, 3000, 16, np.float32) == 1024
     assert chosen(sim.sgemm, 2048, 16, np.float32) == 2048       # one tile
