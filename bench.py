@@ -53,7 +53,7 @@ def main():
     ap.add_argument("--shells", type=int, default=None)
     ap.add_argument("--rs", type=int, default=None)
     ap.add_argument("--prefetch", type=int, default=None)
-    ap.add_argument("--wide", type=int, default=None, help="least k-steps per task for which all tasks advance together when the cache has room (default 12); 0: grouped")
+    ap.add_argument("--wide", type=int, default=None, help="least k-steps per task for which all tasks advance together when the cache has room (default 11); 0: grouped")
     ap.add_argument("--arena-gb", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check", action="store_true", help="also compare sampled outputs with the oracle")

@@ -142,7 +142,7 @@ int blasx_set_cache_bytes(size_t cap);
  *              latest call is "last_group"
  *   "kchain"   consecutive k-steps of a task fused into one launch (1..8; 1 = the paper's
  *              one kernel per (i,j,k)); 0 (default): 8 in the wide schedule (6 for 12 .. 15
- *              k-tiles, which 8 would cut into two rounds only), else 4; TRMM: 1 up to 14 x 14
+ *              k-tiles, which 8 would cut into two rounds only, 4 for 11), else 4; TRMM: 1 up to 14 x 14
  *              tiles in either schedule, 3 for 15 and 16, then as the others (the wide
  *              triangular solve always takes one k-step per round)
  *   "wide"     least number of k-tiles per task from which ALL tasks of a call run together and
@@ -150,7 +150,7 @@ int blasx_set_cache_bytes(size_t cap);
  *              copied from the first launch on, C tiles fetched only for a task's last launch,
  *              results leaving during the whole last round), provided the cache has room for
  *              an accumulator tile per output tile; 0: never (tasks run to completion in
- *              groups, the paper's scheme).  Default 12.  TRSM uses it from a third of the
+ *              groups, the paper's scheme).  Default 11.  TRSM uses it from a third of the
  *              value, one k-tile per round (a right-looking solve, every diagonal tile
  *              inverted before the first round), and so does TRMM: it pins every original
  *              tile of B at once, copies each in when it is first needed, and runs its tasks

@@ -1029,6 +1029,11 @@ int Scheduler::run(Problem& p) {
         if (longest <= 14) grouped_chain = 1;
     } else if (longest >= 12 && longest < 16) {
         wide_chain = 6;
+    } else if (longest >= 9 && longest < 12) {
+        // 11 k-tiles (the least for the wide schedule by default): rounds of 3 + 4 + 4 against the
+        // grouped schedule: DGEMM 62.9 / 65.3 ms, DSYMM 55.6 / 60.5, DSYRK 34.6 / 35.6, SSYMM 30.1 / 32.6.
+        // (9 and 10 k-tiles, reachable through option "wide": within +-4 % of the grouped schedule.)
+        wide_chain = 4;
     }
     kchain_ = p.results_are_operands ? 1 : cfg_.kchain ? cfg_.kchain : wide_chain;
     wide_ = cfg_.wide > 0 && (int)ntasks > cfg_.group && wide_fits(p);

@@ -76,7 +76,7 @@ def _problem(lib, routine, n, k):
     raise ValueError(routine)
 
 
-def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=12, kchain=0, ramp=0, warmup_s=2.0):
+def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=11, kchain=0, ramp=0, warmup_s=2.0):
     lib = blasx.default()
     results = []
     warm = False
@@ -156,7 +156,7 @@ def main(argv=None):
     ap.add_argument("--groups", default="16")
     ap.add_argument("--reps", type=int, default=3)
     ap.add_argument("--arena-gb", type=float, default=24.0)
-    ap.add_argument("--wide", type=int, default=12, help="option \"wide\": least k-steps per task for which all tasks advance together; 0: never")
+    ap.add_argument("--wide", type=int, default=11, help="option \"wide\": least k-steps per task for which all tasks advance together; 0: never")
     ap.add_argument("--kchain", type=int, default=0, help="option \"kchain\": k-tiles per launch and task; 0: the library's choice")
     ap.add_argument("--ramp", type=int, default=0, help="option \"ramp\": k-steps per task in the first round of the wide schedule (8: as in the others); 0: the library's choice")
     ap.add_argument("--warmup-s", type=float, default=2.0, help="seconds of untimed calls of the first problem before anything is timed")

@@ -402,7 +402,7 @@ def c_before(seed, mat, rows):
     return lambda gi, gj: np.array([[synth.element(seed, mat, int(i), int(j), rows) for j in gj] for i in gi])
 
 
-AUTO = dict(group=0, kchain=0, wide=12)      # the library's own choices: what bench.py times
+AUTO = dict(group=0, kchain=0, wide=11)      # the library's own choices: what bench.py times
 
 
 @pytest.mark.parametrize("schedule", ["grouped", "auto"])
