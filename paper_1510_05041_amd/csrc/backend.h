@@ -54,5 +54,7 @@ public:
 Backend* make_backend(void* arena, size_t bytes, void* const* streams, int nstreams, std::string* err);
 void* backend_host_alloc(size_t bytes);
 int   backend_host_free(void* p);
+// Frees device memory that the backend allocated itself and kept for a later init (blasx_shutdown).
+void  backend_release_device_memory();
 
 }  // namespace blasx

@@ -418,6 +418,7 @@ int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int ns
 int blasx_shutdown(void) {
     lib().sched.reset();
     lib().be.reset();
+    backend_release_device_memory();
     return 0;
 }
 

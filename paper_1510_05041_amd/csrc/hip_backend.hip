@@ -120,7 +120,6 @@ public:
         for (hipEvent_t e : events_) (void)hipEventDestroy(e);
         for (size_t s = 0; s < streams_.size(); ++s)
             if (own_stream_[s]) (void)hipStreamDestroy(streams_[s]);
-        if (own_arena_ && arena_) (void)hipFree(arena_);
     }
 
     int init(void* arena, size_t bytes, void* const* streams, int nstreams) {
@@ -130,10 +129,23 @@ public:
         }
         if (arena) {
             arena_ = static_cast<char*>(arena);
-            own_arena_ = false;
         } else {
-            HB_CHECK(hipMalloc(reinterpret_cast<void**>(&arena_), bytes));
-            own_arena_ = true;
+            // An arena the library allocates itself is kept for the next init on the device and
+            // freed by backend_release_device_memory() only: while the driver clears freed device
+            // memory, outbound copies run at half their rate (measured: 29.7 instead of 53.6 GB/s
+            // for 0.3 s after 8 GiB were freed, for 1.5 s after 48 GiB).
+            int dev = 0;
+            HB_CHECK(hipGetDevice(&dev));
+            OwnArena& kept = own_arenas()[dev];
+            if (kept.ptr && kept.bytes < bytes) {
+                (void)hipFree(kept.ptr);
+                kept = OwnArena();
+            }
+            if (!kept.ptr) {
+                HB_CHECK(hipMalloc(reinterpret_cast<void**>(&kept.ptr), bytes));
+                kept.bytes = bytes;
+            }
+            arena_ = kept.ptr;
         }
         bytes_ = bytes;
         for (int s = 0; s < nstreams; ++s) {
@@ -161,6 +173,14 @@ public:
         return 0;
     }
 
+    struct OwnArena {
+        char* ptr = nullptr;
+        size_t bytes = 0;
+    };
+    static std::map<int, OwnArena>& own_arenas() {
+        static std::map<int, OwnArena> m;
+        return m;
+    }
     static std::map<int, std::vector<hipStream_t>>& own_streams() {
         static std::map<int, std::vector<hipStream_t>> m;
         return m;
@@ -277,7 +297,6 @@ public:
 private:
     char* arena_ = nullptr;
     size_t bytes_ = 0;
-    bool own_arena_ = false;
     std::vector<hipStream_t> streams_;
     std::vector<bool> own_stream_;
     std::vector<hipEvent_t> events_;
@@ -302,5 +321,12 @@ void* backend_host_alloc(size_t bytes) {
 }
 
 int backend_host_free(void* p) { return hipHostFree(p) == hipSuccess ? 0 : 1; }
+
+void backend_release_device_memory() {
+    for (auto& kv : HipBackend::own_arenas()) {
+        if (kv.second.ptr) (void)hipFree(kv.second.ptr);
+        kv.second = HipBackend::OwnArena();
+    }
+}
 
 }  // namespace blasx

@@ -84,8 +84,8 @@ def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None
         k = kdim or n
         call, flop, refresh, owners = _problem(lib, routine, n, k)
         if not warm:
-            # The first calls of a process can run with inbound and outbound copies taking turns instead of
-            # overlapping (seen for up to eight calls, then never again in that process): keep them out of the table.
+            # While the driver clears device memory that was freed just before (by the process that ran before this
+            # one, say), outbound copies run at half rate: 1.5 s for 48 GiB.  Keep those calls out of the table.
             lib.init(int(arena_gb * 2 ** 30), nstreams=streams[0])
             lib.set_tile(0)
             t_end = time.perf_counter() + warmup_s

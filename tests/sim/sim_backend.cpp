@@ -363,6 +363,8 @@ Backend* make_backend(void* arena, size_t bytes, void* const* streams, int nstre
 }
 
 void* backend_host_alloc(size_t bytes) { return std::malloc(bytes); }
+void backend_release_device_memory() {}
+
 int backend_host_free(void* p) {
     std::free(p);
     return 0;

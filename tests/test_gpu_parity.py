@@ -70,6 +70,30 @@ def test_config1_dgemm_1024_tile256_two_streams_full_output(lib):
     assert st["bytes_h2d"] == 3 * 8 * n * n and st["bytes_d2h"] == 8 * n * n
 
 
+def test_arena_and_streams_of_the_library_itself_across_inits(lib):
+    """blasx_init with no arena and no streams: the library allocates both; a later init with a smaller
+    or equal arena uses the kept one again, a larger one replaces it, blasx_shutdown frees it."""
+    n = 640
+    A, ka = pinned(n, n, 3, synth.MAT_A)
+    B, kb = pinned(n, n, 3, synth.MAT_B)
+    C, kc = pinned(n, n, 3, synth.MAT_C)
+    C0 = np.array(C, order="F")
+    want = np.array(C0, order="F")
+    ref.gemm(ref.ColMajor, ref.NoTrans, ref.NoTrans, 1.0, np.asarray(A), np.asarray(B), -1.0, want)
+    for step, mib in enumerate((256, 128, 256, 512, 64)):
+        if step == 4:
+            lib.shutdown()
+        lib.init_raw(mib * 2 ** 20, 0)
+        lib.set_tile(128)
+        lib.set_cache_bytes(0)
+        for k, v in dict(group=4, kchain=4, depth=6, rs=32, profile=0, persist=0, wide=0, ramp=0).items():
+            lib.set_option(k, v)
+        C[...] = C0
+        lib.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, -1.0, C, n)
+        assert relerr(C, want) < TOL64, (step, mib)
+    lib.shutdown()
+
+
 @pytest.mark.parametrize("order", [blasx.ColMajor, blasx.RowMajor])
 @pytest.mark.parametrize("ta,tb", list(itertools.product(TRANS, TRANS)))
 def test_dgemm_ragged_all_transposes(lib, order, ta, tb):
