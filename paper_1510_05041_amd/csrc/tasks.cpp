@@ -270,8 +270,14 @@ void build_trmm(Problem& p, int dtype, int T, bool left, bool lower, bool trans,
                 // left:  k runs over tile columns of op(A) row i   -> k <= i (lower) or k >= i (upper)
                 // right: k runs over tile rows of op(A) column j   -> k >= j (lower) or k <= j (upper)
                 const bool below = left ? eff_lower : !eff_lower;
+                // Step q of every task is the same tile index along k: 0, 1, 2 ... where the tasks' ranges
+                // all start at 0, and nt-1, nt-2, ... where they all end at nt-1.  Tasks that advance
+                // together (the wide schedule's rounds) then share the tiles of one k, which arrive one k
+                // after the other; counted from the diagonal instead, the first round alone would touch
+                // every tile of B (measured, N = 12288, wide: 55.4 ms against 40.2 for the mirrored case).
                 const int k0 = below ? 0 : d, k1 = below ? d : cdiv(na, T) - 1;
-                for (int kt = k0; kt <= k1; ++kt) {
+                for (int kq = k0; kq <= k1; ++kq) {
+                    const int kt = below ? kq : k1 - (kq - k0);
                     StepSpec s;
                     if (left) {
                         s.a = trans ? stored_tile(A, lda, p.esize, T, kt, i, na, na) : stored_tile(A, lda, p.esize, T, i, kt, na, na);
