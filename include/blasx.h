@@ -141,8 +141,9 @@ int blasx_set_cache_bytes(size_t cap);
  *   "group"    tile tasks that run together and advance k-step by k-step; 0 (default): chosen
  *              per call from the number of tasks (2 for a few tiles, where a short pipeline of
  *              small launches keeps the link busy, at least 4 from 5 x 5 tiles of up to 8 MB,
- *              up to 16 from 16 x 16 tiles; 16 for the triangular routines); the choice of the
- *              latest call is "last_group"
+ *              up to 16 from 16 x 16 tiles, but 8 at most (tiles of 16 MB: 4) when the k loop is
+ *              too short for the wide schedule; 16 for the triangular routines); the choice of
+ *              the latest call is "last_group"
  *   "kchain"   consecutive k-steps of a task fused into one launch (1..8; 1 = the paper's
  *              one kernel per (i,j,k)); 0 (default): 8 in the wide schedule (6 for 12 .. 15
  *              k-tiles, which 8 would cut into two rounds only, 4 for 11), else 4; TRMM: 1 up to 14 x 14

@@ -116,7 +116,15 @@ int pick_group(const Problem& p) {
     // DSYR2K 14.1 / 12.3 at 5120, 31.7 / 25.2 at 7168; DGEMM 13.5 / 13.2 at 5120); not for tiles of 16 MB, whose
     // copies take twice as long (SSYRK N = 10240, 5 x 5 tiles of 2048: 14.9 / 17.1; SGEMM 25.7 / 27.2).
     const int64_t side = std::max((p.c_rows + p.T - 1) / p.T, (p.c_cols + p.T - 1) / p.T);
-    if (side >= 5 && (size_t)p.T * p.T * p.esize <= ((size_t)8 << 20)) want = std::max<size_t>(want, 4);
+    const bool big_tiles = (size_t)p.T * p.T * p.esize > ((size_t)8 << 20);
+    if (side >= 5 && !big_tiles) want = std::max<size_t>(want, 4);
+    // A k loop too short for the wide schedule (many output tiles, few k-tiles): the call is bound by the link, and
+    // 8 tasks pipeline better than 16 (8 / 16 tasks, ms: DGEMM 16384 x 16384 x 8192 89.1 / 91.8, x 4096 65.3 / 67.8,
+    // 20480 x 20480 x 8192 125.2 / 126.6; DSYRK 16384 x 8192 47.7 / 50.4; DSYR2K 16384 x 4096 47.8 / 50.4; DSYMM 10240
+    // 47.4 / 50.9); tiles of 16 MB: 4 (SGEMM 16384 x 16384 x 8192 with 4 / 8 / 16 tasks: 48.1 / 50.5 / 56.0).
+    size_t longest = 0;
+    for (const Task& t : p.tasks) longest = std::max(longest, t.steps.size());
+    if (L.cfg.wide > 0 && longest < (size_t)L.cfg.wide * (size_t)p.steps_per_k) want = std::min<size_t>(want, big_tiles ? 4 : 8);
     int g = 2;
     while ((size_t)g * 2 <= want) g *= 2;
     return g;
