@@ -105,13 +105,14 @@ int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solv
 // waits for the first tiles of all of them.  When the call is bound by the link (few tiles per
 // dimension) a small running set pipelines better: measured best 2 up to 5 x 5 tiles, 4 at
 // 6 x 6 to 8 x 8, 8 around 12 x 12, 16 from 16 x 16 tiles up (T = 1024, double precision);
-// one eighth of the task count, as a power of two in 2..16, follows that within a few percent
+// one twelfth of the task count, as a power of two in 2..16, follows that within a few percent
+// (one eighth, the first rule, chose 8 at 8 x 8 and 9 x 9 tiles, where 4 is 2 .. 3 % faster: DGEMM 8192 35.1 / 34.0 ms)
 // for the rectangular and the triangular task sets alike.
 int pick_group(const Problem& p) {
     Library& L = lib();
     if (L.cfg.group > 0) return L.cfg.group;
     if (!p.panels.empty() || p.results_are_operands) return 16;   // TRMM / TRSM: parallelism is per dependency level
-    size_t want = std::min<size_t>(16, std::max<size_t>(2, p.tasks.size() / 8));
+    size_t want = std::min<size_t>(16, std::max<size_t>(2, p.tasks.size() / 12));
     // From 5 x 5 tiles of up to 8 MB at least 4 (2 / 4 tasks, ms: DSYRK 11.0 / 12.2 at N = 6144, 17.3 / 14.7 at 7168;
     // DSYR2K 14.1 / 12.3 at 5120, 31.7 / 25.2 at 7168; DGEMM 13.5 / 13.2 at 5120); not for tiles of 16 MB, whose
     // copies take twice as long (SSYRK N = 10240, 5 x 5 tiles of 2048: 14.9 / 17.1; SGEMM 25.7 / 27.2).

@@ -733,7 +733,7 @@ def test_wide_schedule_dtrmm_full_compare(lib, side, uplo, trans, diag):
 
 # ------------------------------------------------------------------ automatic tile size --
 
-@pytest.mark.parametrize("n,expect,group", [(1000, 1008, 2), (4096, 1024, 2), (8192, 1024, 8)])  # all below the wide threshold
+@pytest.mark.parametrize("n,expect,group", [(1000, 1008, 2), (4096, 1024, 2), (8192, 1024, 4)])  # all below the wide threshold
 def test_auto_tile_dgemm_sampled(lib, n, expect, group):
     """blasx_set_tile(0) and group 0: tile and running set are chosen per call; same parity bar as fixed ones."""
     configure(lib, T=0, nstreams=4, arena_gb=4.0, group=0)

@@ -690,15 +690,16 @@ def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
     sim.set_cache_bytes(64 * 2 ** 20)
     assert chosen(sim.dgemm, 8192, 16) == 256
     sim.set_cache_bytes(0)
-    # the running set: 2 for a few tiles, 4 from 5 x 5, 16 from 16 x 16 tiles, 16 for the triangular routines
+    # the running set: a twelfth of the tasks as a power of two: 2 for a few tiles, 4 from 5 x 5, 16 from 14 x 14 tiles;
+    # 16 for the triangular routines
     sim.set_option("group", 0)
     sim.set_tile(16)
     # (a k loop too short for the wide schedule, as here with one k-tile: 8 at most)
-    for n, g in ((32, 2), (64, 2), (80, 4), (96, 4), (128, 8), (192, 8), (400, 8)):   # at least 4 from 5 x 5 tiles
+    for n, g in ((32, 2), (64, 2), (80, 4), (96, 4), (128, 4), (160, 8), (192, 8), (400, 8)):   # at least 4 from 5 x 5 tiles
         assert chosen(sim.dgemm, n, n) == 16 and sim.get_option("last_group") == g, n
-    Ak, Bk, Ck = np.ones((192, 192), order="F"), np.ones((192, 192), order="F"), np.zeros((192, 192), order="F")
-    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 192, 192, 192, 1.0, Ak, 192, Bk, 192, 0.0, Ck, 192)
-    assert np.all(Ck == 192.0) and sim.get_option("last_group") == 16        # 12 k-tiles: 16 from 16 x 16 tiles (here 12 x 12: 144 / 8)
+    Ak, Bk, Ck = np.ones((256, 192), order="F"), np.ones((192, 256), order="F"), np.zeros((256, 256), order="F")
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 256, 256, 192, 1.0, Ak, 256, Bk, 192, 0.0, Ck, 256)
+    assert np.all(Ck == 192.0) and sim.get_option("last_group") == 16        # 12 k-tiles, 16 x 16 tiles: 256 / 12 -> 16
     L = np.asfortranarray(np.tril(np.ones((64, 64))) + 63 * np.eye(64))
     B = np.ones((64, 32), order="F")
     sim.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, 64, 32, 1.0, L, 64, B, 64)
