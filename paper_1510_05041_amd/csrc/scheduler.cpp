@@ -195,8 +195,8 @@ int Scheduler::fetch(const TileRef& t, Block** out) {
         auto it = pending_wb_.find(key);
         if (it != pending_wb_.end()) {
             // the host copy of this tile is still being written by an outbound copy
-            be_.stream_wait_event(STREAM_H2D, it->second);
-            if (be_.num_streams() >= 4) be_.stream_wait_event(STREAM_H2D_B, it->second);
+            if (be_.stream_wait_event(STREAM_H2D, it->second)) return BLASX_ERR_DEVICE;
+            if (be_.num_streams() >= 4 && be_.stream_wait_event(STREAM_H2D_B, it->second)) return BLASX_ERR_DEVICE;
         }
         const int rc = issue_h2d(t, b->slot);
         if (rc) return rc;
@@ -403,7 +403,10 @@ int Scheduler::finish_task(int ri) {
         own.rows = t.m;
         own.cols = t.n;
         Block* b = nullptr;
-        BX_TRY(fetch(own, &b));            // pinned with the panel: always there, copied in now if it was only reserved
+        // pinned with the panel: always there, copied in now if it was only reserved ("no slot right
+        // now" cannot happen for a pinned tile; should it, it is reported as what it means)
+        const int frc = fetch(own, &b);
+        if (frc != 0) return frc < 0 ? BLASX_ERR_ARENA_TOO_SMALL : frc;
         if (fill_seq_[b->slot] > 0 && be_.stream_wait_event(d2h, fill_event(b->slot))) return BLASX_ERR_DEVICE;
     }
     if (be_.copy_d2h(t.c_host, (size_t)p_->ldc * es, slot_ptr(r.c_slot), (size_t)T_ * es, (size_t)t.m * es, (size_t)t.n, d2h))
@@ -969,6 +972,9 @@ int Scheduler::build_solve(int ri) {
     BX_TRY(add_step(op, p_->ta, p_->tb, st, 1.0 * t.m * t.n * st.seg[0].k, 1));
     op.blocks.push_back(inv);
     op.wait_slots.push_back(r.c_slot);
+    // the fresh slot may have been evicted a moment ago with an inbound copy for its previous owner
+    // still queued: the solve, which writes the slot, is ordered after that copy
+    op.wait_slots.push_back(c2);
     op.free_slots.push_back(r.c_slot);
     r.c_slot = c2;
     r.first = false;

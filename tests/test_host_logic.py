@@ -641,6 +641,39 @@ def test_wide_mode_trsm_tight_cache_many_interleavings(sim, seed):
     assert np.array_equal(np.asarray(Bs), X)          # small integers and a unit diagonal: the solve is exact
 
 
+@pytest.mark.parametrize("nstreams", [2, 3, 4])
+@pytest.mark.parametrize("group", [1, 2, 4])
+def test_grouped_trsm_very_tight_cache_many_interleavings(sim, nstreams, group):
+    """The diagonal solve writes into a slot taken fresh from the pool.  Under a cache of a few
+    tiles that slot has just been evicted, and an inbound copy for its previous owner may still be
+    queued: the solve must be ordered after it (regression: it was not, and the stale copy landed
+    on top of the solved tile)."""
+    n, m = 96, 80
+    bad = []
+    for arena_tiles in range(6, 13):
+        for seed in range(4):
+            side = blasx.Left if (seed + arena_tiles) % 2 else blasx.Right
+            uplo = blasx.Lower if seed % 3 else blasx.Upper
+            rng = np.random.default_rng(1000 + 10 * arena_tiles + seed)
+            na = n if side == blasx.Left else m
+            L = np.tril(rng.integers(-2, 3, (na, na)).astype(np.float64), -1) + np.eye(na)
+            if uplo == blasx.Upper:
+                L = L.T.copy()
+            X = rng.integers(-2, 3, (n, m)).astype(np.float64)
+            B = L @ X if side == blasx.Left else X @ L
+            setup(sim, T=16, nstreams=nstreams, arena_tiles=arena_tiles, wide=0, group=group, kchain=1 + seed % 2,
+                  seed=7000 + 97 * arena_tiles + 13 * seed + nstreams)
+            Ls, Bs = store(L, blasx.ColMajor), store(B, blasx.ColMajor)
+            rc = sim.dtrsm(blasx.ColMajor, side, uplo, blasx.NoTrans, blasx.Unit, n, m, 1.0, Ls, na, Bs, n, check=False)
+            if rc == 2:         # BLASX_ERR_ARENA_TOO_SMALL: an honest refusal, never a wrong result
+                continue
+            assert rc == 0
+            assert sim.get_option("last_wide") == 0
+            if not np.array_equal(np.asarray(Bs), X):
+                bad.append((arena_tiles, seed, side, uplo))
+    assert not bad, "wrong solves under a tight cache: %r" % bad
+
+
 # ------------------------------------------------------------------ automatic tile size ---
 
 def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
