@@ -134,6 +134,16 @@ int blasx_shutdown(void);
  * Halved until 64 tiles fit in the cache).  The choice
  * of the latest call is blasx_get_option("last_tile").  The default is 1024. */
 int blasx_set_tile(int T);
+/* Number of streams the scheduler uses (paper Section IV.D: tasks progress on concurrent
+ * streams; its experiments use 4).  n = 2..4 with the roles listed at blasx_init, or 0 for the
+ * measured best (4).  The streams handed to (or made by) blasx_init keep their roles: fewer
+ * streams leave the later ones idle, more takes further streams of the library's own -- no
+ * stream is created anew for a role that had one, because which hardware queue a new stream
+ * lands on depends on what was created before it and two roles sharing a queue serialise.
+ * BLASX_ERR_NOT_INITIALIZED before blasx_init; BLASX_ERR_CONFIG when n is out of range or
+ * exceeds the number of caller-owned streams given to blasx_init.  Only between calls; the
+ * tile cache (option "persist") is kept.  blasx_get_option("streams") reads it back. */
+int blasx_set_streams(int n);
 /* Cap on the bytes of the arena that the tile cache may use (0 = all of it); lowers the
  * number of tile slots so that eviction (Alg. 2, Dequeue) can be exercised. */
 int blasx_set_cache_bytes(size_t cap);
@@ -172,7 +182,10 @@ int blasx_set_cache_bytes(size_t cap);
  *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)
  *   "sb_rows", "sb_cols"  super-block shape used to order the task queue
  *   "shells"   1: super-blocks are visited in growing square shells, 0: block row by block row
- *   "profile"  1: time every launch with events (adds two event records per launch)
+ *   "profile"  1: time every launch with events (adds two event records per launch);
+ *              2: also put an event before and after every tile copy and dissect each call as the
+ *              paper's time profile does (Section V.A): t_kernel_busy_s, t_copy_unoverlapped_s
+ *              and t_device_span_s of blasx_stats
  *   "persist"  1: the tile cache outlives the call (see below); 0 (default): it is dropped
  *              when a call returns
  * Returns BLASX_ERR_CONFIG for an unknown name or an out-of-range value. */
@@ -229,9 +242,18 @@ typedef struct blasx_stats {
     uint64_t profiled_launches;
     double   flops;          /* floating-point operations of the executed tile steps */
     double   t_total_s;      /* wall time inside level-3 calls */
-    double   t_issue_s;      /* of which: host scheduling/issue time (not waiting) */
-    double   t_kernel_s;     /* sum of event-timed launch durations ("profile" = 1) */
+    double   t_issue_s;      /* of which: host scheduling/issue time (t_total_s - t_wait_s) */
+    double   t_kernel_s;     /* sum of event-timed launch durations ("profile" >= 1) */
     uint64_t invalidations;  /* cached tiles forgotten because their host copy changed (persistent cache) */
+    double   t_wait_s;       /* of t_total_s: host blocked on the device (run-ahead bound reached, no free slot,
+                                final drain) */
+    /* The paper's time profile (Section V.A: computation / communication that is not overlapped /
+     * other), from events on the device's own clock; filled with "profile" = 2 only: */
+    double   t_kernel_busy_s;        /* time during which at least one tile kernel ran (COMPT) */
+    double   t_copy_unoverlapped_s;  /* time during which a tile copy ran, in either direction, and no
+                                        kernel did (COMM) */
+    double   t_device_span_s;        /* first device operation of each call to its last; the rest of it
+                                        is OTHER = span - COMPT - COMM */
 } blasx_stats;
 
 int blasx_get_stats(blasx_stats* out);

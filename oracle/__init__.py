@@ -37,7 +37,8 @@ def build(force=False):
 def _load():
     global _lib
     if _lib is None:
-        # tests/test_oracle_mutants.py points this at deliberately broken builds to show that the pins notice
+        # tests/test_oracle_mutants.py points this at deliberately broken builds to show that the pins
+        # notice; nothing that judges the GPU path may run with it set (those callers check overridden())
         override = os.environ.get("ORACLE_LIB_OVERRIDE")
         if not override:
             build()
@@ -56,6 +57,11 @@ def _load():
         lib.ref_max_threads.restype = ci
         _lib = lib
     return _lib
+
+
+def overridden():
+    """True when the environment replaces the oracle's library (the mutant tests of the pins do)."""
+    return bool(os.environ.get("ORACLE_LIB_OVERRIDE"))
 
 
 def threads():

@@ -64,10 +64,10 @@ int NAME(int order, int ta, int tb, int M, int N, int K, double alpha,          
     if (K < 0) return -6;                                                           \
     if (M == 0 || N == 0) return 0;                                                 \
     int bad = 0;                                                                    \
-    _Pragma("omp parallel for schedule(dynamic, 1)")                                \
+    _Pragma("omp parallel for schedule(dynamic, 1) reduction(|:bad)")               \
     for (long j = 0; j < N; ++j) {                                                  \
         double *acc = (double *)calloc((size_t)M, sizeof(double));                  \
-        if (!acc) { bad = 1; continue; }                                            \
+        if (!acc) { bad |= 1; continue; }                                           \
         if (alpha != 0.0) {                                                         \
             for (long l = 0; l < K; ++l) {                                          \
                 double b = is_tr(tb) ? (double)B[at(order, j, l, ldb)]              \

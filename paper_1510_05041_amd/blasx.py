@@ -26,7 +26,8 @@ class Stats(ctypes.Structure):
         "calls", "tasks", "tile_steps", "launches", "hits", "misses", "evictions", "refetches",
         "copies_h2d", "copies_d2h", "bytes_h2d", "bytes_d2h", "slot_waits", "peak_slots",
         "profiled_launches")] + [(n, ctypes.c_double) for n in ("flops", "t_total_s", "t_issue_s", "t_kernel_s")] + [
-        ("invalidations", ctypes.c_uint64)]
+        ("invalidations", ctypes.c_uint64)] + [(n, ctypes.c_double) for n in (
+            "t_wait_s", "t_kernel_busy_s", "t_copy_unoverlapped_s", "t_device_span_s")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -86,6 +87,7 @@ class Library:
         lib.blasx_strmm.argtypes = [ci, ci, ci, ci, ci, ci, ci, cf, vp, ci, vp, ci]
         lib.blasx_init.argtypes = [vp, sz, ctypes.POINTER(vp), ci]
         lib.blasx_set_tile.argtypes = [ci]
+        lib.blasx_set_streams.argtypes = [ci]
         lib.blasx_set_cache_bytes.argtypes = [sz]
         lib.blasx_set_option.argtypes = [ctypes.c_char_p, ctypes.c_long]
         lib.blasx_get_option.argtypes = [ctypes.c_char_p]
@@ -146,6 +148,9 @@ class Library:
 
     def set_tile(self, T):
         self._check("blasx_set_tile", self._lib.blasx_set_tile(T))
+
+    def set_streams(self, n):
+        self._check("blasx_set_streams", self._lib.blasx_set_streams(n))
 
     def set_cache_bytes(self, cap):
         self._check("blasx_set_cache_bytes", self._lib.blasx_set_cache_bytes(int(cap)))

@@ -21,6 +21,10 @@ public:
     virtual char*  arena() = 0;            // device base address of the tile arena
     virtual size_t arena_bytes() = 0;
     virtual int    num_streams() = 0;      // 2..4
+    // Use the first n (2..4) of the streams this backend was given or has made for the roles
+    // below; streams are neither created anew nor destroyed.  Non-zero: n is out of range or
+    // more than the caller handed over.  Only between calls (nothing in flight).
+    virtual int    set_num_streams(int n) = 0;
     // Strided tile copies: `height` runs of `width` bytes.  Host pointers may be pageable.
     virtual int copy_h2d(void* dev_dst, size_t dpitch, const void* host_src, size_t spitch,
                          size_t width, size_t height, int stream) = 0;

@@ -437,6 +437,17 @@ int blasx_set_tile(int T) {
     return 0;
 }
 
+int blasx_set_streams(int n) {
+    Library& L = lib();
+    if (!L.be) return BLASX_ERR_NOT_INITIALIZED;
+    if (n == 0) n = 4;
+    if (L.be->set_num_streams(n)) {
+        L.last_error = L.be->last_error();
+        return BLASX_ERR_CONFIG;
+    }
+    return 0;
+}
+
 int blasx_set_cache_bytes(size_t cap) {
     lib().cache_cap = cap;
     return 0;
@@ -456,7 +467,7 @@ int blasx_set_option(const char* name, long value) {
     else if (n == "wide") { if (value < 0 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.wide = (int)value; }
     else if (n == "ramp") { if (value < 0 || value > kMaxChain) return BLASX_ERR_CONFIG; L.cfg.ramp = (int)value; }
     else if (n == "prefetch") { if (value < 0 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.prefetch = (int)value; }
-    else if (n == "profile") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.profile = value != 0; }
+    else if (n == "profile") { if (value < 0 || value > 2) return BLASX_ERR_CONFIG; L.cfg.profile = (int)value; }
     else if (n == "persist") {
         if (value < 0 || value > 1) return BLASX_ERR_CONFIG;
         L.persist = value != 0;
@@ -480,7 +491,8 @@ long blasx_get_option(const char* name) {
     if (n == "wide") return L.cfg.wide;
     if (n == "prefetch") return L.cfg.prefetch;
     if (n == "ramp") return L.cfg.ramp;
-    if (n == "profile") return L.cfg.profile ? 1 : 0;
+    if (n == "profile") return L.cfg.profile;
+    if (n == "streams") return L.be ? L.be->num_streams() : 0;
     if (n == "persist") return L.persist ? 1 : 0;
     if (n == "cached_tiles") return L.sched ? (long)L.sched->cached_blocks() : 0;
     if (n == "tile") return L.T;
@@ -528,6 +540,8 @@ int blasx_get_stats(blasx_stats* out) {
     out->copies_h2d = s.copies_h2d; out->copies_d2h = s.copies_d2h; out->bytes_h2d = s.bytes_h2d; out->bytes_d2h = s.bytes_d2h;
     out->slot_waits = s.slot_waits; out->peak_slots = s.peak_slots; out->profiled_launches = s.profiled_launches; out->invalidations = s.invalidations;
     out->flops = s.flops; out->t_total_s = s.t_total_s; out->t_issue_s = s.t_issue_s; out->t_kernel_s = s.t_kernel_s;
+    out->t_wait_s = s.t_wait_s; out->t_kernel_busy_s = s.t_kernel_busy_s; out->t_copy_unoverlapped_s = s.t_copy_unoverlapped_s;
+    out->t_device_span_s = s.t_device_span_s;
     return 0;
 }
 

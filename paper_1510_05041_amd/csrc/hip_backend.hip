@@ -148,28 +148,54 @@ public:
             arena_ = kept.ptr;
         }
         bytes_ = bytes;
+        caller_streams_ = streams != nullptr;
         for (int s = 0; s < nstreams; ++s) {
             hipStream_t st = nullptr;
-            bool own = false;
-            if (streams && streams[s]) {
-                st = static_cast<hipStream_t>(streams[s]);
-            } else {
-                // Streams the library makes itself live as long as the process and are reused by
-                // every later init on the device: which hardware queue a stream lands on depends
-                // on what was created before it, and two roles sharing one queue serialise.
-                int dev = 0;
-                HB_CHECK(hipGetDevice(&dev));
-                std::vector<hipStream_t>& made = own_streams()[dev];
-                while ((int)made.size() <= s) {
-                    hipStream_t fresh = nullptr;
-                    HB_CHECK(hipStreamCreateWithFlags(&fresh, hipStreamNonBlocking));
-                    made.push_back(fresh);
-                }
-                st = made[s];
-            }
+            if (streams && streams[s]) st = static_cast<hipStream_t>(streams[s]);
+            else HB_CHECK(own_stream(s, &st));
             streams_.push_back(st);
-            own_stream_.push_back(own);
+            own_stream_.push_back(false);
         }
+        active_ = nstreams;
+        return 0;
+    }
+
+    // Streams the library makes itself live as long as the process and are reused by every later
+    // init on the device: which hardware queue a stream lands on depends on what was created
+    // before it, and two roles sharing one queue serialise.
+    hipError_t own_stream(int s, hipStream_t* out) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        std::vector<hipStream_t>& made = own_streams()[dev];
+        while ((int)made.size() <= s) {
+            hipStream_t fresh = nullptr;
+            e = hipStreamCreateWithFlags(&fresh, hipStreamNonBlocking);
+            if (e != hipSuccess) return e;
+            made.push_back(fresh);
+        }
+        *out = made[s];
+        return hipSuccess;
+    }
+
+    int set_num_streams(int n) override {
+        if (n < 2 || n > 4) {
+            err_ = "the number of streams must be 2..4";
+            return 1;
+        }
+        if (n > (int)streams_.size()) {
+            if (caller_streams_) {
+                err_ = "more streams asked for than blasx_init was given";
+                return 1;
+            }
+            for (int s = (int)streams_.size(); s < n; ++s) {
+                hipStream_t st = nullptr;
+                HB_CHECK(own_stream(s, &st));
+                streams_.push_back(st);
+                own_stream_.push_back(false);
+            }
+        }
+        active_ = n;
         return 0;
     }
 
@@ -188,10 +214,10 @@ public:
 
     char* arena() override { return arena_; }
     size_t arena_bytes() override { return bytes_; }
-    int num_streams() override { return (int)streams_.size(); }
+    int num_streams() override { return active_; }
 
     hipStream_t stream(int role) {
-        const int n = (int)streams_.size();
+        const int n = active_;
         if (role < n) return streams_[role];
         return streams_[STREAM_H2D];           // fewer streams: copy roles share one
     }
@@ -298,6 +324,8 @@ private:
     char* arena_ = nullptr;
     size_t bytes_ = 0;
     std::vector<hipStream_t> streams_;
+    int active_ = 0;                 // streams in use (set_num_streams); the others idle
+    bool caller_streams_ = false;
     std::vector<bool> own_stream_;
     std::vector<hipEvent_t> events_;
     std::vector<int> free_;

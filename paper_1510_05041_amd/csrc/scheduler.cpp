@@ -93,23 +93,35 @@ int Scheduler::new_event() {
 // Alg. 1 "ReaderUpdate": drop the readers of every launch the device has finished.  The
 // paper does this after a full StreamsSynch; here one event per launch tells the same thing
 // without draining the streams.
+void Scheduler::wait_event(int ev) {
+    const double t = now_s();
+    be_.event_sync(ev);
+    t_wait_ += now_s() - t;
+}
+
 bool Scheduler::retire(bool block_on_oldest) {
     bool any = false;
     while (!inflight_.empty()) {
         InFlight& f = inflight_.front();
         if (!be_.event_done(f.done_ev)) {
             if (!block_on_oldest) break;
-            be_.event_sync(f.done_ev);
+            wait_event(f.done_ev);
         }
         block_on_oldest = false;
+        bool keep_events = false;
         if (f.start_ev >= 0) {
             stats_.t_kernel_s += be_.event_elapsed_s(f.start_ev, f.done_ev);
             ++stats_.profiled_launches;
-            put_event(f.start_ev);
+            if (cfg_.profile >= 2) {
+                kernel_iv_.push_back(Interval{f.start_ev, f.done_ev});   // handed back by dissect_time()
+                keep_events = true;
+            } else {
+                put_event(f.start_ev);
+            }
         }
         for (Block* b : f.blocks) cache_.release(b);
         for (int s : f.free_slots) cache_.give_slot(s);
-        put_event(f.done_ev);
+        if (!keep_events) put_event(f.done_ev);
         inflight_.pop_front();
         any = true;
     }
@@ -123,7 +135,7 @@ void Scheduler::poll_writebacks(bool block) {
         WriteBack& w = writebacks_.front();
         if (!be_.event_done(w.ev)) {
             if (!block) break;
-            be_.event_sync(w.ev);
+            wait_event(w.ev);
         }
         if (w.block) {
             cache_.release(w.block);
@@ -161,6 +173,69 @@ int Scheduler::take_slot_blocking(int* slot) {
 
 // ---------------------------------------------------------------- tile movement ----------
 
+// profile 2: an event before and one after every tile copy, on the copy's own stream
+int Scheduler::profiled_copy_begin(int stream) {
+    if (cfg_.profile < 2) return 0;
+    const int ev = new_event();
+    if (ev < 0 || be_.event_record(ev, stream)) return BLASX_ERR_DEVICE;
+    copy_iv_.push_back(Interval{ev, -1});
+    return 0;
+}
+
+int Scheduler::profiled_copy_end(int stream) {
+    if (cfg_.profile < 2) return 0;
+    const int ev = new_event();
+    if (ev < 0 || be_.event_record(ev, stream)) return BLASX_ERR_DEVICE;
+    copy_iv_.back().end_ev = ev;
+    return 0;
+}
+
+// Section V.A dissects a run into computation, communication that no computation hides, and the
+// rest.  From the event pairs of this run: the time covered by kernels, and the time covered by
+// tile copies but by no kernel.  Every event has completed when this runs.
+void Scheduler::dissect_time() {
+    if (base_ev_ < 0) return;
+    auto spans = [&](std::vector<Interval>& iv) {
+        std::vector<std::pair<double, double>> out;
+        for (const Interval& q : iv) {
+            if (q.end_ev >= 0) {
+                const double b = be_.event_elapsed_s(base_ev_, q.begin_ev), e = be_.event_elapsed_s(base_ev_, q.end_ev);
+                if (e > b) out.emplace_back(b, e);
+                put_event(q.end_ev);
+            }
+            put_event(q.begin_ev);
+        }
+        iv.clear();
+        std::sort(out.begin(), out.end());
+        std::vector<std::pair<double, double>> merged;      // disjoint, ascending
+        for (const auto& q : out) {
+            if (!merged.empty() && q.first <= merged.back().second) merged.back().second = std::max(merged.back().second, q.second);
+            else merged.push_back(q);
+        }
+        return merged;
+    };
+    const auto kern = spans(kernel_iv_), copy = spans(copy_iv_);
+    double busy = 0, hidden = 0, copying = 0, first = 1e300, last = 0;
+    for (const auto& q : kern) busy += q.second - q.first;
+    size_t k = 0;
+    for (const auto& c : copy) {
+        copying += c.second - c.first;
+        while (k < kern.size() && kern[k].second <= c.first) ++k;
+        for (size_t q = k; q < kern.size() && kern[q].first < c.second; ++q)
+            hidden += std::min(c.second, kern[q].second) - std::max(c.first, kern[q].first);
+    }
+    for (const auto* v : {&kern, &copy})
+        if (!v->empty()) {
+            first = std::min(first, v->front().first);
+            last = std::max(last, v->back().second);
+        }
+    stats_.t_kernel_busy_s += busy;
+    stats_.t_copy_unoverlapped_s += copying - hidden;
+    if (last > first) stats_.t_device_span_s += last - first;
+    put_event(base_ev_);
+    base_ev_ = -1;
+}
+
 int Scheduler::issue_h2d(const TileRef& t, int slot) {
     int stream = STREAM_H2D;
     if (be_.num_streams() >= 4) {
@@ -172,8 +247,10 @@ int Scheduler::issue_h2d(const TileRef& t, int slot) {
     if (fill_seq_[slot] != 0 && fill_stream_[slot] != stream) {
         if (be_.stream_wait_event(stream, fill_event(slot))) return BLASX_ERR_DEVICE;
     }
+    BX_TRY(profiled_copy_begin(stream));
     if (be_.copy_h2d(slot_ptr(slot), (size_t)T_ * es, t.host, (size_t)t.ld * es, (size_t)t.rows * es, (size_t)t.cols, stream))
         return BLASX_ERR_DEVICE;
+    BX_TRY(profiled_copy_end(stream));
     if (fill_ev_[slot] < 0) fill_ev_[slot] = be_.event_create();
     if (be_.event_record(fill_ev_[slot], stream)) return BLASX_ERR_DEVICE;
     fill_seq_[slot] = ++h2d_issued_[stream];
@@ -409,8 +486,10 @@ int Scheduler::finish_task(int ri) {
         if (frc != 0) return frc < 0 ? BLASX_ERR_ARENA_TOO_SMALL : frc;
         if (fill_seq_[b->slot] > 0 && be_.stream_wait_event(d2h, fill_event(b->slot))) return BLASX_ERR_DEVICE;
     }
+    BX_TRY(profiled_copy_begin(d2h));
     if (be_.copy_d2h(t.c_host, (size_t)p_->ldc * es, slot_ptr(r.c_slot), (size_t)T_ * es, (size_t)t.m * es, (size_t)t.n, d2h))
         return BLASX_ERR_DEVICE;
+    BX_TRY(profiled_copy_end(d2h));
     WriteBack w;            // the caller records the event that covers this copy
     w.slot = r.c_slot;
     ++stats_.copies_d2h;
@@ -989,7 +1068,7 @@ int Scheduler::build_solve(int ri) {
 
 int Scheduler::run(Problem& p) {
     const double t0 = now_s();
-    double t_wait = 0;
+    t_wait_ = 0;
     p_ = &p;
     T_ = p.T;
     const size_t ntasks = p.tasks.size();
@@ -1004,6 +1083,10 @@ int Scheduler::run(Problem& p) {
     panels_.assign(p.panels.size(), PanelState());
     for (size_t q = 0; q < p.panels.size(); ++q) panels_[q].remaining = p.panels[q].ntasks;
     int rc = 0;
+    if (cfg_.profile >= 2) {
+        base_ev_ = new_event();
+        if (base_ev_ < 0 || be_.event_record(base_ev_, STREAM_COMPUTE)) rc = BLASX_ERR_DEVICE;
+    }
     // Wide mode: every task of the call runs at once and all advance k-chunk by k-chunk (an
     // outer-product order).  A launch then shares its operand tiles with many others, so the
     // device has enough products per tile copied from the first launches on, instead of starving
@@ -1095,7 +1178,7 @@ int Scheduler::run(Problem& p) {
     // Made on demand, the inverse of block row k stands between rounds k - 1 and k: its diagonal
     // tile would be requested behind all the copies already queued, and its ten merge levels keep
     // the device nearly idle for half a millisecond per round.
-    if (wide_ && p.results_are_operands) {
+    if (rc == 0 && wide_ && p.results_are_operands) {
         const std::vector<const Task*> diag = diag_tasks(p);
         rc = make_inverses(diag.data(), diag.size());
     }
@@ -1172,22 +1255,19 @@ int Scheduler::run(Problem& p) {
             rc = BLASX_ERR_DEVICE;
             break;
         }
-        while ((int)inflight_.size() > cfg_.depth) {
-            const double tw = now_s();
-            retire(true);
-            t_wait += now_s() - tw;
-        }
+        while ((int)inflight_.size() > cfg_.depth) retire(true);
     }
 
     // drain: wait for everything that was issued, even after an error
     {
-        const double tw = now_s();
         if (rc == 0) rc = flush_all();
         while (!inflight_.empty()) retire(true);
         poll_writebacks(true);
+        const double tw = now_s();
         if (be_.sync_all() && rc == 0) rc = BLASX_ERR_DEVICE;
-        t_wait += now_s() - tw;
+        t_wait_ += now_s() - tw;
     }
+    dissect_time();
     for (PanelState& ps : panels_) {
         for (Block* b : ps.blocks) cache_.release(b);
         ps.blocks.clear();
@@ -1212,7 +1292,8 @@ int Scheduler::run(Problem& p) {
     cache_.hits = cache_.misses = cache_.evictions = cache_.refetches = 0;
     const double dt = now_s() - t0;
     stats_.t_total_s += dt;
-    stats_.t_issue_s += dt - t_wait;
+    stats_.t_wait_s += t_wait_;
+    stats_.t_issue_s += dt - t_wait_;
     p_ = nullptr;
     return rc;
 }

@@ -50,7 +50,8 @@ struct SchedConfig {
     int prefetch = 24;  // wide mode: inbound copies are started this many launches ahead of the launch being built
     int ramp = 0;       // wide mode: k-steps per task in the first round (1..kMaxChain, cut to the chain length of
                         // the run, i.e. kMaxChain = no shorter first round; 0: chosen per run, see run())
-    bool profile = false;
+    int profile = 0;    // 1: time every launch with events; 2: also every tile copy, and dissect the call's time on the
+                        // device into kernels / copies not hidden under a kernel / neither (Section V.A, time profile)
 };
 
 struct Stats {
@@ -59,6 +60,10 @@ struct Stats {
     uint64_t copies_h2d = 0, copies_d2h = 0, bytes_h2d = 0, bytes_d2h = 0;
     uint64_t slot_waits = 0, peak_slots = 0, profiled_launches = 0, invalidations = 0;
     double flops = 0, t_total_s = 0, t_issue_s = 0, t_kernel_s = 0;
+    double t_wait_s = 0;               // host blocked on the device (events, final drain)
+    double t_kernel_busy_s = 0;        // profile 2: time during which at least one kernel ran (COMPT)
+    double t_copy_unoverlapped_s = 0;  // profile 2: time during which a tile copy ran and no kernel did (COMM)
+    double t_device_span_s = 0;        // profile 2: first device operation of a call to its last
 };
 
 class Scheduler {
@@ -159,6 +164,10 @@ private:
     int  fill_event(int slot) const;
     bool retire(bool block_on_oldest);
     void poll_writebacks(bool block);
+    void wait_event(int ev);            // blocks the host; the time counts as waiting, not issuing
+    int  profiled_copy_begin(int stream);
+    int  profiled_copy_end(int stream);
+    void dissect_time();
     void refill_rs();
     int  pick_from_rs();
     bool deps_started(const Task& t) const;
@@ -208,6 +217,11 @@ private:
     std::deque<WriteBack> writebacks_;
     std::unordered_map<TileKey, int, TileKeyHash> pending_wb_;   // host tile -> event of its outbound copy
     std::vector<int> free_events_;
+    double t_wait_ = 0;                 // this run: host time spent blocked on the device
+    // profile 2: event pairs around every launch and every tile copy of this run, and the event all times count from
+    struct Interval { int begin_ev, end_ev; };
+    std::vector<Interval> kernel_iv_, copy_iv_;
+    int base_ev_ = -1;
     int err_ = 0;
 };
 

@@ -41,6 +41,9 @@ def _load():
         for name in ("synth_dominant_diag_f64", "synth_dominant_diag_f32"):
             getattr(lib, name).argtypes = [ctypes.c_void_p, i64, i64, u64, ci]
             getattr(lib, name).restype = None
+        for name in ("synth_block_f64", "synth_block_f32"):
+            getattr(lib, name).argtypes = [ctypes.c_void_p, i64, i64, i64, i64, i64, i64, u64, ci]
+            getattr(lib, name).restype = None
         lib.synth_element.argtypes = [u64, ci, i64, i64, i64]
         lib.synth_element.restype = ctypes.c_double
         _lib = lib
@@ -83,6 +86,15 @@ def dominant_diag(a, seed, mat):
     kind = {np.dtype(np.float64): "f64", np.dtype(np.float32): "f32"}[a.dtype]
     getattr(lib, "synth_dominant_diag_" + kind)(a.ctypes.data, n, ld, seed, mat)
     return a
+
+
+def block(seed, mat, rows, r0, c0, nr, nc, dtype=np.float64):
+    """The nr x nc block at (r0, c0) of the matrix ``fill`` makes for a ``rows``-row array, regenerated on its own."""
+    out = np.zeros((nr, nc), dtype=dtype, order="F")
+    kind = {np.dtype(np.float64): "f64", np.dtype(np.float32): "f32"}[out.dtype]
+    if nr and nc:
+        getattr(_load(), "synth_block_" + kind)(out.ctypes.data, r0, c0, nr, nc, nr, rows, seed, mat)
+    return out
 
 
 def element(seed, mat, i, j, rows):

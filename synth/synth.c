@@ -61,6 +61,24 @@ void synth_fill_f32(float *p, int64_t rows, int64_t cols, int64_t ld, uint64_t s
     }
 }
 
+/* The nr x nc block at (r0, c0) of the rows x (anything) matrix that synth_fill_* would make,
+ * regenerated on its own into a column-major buffer with leading dimension ld. */
+void synth_block_f64(double *p, int64_t r0, int64_t c0, int64_t nr, int64_t nc, int64_t ld, int64_t rows, uint64_t seed, int mat)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < nc; ++j)
+        for (int64_t i = 0; i < nr; ++i)
+            p[(size_t)i + (size_t)j * (size_t)ld] = unit_pm1(seed, (uint64_t)mat, (uint64_t)(r0 + i), (uint64_t)(c0 + j), (uint64_t)rows);
+}
+
+void synth_block_f32(float *p, int64_t r0, int64_t c0, int64_t nr, int64_t nc, int64_t ld, int64_t rows, uint64_t seed, int mat)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < nc; ++j)
+        for (int64_t i = 0; i < nr; ++i)
+            p[(size_t)i + (size_t)j * (size_t)ld] = (float)unit_pm1(seed, (uint64_t)mat, (uint64_t)(r0 + i), (uint64_t)(c0 + j), (uint64_t)rows);
+}
+
 /*
  * Overwrite the diagonal of an n x n column-major matrix with n + uniform[0,1)
  * so that a triangle of it is strongly diagonally dominant (the triangular

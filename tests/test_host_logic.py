@@ -200,6 +200,52 @@ def test_argument_errors_follow_the_prototype_positions(sim):
     assert sim.set_option.__self__._lib.blasx_set_tile(20) == 4
 
 
+def test_set_streams_changes_the_stream_count_between_calls_and_keeps_results(sim):
+    """Section IV.D: tasks progress on concurrent streams.  blasx_set_streams re-roles the streams
+    of the current initialisation; every count gives the same (integer-exact) product."""
+    setup(sim, T=16, nstreams=4, group=3)
+    rng = np.random.default_rng(12)
+    A = np.asfortranarray(rng.integers(-2, 3, (70, 50)).astype(np.float64))
+    B = np.asfortranarray(rng.integers(-2, 3, (50, 60)).astype(np.float64))
+    assert sim.get_option("streams") == 4
+    for n in (2, 3, 4, 0, 2):
+        sim.set_streams(n)
+        assert sim.get_option("streams") == (n or 4)
+        C = np.full((70, 60), np.nan, order="F")
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 70, 60, 50, 1.0, A, 70, B, 50, 0.0, C, 70)
+        assert np.array_equal(C, A @ B)
+    assert sim._lib.blasx_set_streams(1) == 4 and sim._lib.blasx_set_streams(5) == 4      # BLASX_ERR_CONFIG
+    assert sim.get_option("streams") == 2
+    sim.shutdown()
+    assert sim._lib.blasx_set_streams(4) == 1                                             # BLASX_ERR_NOT_INITIALIZED
+
+
+def test_host_time_is_split_into_issuing_and_waiting_and_the_device_time_is_dissected(sim):
+    """t_total = t_issue + t_wait; with "profile" = 2 the call is dissected as in the paper's time
+    profile (Section V.A): kernels (COMPT), copies under no kernel (COMM), and the rest of the span."""
+    n = 96
+    A, B = synth.matrix(n, n, 3, 0), synth.matrix(n, n, 3, 1)
+    for profile in (0, 1, 2):
+        setup(sim, T=16, group=4, kchain=2, profile=profile, seed=5 + profile, arena_tiles=128)
+        C = np.zeros((n, n), order="F")
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 0.0, C, n)
+        st = sim.get_stats()
+        assert st["t_wait_s"] >= 0 and st["t_issue_s"] >= 0
+        assert abs(st["t_total_s"] - st["t_issue_s"] - st["t_wait_s"]) < 1e-9
+        assert st["profiled_launches"] == (st["launches"] if profile else 0)
+        if profile < 2:
+            assert st["t_kernel_busy_s"] == 0 and st["t_copy_unoverlapped_s"] == 0 and st["t_device_span_s"] == 0
+        else:
+            # the double's clock: 5 us per launch, 2 us per tile copy, one operation at a time (an
+            # interval between two events of one stream also covers what other streams ran meanwhile)
+            busy, comm, span = st["t_kernel_busy_s"], st["t_copy_unoverlapped_s"], st["t_device_span_s"]
+            assert busy >= st["launches"] * 5e-6 - 1e-12
+            assert comm > 0 and busy + comm <= span + 1e-12
+            ncopies = st["copies_h2d"] + st["copies_d2h"]
+            assert ncopies == 36 * 2 + 36 and span <= st["launches"] * 5e-6 + ncopies * 2e-6 + 1e-12
+    sim.set_option("profile", 0)
+
+
 # ------------------------------------------------------------------ SYRK ----------
 
 @pytest.mark.parametrize("order", ORDERS)
@@ -687,6 +733,7 @@ def test_tile_zero_chooses_the_tile_from_extent_type_and_cache_room(sim):
     sim.init_raw(2 ** 31, 0)                     # 0 streams = the measured best
     sim.set_cache_bytes(0)
     sim.set_tile(0)
+    sim.set_option("wide", 11)                   # the library's default: the running-set rule below depends on it
     assert sim.get_option("tile") == 0
     assert chosen(sim.dgemm, 32768, 16) == 1024
     assert chosen(sim.dgemm, 16, 16384) == 1024

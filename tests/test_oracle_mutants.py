@@ -31,6 +31,21 @@ MUTANTS = {
     "trmm_forgets_alpha": ("B[at(order, i, j, ldb)] = (T)((alpha != 0.0) ? alpha * s : 0.0);", "B[at(order, i, j, ldb)] = (T)s;"),
     "trsm_forgets_alpha": ("double s = (alpha != 0.0) ? alpha * (double)B[at(order, i, j, ldb)] : 0.0;", "double s = (double)B[at(order, i, j, ldb)];"),
     "trsm_right_wrong_direction": ("long c = eff_lower ? N - 1 - t : t;", "long c = eff_lower ? t : N - 1 - t;"),
+    # mistakes in the single-precision instantiations only (the double-precision pins cannot see them)
+    "ssyrk_instantiated_for_double": ("DEFINE_SYRK(ref_ssyrk, float)", "DEFINE_SYRK(ref_ssyrk, double)"),
+    "ssyr2k_instantiated_for_double": ("DEFINE_SYR2K(ref_ssyr2k, float)", "DEFINE_SYR2K(ref_ssyr2k, double)"),
+    "ssymm_instantiated_for_double": ("DEFINE_SYMM(ref_ssymm, float)", "DEFINE_SYMM(ref_ssymm, double)"),
+    "strmm_reads_the_triangle_as_double": ("DEFINE_TRMM(ref_strmm, float, s)", "DEFINE_TRMM(ref_strmm, float, d)"),
+    "strsm_reads_the_triangle_as_double": ("DEFINE_TRSM(ref_strsm, float, s)", "DEFINE_TRSM(ref_strsm, float, d)"),
+    "single_precision_triangle_ignores_unit_diagonal": (
+        "DEFINE_TRI(float, s)",
+        "static inline double tri_s(int order, int uplo, int diag, const float *A, long lda, long r, long c)\n"
+        "{ (void)diag; if (r == c) return (double)A[at(order, r, r, lda)];\n"
+        "  int inside = (uplo == LO) ? (r > c) : (r < c); return inside ? (double)A[at(order, r, c, lda)] : 0.0; }\n"
+        "static inline double top_s(int order, int uplo, int trans, int diag, const float *A, long lda, long r, long c)\n"
+        "{ return is_tr(trans) ? tri_s(order, uplo, diag, A, lda, c, r) : tri_s(order, uplo, diag, A, lda, r, c); }"),
+    "syrk_accumulates_in_float": ("            double s = 0.0;                                                         \\\n            if (alpha != 0.0)                                                       \\\n                for (long l = 0; l < K; ++l) {                                      \\\n                    double x = is_tr(trans)",
+                                  "            float s = 0.0f;                                                         \\\n            if (alpha != 0.0)                                                       \\\n                for (long l = 0; l < K; ++l) {                                      \\\n                    double x = is_tr(trans)"),
     "trsm_skips_division": ("x[i] = s / top_##SFX(order, uplo, trans, diag, A, lda, i, i);", "x[i] = s;"),
 }
 

@@ -481,3 +481,210 @@ def test_symm_equals_gemm_with_the_full_symmetric_matrix():
     ref.symm(ref.ColMajor, ref.Left, ref.Lower, 1.0, store(np.tril(S) + np.triu(np.full((M, M), 77.0), 1), ref.ColMajor),
              store(B, ref.ColMajor), 0.0, Cs)
     assert np.array_equal(Cs, Cg)
+
+
+# ------------------------------------------- single-precision entry points -----
+# ref_ssyrk / ref_ssyr2k / ref_ssymm / ref_strmm / ref_strsm are instantiations of the bodies
+# pinned above with float storage: they read float32, accumulate in double and round once.  Each is
+# pinned on its own (exact rationals with a one-rounding bound, integers bit-exact, NaN on everything
+# that must not be read), through the same binding the GPU parity tests use.
+
+U32 = 2.0 ** -24
+
+
+def one_rounding(got, want, slack=0.0):
+    """|got - want| within one float32 rounding of a double-precision result of relative error `slack`."""
+    want = float(want)
+    return abs(float(got) - want) <= (U32 * 1.0001 + slack) * abs(want) + 1e-37
+
+
+def f32(a):
+    return np.asarray(a, dtype=np.float32)
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("uplo", [ref.Upper, ref.Lower])
+@pytest.mark.parametrize("trans", TRANS)
+def test_ssyrk_one_rounding_and_other_triangle_untouched(order, uplo, trans):
+    rng = np.random.default_rng(70 + uplo + trans + order)
+    N, K = 5, 40
+    A = f32(rnd(rng, *((N, K) if trans == ref.NoTrans else (K, N))))
+    C = f32(rnd(rng, N, N))
+    Cin = C.copy()
+    outside = [(i, j) for i in range(N) for j in range(N) if ((i < j) if uplo == ref.Lower else (i > j))]
+    for (i, j) in outside:
+        Cin[i, j] = np.float32(-777.5)
+    alpha, beta = 0.75, -0.5
+    Cs = store(Cin, order, 2, dtype=np.float32)
+    ref.syrk(order, uplo, trans, alpha, store(A, order, 1, dtype=np.float32), beta, Cs)
+    assert Cs.dtype == np.float32
+    Ae = exact.frac(A) if trans == ref.NoTrans else exact.transpose(exact.frac(A))
+    P = exact.matmul(Ae, exact.transpose(Ae))
+    for i in range(N):
+        for j in range(N):
+            if (i, j) in outside:
+                assert Cs[i, j] == np.float32(-777.5)
+                continue
+            want = Fraction(alpha) * P[i][j] + Fraction(beta) * Fraction(float(C[i, j]))
+            assert one_rounding(Cs[i, j], want, (K + 4) * U * 8), (i, j)
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("uplo", [ref.Upper, ref.Lower])
+@pytest.mark.parametrize("trans", TRANS)
+def test_ssyr2k_one_rounding_integers_exact_and_other_triangle_untouched(order, uplo, trans):
+    rng = np.random.default_rng(80 + uplo + trans + order)
+    N, K = 6, 30
+    shape = (N, K) if trans == ref.NoTrans else (K, N)
+    A, B = f32(rnd(rng, *shape)), f32(rnd(rng, *shape))
+    Cin = np.full((N, N), np.nan, dtype=np.float32)        # beta = 0: nothing of C is read
+    Cs = store(Cin, order, 1, dtype=np.float32)
+    ref.syr2k(order, uplo, trans, -1.25, store(A, order, 2, dtype=np.float32), store(B, order, dtype=np.float32), 0.0, Cs)
+    Ae = exact.frac(A) if trans == ref.NoTrans else exact.transpose(exact.frac(A))
+    Be = exact.frac(B) if trans == ref.NoTrans else exact.transpose(exact.frac(B))
+    P1, P2 = exact.matmul(Ae, exact.transpose(Be)), exact.matmul(Be, exact.transpose(Ae))
+    Q = exact.abs_matmul(Ae, exact.transpose(Be))
+    for i in range(N):
+        for j in range(N):
+            inside = (i >= j) if uplo == ref.Lower else (i <= j)
+            if not inside:
+                assert np.isnan(Cs[i, j])
+                continue
+            want = Fraction(-1.25) * (P1[i][j] + P2[i][j])
+            err = abs(Fraction(float(Cs[i, j])) - want)
+            assert err <= U32 * 1.0001 * abs(want) + (2 * K + 6) * U * float(2 * 1.25 * Q[i][j]), (i, j)
+    # small integers: every product and sum is exact, also after the rounding to float32
+    Ai = f32(np.asarray(synth.matrix(N, K, 81, 0, integers=True)))
+    Bi = f32(np.asarray(synth.matrix(N, K, 81, 1, integers=True)))
+    Ci = np.zeros((N, N), dtype=np.float32, order="F")
+    ref.syr2k(ref.ColMajor, uplo, ref.NoTrans, 1.0, store(Ai, ref.ColMajor, dtype=np.float32), store(Bi, ref.ColMajor, dtype=np.float32), 0.0, Ci)
+    full = Ai.astype(np.float64) @ Bi.astype(np.float64).T + Bi.astype(np.float64) @ Ai.astype(np.float64).T
+    tri = np.tril if uplo == ref.Lower else np.triu
+    assert np.array_equal(tri(Ci).astype(np.float64), tri(full))
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("side", [ref.Left, ref.Right])
+@pytest.mark.parametrize("uplo", [ref.Upper, ref.Lower])
+def test_ssymm_one_rounding_with_poisoned_other_triangle(order, side, uplo):
+    rng = np.random.default_rng(90 + side + uplo + order)
+    M, N = 6, 5
+    n = M if side == ref.Left else N
+    S = f32(rnd(rng, n, n))
+    S = np.tril(S) + np.tril(S, -1).T                     # symmetric, exactly representable
+    P = S.copy()
+    for r in range(n):
+        for c in range(n):
+            if (r < c) if uplo == ref.Lower else (r > c):
+                P[r, c] = np.nan
+    B, C = f32(rnd(rng, M, N)), f32(rnd(rng, M, N))
+    alpha, beta = 1.5, 0.25
+    Cs = store(C, order, 2, dtype=np.float32)
+    ref.symm(order, side, uplo, alpha, store(P, order, 1, dtype=np.float32), store(B, order, dtype=np.float32), beta, Cs)
+    Se, Be = exact.frac(S), exact.frac(B)
+    W = exact.matmul(Se, Be) if side == ref.Left else exact.matmul(Be, Se)
+    Wabs = exact.abs_matmul(Se, Be) if side == ref.Left else exact.abs_matmul(Be, Se)
+    for i in range(M):
+        for j in range(N):
+            want = Fraction(alpha) * W[i][j] + Fraction(beta) * Fraction(float(C[i, j]))
+            err = abs(Fraction(float(Cs[i, j])) - want)
+            assert err <= U32 * 1.0001 * abs(want) + (n + 4) * U * float(alpha * Wabs[i][j] + abs(beta * C[i, j])), (i, j)
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS)
+def test_strmm_one_rounding_with_poison(order, side, uplo, trans, diag):
+    rng = np.random.default_rng(110 + side + 3 * uplo + 5 * trans + 7 * diag + order)
+    M, N = 5, 6
+    n = M if side == ref.Left else N
+    A, P = poisoned_triangular(rng, n, uplo, diag)
+    A, P = f32(A), f32(P)
+    B = f32(rnd(rng, M, N))
+    alpha = -0.75
+    Bs = store(B, order, 1, dtype=np.float32)
+    ref.trmm(order, side, uplo, trans, diag, alpha, store(P, order, 2, dtype=np.float32), Bs)
+    Tm = exact.triangle(exact.frac(A), uplo == ref.Lower, diag == ref.Unit)
+    if trans == ref.Trans:
+        Tm = exact.transpose(Tm)
+    Be = exact.frac(B)
+    W = exact.matmul(Tm, Be) if side == ref.Left else exact.matmul(Be, Tm)
+    Wabs = exact.abs_matmul(Tm, Be) if side == ref.Left else exact.abs_matmul(Be, Tm)
+    for i in range(M):
+        for j in range(N):
+            want = Fraction(alpha) * W[i][j]
+            err = abs(Fraction(float(Bs[i, j])) - want)
+            assert err <= U32 * 1.0001 * abs(want) + (n + 4) * U * float(Wabs[i][j]), (i, j)
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("side,uplo,trans,diag", FLAGS)
+def test_strsm_one_rounding_with_poison(order, side, uplo, trans, diag):
+    rng = np.random.default_rng(130 + side + 3 * uplo + 5 * trans + 7 * diag + order)
+    M, N = 5, 4
+    n = M if side == ref.Left else N
+    A, P = poisoned_triangular(rng, n, uplo, diag)
+    A, P = f32(A), f32(P)
+    B = f32(rnd(rng, M, N))
+    alpha = 2.5
+    Bs = store(B, order, 2, dtype=np.float32)
+    ref.trsm(order, side, uplo, trans, diag, alpha, store(P, order, 1, dtype=np.float32), Bs)
+    Tm = exact.triangle(exact.frac(A), uplo == ref.Lower, diag == ref.Unit)
+    if trans == ref.Trans:
+        Tm = exact.transpose(Tm)
+    aB = [[Fraction(alpha) * v for v in row] for row in exact.frac(B)]
+    if side == ref.Left:
+        X = exact.solve_triangular(Tm, aB)
+    else:
+        X = exact.transpose(exact.solve_triangular(exact.transpose(Tm), exact.transpose(aB)))
+    got, want = np.asarray(Bs, dtype=np.float64), exact.to_float(X)
+    assert Bs.dtype == np.float32 and np.all(np.isfinite(got))
+    # the substitution runs in double (error as in the double-precision pin), then one float32 rounding
+    assert np.all(np.abs(got - want) <= U32 * 1.0001 * np.abs(want) + 200 * U * np.max(np.abs(want)))
+
+
+@pytest.mark.parametrize("side,uplo,trans", list(itertools.product([ref.Left, ref.Right], [ref.Upper, ref.Lower], TRANS)))
+def test_strsm_recovers_known_integer_solution_and_strmm_forms_it_exactly(side, uplo, trans):
+    rng = np.random.default_rng(150 + side + uplo + trans)
+    M, N = 7, 6
+    n = M if side == ref.Left else N
+    L = np.tril(rng.integers(-2, 3, (n, n)), -1) + np.diag(rng.choice([1, 2, 4], n))      # powers of two divide exactly
+    Tm = (L if uplo == ref.Lower else L.T).astype(np.float32)
+    X = rng.integers(-3, 4, (M, N)).astype(np.float32)
+    op = Tm.T if trans == ref.Trans else Tm
+    Bv = (op.astype(np.float64) @ X if side == ref.Left else X @ op.astype(np.float64)).astype(np.float32)
+    Bt = store(X, ref.ColMajor, dtype=np.float32)
+    ref.trmm(ref.ColMajor, side, uplo, trans, ref.NonUnit, 1.0, store(Tm, ref.ColMajor, dtype=np.float32), Bt)
+    assert np.array_equal(np.asarray(Bt), Bv)
+    Bs = store(Bv, ref.ColMajor, 1, dtype=np.float32)
+    ref.trsm(ref.ColMajor, side, uplo, trans, ref.NonUnit, 1.0, store(Tm, ref.ColMajor, dtype=np.float32), Bs)
+    assert np.array_equal(np.asarray(Bs), X)
+
+
+def test_single_precision_entry_points_agree_with_double_ones_rounded_once():
+    """Inputs that float32 holds exactly: the s-function must return the d-function's result rounded."""
+    rng = np.random.default_rng(170)
+    N, K = 9, 11
+    A32, B32, C32 = f32(rnd(rng, N, K)), f32(rnd(rng, N, K)), f32(rnd(rng, N, N))
+    A64, B64, C64 = A32.astype(np.float64), B32.astype(np.float64), C32.astype(np.float64)
+    F = lambda a, dt: store(a, ref.ColMajor, dtype=dt)
+    for uplo in (ref.Upper, ref.Lower):
+        tri = np.tril if uplo == ref.Lower else np.triu
+        cs, cd = F(C32, np.float32), F(C64, np.float64)
+        ref.syrk(ref.ColMajor, uplo, ref.NoTrans, 0.3, F(A32, np.float32), 1.7, cs)
+        ref.syrk(ref.ColMajor, uplo, ref.NoTrans, 0.3, F(A64, np.float64), 1.7, cd)
+        assert np.array_equal(tri(np.asarray(cs)), tri(np.asarray(cd).astype(np.float32)))
+        cs, cd = F(C32, np.float32), F(C64, np.float64)
+        ref.syr2k(ref.ColMajor, uplo, ref.NoTrans, 0.3, F(A32, np.float32), F(B32, np.float32), 1.7, cs)
+        ref.syr2k(ref.ColMajor, uplo, ref.NoTrans, 0.3, F(A64, np.float64), F(B64, np.float64), 1.7, cd)
+        assert np.array_equal(tri(np.asarray(cs)), tri(np.asarray(cd).astype(np.float32)))
+        S32 = f32(rnd(rng, N, N))
+        bs, bd = F(A32, np.float32), F(A64, np.float64)
+        ref.symm(ref.ColMajor, ref.Left, uplo, 1.0, F(S32, np.float32), F(B32, np.float32), 0.0, bs)
+        ref.symm(ref.ColMajor, ref.Left, uplo, 1.0, F(S32.astype(np.float64), np.float64), F(B64, np.float64), 0.0, bd)
+        assert np.array_equal(np.asarray(bs), np.asarray(bd).astype(np.float32))
+        T32 = S32 + np.diag(np.full(N, 4.0, dtype=np.float32))
+        for fn in (ref.trmm, ref.trsm):
+            bs, bd = F(B32, np.float32), F(B64, np.float64)
+            fn(ref.ColMajor, ref.Left, uplo, ref.Trans, ref.NonUnit, 0.5, F(T32, np.float32), bs)
+            fn(ref.ColMajor, ref.Left, uplo, ref.Trans, ref.NonUnit, 0.5, F(T32.astype(np.float64), np.float64), bd)
+            assert np.array_equal(np.asarray(bs), np.asarray(bd).astype(np.float32))
