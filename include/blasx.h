@@ -180,6 +180,9 @@ int blasx_set_cache_bytes(size_t cap);
  *   "prefetch" wide schedule: inbound copies are started this many launches ahead (default 24)
  *   "depth"    launches the host may run ahead of the device (>= 1)
  *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)
+ *   "priority" 1 (default): the next task to start is the one of the reservation station with the
+ *              most operand tiles already cached (paper Eq. 2; ties go to queue order);
+ *              0: queue order, for comparison
  *   "sb_rows", "sb_cols"  super-block shape used to order the task queue
  *   "shells"   1: super-blocks are visited in growing square shells, 0: block row by block row
  *   "profile"  1: time every launch with events (adds two event records per launch);

@@ -461,6 +461,7 @@ int blasx_set_option(const char* name, long value) {
     else if (n == "kchain") { if (value < 0 || value > kMaxChain) return BLASX_ERR_CONFIG; L.cfg.kchain = (int)value; }
     else if (n == "depth") { if (value < 1 || value > 1024) return BLASX_ERR_CONFIG; L.cfg.depth = (int)value; }
     else if (n == "rs") { if (value < 1 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.rs = (int)value; }
+    else if (n == "priority") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.priority = value != 0; }
     else if (n == "sb_rows") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_rows = (int)value; }
     else if (n == "sb_cols") { if (value < 1 || value > 4096) return BLASX_ERR_CONFIG; L.order.sb_cols = (int)value; }
     else if (n == "shells") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.order.shells = (int)value; }
@@ -485,6 +486,7 @@ long blasx_get_option(const char* name) {
     if (n == "kchain") return L.cfg.kchain;
     if (n == "depth") return L.cfg.depth;
     if (n == "rs") return L.cfg.rs;
+    if (n == "priority") return L.cfg.priority ? 1 : 0;
     if (n == "sb_rows") return L.order.sb_rows;
     if (n == "sb_cols") return L.order.sb_cols;
     if (n == "shells") return L.order.shells;

@@ -337,6 +337,7 @@ bool Scheduler::deps_started(const Task& t) const {
 // the (single-level) cache and 0 otherwise.
 int64_t Scheduler::priority(const Task& t) const {
     int64_t pr = 0;
+    if (!cfg_.priority) return 0;
     for (const StepSpec& s : t.steps) {
         if (cache_.find(key_of(s.a))) pr += 2;
         if (cache_.find(key_of(s.b))) pr += 2;

@@ -45,6 +45,7 @@ struct SchedConfig {
     int kchain = 0;     // k-steps fused per launch (1..kMaxChain; 0: chosen per run)
     int depth = 6;      // launches in flight before the host waits
     int rs = 32;        // reservation-station size
+    bool priority = true;   // rank the tasks of the reservation station by Eq. 2; false: queue order (for comparison)
     int wide = 11;      // let every task of a call advance together when the cache has room and every
                         // task has at least this many k-steps (see run()); 0: never
     int prefetch = 24;  // wide mode: inbound copies are started this many launches ahead of the launch being built

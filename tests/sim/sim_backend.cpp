@@ -46,6 +46,7 @@ struct Ev {
     double time = 0;      // simulated device clock when the latest record ran
 };
 
+std::vector<const void*> g_h2d_sources;      // host source of every inbound copy, in issue order (trace for tests)
 uint64_t g_seed = 12345;
 uint64_t g_ops_run = 0, g_max_pending = 0;
 bool g_deadlock = false;
@@ -157,6 +158,7 @@ public:
     }
 
     int copy_h2d(void* dst, size_t dp, const void* src, size_t sp, size_t w, size_t h, int s) override {
+        g_h2d_sources.push_back(src);
         return copy(dst, dp, src, sp, w, h, s);
     }
     int copy_d2h(void* dst, size_t dp, const void* src, size_t sp, size_t w, size_t h, int s) override {
@@ -389,4 +391,11 @@ void blasx_sim_seed(uint64_t seed) { blasx::g_seed = seed ? seed : 1; }
 uint64_t blasx_sim_ops_run(void) { return blasx::g_ops_run; }
 uint64_t blasx_sim_max_pending(void) { return blasx::g_max_pending; }
 int blasx_sim_deadlocked(void) { return blasx::g_deadlock ? 1 : 0; }
+// Trace of inbound copies: host source addresses in the order the scheduler issued them.
+void blasx_sim_trace_reset(void) { blasx::g_h2d_sources.clear(); }
+uint64_t blasx_sim_trace_h2d(const void** out, uint64_t max) {
+    const uint64_t n = blasx::g_h2d_sources.size();
+    for (uint64_t q = 0; q < n && q < max; ++q) out[q] = blasx::g_h2d_sources[q];
+    return n;
+}
 }

@@ -30,7 +30,7 @@ def setup(sim, T, nstreams=4, arena_tiles=64, cap_tiles=0, seed=1, esize=8, **op
     sim.init_raw(arena_tiles * T * T * esize, nstreams)
     sim.set_tile(T)
     sim.set_cache_bytes(cap_tiles * T * T * esize)
-    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, profile=0, persist=0, wide=0, ramp=0)
+    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, shells=1, priority=1, profile=0, persist=0, wide=0, ramp=0)
     defaults.update(opts)
     for k, v in defaults.items():
         sim.set_option(k, v)
@@ -244,6 +244,86 @@ def test_host_time_is_split_into_issuing_and_waiting_and_the_device_time_is_diss
             ncopies = st["copies_h2d"] + st["copies_d2h"]
             assert ncopies == 36 * 2 + 36 and span <= st["launches"] * 5e-6 + ncopies * 2e-6 + 1e-12
     sim.set_option("profile", 0)
+
+
+def start_order(sim, C, T):
+    """Tile indices (i, j) of the output tiles in the order their tasks were started, read from the test double's
+    trace of inbound copies: with beta != 0 a task's first device operation is the copy of its own tile of C."""
+    import ctypes
+    buf = (ctypes.c_void_p * 65536)()
+    sim._lib.blasx_sim_trace_h2d.restype = ctypes.c_uint64
+    n = sim._lib.blasx_sim_trace_h2d(buf, 65536)
+    lo, ld = C.ctypes.data, C.strides[1] // 8
+    out = []
+    for q in range(n):
+        off = (buf[q] or 0) - lo
+        if 0 <= off < C.shape[1] * ld * 8:
+            e = off // 8
+            out.append((int(e % ld) // T, int(e // ld) // T))
+    return out
+
+
+def test_reservation_station_starts_the_task_with_most_cached_operands_and_ties_go_to_queue_order(sim):
+    """Alg. 1 lines 10-15 and Eq. 2: the priority of a waiting task is 2 per operand tile already in the cache; the
+    station hands out the highest priority first, equal ones in queue order.  A first call leaves block row r of A and
+    block column c of B in the (persistent) cache; the second call must then start task (r, c), whose operands are all
+    there, then the tasks of row r and column c in queue order, then the others in queue order.  With the priorities
+    switched off the same call starts in queue order."""
+    T, nt, nk, r, c = 16, 4, 3, 2, 3
+    rng = np.random.default_rng(33)
+    A = np.asfortranarray(rng.integers(-2, 3, (nt * T, nk * T)).astype(np.float64))
+    B = np.asfortranarray(rng.integers(-2, 3, (nk * T, nt * T)).astype(np.float64))
+    C0 = np.asfortranarray(rng.integers(-2, 3, (nt * T, nt * T)).astype(np.float64))
+    n = nt * T
+    orders, misses = {}, {}
+    for prio in (0, 1):
+        # the station holds every task of the call, so the priorities are worked out once, when the tasks come in
+        setup(sim, T=T, arena_tiles=64, group=1, rs=64, kchain=1, persist=1, priority=prio, sb_rows=2, sb_cols=2)
+        W = np.zeros((T, T), order="F")
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, T, T, nk * T, 1.0, A[r * T:, :], n, B[:, c * T:], nk * T, 0.0, W, T)
+        assert np.array_equal(W, A[r * T:(r + 1) * T, :] @ B[:, c * T:(c + 1) * T])
+        assert sim.get_option("cached_tiles") == 2 * nk
+        C = C0.copy(order="F")
+        sim._lib.blasx_sim_trace_reset()
+        sim.reset_stats()
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, nk * T, 1.0, A, n, B, nk * T, 1.0, C, n)
+        assert np.array_equal(C, A @ B + C0)
+        orders[prio] = start_order(sim, C, T)
+        misses[prio] = sim.get_stats()["misses"]
+        assert len(orders[prio]) == nt * nt and len(set(orders[prio])) == nt * nt
+        sim.set_option("persist", 0)
+    queue = orders[0]
+    priority = lambda ij: 2 * nk * (ij[0] == r) + 2 * nk * (ij[1] == c)
+    expect = sorted(queue, key=lambda ij: -priority(ij))           # stable: ties keep queue order
+    assert queue[0] != (r, c) and expect[0] == (r, c)
+    assert orders[1] == expect
+    # room for everything: each tile is fetched once whatever the order, the cached ones never
+    assert misses[0] == misses[1] == 2 * nt * nk - 2 * nk
+    sim.set_option("priority", 1)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_priorities_save_tile_fetches_under_a_small_cache(sim, seed):
+    """What Eq. 2 is for: with a cache of 12 tiles, one task running and a station of 4 (refreshed whenever a task
+    comes in), the task started next is the one that finds most of its operands still cached, and an 8 x 8-tile
+    product with 4 k-tiles fetches a third fewer tiles than in queue order -- for every interleaving of the device."""
+    T, nt, nk = 16, 8, 4
+    rng = np.random.default_rng(34)
+    A = np.asfortranarray(rng.integers(-2, 3, (nt * T, nk * T)).astype(np.float64))
+    B = np.asfortranarray(rng.integers(-2, 3, (nk * T, nt * T)).astype(np.float64))
+    n = nt * T
+    misses = {}
+    for prio in (0, 1):
+        setup(sim, T=T, arena_tiles=64, cap_tiles=12, group=1, rs=4, kchain=1, priority=prio, sb_rows=2, sb_cols=2, shells=0, seed=900 + seed)
+        C = np.zeros((n, n), order="F")
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, nk * T, 1.0, A, n, B, nk * T, 0.0, C, n)
+        assert np.array_equal(C, A @ B)
+        st = sim.get_stats()
+        assert st["misses"] == 2 * nt * nk + st["refetches"]
+        misses[prio] = st["misses"]
+    assert misses[1] < 0.8 * misses[0], misses
+    sim.set_option("priority", 1)
+    sim.set_option("shells", 1)
 
 
 # ------------------------------------------------------------------ SYRK ----------
