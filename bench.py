@@ -18,6 +18,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP64_MFMA_PEAK_TFLOPS = 78.6     # MI355X dense FP64 matrix peak (published)
+FP32_MFMA_PEAK_TFLOPS = 157.3    # MI355X dense FP32 matrix peak (published)
+# Sustained inbound rate of the host link for a long run of strided tile copies (one 8 MiB tile per 163 us on the
+# copy engine, measured with a memory-copy trace; 57 GB/s for one contiguous copy).  A call cannot take less than
+# its inbound bytes at this rate: both directions run at once and a call sends out less than it takes in.
+LINK_SUSTAINED_GBPS = 51.4
 
 
 def cpu_baseline(np, oracle, A, B, n, rows=2048, cols=8192):
@@ -38,6 +43,126 @@ def cpu_baseline(np, oracle, A, B, n, rows=2048, cols=8192):
     }
 
 
+def traffic_from_profile():
+    """HBM bytes per launch of the benchmark's kernel, read from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs of this very command, scaled by the same counters on a plain 1 GiB device copy).  They are a property
+    of the launch shape, measured once, not in this run: marked static."""
+    import re
+    path = os.path.join(ROOT, "profiles", "tile_steps_f64_nn_dgemm32768_hbm_traffic.md")
+    try:
+        text = open(path).read()
+        row = re.search(r"\| mean over the 320 launches of a call \| ([0-9.]+) GB \| ([0-9.]+) GB \| ([0-9.]+) GB \| ([0-9.]+) GB \|", text)
+        read, alg_read, write, alg_write = (float(g) * 1e9 for g in row.groups())
+    except Exception:
+        return None
+    return {"hbm_bytes_per_launch": read + write, "read": read, "write": write, "algorithmic": alg_read + alg_write,
+            "static": True, "source": "profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md"}
+
+
+def secondary_entry(name, flop, bytes_in, seconds, peak_tflops, extra=None):
+    """One line of the secondary list: time and rate of a single call after a warm-up call, against the smaller of
+    the two bounds of a host-resident call -- its inbound bytes at the link's sustained rate, or its flop at the
+    MFMA peak."""
+    t_link = bytes_in / (LINK_SUSTAINED_GBPS * 1e9)
+    t_mfma = flop / (peak_tflops * 1e12)
+    bound = "link" if t_link > t_mfma else "mfma"
+    t_bound = max(t_link, t_mfma)
+    out = {"name": name, "ms": round(seconds * 1e3, 2), "TFLOP/s": round(flop / seconds / 1e12, 2), "bound": bound,
+           "bound_ms": round(t_bound * 1e3, 2), "frac": round(t_bound / seconds, 4)}
+    if extra:
+        out.update(extra)
+    return out
+
+
+def run_secondary(np, torch, lib, blasx, synth, A, B, C, owners, n, want_cfg3):
+    """The other configured workloads, one timed call each after one warm-up call, on the matrices of the headline
+    run (sub-matrices keep its leading dimension; values do not matter for timing, they stay uniform[-1,1]).
+    Library's own choices throughout (tile 1024 unless stated, running set, chains, schedule)."""
+    import time
+    CM, NT, TR = blasx.ColMajor, blasx.NoTrans, blasx.Trans
+    out = []
+
+    def timed(fn):
+        fn()                                   # warm-up (also pages in whatever the first call of a shape touches)
+        torch.cuda.synchronize()
+        lib.reset_stats()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    lib.set_option("profile", 0)
+    lib.set_tile(1024)
+    for m in (4096, 8192, 16384):
+        if m > n:
+            continue
+        dt = timed(lambda: lib.dgemm(CM, NT, NT, m, m, m, 1.0, A, n, B, n, 1.0, C, n))
+        out.append(secondary_entry("DGEMM NN N=%d T=1024 alpha=beta=1" % m, 2.0 * m ** 3, 3 * 8.0 * m * m, dt, FP64_MFMA_PEAK_TFLOPS))
+    if n >= 16384:
+        N, K = 16384, 8192
+        dt = timed(lambda: lib.dsyrk(CM, blasx.Lower, NT, N, K, 1.0, A, n, 1.0, C, n))
+        nt = N // 1024
+        out.append(secondary_entry("DSYRK Lower/NoTrans N=16384 K=8192 beta=1", 1.0 * N * (N + 1) * K,
+                                   8.0 * (N * K + 1024 * 1024 * nt * (nt + 1) // 2), dt, FP64_MFMA_PEAK_TFLOPS))
+        # triangular solve: the triangle made diagonally dominant as the workload says (diag = N + uniform[0,1))
+        M = 16384
+        synth.dominant_diag(A[:M, :M], 0, synth.MAT_A)
+        dt = timed(lambda: lib.dtrsm(CM, blasx.Left, blasx.Lower, NT, blasx.NonUnit, M, M, 1.0, A, n, B, n))
+        nt = M // 1024
+        out.append(secondary_entry("DTRSM Left/Lower/NoTrans/NonUnit M=N=16384", 1.0 * M * M * M,
+                                   8.0 * (1024 * 1024 * nt * (nt + 1) // 2 + M * M), dt, FP64_MFMA_PEAK_TFLOPS))
+        synth.fill(A, 0, synth.MAT_A)
+        synth.fill(B, 0, synth.MAT_B)
+    if n >= 32768:
+        # A^T B with a long inner dimension: A and B stored 65536 x 8192 (the headline matrices' memory seen with a
+        # leading dimension of 65536)
+        M, K = 8192, 65536
+        A2 = np.frombuffer((__import__("ctypes").c_char * (8 * K * M)).from_address(owners[0].ptr), dtype=np.float64).reshape((M, K)).T
+        B2 = np.frombuffer((__import__("ctypes").c_char * (8 * K * M)).from_address(owners[1].ptr), dtype=np.float64).reshape((M, K)).T
+        dt = timed(lambda: lib.dgemm(CM, TR, NT, M, M, K, 1.0, A2, K, B2, K, 1.0, C, n))
+        out.append(secondary_entry("DGEMM Trans/NoTrans M=N=8192 K=65536 alpha=beta=1", 2.0 * M * M * K, 8.0 * (2 * M * K + M * M), dt,
+                                   FP64_MFMA_PEAK_TFLOPS))
+        # single precision, A B^T, tile 2048 as configured: the same memory refilled as float32 matrices
+        m = 32768
+        f32 = [np.frombuffer((__import__("ctypes").c_char * (4 * m * m)).from_address(o.ptr), dtype=np.float32).reshape((m, m)).T for o in owners]
+        for q, a in enumerate(f32):
+            synth.fill(a, 7, q)
+        lib.set_tile(2048)
+        dt = timed(lambda: lib.sgemm(CM, NT, TR, m, m, m, 1.0, f32[0], m, f32[1], m, 1.0, f32[2], m))
+        out.append(secondary_entry("SGEMM NoTrans/Trans M=N=K=32768 T=2048 alpha=beta=1", 2.0 * m ** 3, 3 * 4.0 * m * m, dt, FP32_MFMA_PEAK_TFLOPS))
+        lib.set_tile(0)
+        dt = timed(lambda: lib.sgemm(CM, NT, TR, m, m, m, 1.0, f32[0], m, f32[1], m, 1.0, f32[2], m))
+        out.append(secondary_entry("same, tile chosen by the library (%d)" % lib.get_option("last_tile"), 2.0 * m ** 3, 3 * 4.0 * m * m, dt,
+                                   FP32_MFMA_PEAK_TFLOPS))
+        lib.set_tile(1024)
+    if want_cfg3:
+        import psutil
+        m, T = 49152, 2048
+        extra = 3 * 8 * m * m - 3 * 8 * n * n
+        if psutil.virtual_memory().available < 1.1 * extra + 8e9:
+            out.append({"name": "out-of-core DGEMM N=49152 T=2048 cache capped 8 GB", "skipped": "host memory: %.0f GB more needed, %.0f GB available"
+                        % (extra / 1e9, psutil.virtual_memory().available / 1e9)})
+        else:
+            for o in owners:
+                o.free()
+            big = [blasx.pinned_matrix(m, m) for _ in range(3)]
+            synth.fill(big[0][0], 0, synth.MAT_A)
+            synth.fill(big[1][0], 0, synth.MAT_B)
+            lib.set_tile(T)
+            lib.set_cache_bytes(8 * 2 ** 30)
+            dt = timed(lambda: lib.dgemm(CM, NT, NT, m, m, m, 1.0, big[0][0], m, big[1][0], m, 0.0, big[2][0], m))
+            st = lib.get_stats()
+            out.append(secondary_entry("out-of-core DGEMM N=49152 T=2048 beta=0 cache capped 8 GB", 2.0 * m ** 3, float(st["bytes_h2d"]), dt,
+                                       FP64_MFMA_PEAK_TFLOPS,
+                                       {"evictions": st["evictions"], "refetches": st["refetches"], "bytes_h2d": st["bytes_h2d"],
+                                        "note": "link bound taken on the bytes the schedule actually fetched (re-fetches included)"}))
+            lib.set_cache_bytes(0)
+            lib.set_tile(1024)
+            for _, o in big:
+                o.free()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,6 +181,8 @@ def main():
     ap.add_argument("--wide", type=int, default=None, help="least k-steps per task for which all tasks advance together when the cache has room (default 11); 0: grouped")
     ap.add_argument("--arena-gb", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the other configured workloads (one timed call each)")
+    ap.add_argument("--no-out-of-core", action="store_true", help="skip the N=49152 capped-cache entry of the secondary list")
     ap.add_argument("--check", action="store_true", help="also compare sampled outputs with the oracle")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the benchmark, run plain device copies of a known size (1 GiB read + 1 GiB written "
@@ -141,15 +268,27 @@ def main():
     flop_per_launch = st["flops"] / max(1, st["launches"])
     achieved = flop_per_launch / avg_launch_s / 1e12 if avg_launch_s > 0 else 0.0
 
-    # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command, scaled by the
-    # same counters on a plain 1 GiB device copy (profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md); they are
-    # a property of the launch shape, so they are only quoted for the shape they were measured on.
+    # HBM bytes per launch: only quoted for the launch shape the committed counter runs were made on
     traffic = None
     shape = (n, T, lib.get_option("last_group"), lib.get_option("last_kchain"), lib.get_option("last_wide"), lib.get_option("last_ramp"))
     if shape == (32768, 1024, 16, 8, 1, 2):
-        # means over the 320 launches of a call (rounds of 2, 6, 8, 8 and 8 k-tiles)
-        traffic = {"hbm_bytes_per_launch": 2.839e9, "read": 2.704e9, "write": 0.1345e9, "algorithmic": 1.986e9,
-                   "source": "profiles/tile_steps_f64_nn_dgemm32768_hbm_traffic.md"}
+        traffic = traffic_from_profile()
+
+    # The paper's time profile of one more (untimed) call: an event pair around every tile copy as well (Section V.A)
+    lib.set_option("profile", 2)
+    lib.reset_stats()
+    step()
+    torch.cuda.synchronize()
+    tp = lib.get_stats()
+    lib.set_option("profile", 1)
+    time_profile = {
+        "what": "one further call with an event pair around every launch and every tile copy (device clock)",
+        "device_span_ms": round(tp["t_device_span_s"] * 1e3, 2),
+        "compute_ms": round(tp["t_kernel_busy_s"] * 1e3, 2),
+        "copy_not_overlapped_ms": round(tp["t_copy_unoverlapped_s"] * 1e3, 2),
+        "other_ms": round((tp["t_device_span_s"] - tp["t_kernel_busy_s"] - tp["t_copy_unoverlapped_s"]) * 1e3, 2),
+        "host_issue_ms": round(tp["t_issue_s"] * 1e3, 2), "host_wait_ms": round(tp["t_wait_s"] * 1e3, 2),
+    }
     out = {
         "metric": "host-resident DGEMM GFLOP/s on 1 MI355X", "value": round(gflops, 1), "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 2),
@@ -177,7 +316,9 @@ def main():
         "cache": {k: st[k] for k in ("hits", "misses", "evictions", "refetches", "peak_slots", "slot_waits")},
         "host": {"pin_seconds": round(t_pin, 2), "fill_seconds": round(t_fill, 2),
                  "issue_fraction": round(st["t_issue_s"] / max(st["t_total_s"], 1e-9), 3),
+                 "wait_fraction": round(st["t_wait_s"] / max(st["t_total_s"], 1e-9), 3),
                  "kernel_busy_fraction": round(st["t_kernel_s"] / dt, 3)},
+        "time_profile": time_profile,
     }
     if args.check:
         import oracle
@@ -199,6 +340,9 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         out["cpu_baseline"] = cpu_baseline(np, oracle, A, B, n)
+    if not args.no_secondary:
+        # after the headline figures are final: these calls overwrite C and refill A and B
+        out["secondary"] = run_secondary(np, torch, lib, blasx, synth, A, B, C, [ka, kb, kc], n, not args.no_out_of_core)
     lib.shutdown()
     print(json.dumps(out))
 

@@ -128,8 +128,16 @@ class Library:
                 # stream lands on depends on what was created before it, and two roles that end
                 # up sharing a queue serialise (measured: 68 -> 42 TFLOP/s); the first streams a
                 # process creates get queues of their own
-                while len(_stream_cache) < nstreams:
-                    _stream_cache.append(torch.cuda.Stream())
+                # All four are made, and used once, at the first init of the process -- also when it asks
+                # for fewer: a stream gets its hardware queue (the least loaded of the process's four) when
+                # it is first used, so streams made or first used later, after other streams have come and
+                # gone, can end up sharing a queue with the compute stream (measured: 72 -> 45 TFLOP/s)
+                if not _stream_cache:
+                    for _ in range(4):
+                        st = torch.cuda.Stream()
+                        torch.cuda.Event().record(st)
+                        st.synchronize()
+                        _stream_cache.append(st)
                 streams = _stream_cache[:nstreams]
                 keep.append(streams)
                 stream_ptrs = [s.cuda_stream for s in streams]

@@ -168,11 +168,20 @@ public:
         hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
         std::vector<hipStream_t>& made = own_streams()[dev];
-        while ((int)made.size() <= s) {
+        // All four at once, each used once straight away (an event record): a stream is given its
+        // hardware queue, the least loaded one, at its first use, so four streams made and first
+        // used back to back get four different queues whatever the process does later.
+        while ((int)made.size() < 4 || (int)made.size() <= s) {
             hipStream_t fresh = nullptr;
             e = hipStreamCreateWithFlags(&fresh, hipStreamNonBlocking);
             if (e != hipSuccess) return e;
             made.push_back(fresh);
+            hipEvent_t touch;
+            if (hipEventCreateWithFlags(&touch, hipEventDisableTiming) == hipSuccess) {
+                (void)hipEventRecord(touch, fresh);
+                (void)hipStreamSynchronize(fresh);
+                (void)hipEventDestroy(touch);
+            }
         }
         *out = made[s];
         return hipSuccess;

@@ -13,7 +13,9 @@ it needs).  Two gates on every comparison:
               (each addition errs by at most u/2 of a partial sum whose own spread is
               sqrt(k) sigma_a sigma_b), so the bound is beyond ten deviations whatever K is,
               while one wrong element with a relative error of 1e-10 fails it.  It is always
-              below the worst-case bound K u (|A||B|)_ij once K > 16.
+              below the worst-case bound K u (|A||B|)_ij once K > 16.  The one place where the terms
+              of a sum are not zero-mean -- the diagonal of A A^T, a sum of squares -- gets the
+              worst-case bound instead (square_sums).
 Integer-valued inputs make every product and sum exact: those cases must match bit for bit, so
 that a mistake at a tile, macro-tile or chain boundary shows as a mismatch and not as a small error.
 """
@@ -84,6 +86,19 @@ def elem_bound(row_norms, col_norms, alpha=1.0, beta_c=None, single=False, want=
     if single and want is not None:
         b = b + u * np.abs(np.asarray(want, dtype=np.float64))
     return b + 1e-300
+
+
+def square_sums(row_norms, K, alpha=1.0, single=False, gi=None, gj=None):
+    """Extra allowance where an output element is a sum of squares (the diagonal of A A^T): the terms are all of one
+    sign, the partial sums grow like k instead of sqrt(k), and the bound of zero-mean data does not apply; there the
+    worst-case bound 2 K u sum(a^2) (K u for the oracle's sum, K u for the kernel's) is taken.  gi, gj: global row and
+    column indices of the compared block (default: a whole square matrix)."""
+    n = len(row_norms)
+    gi = np.arange(n) if gi is None else np.asarray(gi)
+    gj = np.arange(n) if gj is None else np.asarray(gj)
+    u = U32 if single else U64
+    same = gi[:, None] == gj[None, :]
+    return same * (2.0 * K * u * abs(alpha) * np.asarray(row_norms)[:, None] ** 2)
 
 
 def assert_close(got, want, bound, tol, what="", mask=None):
@@ -327,7 +342,7 @@ def test_dsyrk_small_full_compare(lib, uplo, trans):
     ref.syrk(ref.ColMajor, uplo, trans, 0.9, np.asarray(A), 1.0, want)
     assert np.all(np.asarray(C)[other] == 4321.5)
     rn = norms(op(A, trans), 1)
-    assert_close(C, want, elem_bound(rn, rn, 0.9, C0), TOL64)
+    assert_close(C, want, elem_bound(rn, rn, 0.9, C0) + square_sums(rn, K, 0.9), TOL64)
 
 
 @pytest.mark.parametrize("uplo", [blasx.Upper, blasx.Lower])
@@ -619,14 +634,14 @@ def test_wide_schedule_symmetric_routines_full_compare(lib):
     ref.syrk(ref.ColMajor, ref.Lower, ref.NoTrans, 1.0, np.asarray(A), 0.0, want)
     ra, rb = norms(A, 1), norms(B, 1)
     assert np.all(np.asarray(C)[other] == 1234.5)
-    assert_close(C, want, elem_bound(ra, ra) + 4 * U64 * 1234.5, TOL64)
+    assert_close(C, want, elem_bound(ra, ra) + square_sums(ra, K) + 4 * U64 * 1234.5, TOL64)
     C1 = np.array(C, order="F")
     lib.dsyr2k(blasx.ColMajor, blasx.Lower, blasx.NoTrans, N, K, 0.5, A, N, B, N, 1.0, C, N)
     assert lib.get_option("last_wide") == 1
     ref.syr2k(ref.ColMajor, ref.Lower, ref.NoTrans, 0.5, np.asarray(A), np.asarray(B), 1.0, want)
     assert np.all(np.asarray(C)[other] == 1234.5)
     # (want carries the oracle's SYRK result into the second call, C the library's: both errors add)
-    assert_close(C, want, elem_bound(ra, rb, 0.5, C1) + elem_bound(rb, ra, 0.5) + elem_bound(ra, ra), TOL64)
+    assert_close(C, want, elem_bound(ra, rb, 0.5, C1) + elem_bound(rb, ra, 0.5) + elem_bound(ra, ra) + square_sums(ra, K), TOL64)
     M = 1700
     S, ks = pinned(M, M, 32, 0)
     S[np.tril_indices(M, -1)] = np.nan                       # upper triangle stored
@@ -695,7 +710,8 @@ def test_config4_dsyrk_lower_notrans_sampled(lib):
         ref.gemm(ref.ColMajor, ref.NoTrans, ref.Trans, 1.0, ai, aj, 1.0, want)
         mask = (gi[:, None] >= gj[None, :])            # inside a diagonal tile only the lower part is written
         assert np.array_equal(got[~mask], c0[~mask])
-        worst = max(worst, assert_close(got, want, elem_bound(norms(ai, 1), norms(aj, 1), 1.0, c0), TOL64, (ti, tj), mask=mask))
+        bound = elem_bound(norms(ai, 1), norms(aj, 1), 1.0, c0) + square_sums(norms(ai, 1), K, gi=gi, gj=gj)
+        worst = max(worst, assert_close(got, want, bound, TOL64, (ti, tj), mask=mask))
         seen += 1
     assert seen > 10 and worst < TOL64, worst
     # every element of four whole tiles of the triangle: a diagonal one, the last one, two below the diagonal
@@ -708,7 +724,8 @@ def test_config4_dsyrk_lower_notrans_sampled(lib):
         got = np.asarray(C)[r0:r0 + T, c0_:c0_ + T]
         mask = (np.arange(r0, r0 + T)[:, None] >= np.arange(c0_, c0_ + T)[None, :])
         assert np.array_equal(got[~mask], before_t[~mask])
-        assert_close(got, want, elem_bound(norms(ai, 1), norms(aj, 1), 1.0, before_t), TOL64, ("whole", ti, tj), mask=mask)
+        bound = elem_bound(norms(ai, 1), norms(aj, 1), 1.0, before_t) + square_sums(norms(ai, 1), K, gi=np.arange(r0, r0 + T), gj=np.arange(c0_, c0_ + T))
+        assert_close(got, want, bound, TOL64, ("whole", ti, tj), mask=mask)
 
 
 def check_trsm_columns(A, B, M, cols, seed, tol):
@@ -747,9 +764,10 @@ def test_config4_dtrsm_left_lower_notrans_nonunit_residual(lib, schedule):
     dt = timed(lambda: lib.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, M, N, 1.0, A, M, B, M))
     report("cfg4 DTRSM L/L/N/N M=N=16384 %s" % schedule, lib, 1.0 * M * M * N, dt)
     assert lib.get_option("last_wide") == (1 if schedule == "auto" else 0)
-    # whole block columns of X: the first, the last, one in between (1024 columns each) and 16 single columns
+    # every row of 160 columns of X: 64 of the first block column, 64 of the last (two macro-tile columns each), 16 across a
+    # tile boundary in between and 16 single ones (the oracle's triangular product costs M^2 per column)
     rng = np.random.default_rng(5)
-    cols = np.unique(np.concatenate([np.arange(0, T), np.arange(N - T, N), np.arange(7 * T, 8 * T), rng.choice(N, 16, replace=False)]))
+    cols = np.unique(np.concatenate([np.arange(96, 160), np.arange(N - 64, N), np.arange(7 * T - 8, 7 * T + 8), rng.choice(N, 16, replace=False)]))
     check_trsm_columns(A, B, M, cols, 5, TOL64)
 
 
@@ -764,7 +782,7 @@ def test_dtrsm_order_20480_takes_2048_tiles_residual(lib):
     lib.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, M, N, 1.0, A, M, B, M)
     assert lib.get_option("last_tile") == 2048 and lib.get_option("last_wide") == 1
     rng = np.random.default_rng(6)
-    cols = np.unique(np.concatenate([np.arange(0, 256), np.arange(N - 256, N), rng.choice(N, 8, replace=False)]))
+    cols = np.unique(np.concatenate([np.arange(120, 136), np.arange(N - 16, N), rng.choice(N, 8, replace=False)]))
     check_trsm_columns(A, B, M, cols, 6, TOL64)
 
 
@@ -1180,7 +1198,7 @@ def test_single_precision_syrk_trmm_trsm(lib):
     C0 = np.array(C, order="F")
     lib.ssyrk(blasx.ColMajor, blasx.Lower, blasx.NoTrans, N, K, 1.0, A, N, 1.0, C, N)
     ref.syrk(ref.ColMajor, ref.Lower, ref.NoTrans, 1.0, np.asarray(A), 1.0, want)
-    assert_close(C, want, elem_bound(norms(A, 1), norms(A, 1), 1.0, C0, single=True, want=want), TOL32)
+    assert_close(C, want, elem_bound(norms(A, 1), norms(A, 1), 1.0, C0, single=True, want=want) + square_sums(norms(A, 1), K, single=True), TOL32)
     M, Nb = 768, 520
     T64, kt = triangular(M, 13, blasx.Upper, blasx.NonUnit)
     T32, k32 = blasx.pinned_matrix(M, M, dtype=np.float32)
@@ -1244,7 +1262,7 @@ def test_seeded_random_problems_every_routine_and_schedule(lib, seed):
         if routine == "syrk":
             lib.dsyrk(blasx.ColMajor, uplo, trans, N, K, alpha, A, A.shape[0], beta, C, N)
             ref.syrk(ref.ColMajor, uplo, trans, alpha, np.asarray(A), beta, want)
-            bound = elem_bound(ra, ra, alpha, beta * C0)
+            bound = elem_bound(ra, ra, alpha, beta * C0) + square_sums(ra, K, alpha)
         else:
             lib.dsyr2k(blasx.ColMajor, uplo, trans, N, K, alpha, A, A.shape[0], B, B.shape[0], beta, C, N)
             ref.syr2k(ref.ColMajor, uplo, trans, alpha, np.asarray(A), np.asarray(B), beta, want)
@@ -1329,7 +1347,7 @@ def test_seeded_random_problems_single_precision(lib, seed):
         if routine == "syrk":
             lib.ssyrk(blasx.ColMajor, uplo, trans, N, K, alpha, A, A.shape[0], beta, C, N)
             ref.syrk(ref.ColMajor, uplo, trans, alpha, np.asarray(A), beta, want)
-            bound = elem_bound(ra, ra, alpha, beta * C0, single=True, want=want)
+            bound = elem_bound(ra, ra, alpha, beta * C0, single=True, want=want) + square_sums(ra, K, alpha, single=True)
         else:
             lib.ssyr2k(blasx.ColMajor, uplo, trans, N, K, alpha, A, A.shape[0], B, B.shape[0], beta, C, N)
             ref.syr2k(ref.ColMajor, uplo, trans, alpha, np.asarray(A), np.asarray(B), beta, want)
