@@ -48,7 +48,8 @@ enum {
     BLASX_ERR_DEVICE = 3,           /* a HIP call failed; see blasx_last_error() */
     BLASX_ERR_CONFIG = 4,           /* invalid tile size / stream count / option value */
     BLASX_ERR_NO_MEMORY = 5,        /* host allocation failed */
-    BLASX_ERR_UNSUPPORTED = 6       /* valid BLAS arguments that this build does not cover */
+    BLASX_ERR_UNSUPPORTED = 6,      /* valid BLAS arguments that this build does not cover */
+    BLASX_ERR_TOO_LARGE = 7         /* blasx_dgemm_noalloc: the operands do not fit the static scratch */
 };
 
 /* ------------------------------------------------------------------ level-3 routines -- */
@@ -60,6 +61,27 @@ int blasx_dgemm(int Order, int TransA, int TransB, int M, int N, int K, double a
                 const double* A, int lda, const double* B, int ldb, double beta, double* C, int ldc);
 int blasx_sgemm(int Order, int TransA, int TransB, int M, int N, int K, float alpha,
                 const float* A, int lda, const float* B, int ldb, float beta, float* C, int ldc);
+
+/* blasx_dgemm for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result, same error codes as
+ * blasx_dgemm, but the tile slots live in an array that is part of the library's device image
+ * (256 MiB per GPU the library runs on, held until the process ends) instead of the arena given to
+ * blasx_init, and the call makes no hipMalloc, hipFree, stream or event creation and no other allocating
+ * call: blasx_init (which must have been called, on this device) has looked the array's address up
+ * and created the events it uses.
+ *   - A, B and C must be page-locked (BLASX_ERR_UNSUPPORTED otherwise: the runtime would stage
+ *     pageable memory through buffers of its own).
+ *   - Tile edge: the configured one (blasx_set_tile) if it is between 16 and 512, else 512.  Every tile of
+ *     A, B and C gets a slot of its own and nothing is evicted, so the call is accepted when
+ *         nt(M) nt(K) + nt(K) nt(N) + nt(M) nt(N) + 8 <= 256 MiB / (T * T * 8 bytes),   nt(x) = ceil(x / T)
+ *     (T = 512: 128 slots, e.g. M = N = K <= 3072 rounded down to what the count allows: 2560), and
+ *     refused with BLASX_ERR_TOO_LARGE (text in blasx_last_error) otherwise.  Nothing is computed then.
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's contents; nothing in
+ *     it needs to start at zero (an accumulator tile is written before it is read).  Calls that
+ *     overlap on one GPU would race: like the rest of the library, one call at a time.
+ *   - "persist", "profile" and blasx_set_cache_bytes do not apply; the other options do. */
+int blasx_dgemm_noalloc(int Order, int TransA, int TransB, int M, int N, int K, double alpha,
+                        const double* A, int lda, const double* B, int ldb, double beta, double* C, int ldc);
 
 /* C <- alpha * A * A^T + beta * C (Trans = none, A is N x K) or
  * C <- alpha * A^T * A + beta * C (Trans = transpose, A is K x N)      (paper Eq. 1b)

@@ -74,6 +74,7 @@ class Library:
         self._lib = lib = ctypes.CDLL(path)
         ci, cd, cf, vp, sz = ctypes.c_int, ctypes.c_double, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
         lib.blasx_dgemm.argtypes = [ci, ci, ci, ci, ci, ci, cd, vp, ci, vp, ci, cd, vp, ci]
+        lib.blasx_dgemm_noalloc.argtypes = lib.blasx_dgemm.argtypes
         lib.blasx_sgemm.argtypes = [ci, ci, ci, ci, ci, ci, cf, vp, ci, vp, ci, cf, vp, ci]
         lib.blasx_dsyrk.argtypes = [ci, ci, ci, ci, ci, cd, vp, ci, cd, vp, ci]
         lib.blasx_ssyrk.argtypes = [ci, ci, ci, ci, ci, cf, vp, ci, cf, vp, ci]
@@ -209,6 +210,12 @@ class Library:
         rc = self._lib.blasx_dgemm(Order, TransA, TransB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc)
         if check:
             self._check("blasx_dgemm", rc)
+        return rc
+
+    def dgemm_noalloc(self, Order, TransA, TransB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, check=True):
+        rc = self._lib.blasx_dgemm_noalloc(Order, TransA, TransB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc)
+        if check:
+            self._check("blasx_dgemm_noalloc", rc)
         return rc
 
     def sgemm(self, Order, TransA, TransB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, check=True):

@@ -41,7 +41,10 @@ public:
                                   int stream) = 0;
     // dst (cols x rows) <- transpose of src (rows x cols); device pointers, column-major.
     virtual int launch_transpose(int dtype, const void* src, int ld_src, int rows, int cols, void* dst, int ld_dst, int stream) = 0;
-    // Events are small integers; event_destroy() hands one back for reuse.
+    // Events are small integers; event_destroy() hands one back for reuse.  After reserve_events(n)
+    // the backend owns at least n events and event_create() never makes another one: it returns -1
+    // when they are all in use (the allocation-free entry point must not create anything).
+    virtual int  reserve_events(int n) = 0;
     virtual int  event_create() = 0;
     virtual void event_destroy(int ev) = 0;
     virtual int  event_record(int ev, int stream) = 0;
@@ -60,5 +63,13 @@ void* backend_host_alloc(size_t bytes);
 int   backend_host_free(void* p);
 // Frees device memory that the backend allocated itself and kept for a later init (blasx_shutdown).
 void  backend_release_device_memory();
+// The statically allocated tile arena of the current device (for callers that cannot allocate):
+// device address and size.  Looked up once per device; non-zero on failure.
+int   backend_static_arena(void** ptr, size_t* bytes);
+// Whether [p, p + bytes) is host memory that the device can reach without staging (page-locked).
+bool  backend_host_is_pinned(const void* p);
+// Runs every instantiation of the tile kernel for `dtype` once with no work, so that the runtime
+// has loaded them before a caller that cannot allocate launches them.  Non-zero on failure.
+int   backend_warm_kernels(Backend& be, int dtype);
 
 }  // namespace blasx

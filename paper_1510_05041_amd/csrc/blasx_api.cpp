@@ -17,6 +17,9 @@ namespace {
 
 struct Library {
     std::unique_ptr<Backend> be;
+    // the same streams over the statically allocated tile arena, with a fixed pool of events: what the
+    // allocation-free entry point runs on
+    std::unique_ptr<Backend> be_static;
     int T = 1024;
     size_t cache_cap = 0;
     SchedConfig cfg;
@@ -134,19 +137,26 @@ int pick_group(const Problem& p) {
 bool is_trans(int t) { return t == BLASX_TRANS || t == BLASX_CONJ_TRANS; }
 bool ok_trans(int t) { return t == BLASX_NO_TRANS || is_trans(t); }
 
-int run_problem(Problem& p) {
+constexpr int kStaticTile = 512;        // largest tile edge of the allocation-free entry point
+constexpr int kStaticEvents = 1024;     // its event pool: a fill event per slot, one per launch in flight and per pending result
+
+size_t slot_bytes_of(int T, size_t esize) { return ((size_t)T * (size_t)T * esize + 255) / 256 * 256; }
+
+// on_static: run on the statically allocated arena (whole of it, no cap, cache dropped at return)
+int run_problem(Problem& p, bool on_static = false) {
     Library& L = lib();
-    const size_t tile_bytes = (size_t)p.T * (size_t)p.T * p.esize;
+    Backend& be = on_static ? *L.be_static : *L.be;
     L.last_T = p.T;
-    const size_t slot_bytes = (tile_bytes + 255) / 256 * 256;
-    size_t usable = L.be->arena_bytes();
-    if (L.cache_cap && L.cache_cap < usable) usable = L.cache_cap;
+    const size_t slot_bytes = slot_bytes_of(p.T, p.esize);
+    size_t usable = be.arena_bytes();
+    if (!on_static && L.cache_cap && L.cache_cap < usable) usable = L.cache_cap;
     const size_t nslots = usable / slot_bytes;
     if (nslots < 4) {
         L.last_error = "tile cache holds fewer than 4 tiles of the configured size";
         return BLASX_ERR_ARENA_TOO_SMALL;
     }
     SchedConfig cfg = L.cfg;
+    if (on_static) cfg.profile = 0;      // event-timed launches would draw on the fixed event pool
     cfg.group = pick_group(p);
     cfg.rs = std::max(cfg.rs, 2 * cfg.group);
     // the running set and its operands must fit: each running task owns an accumulator slot
@@ -160,7 +170,13 @@ int run_problem(Problem& p) {
     ++L.stats.calls;
     int rc;
     const size_t ns = std::min<size_t>(nslots, 1u << 30);
-    if (L.persist) {
+    if (on_static) {
+        Scheduler sched(be, (int)ns, slot_bytes, cfg, L.stats);
+        rc = sched.run(p);
+        L.last_wide = sched.last_run_was_wide();
+        L.last_kchain = sched.last_run_kchain();
+        L.last_ramp = sched.last_run_first_chain();
+    } else if (L.persist) {
         // the cached tiles survive as long as the slot geometry does
         if (!L.sched || L.sched_slot_bytes != slot_bytes || L.sched_nslots != ns || L.sched_T != p.T) {
             L.sched.reset(new Scheduler(*L.be, (int)ns, slot_bytes, cfg, L.stats));
@@ -182,14 +198,14 @@ int run_problem(Problem& p) {
         L.last_kchain = sched.last_run_kchain();
         L.last_ramp = sched.last_run_first_chain();
     }
-    if (rc == BLASX_ERR_DEVICE) L.last_error = L.be->last_error();
+    if (rc == BLASX_ERR_DEVICE) L.last_error = be.last_error();
     if (rc == BLASX_ERR_ARENA_TOO_SMALL) L.last_error = "tile cache too small for the working set of this call";
     return rc;
 }
 
 template <typename T>
 int gemm_impl(int dtype, int Order, int TransA, int TransB, int M, int N, int K, double alpha, const T* A, int lda,
-              const T* B, int ldb, double beta, T* C, int ldc) {
+              const T* B, int ldb, double beta, T* C, int ldc, bool no_alloc = false) {
     if (Order != BLASX_ROW_MAJOR && Order != BLASX_COL_MAJOR) return -1;
     if (!ok_trans(TransA)) return -2;
     if (!ok_trans(TransB)) return -3;
@@ -209,12 +225,38 @@ int gemm_impl(int dtype, int Order, int TransA, int TransB, int M, int N, int K,
     if (!lib().be) return BLASX_ERR_NOT_INITIALIZED;
     if ((!A || !B) && alpha != 0.0 && K > 0) return A ? -10 : -8;
     if (!C) return -13;
+    int T_call = 0;
+    if (no_alloc) {
+        Library& L = lib();
+        if (!L.be_static) {
+            L.last_error = "the statically allocated tile arena could not be set up by blasx_init";
+            return BLASX_ERR_DEVICE;
+        }
+        const bool reads_ab = alpha != 0.0 && K > 0;
+        if ((reads_ab && (!backend_host_is_pinned(A) || !backend_host_is_pinned(B))) || !backend_host_is_pinned(C)) {
+            L.last_error = "the allocation-free entry point needs page-locked matrices (the runtime stages pageable memory through buffers of its own)";
+            return BLASX_ERR_UNSUPPORTED;
+        }
+        // every tile of A, B and C must have a slot of its own (plus the few the pipeline holds besides): nothing is
+        // ever evicted, and the call is refused rather than squeezed
+        T_call = L.T > 0 && L.T < kStaticTile ? L.T : kStaticTile;
+        auto nt = [&](int64_t x) { return (size_t)((x + T_call - 1) / T_call); };
+        const size_t tiles = (reads_ab ? nt(M) * nt(K) + nt(K) * nt(N) : 0) + nt(M) * nt(N);
+        const size_t slots = L.be_static->arena_bytes() / slot_bytes_of(T_call, sizeof(T));
+        if (tiles + 8 > slots) {
+            L.last_error = "too large for the allocation-free entry point: " + std::to_string(tiles) + " tiles of " + std::to_string(T_call) +
+                           " x " + std::to_string(T_call) + " (+ 8) against " + std::to_string(slots) + " slots of static scratch";
+            return BLASX_ERR_TOO_LARGE;
+        }
+    } else {
+        T_call = pick_tile(dtype, M, N, K);
+    }
     Problem p;
     if (col)
-        build_gemm(p, dtype, pick_tile(dtype, M, N, K), is_trans(TransA), is_trans(TransB), M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+        build_gemm(p, dtype, T_call, is_trans(TransA), is_trans(TransB), M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
     else   // C^T = op(B)^T op(A)^T: the row-major arrays are the column-major transposes
-        build_gemm(p, dtype, pick_tile(dtype, M, N, K), is_trans(TransB), is_trans(TransA), N, M, K, alpha, B, ldb, A, lda, beta, C, ldc, lib().order);
-    return run_problem(p);
+        build_gemm(p, dtype, T_call, is_trans(TransB), is_trans(TransA), N, M, K, alpha, B, ldb, A, lda, beta, C, ldc, lib().order);
+    return run_problem(p, no_alloc);
 }
 
 int tri_check(int Order, int Side, int Uplo, int TransA, int Diag, int M, int N, const void* A, int lda, const void* B,
@@ -358,6 +400,11 @@ int blasx_dgemm(int Order, int TransA, int TransB, int M, int N, int K, double a
     return gemm_impl<double>(0, Order, TransA, TransB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
 }
 
+int blasx_dgemm_noalloc(int Order, int TransA, int TransB, int M, int N, int K, double alpha, const double* A, int lda,
+                        const double* B, int ldb, double beta, double* C, int ldc) {
+    return gemm_impl<double>(0, Order, TransA, TransB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, true);
+}
+
 int blasx_sgemm(int Order, int TransA, int TransB, int M, int N, int K, float alpha, const float* A, int lda,
                 const float* B, int ldb, float beta, float* C, int ldc) {
     return gemm_impl<float>(1, Order, TransA, TransB, M, N, K, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc);
@@ -411,6 +458,7 @@ int blasx_strsm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int 
 int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int nstreams) {
     Library& L = lib();
     L.sched.reset();
+    L.be_static.reset();
     L.be.reset();
     if (nstreams == 0) nstreams = 4;   // measured best at every size (a second inbound stream hides per-copy latency)
     if (nstreams < 2 || nstreams > 4 || arena_bytes == 0) return BLASX_ERR_CONFIG;
@@ -421,11 +469,22 @@ int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int ns
         return BLASX_ERR_DEVICE;
     }
     L.be.reset(b);
+    // Set-up of the allocation-free entry point, here so that the entry point itself creates nothing: the device
+    // address of this GPU's statically allocated arena, the same streams over it, a fixed pool of events, and the
+    // double-precision kernels loaded.  A failure is not an error of blasx_init; the entry point reports it.
+    void* sptr = nullptr;
+    size_t sbytes = 0;
+    if (backend_static_arena(&sptr, &sbytes) == 0) {
+        std::string serr;
+        std::unique_ptr<Backend> s(make_backend(sptr, sbytes, hip_streams, nstreams, &serr));
+        if (s && s->reserve_events(kStaticEvents) == 0 && backend_warm_kernels(*s, 0) == 0) L.be_static = std::move(s);
+    }
     return 0;
 }
 
 int blasx_shutdown(void) {
     lib().sched.reset();
+    lib().be_static.reset();
     lib().be.reset();
     backend_release_device_memory();
     return 0;
@@ -445,6 +504,7 @@ int blasx_set_streams(int n) {
         L.last_error = L.be->last_error();
         return BLASX_ERR_CONFIG;
     }
+    if (L.be_static) L.be_static->set_num_streams(n);
     return 0;
 }
 
@@ -562,6 +622,7 @@ const char* blasx_strerror(int rc) {
         case BLASX_ERR_CONFIG: return "invalid configuration value";
         case BLASX_ERR_NO_MEMORY: return "out of host memory";
         case BLASX_ERR_UNSUPPORTED: return "not supported";
+        case BLASX_ERR_TOO_LARGE: return "problem too large for the allocation-free entry point";
         default: return "unknown error";
     }
 }

@@ -11,6 +11,15 @@
 namespace blasx {
 
 hipError_t launch_tile_steps(int dtype, bool ta, bool tb, int mode, const LaunchPack& pack, hipStream_t stream);
+hipError_t launch_tile_steps_empty(int dtype, hipStream_t stream);
+
+// Tile arena for callers that cannot allocate device memory (code under graph capture, serving loops,
+// harnesses that forbid it): tile slots live in this file-scope array instead of an arena that someone
+// allocated.  Every GPU the library runs on holds its own copy until the process ends.  In host code the
+// array's name is only a stand-in: its device address is looked up once per device with
+// hipGetSymbolAddress (backend_static_arena) and that address is what kernels and copies get.
+constexpr size_t kStaticArenaBytes = (size_t)256 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticArenaBytes];
 
 // Inverse of the nb x nb diagonal blocks of a triangular tile (the base case of the TRSM
 // diagonal step; paper Eq. 1c needs A_ii^{-1}).  One wave per block, thread c solves for
@@ -288,11 +297,25 @@ public:
         return 0;
     }
 
+    int reserve_events(int n) override {
+        while ((int)events_.size() < n) {
+            hipEvent_t e;
+            HB_CHECK(hipEventCreate(&e));
+            events_.push_back(e);
+            free_.push_back((int)events_.size() - 1);
+        }
+        fixed_events_ = true;
+        return 0;
+    }
     int event_create() override {
         if (!free_.empty()) {
             const int ev = free_.back();
             free_.pop_back();
             return ev;
+        }
+        if (fixed_events_) {
+            err_ = "event pool exhausted";
+            return -1;
         }
         hipEvent_t e;
         if (hipEventCreate(&e) != hipSuccess) {
@@ -338,7 +361,11 @@ private:
     std::vector<bool> own_stream_;
     std::vector<hipEvent_t> events_;
     std::vector<int> free_;
+    bool fixed_events_ = false;      // reserve_events() was called: no event is created after it
     std::string err_;
+
+public:
+    hipStream_t compute_stream() { return stream(STREAM_COMPUTE); }
 };
 
 Backend* make_backend(void* arena, size_t bytes, void* const* streams, int nstreams, std::string* err) {
@@ -358,6 +385,36 @@ void* backend_host_alloc(size_t bytes) {
 }
 
 int backend_host_free(void* p) { return hipHostFree(p) == hipSuccess ? 0 : 1; }
+
+int backend_static_arena(void** ptr, size_t* bytes) {
+    static std::map<int, void*> per_device;       // each GPU holds its own copy of the array at its own address
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 1;
+    auto it = per_device.find(dev);
+    if (it == per_device.end()) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return 1;
+        it = per_device.emplace(dev, p).first;
+    }
+    *ptr = it->second;
+    *bytes = kStaticArenaBytes;
+    return 0;
+}
+
+bool backend_host_is_pinned(const void* p) {
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();       // plain pageable memory is reported as an error: clear it
+        return false;
+    }
+    return attr.type == hipMemoryTypeHost;
+}
+
+int backend_warm_kernels(Backend& be, int dtype) {
+    HipBackend& hb = static_cast<HipBackend&>(be);
+    if (launch_tile_steps_empty(dtype, hb.compute_stream()) != hipSuccess) return 1;
+    return hipStreamSynchronize(hb.compute_stream()) == hipSuccess ? 0 : 1;
+}
 
 void backend_release_device_memory() {
     for (auto& kv : HipBackend::own_arenas()) {

@@ -729,9 +729,35 @@ hipError_t launch_tile_steps(int dtype, bool ta, bool tb, int mode, const Launch
         else if (ta && !tb) BLASX_LAUNCH(float, true, false);
         else BLASX_LAUNCH(float, true, true);
     }
-#undef BLASX_LAUNCH
-#undef BLASX_LAUNCH_MODE
     return hipGetLastError();
 }
+
+// Every instantiation for one element type with an empty pack: each workgroup finds its virtual index
+// beyond total_wg = 0 and returns at once.  Makes the runtime load the kernels ahead of their first use.
+hipError_t launch_tile_steps_empty(int dtype, hipStream_t stream) {
+    LaunchPack pack = {};             // nsteps = 0, total_wg = 0
+    const uint32_t grid = NXCD;
+    for (int mode = MODE_FAST; mode <= MODE_GENERAL; ++mode) {
+        for (int v = 0; v < 4; ++v) {
+            const bool ta = v & 1, tb = v & 2;
+            if (dtype == 0) {
+                if (!ta && !tb) BLASX_LAUNCH(double, false, false);
+                else if (!ta && tb) BLASX_LAUNCH(double, false, true);
+                else if (ta && !tb) BLASX_LAUNCH(double, true, false);
+                else BLASX_LAUNCH(double, true, true);
+            } else {
+                if (!ta && !tb) BLASX_LAUNCH(float, false, false);
+                else if (!ta && tb) BLASX_LAUNCH(float, false, true);
+                else if (ta && !tb) BLASX_LAUNCH(float, true, false);
+                else BLASX_LAUNCH(float, true, true);
+            }
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+#undef BLASX_LAUNCH
+#undef BLASX_LAUNCH_MODE
 
 }  // namespace blasx

@@ -221,7 +221,19 @@ public:
         push(s, op);
         return 0;
     }
+    int reserve_events(int n) override {
+        while ((int)events_.size() < n) {
+            events_.push_back(Ev());
+            free_.push_back((int)events_.size() - 1);
+        }
+        fixed_events_ = true;
+        return 0;
+    }
     int event_create() override {
+        if (free_.empty() && fixed_events_) {
+            err_ = "event pool exhausted";
+            return -1;
+        }
         if (!free_.empty()) {
             const int e = free_.back();
             free_.pop_back();
@@ -362,6 +374,7 @@ private:
     std::vector<Ev> events_;
     std::vector<int> free_;
     uint64_t rng_;
+    bool fixed_events_ = false;
     double clock_ = 0;
     std::string err_;
 };
@@ -374,6 +387,17 @@ Backend* make_backend(void* arena, size_t bytes, void* const* streams, int nstre
     (void)err;
     return new SimBackend(bytes, nstreams);
 }
+
+// The double has no device: the "static arena" is only a size (make_backend brings its own buffer),
+// every host pointer counts as page-locked, and there are no kernels to load.
+int backend_static_arena(void** ptr, size_t* bytes) {
+    static char token;
+    *ptr = &token;
+    *bytes = (size_t)8 << 20;
+    return 0;
+}
+bool backend_host_is_pinned(const void*) { return true; }
+int backend_warm_kernels(Backend&, int) { return 0; }
 
 void* backend_host_alloc(size_t bytes) { return std::malloc(bytes); }
 void backend_release_device_memory() {}

@@ -246,6 +246,32 @@ def test_host_time_is_split_into_issuing_and_waiting_and_the_device_time_is_diss
     sim.set_option("profile", 0)
 
 
+def test_noalloc_entry_point_host_logic(sim):
+    """blasx_dgemm_noalloc on the host-only double (its static arena is 8 MiB): same results as blasx_dgemm, two calls in
+    a row with the second smaller, sizes beyond the slot count refused with their own code before anything is written."""
+    setup(sim, T=16, group=0, kchain=0, wide=11)
+    rng = np.random.default_rng(70)
+    for (M, N, K, ta, tb) in ((150, 90, 200, blasx.Trans, blasx.NoTrans), (40, 70, 33, blasx.NoTrans, blasx.Trans)):
+        A = np.asfortranarray(rng.integers(-2, 3, (M, K) if ta == blasx.NoTrans else (K, M)).astype(np.float64))
+        B = np.asfortranarray(rng.integers(-2, 3, (K, N) if tb == blasx.NoTrans else (N, K)).astype(np.float64))
+        C0 = np.asfortranarray(rng.integers(-2, 3, (M, N)).astype(np.float64))
+        C1, C2 = C0.copy(order="F"), C0.copy(order="F")
+        sim.dgemm_noalloc(blasx.ColMajor, ta, tb, M, N, K, 2.0, A, A.shape[0], B, B.shape[0], -1.0, C1, M)
+        sim.dgemm(blasx.ColMajor, ta, tb, M, N, K, 2.0, A, A.shape[0], B, B.shape[0], -1.0, C2, M)
+        assert np.array_equal(C1, C2)
+        assert np.array_equal(C1, 2.0 * ((A if ta == blasx.NoTrans else A.T) @ (B if tb == blasx.NoTrans else B.T)) - C0)
+    n = 1024                                    # 3 * 64 * 64 tiles of 16 x 16 against 4096 slots
+    big = np.ones((n, n), order="F")
+    out = np.full((n, n), 7.0, order="F")
+    assert sim.dgemm_noalloc(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, big, n, big, n, 0.0, out, n, check=False) == 7
+    assert "too large" in sim.last_error() and np.all(out == 7.0)
+    assert sim.strerror(7).startswith("problem too large")
+    a = np.zeros((8, 8), order="F")
+    assert sim.dgemm_noalloc(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 8, 8, 8, 1.0, a, 7, a, 8, 0.0, a, 8, check=False) == -9
+    sim.shutdown()
+    assert sim.dgemm_noalloc(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 8, 8, 8, 1.0, a, 8, a, 8, 0.0, a, 8, check=False) == 1
+
+
 def start_order(sim, C, T):
     """Tile indices (i, j) of the output tiles in the order their tasks were started, read from the test double's
     trace of inbound copies: with beta != 0 a task's first device operation is the copy of its own tile of C."""
