@@ -146,15 +146,11 @@ int blasx_strmm(int Order, int Side, int Uplo, int TransA, int Diag, int M, int 
 int blasx_init(void* arena, size_t arena_bytes, void* const* hip_streams, int nstreams);
 int blasx_shutdown(void);
 
-/* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192, or
- * 0: chosen per call from the extent of the output matrix, the element type and the room in
- * the tile cache (double precision: 1024 from 2048 rows/columns up, one tile per matrix below;
- * single precision: 1024 above 2048 rows/columns, 2048 from 6656, 1024 again when output and
- * inner dimensions are both at least 11264; STRMM: 1024 throughout.  By the order of the
- * triangular matrix: TRSM and DTRMM 512 for 2560 .. 4096 (five block rows, from which all
- * tasks advance together); STRSM 1024 for 4097 .. 12288, 2048 above; DTRSM 2048 from 20480.
- * Halved until 64 tiles fit in the cache).  The choice
- * of the latest call is blasx_get_option("last_tile").  The default is 1024. */
+/* Tile edge T (paper Section V.B: the one tuning parameter).  Multiple of 16, 16..8192, or 0: chosen per
+ * call from the extent of the output matrix, the element type and the room in the tile cache (1024 for
+ * most double-precision calls, 1024 or 2048 in single precision, 512 or 2048 for some triangular
+ * orders; halved until 64 tiles fit in the cache).  The choice of the latest call is
+ * blasx_get_option("last_tile").  The default is 1024. */
 int blasx_set_tile(int T);
 /* Number of streams the scheduler uses (paper Section IV.D: tasks progress on concurrent
  * streams; its experiments use 4).  n = 2..4 with the roles listed at blasx_init, or 0 for the
@@ -170,35 +166,24 @@ int blasx_set_streams(int n);
  * number of tile slots so that eviction (Alg. 2, Dequeue) can be exercised. */
 int blasx_set_cache_bytes(size_t cap);
 /* Scheduling knobs.  name is one of
- *   "group"    tile tasks that run together and advance k-step by k-step; 0 (default): chosen
- *              per call from the number of tasks (2 for a few tiles, where a short pipeline of
- *              small launches keeps the link busy, at least 4 from 5 x 5 tiles of up to 8 MB,
- *              up to 16 from 16 x 16 tiles, but 8 at most (tiles of 16 MB: 4) when the k loop is
- *              too short for the wide schedule; 16 for the triangular routines); the choice of
+ *   "group"    tile tasks that run together and advance k-step by k-step; 0 (default): chosen per
+ *              call from the number of tasks (2 .. 16; 16 for the triangular routines); the choice of
  *              the latest call is "last_group"
- *   "kchain"   consecutive k-steps of a task fused into one launch (1..8; 1 = the paper's
- *              one kernel per (i,j,k)); 0 (default): 8 in the wide schedule (6 for 12 .. 15
- *              k-tiles, which 8 would cut into two rounds only, 4 for 11), else 4; TRMM: 1 up to 14 x 14
- *              tiles in either schedule, 3 for 15 and 16, then as the others (the wide
- *              triangular solve always takes one k-step per round)
+ *   "kchain"   consecutive k-steps of a task fused into one launch (1..8; 1 = the paper's one kernel
+ *              per (i,j,k)); 0 (default): chosen per call (8 in the wide schedule when the k loop is
+ *              long enough, else 4 .. 6; 1 .. 3 for the triangular product up to 16 x 16 tiles; the
+ *              wide triangular solve always takes one k-step per round); "last_kchain"
  *   "wide"     least number of k-tiles per task from which ALL tasks of a call run together and
- *              advance k-chunk by k-chunk (an outer-product order: enough products per tile
- *              copied from the first launch on, C tiles fetched only for a task's last launch,
- *              results leaving during the whole last round), provided the cache has room for
- *              an accumulator tile per output tile; 0: never (tasks run to completion in
- *              groups, the paper's scheme).  Default 11.  TRSM uses it from a third of the
- *              value, one k-tile per round (a right-looking solve, every diagonal tile
- *              inverted before the first round), and so does TRMM: it pins every original
- *              tile of B at once, copies each in when it is first needed, and runs its tasks
- *              shortest first.
+ *              advance k-chunk by k-chunk (an outer-product order: enough products per tile copied
+ *              from the first launch on, C tiles fetched only for a task's last launch, results
+ *              leaving during the whole last round), provided the cache has room for an accumulator
+ *              tile per output tile; 0: never (tasks run to completion in groups, the paper's
+ *              scheme).  Default 11; the triangular routines use it from a third of the value.
+ *              "last_wide" tells whether the latest call ran that way
  *   "ramp"     wide schedule: k-steps per task in the first round (1..8; 8 = as in every other
- *              round).  0 (default): the steps left over when the k loop is cut into rounds
- *              are taken in the first round rather than the last (a short last round cannot
- *              hide the result tiles leaving and the C tiles arriving); when nothing is left
- *              over the first full round is split into 2 steps and the rest (the device
- *              starts earlier); with fewer than two rounds' worth of steps the first round
- *              stays full.
- *              The choice of the latest call is "last_ramp".
+ *              round).  0 (default): the steps left over when the k loop is cut into rounds come
+ *              first rather than last, and when nothing is left over the first full round is split
+ *              into 2 steps and the rest.  The choice of the latest call is "last_ramp"
  *   "prefetch" wide schedule: inbound copies are started this many launches ahead (default 24)
  *   "depth"    launches the host may run ahead of the device (>= 1)
  *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)

@@ -43,39 +43,20 @@ Library& lib() {
     return L;
 }
 
-// Tile edge for one call: the configured one, or (tile = 0) chosen from the extent of the output
-// matrix, the element type and the room in the tile cache.  The table behind it was measured
-// with the sweep in paper_1510_05041_amd/tune.py on an MI355X (end to end, host-resident
-// operands, running-set size chosen by pick_group): a tile must be large enough that the fixed
-// cost of one strided copy (~10 us on the copy engine) is small beside its transfer time; 1024
-// (8 MB in double precision) is, and stays best down to 2 x 2 tiles; larger tiles only shorten
-// the k loop that the wide schedule pipelines.  Single precision: 2048 (16 MB) from 6656 up, but
-// 1024 where the wide schedule applies or nearly (output and inner dimension from 11264; at 12288 = 12 k-tiles measured
-// 91.6 against 86.5 TFLOP/s at 12288, 110 against 101 at 14336, 123 against 105 at 16384, 131 against
-// 130 at 32768; below, 77 against 84 at 10240; STRMM 1024 / 2048: 66.9 / 53.5 at 12288, 100.6 / 68.7 at 16384, 114.4 / 105.8
-// at 24576).  `inner` is 0 for the triangular solve, whose large single-precision calls do better with 2048
-// (STRSM 1024 / 2048: 105.3 / 112.9 TFLOP/s at 24576).
-// `solve_order` is the order of the triangular matrix of a TRSM (0 otherwise): the solve advances one
-// k-tile per round, so its update launches are one tile deep, and from 20 tiles of 1024 on the twice
-// as deep launches of 2048-tiles win (double precision, 1024 / 2048: 58.0 / 59.2 TFLOP/s at 20480,
-// 60.6 / 62.2 at 24576, 62.0 / 64.8 at 28672, 63.7 / 67.1 at 32768; 54.4 / 54.7 at 16384, 45.6 / 42.9 at 12288).
-// Small triangular calls take the tile that gives them the five block rows from which the wide schedule
-// runs.  Orders 2560 .. 4096, 512 / 1024: DTRSM 2.67 / 3.52 ms at 2560, 3.70 / 4.57 at 3072, 4.69 / 5.77 at 3584,
-// 6.06 / 6.98 at 4096 (7.42 / 7.01 at 4608, 3.08 / 2.64 at 2048); DTRMM 2.46 / 2.85 at 2560, 3.39 / 3.89 at 3072,
-// 5.70 / 6.50 at 4096 (7.09 / 6.50 at 4608); STRSM 1.73 / 2.25 at 2560, 2.33 / 2.82 at 3072, 3.97 / 4.32 at 4096
-// (4.73 / 4.02 at 4608); STRMM the same either way (1.57 / 1.61, 2.12 / 2.14, 3.65 / 3.52), so it keeps 1024.
-// Single-precision solves of orders 4097 .. 12288: 1024 (1024 / 2048: 4.62 / 6.08 ms at 5120, 6.34 / 8.58 at 6144,
-// 10.43 / 14.33 at 8192, 15.77 / 16.96 at 10240, 23.37 / 23.60 at 12288; 33.5 / 33.0 at 14336, 46.7 / 44.8 at 16384).
-// Between 5120 and 11264 the other single-precision routines differ (1024 / 2048, ms, running set as chosen:
-// 5120: SGEMM 7.13 / 6.98, SSYRK 4.19 / 4.54, SSYMM 6.28 / 6.68, SSYR2K 6.60 / 7.28; 6144: 10.29 / 9.89, 5.91 / 6.40,
-// 8.91 / 9.25, 10.15 / 10.33; 8192: 18.83 / 17.16, 10.30 / 10.29, 16.30 / 16.51, 17.85 / 17.02; 10240: 27.81 / 25.61,
-// 15.91 / 14.95, 25.43 / 25.40, 28.42 / 26.63; 11264: 34.75 / 35.00, 19.24 / 19.76, 32.56 / 33.81, 34.45 / 35.92):
-// 1024 below 6656 and from 11264, 2048 between.
-// The single-precision triangular product: 1024 throughout (1024 / 2048: 4.25 / 5.76 ms at 5120, 5.82 / 7.85 at
-// 6144, 9.9 / 13.8 at 8192, 15.3 / 16.3 at 10240, 18.7 / 19.5 at 11264).  Single precision otherwise, below 5120:
-// 1024 (1024 / 2048 at 3072 and 4096: SGEMM 2.81 / 2.86 and 4.75 / 4.97 ms, SSYRK 1.79 / 2.22 and 2.87 / 3.42, SSYR2K
-// 2.82 / 3.35 and 4.66 / 5.25, SSYMM 2.58 / 2.86 and 4.49 / 4.66; at 5120: SGEMM 7.27 / 6.97, SSYMM 7.19 / 6.68,
-// SSYR2K 7.59 / 7.28, SSYRK 4.30 / 4.53; double precision 512 / 1024: DGEMM 3.27 / 2.57 at 2048, 10.5 / 8.8 at 4096).
+// Tile edge for one call: the configured one, or (tile = 0) chosen from the extent of the output matrix,
+// the element type and the room in the tile cache.  The rules (measured end to end on an MI355X with
+// paper_1510_05041_amd/tune.py; the tables are in profiles/tile_stream_sweep_mi355x.md):
+//   - a tile must be large enough that the fixed cost of one strided copy (~10 us on the copy engine) is
+//     small beside its transfer time: 1024 (8 MB) in double precision from 2048 rows or columns up, one tile
+//     per matrix below; larger tiles only shorten the k loop that the wide schedule pipelines;
+//   - single precision: 2048 (the same 16 MB) from 6656 up, but 1024 where the wide schedule applies or nearly
+//     (output and inner dimension from 11264), below 6656, and for the triangular product throughout;
+//   - `solve_order` (order of the triangular matrix of a TRSM, else 0): the wide solve advances one k-tile per
+//     round, so its update launches are one tile deep, and from 20 tiles of 1024 on the twice as deep launches
+//     of 2048-tiles win (double precision from 20480; single precision above 12288, 1024 from 4097);
+//   - small triangular calls take the tile that gives them the five block rows from which the wide schedule
+//     runs: 512 for orders 2560 .. 4096 (TRSM in both precisions, DTRMM);
+//   - halved until 64 tiles fit the cache (running set + operands), else eviction thrashes.
 int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solve_order = 0, bool tri_product = false) {
     Library& L = lib();
     if (L.T > 0) return L.T;
@@ -103,29 +84,22 @@ int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solv
     return T;
 }
 
-// Number of tile tasks that run together.  Many tasks in lockstep fill the chip with one
-// launch but also finish together: their write-backs bunch up at the end and the first launch
-// waits for the first tiles of all of them.  When the call is bound by the link (few tiles per
-// dimension) a small running set pipelines better: measured best 2 up to 5 x 5 tiles, 4 at
-// 6 x 6 to 8 x 8, 8 around 12 x 12, 16 from 16 x 16 tiles up (T = 1024, double precision);
-// one twelfth of the task count, as a power of two in 2..16, follows that within a few percent
-// (one eighth, the first rule, chose 8 at 8 x 8 and 9 x 9 tiles, where 4 is 2 .. 3 % faster: DGEMM 8192 35.1 / 34.0 ms)
-// for the rectangular and the triangular task sets alike.
+// Number of tile tasks that run together.  Many tasks in lockstep fill the chip with one launch but also
+// finish together: their write-backs bunch up at the end and the first launch waits for the first tiles of
+// all of them.  When the call is bound by the link (few tiles per dimension) a small running set pipelines
+// better.  Rule (tables in profiles/tile_stream_sweep_mi355x.md): one twelfth of the task count as a power
+// of two in 2..16, for the rectangular and the triangular task sets alike.
 int pick_group(const Problem& p) {
     Library& L = lib();
     if (L.cfg.group > 0) return L.cfg.group;
     if (!p.panels.empty() || p.results_are_operands) return 16;   // TRMM / TRSM: parallelism is per dependency level
     size_t want = std::min<size_t>(16, std::max<size_t>(2, p.tasks.size() / 12));
-    // From 5 x 5 tiles of up to 8 MB at least 4 (2 / 4 tasks, ms: DSYRK 11.0 / 12.2 at N = 6144, 17.3 / 14.7 at 7168;
-    // DSYR2K 14.1 / 12.3 at 5120, 31.7 / 25.2 at 7168; DGEMM 13.5 / 13.2 at 5120); not for tiles of 16 MB, whose
-    // copies take twice as long (SSYRK N = 10240, 5 x 5 tiles of 2048: 14.9 / 17.1; SGEMM 25.7 / 27.2).
+    // from 5 x 5 tiles of up to 8 MB at least 4 (not for tiles of 16 MB, whose copies take twice as long)
     const int64_t side = std::max((p.c_rows + p.T - 1) / p.T, (p.c_cols + p.T - 1) / p.T);
     const bool big_tiles = (size_t)p.T * p.T * p.esize > ((size_t)8 << 20);
     if (side >= 5 && !big_tiles) want = std::max<size_t>(want, 4);
-    // A k loop too short for the wide schedule (many output tiles, few k-tiles): the call is bound by the link, and
-    // 8 tasks pipeline better than 16 (8 / 16 tasks, ms: DGEMM 16384 x 16384 x 8192 89.1 / 91.8, x 4096 65.3 / 67.8,
-    // 20480 x 20480 x 8192 125.2 / 126.6; DSYRK 16384 x 8192 47.7 / 50.4; DSYR2K 16384 x 4096 47.8 / 50.4; DSYMM 10240
-    // 47.4 / 50.9); tiles of 16 MB: 4 (SGEMM 16384 x 16384 x 8192 with 4 / 8 / 16 tasks: 48.1 / 50.5 / 56.0).
+    // a k loop too short for the wide schedule (many output tiles, few k-tiles): the call is bound by the link, and
+    // 8 tasks pipeline better than 16 (tiles of 16 MB: 4)
     size_t longest = 0;
     for (const Task& t : p.tasks) longest = std::max(longest, t.steps.size());
     if (L.cfg.wide > 0 && longest < (size_t)L.cfg.wide * (size_t)p.steps_per_k) want = std::min<size_t>(want, big_tiles ? 4 : 8);

@@ -1094,22 +1094,17 @@ int Scheduler::run(Problem& p) {
     // while the first few output tiles wait for whole rows of A and columns of B; and result
     // tiles leave during the whole last round instead of in bursts.  The price is an
     // accumulator slot per output tile, so it is used only when the cache has that room.
-    // Chains: 8 k-tiles per launch in wide mode (fewer, longer launches; fewer rounds), 4 otherwise
-    // (shorter pipeline stages for the link-bound sizes), unless the caller fixed the number.
-    // A triangular solve runs wide one k-step at a time (a right-looking solve): step k of every
-    // task below block row k needs the results of block row k, which are solved in the same round.
-    // Shorter chains where 8 would leave two rounds only: the device then waits for eight k-tiles
-    // of operands before its first launch and the results leave in two bursts, which the outbound
-    // link cannot absorb (one tile per 160 us).  12 .. 15 k-tiles: 6 per launch, which with the
-    // short first round below gives three rounds (DSYRK / DSYMM at 12 and 14 k-tiles: +7 .. +14 %;
-    // DGEMM, which is bound by its inbound bytes there: unchanged).
-    // The triangular product has half the products per byte of the others, so it is bound by the
-    // link up to twice the order, and its tasks differ in length: one k-tile per launch lets every
-    // launch start as soon as its own few tiles have landed and lets the short tasks' results
-    // leave from the first round on (grouped, single precision, 3 x 3 and 4 x 4 tiles of 2048:
-    // +30 / +44 % over chains of 4; wide, 5 .. 8 tiles: +10 .. +50 % over grouped; 9 .. 14 tiles:
-    // +15 .. +35 % over chains of 8).  15 and 16 tiles: 3 per launch (+1 .. +2 %); from there on 8
-    // is as good or better.
+    // Chain length (k-tiles per launch) unless the caller fixed it:
+    //   wide: 8 (fewer, longer launches; fewer rounds); 6 for 12 .. 15 k-tiles and 4 for 9 .. 11, where
+    //     8 would leave two rounds only: the device then waits for eight k-tiles of operands before
+    //     its first launch and the results leave in two bursts that the outbound link cannot absorb;
+    //   grouped: 4 (shorter pipeline stages for the link-bound sizes);
+    //   triangular solve, wide: 1 (right-looking: step k of every task below block row k needs the
+    //     results of block row k, which are solved in the same round);
+    //   triangular product: 1 up to 14 x 14 tiles in either schedule, 3 for 15 and 16, then as the
+    //     others: it has half the products per byte, so the link bounds it up to twice the order, and
+    //     its tasks differ in length: one k-tile per launch lets every launch start as soon as its own
+    //     few tiles have landed and lets the short tasks' results leave from the first round on.
     size_t longest = 0;
     for (const Task& t : p.tasks) longest = std::max(longest, t.steps.size());
     const bool tri_product = !p.panels.empty();
@@ -1120,22 +1115,16 @@ int Scheduler::run(Problem& p) {
     } else if (longest >= 12 && longest < 16) {
         wide_chain = 6;
     } else if (longest >= 9 && longest < 12) {
-        // 11 k-tiles (the least for the wide schedule by default): rounds of 3 + 4 + 4 against the
-        // grouped schedule: DGEMM 62.9 / 65.3 ms, DSYMM 55.6 / 60.5, DSYRK 34.6 / 35.6, SSYMM 30.1 / 32.6.
-        // (9 and 10 k-tiles, reachable through option "wide": within +-4 % of the grouped schedule.)
-        wide_chain = 4;
+        wide_chain = 4;      // 11 k-tiles (the least for the wide schedule by default): rounds of 3 + 4 + 4
     }
     kchain_ = p.results_are_operands ? 1 : cfg_.kchain ? cfg_.kchain : wide_chain;
     wide_ = cfg_.wide > 0 && (int)ntasks > cfg_.group && wide_fits(p);
     if (!wide_) kchain_ = cfg_.kchain ? cfg_.kchain : grouped_chain;
     // Length of the first round.  The last round is the one in which every result tile leaves and
-    // every late C tile arrives: a short one cannot hide that traffic (measured at 8 k-steps per
-    // round: a last round of 1 / 2 / 3 / 4 / 5 / 6 steps costs 20 / 18 / 14 / 8 / 4 / 1 % of the
-    // call).  So the odd steps are taken first, not last; and when there are none the first full
-    // round is split into one of two steps and one of the rest, which starts the device a few
-    // milliseconds earlier (+3 % at 16 k-tiles, +1 % at 32) and still leaves a full last round.
-    // With only two rounds the remainder stays where it was (12 .. 15 k-tiles: measured 0 .. 4 %
-    // better that way).
+    // every late C tile arrives: a short one cannot hide that traffic.  So the left-over steps are
+    // taken first, not last; and when there are none the first full round is split into one of two
+    // steps and one of the rest, which starts the device a few milliseconds earlier and still
+    // leaves a full last round.  With only two rounds the remainder stays where it was.
     first_chain_ = second_chain_ = kchain_;
     if (wide_ && !p.results_are_operands && kchain_ > 2) {
         size_t max_steps = 0;

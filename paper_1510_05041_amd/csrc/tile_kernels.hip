@@ -271,14 +271,17 @@ __device__ __forceinline__ void macro_tile(const TileStep& st, int i_base, int j
 // position in the chunk), the same assignment for both operands, so either layout pairs with
 // either and the four transpose variants run at the same speed.
 //
-// Shape: 512 threads = 8 waves (2 x 4) per workgroup, each wave owning 64 x 32 of the macro-tile
-// (4 x 2 MFMA blocks), two workgroups per CU = 4 waves per SIMD to cover barrier and LDS latencies.
+// Shape, double precision: 512 threads = 8 waves (2 x 4) per workgroup, each wave owning 64 x 32 of the
+// macro-tile (4 x 2 MFMA blocks, 64 accumulator registers), two workgroups per CU = 4 waves per SIMD to
+// cover barrier and LDS latencies.
+// Shape, single precision: 256 threads = 4 waves (2 x 2), each wave owning 64 x 64 (4 x 4 blocks, again 64
+// accumulator registers), two workgroups per CU = 2 waves per SIMD.  A single-precision MFMA takes half the
+// cycles of a double-precision one for the same two operand registers, so with the 64 x 32 shape a wave
+// had to fetch its operands from LDS twice as often per MFMA cycle (the MFMA pipes were busy 87.6 % of the
+// time against 94 % in double precision); the square 64 x 64 wave tile needs a third fewer operand reads
+// per flop and gives groups of 16 MFMAs (512 cycles) per block row instead of 8 (256 cycles).
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
-
-constexpr int FAST_THREADS = 512;
-constexpr int FAST_WAVES = 8;
-constexpr int DMA_PER_WAVE = 16 / FAST_WAVES;   // wave-wide copies per operand slab and wave
 
 template <typename T> struct FastShape {
     static constexpr int EPC = 16 / (int)sizeof(T);      // elements per 16-byte chunk
@@ -286,51 +289,90 @@ template <typename T> struct FastShape {
     static constexpr int ROWS_PER_COPY = 1024 / (128 * (int)sizeof(T));   // k rows one wave-wide copy covers
     static constexpr int LANES_PER_ROW = 64 / ROWS_PER_COPY;
     static constexpr int STAGE = 128 * SLAB_K;           // elements per operand stage (16 KB)
+    static constexpr int WAVES_N = sizeof(T) == 8 ? 4 : 2;   // waves form a 2 x WAVES_N grid over the macro-tile
+    static constexpr int NBJ = 128 / (16 * WAVES_N);     // 16-column MFMA blocks per wave: 2 or 4 (rows: always 4)
+    static constexpr int WAVE_N = 16 * NBJ;              // columns of C per wave
+    static constexpr int WAVES = 2 * WAVES_N;
+    static constexpr int THREADS = 64 * WAVES;
+    static constexpr int DMA_PER_WAVE = 16 / WAVES;      // wave-wide copies per operand slab and wave
 };
 
+// Source of this lane for the first of its wave's copies of an operand slab, as an element offset from
+// the tile's first element.
 template <typename T, bool KCONTIG>
-__device__ __forceinline__ const T* dma_origin(const T* p, int ld, int mn_base, int wave, int lane) {
+__device__ __forceinline__ size_t dma_offset(int ld, int mn_base, int wave, int lane) {
     typedef FastShape<T> S;
     if (!KCONTIG) {
-        const int row = wave * DMA_PER_WAVE * S::ROWS_PER_COPY + lane / S::LANES_PER_ROW;
+        const int row = wave * S::DMA_PER_WAVE * S::ROWS_PER_COPY + lane / S::LANES_PER_ROW;
         // fp32: a 4-byte fragment read serves 32 lanes per pass = two lane groups g, whose rows are
         // 4 apart and would start at the same bank; every other group of 4 rows is therefore stored
-        // with its columns shifted by half the banks (col ^ 16).  All rows of one wave's copies
-        // fall in the same group of 4, so the shift is the same for the whole wave.
+        // with its columns shifted by half the banks (col ^ 16), i.e. chunk ^ 4.  The two rows of one
+        // copy fall in the same group of 4; a wave's later copies may fall in the other one (dma_alt).
         const int chunk = (lane % S::LANES_PER_ROW) ^ (sizeof(T) == 4 ? 4 * ((row >> 2) & 1) : 0);
-        return p + (size_t)(mn_base + chunk * S::EPC) + (size_t)row * ld;
+        return (size_t)(mn_base + chunk * S::EPC) + (size_t)row * ld;
     }
     const int m = lane >> 3, q = (lane & 7) ^ m;
-    return p + (size_t)(S::EPC * q) + (size_t)(mn_base + wave * DMA_PER_WAVE * 8 + m) * ld;
+    return (size_t)(S::EPC * q) + (size_t)(mn_base + wave * S::DMA_PER_WAVE * 8 + m) * ld;
+}
+template <typename T, bool KCONTIG>
+__device__ __forceinline__ const T* dma_origin(const T* p, int ld, int mn_base, int wave, int lane) {
+    return p + dma_offset<T, KCONTIG>(ld, mn_base, wave, lane);
+}
+
+// What to add (in elements) to this lane's source address for a copy whose rows lie in the other kind
+// of 4-row group than the wave's first copy (mn-contiguous fp32 sources only, else 0): chunk ^ 4.
+template <typename T, bool KCONTIG>
+__device__ __forceinline__ int dma_alt(int wave, int lane) {
+    typedef FastShape<T> S;
+    if (KCONTIG || sizeof(T) != 4) return 0;
+    const int row = wave * S::DMA_PER_WAVE * S::ROWS_PER_COPY + lane / S::LANES_PER_ROW;
+    const int chunk = (lane % S::LANES_PER_ROW) ^ (4 * ((row >> 2) & 1));
+    return (chunk & 4) ? -4 * S::EPC : 4 * S::EPC;
 }
 
 // This wave's copies of one operand slab into the operand's 16 KB LDS window `stage`.
 template <typename T, bool KCONTIG>
-__device__ __forceinline__ void dma_slab(const T* origin, int ld, T* stage, int wave) {
+__device__ __forceinline__ void dma_slab(const T* origin, int ld, T* stage, int wave, int alt) {
     typedef FastShape<T> S;
+    const int row0 = wave * S::DMA_PER_WAVE * S::ROWS_PER_COPY;      // first row of the wave's first copy
 #pragma unroll
-    for (int i = 0; i < DMA_PER_WAVE; ++i) {
+    for (int i = 0; i < S::DMA_PER_WAVE; ++i) {
         const T* src = origin + (size_t)(KCONTIG ? 8 * i : S::ROWS_PER_COPY * i) * ld;
-        T* dst = stage + (wave * DMA_PER_WAVE + i) * (1024 / (int)sizeof(T));
+        if (!KCONTIG && sizeof(T) == 4 && ((((row0 + S::ROWS_PER_COPY * i) >> 2) ^ (row0 >> 2)) & 1)) src += alt;
+        T* dst = stage + (wave * S::DMA_PER_WAVE + i) * (1024 / (int)sizeof(T));
         __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
     }
 }
 
-// Fragments of MFMA group (c, h): one element per 16 x 16 block.
-template <typename T, bool KCONTIG, int NB>
-__device__ __forceinline__ void frag_read(T (&f)[NB], const T* stage, int c, int h, int base, int g, int r16) {
-    typedef FastShape<T> S;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
+// Where a lane finds its operand values in an operand's LDS stage: the lane-dependent part of the element
+// index, worked out once per macro-tile; everything else (block b, half slab c, position h) is a constant of
+// the instruction.  `base` = first row / column of the wave's part of the macro-tile.
+//   mn-contiguous layout: element (k, mn) at k * 128 + (mn ^ swz(k)); fp32 rows of odd 4-row groups have their
+//     columns shifted by 16 (swz = 16 for lane groups g = 1, 3): mn ^ 16 is mn + 16 for even blocks b and mn - 16
+//     for odd ones, hence two bases.
+//   k-contiguous layout: chunk (mn, q) at mn * 8 + (q ^ (mn & 7)), q = 4 c + g: the chunk index of c = 1 is that
+//     of c = 0 with bit 2 flipped, hence two bases again.
+template <typename T, bool KCONTIG> struct LaneBase {
+    int v[2];
+    __device__ __forceinline__ LaneBase(int base, int g, int r16) {
+        typedef FastShape<T> S;
         if (!KCONTIG) {
-            const int swz = sizeof(T) == 4 ? 16 * (g & 1) : 0;      // see dma_origin
-            f[b] = stage[(4 * S::EPC * c + S::EPC * g + h) * 128 + ((base + b * 16 + r16) ^ swz)];
+            const int sh = sizeof(T) == 4 ? 16 * (g & 1) : 0;
+            v[0] = S::EPC * g * 128 + base + r16 + sh;       // even blocks
+            v[1] = S::EPC * g * 128 + base + r16 - sh;       // odd blocks
         } else {
-            const int mn = base + b * 16 + r16;
-            f[b] = stage[(mn * 8 + ((4 * c + g) ^ (r16 & 7))) * S::EPC + h];
+            const int q0 = g ^ (r16 & 7);
+            v[0] = ((base + r16) * 8 + q0) * S::EPC;          // c = 0
+            v[1] = ((base + r16) * 8 + (q0 ^ 4)) * S::EPC;    // c = 1
         }
     }
-}
+    // element index of position h (k = 4 EPC c + EPC g + h) of block b
+    __device__ __forceinline__ int at(int b, int c, int h) const {
+        typedef FastShape<T> S;
+        if (!KCONTIG) return v[b & 1] + (4 * S::EPC * c + h) * 128 + b * 16;
+        return v[c] + b * 128 * S::EPC + h;
+    }
+};
 
 // Element (r, c) of a stored triangular tile, given the value v that memory holds there.
 template <typename T>
@@ -350,113 +392,125 @@ __device__ __forceinline__ void lds_fence() {
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// MFMAs of one slab.  MASK: one operand of this chained pair is a diagonal tile of a triangular
-// matrix (sflags says which and how); its fragments are masked on their way out of LDS, so what
-// the other triangle holds in memory never reaches an MFMA.  k0 = k offset of the slab in the pair.
-template <typename T, bool TA, bool TB, bool MASK>
-__device__ __forceinline__ void compute_stage(typename Mfma<T>::acc_t (&acc)[4][2], const T* sa, const T* sb,
-                                              int wm, int wn, int g, int r16, uint32_t sflags, int k0,
-                                              int i_base, int j_base) {
+// The MFMAs of a slab are issued in units, and the unit is the stage of a software pipeline that runs
+// across the slabs of a macro-tile without ever draining: while the MFMAs of unit u are being issued the
+// operand values of unit u + 1 are on their way from LDS to registers -- also when u is the last unit
+// of its slab, in which case u + 1 is the first unit of the next slab, read from the other stage right
+// after the barrier that says the stage is complete (see macro_tile_fast).
+//   double precision: a unit is one MFMA group (c, h), k = 8 c + 2 g + h: 4 values of A, NBJ of B,
+//     4 x NBJ MFMAs of 64 cycles; 4 units per slab; the values are double buffered by unit parity.
+//   single precision: a unit is (c, block row bi): the 4 values h = 0..3 of A for that block row (one
+//     16-byte chunk when A is k-contiguous: conflict-free thanks to the XOR in the layout, where four
+//     separate 4-byte reads would collide four ways) and 4 x NBJ MFMAs of 32 cycles against the B values of
+//     half-slab c (NBJ chunks, requested together with the A values of unit 0 for c = 0 and of unit 2 for
+//     c = 1); 8 units per slab; A double buffered by parity, B by c.
+// MASK: one operand of the chained pair is a diagonal tile of a triangular matrix (sflags says which and
+// how); its values are masked in registers just before the MFMAs use them, so what the other triangle
+// holds in memory never reaches an MFMA.  k0 = k offset of the unit's slab in its pair.
+template <typename T> struct FastRegs;
+template <> struct FastRegs<double> {
+    static constexpr int NU = 4;                               // units per slab
+    double a[2][4], b[2][FastShape<double>::NBJ];
+};
+template <> struct FastRegs<float> {
+    static constexpr int NU = 8;
+    float a[2][4], b[2][FastShape<float>::NBJ][4];
+};
+
+// Requests the operand values of unit u of the slab in (sa, sb).
+template <typename T, bool TA, bool TB>
+__device__ __forceinline__ void unit_load(FastRegs<T>& R, const T* sa, const T* sb, int u, const LaneBase<T, TA>& la,
+                                          const LaneBase<T, !TB>& lb) {
     typedef FastShape<T> S;
-    constexpr int NGROUP = 2 * S::EPC;
-    auto load_group = [&](T (&fa)[4], T (&fb)[2], int t) {
-        const int c = t / S::EPC, h = t % S::EPC;
-        frag_read<T, TA, 4>(fa, sa, c, h, wm * 64, g, r16);
-        frag_read<T, !TB, 2>(fb, sb, c, h, wn * 32, g, r16);
+    constexpr int NBJ = S::NBJ;
+    if constexpr (sizeof(T) == 8) {
+        const int c = u / S::EPC, h = u % S::EPC;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) R.a[u & 1][b] = sa[la.at(b, c, h)];
+#pragma unroll
+        for (int b = 0; b < NBJ; ++b) R.b[u & 1][b] = sb[lb.at(b, c, h)];
+    } else {
+        const int c = u >> 2, bi = u & 3;
+        if (TA) {
+            const float4 x = *reinterpret_cast<const float4*>(sa + la.at(bi, c, 0));
+            R.a[u & 1][0] = x.x; R.a[u & 1][1] = x.y; R.a[u & 1][2] = x.z; R.a[u & 1][3] = x.w;
+        } else {
+#pragma unroll
+            for (int h = 0; h < 4; ++h) R.a[u & 1][h] = sa[la.at(bi, c, h)];
+        }
+        // the B values of half slab 0 come with unit 0, those of half slab 1 with unit 2 (two units early)
+        if (u == 0 || u == 2) {
+            const int cb = u >> 1;
+#pragma unroll
+            for (int b = 0; b < NBJ; ++b) {
+                if (!TB) {
+                    const float4 x = *reinterpret_cast<const float4*>(sb + lb.at(b, cb, 0));
+                    R.b[cb][b][0] = x.x; R.b[cb][b][1] = x.y; R.b[cb][b][2] = x.z; R.b[cb][b][3] = x.w;
+                } else {
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) R.b[cb][b][h] = sb[lb.at(b, cb, h)];
+                }
+            }
+        }
+    }
+}
+
+// Masks (MASK) and multiplies unit u; its values must have arrived.
+template <typename T, bool TA, bool TB, bool MASK>
+__device__ __forceinline__ void unit_mfma(typename Mfma<T>::acc_t (&acc)[4][FastShape<T>::NBJ], FastRegs<T>& R, int u,
+                                          int wm, int wn, int g, int r16, uint32_t sflags, int k0, int i_base, int j_base) {
+    typedef FastShape<T> S;
+    constexpr int NBJ = S::NBJ;
+    if constexpr (sizeof(T) == 8) {
+        const int c = u / S::EPC, h = u % S::EPC, cur = u & 1;
         if (MASK) {
             const int kg = k0 + 4 * S::EPC * c + S::EPC * g + h;
             if (sflags & TS_TRI_A) {
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     const int i = i_base + wm * 64 + b * 16 + r16;
-                    fa[b] = TA ? tri_select(fa[b], kg, i, sflags) : tri_select(fa[b], i, kg, sflags);
+                    R.a[cur][b] = TA ? tri_select(R.a[cur][b], kg, i, sflags) : tri_select(R.a[cur][b], i, kg, sflags);
                 }
             }
             if (sflags & TS_TRI_B) {
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    const int j = j_base + wn * 32 + b * 16 + r16;
-                    fb[b] = TB ? tri_select(fb[b], j, kg, sflags) : tri_select(fb[b], kg, j, sflags);
+                for (int b = 0; b < NBJ; ++b) {
+                    const int j = j_base + wn * S::WAVE_N + b * 16 + r16;
+                    R.b[cur][b] = TB ? tri_select(R.b[cur][b], j, kg, sflags) : tri_select(R.b[cur][b], kg, j, sflags);
                 }
             }
         }
-    };
-    if constexpr (sizeof(T) == 4) {
-        // fp32: the four MFMA groups h = 0..3 of one c share their 16-byte chunks, so a k-contiguous
-        // operand is read one whole chunk per lane (conflict-free for 16-byte reads thanks to the
-        // XOR in the layout; four separate 4-byte reads of it would collide four ways).  The unit
-        // of the software pipeline is therefore (c, block row bi): 8 MFMAs (4 h x 2 bj) on the A
-        // values of one block and the B values of c; the A values of the next unit are requested
-        // before the MFMAs of this one, the B values of c = 1 during the first units of c = 0, so
-        // that only three chunks per lane stand between the barrier and a wave's first MFMA.
-        auto load_a = [&](T (&va)[4], int c, int bi) {
-            if (TA) {
-                const int mn = wm * 64 + bi * 16 + r16;
-                const float4 v = reinterpret_cast<const float4*>(sa)[mn * 8 + ((4 * c + g) ^ (r16 & 7))];
-                va[0] = v.x; va[1] = v.y; va[2] = v.z; va[3] = v.w;
-            } else {
 #pragma unroll
-                for (int h = 0; h < 4; ++h) va[h] = sa[(16 * c + 4 * g + h) * 128 + ((wm * 64 + bi * 16 + r16) ^ (16 * (g & 1)))];
-            }
-            if (MASK && (sflags & TS_TRI_A)) {
+        for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < NBJ; ++bj) acc[bi][bj] = Mfma<T>::run(R.b[cur][bj], R.a[cur][bi], acc[bi][bj]);
+    } else {
+        const int c = u >> 2, bi = u & 3, cur = u & 1;
+        if (MASK) {
+            if (sflags & TS_TRI_A) {
                 const int i = i_base + wm * 64 + bi * 16 + r16;
 #pragma unroll
                 for (int h = 0; h < 4; ++h) {
                     const int kg = k0 + 16 * c + 4 * g + h;
-                    va[h] = TA ? tri_select(va[h], kg, i, sflags) : tri_select(va[h], i, kg, sflags);
+                    R.a[cur][h] = TA ? tri_select(R.a[cur][h], kg, i, sflags) : tri_select(R.a[cur][h], i, kg, sflags);
                 }
             }
-        };
-        auto load_b = [&](T (&vb)[2][4], int c) {
+            if ((sflags & TS_TRI_B) && bi == 0) {      // once per half slab, when its first unit is up
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                if (!TB) {
-                    const int mn = wn * 32 + b * 16 + r16;
-                    const float4 v = reinterpret_cast<const float4*>(sb)[mn * 8 + ((4 * c + g) ^ (r16 & 7))];
-                    vb[b][0] = v.x; vb[b][1] = v.y; vb[b][2] = v.z; vb[b][3] = v.w;
-                } else {
-#pragma unroll
-                    for (int h = 0; h < 4; ++h) vb[b][h] = sb[(16 * c + 4 * g + h) * 128 + ((wn * 32 + b * 16 + r16) ^ (16 * (g & 1)))];
-                }
-                if (MASK && (sflags & TS_TRI_B)) {
-                    const int j = j_base + wn * 32 + b * 16 + r16;
+                for (int b = 0; b < NBJ; ++b) {
+                    const int j = j_base + wn * S::WAVE_N + b * 16 + r16;
 #pragma unroll
                     for (int h = 0; h < 4; ++h) {
                         const int kg = k0 + 16 * c + 4 * g + h;
-                        vb[b][h] = TB ? tri_select(vb[b][h], j, kg, sflags) : tri_select(vb[b][h], kg, j, sflags);
+                        R.b[c][b][h] = TB ? tri_select(R.b[c][b][h], j, kg, sflags) : tri_select(R.b[c][b][h], kg, j, sflags);
                     }
                 }
             }
-        };
-        T va[2][4], vb[2][2][4];
-        load_b(vb[0], 0);
-        load_a(va[0], 0, 0);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int c = u >> 2, bi = u & 3, cur = u & 1;
-            lds_fence();      // the values of this unit, requested one unit earlier, have arrived
-            if (u + 1 < 8) load_a(va[cur ^ 1], (u + 1) >> 2, (u + 1) & 3);
-            if (u == 1) load_b(vb[1], 1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int h = 0; h < 4; ++h)
-#pragma unroll
-                for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = Mfma<T>::run(vb[c][bj][h], va[cur][h], acc[bi][bj]);
-            __builtin_amdgcn_sched_barrier(0);
         }
-        return;
-    }
-    // fragments are double buffered: those of group t+1 are requested before the MFMAs of group t
-    T fa[2][4], fb[2][2];
-    load_group(fa[0], fb[0], 0);
 #pragma unroll
-    for (int t = 0; t < NGROUP; ++t) {
-        const int cur = t & 1, nx = cur ^ 1;
-        if (t + 1 < NGROUP) load_group(fa[nx], fb[nx], t + 1);
+        for (int h = 0; h < 4; ++h)
 #pragma unroll
-        for (int bi = 0; bi < 4; ++bi)
-#pragma unroll
-            for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = Mfma<T>::run(fb[cur][bj], fa[cur][bi], acc[bi][bj]);
+            for (int bj = 0; bj < NBJ; ++bj) acc[bi][bj] = Mfma<T>::run(R.b[c][bj][h], R.a[cur][h], acc[bi][bj]);
     }
 }
 
@@ -534,11 +588,12 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     const int lda = st.lda, ldb = st.ldb;
     const int nseg = st.nseg;
 
-    acc_t acc[4][2];
+    acc_t acc[4][S::NBJ];
 #pragma unroll
     for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
-        for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = acc_t{0, 0, 0, 0};
+        for (int bj = 0; bj < S::NBJ; ++bj) acc[bi][bj] = acc_t{0, 0, 0, 0};
+    const int alt_a = dma_alt<T, TA>(wave, lane), alt_b = dma_alt<T, !TB>(wave, lane);
 
     const size_t step_a = TA ? (size_t)S::SLAB_K : (size_t)S::SLAB_K * lda;
     const size_t step_b = !TB ? (size_t)S::SLAB_K : (size_t)S::SLAB_K * ldb;
@@ -581,53 +636,82 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
         total += (ke - kb) / S::SLAB_K;
     }
     if (next_pair()) {
-        dma_slab<T, TA>(pa, lda, sA0, wave);
-        dma_slab<T, !TB>(pb, ldb, sB0, wave);
+        dma_slab<T, TA>(pa, lda, sA0, wave, alt_a);
+        dma_slab<T, !TB>(pb, ldb, sB0, wave, alt_b);
     }
-    // Compute cursor: the slab now being multiplied (one behind the copy cursor); only the masks
-    // need to know where in its pair a slab lies.
+    // Compute cursor: where in its pair the slab being multiplied lies and whether it needs masking (only
+    // the masks need to know); `cur` describes the slab whose units are being issued, `nxt` the one after.
+    struct SlabInfo { int k0; uint32_t mflags; };
     int cseg = pseg, cslab = 0, ckb = pkb, cke = pke;
-    uint32_t cflags = MASK && cseg < nseg ? st.seg[cseg].flags : 0;
-    auto multiply = [&](const T* sa, const T* sb) {
-        if constexpr (!MASK) {
-            compute_stage<T, TA, TB, false>(acc, sa, sb, wm, wn, g, r16, 0u, 0, i_base, j_base);
-            return;
-        }
+    auto slab_info = [&]() -> SlabInfo {            // of the slab the compute cursor is on; moves the cursor on
+        if constexpr (!MASK) return SlabInfo{0, 0u};
+        const uint32_t cflags = cseg < nseg ? st.seg[cseg].flags : 0u;
         const int k0 = ckb + cslab * S::SLAB_K;
-        const uint32_t mflags = slab_inside_triangle<TA, TB>(cflags, k0, S::SLAB_K, i_base, j_base) ? 0u : cflags;
-        compute_stage<T, TA, TB, MASK>(acc, sa, sb, wm, wn, g, r16, mflags, k0, i_base, j_base);
-        if (MASK) {
-            ++cslab;
-            if (ckb + cslab * S::SLAB_K >= cke) {
-                for (++cseg; cseg < nseg; ++cseg) {
-                    ckb = 0;
-                    cke = st.seg[cseg].k;
-                    masked_k_range<TA, TB>(st.seg[cseg].flags, st.seg[cseg].k, i_base, j_base, ckb, cke);
-                    if (cke > ckb) break;
-                }
-                cslab = 0;
-                cflags = cseg < nseg ? st.seg[cseg].flags : 0;
+        const SlabInfo info{k0, slab_inside_triangle<TA, TB>(cflags, k0, S::SLAB_K, i_base, j_base) ? 0u : cflags};
+        ++cslab;
+        if (ckb + cslab * S::SLAB_K >= cke) {
+            for (++cseg; cseg < nseg; ++cseg) {
+                ckb = 0;
+                cke = st.seg[cseg].k;
+                masked_k_range<TA, TB>(st.seg[cseg].flags, st.seg[cseg].k, i_base, j_base, ckb, cke);
+                if (cke > ckb) break;
             }
+            cslab = 0;
         }
+        return info;
+    };
+    FastRegs<T> R;
+    constexpr int NU = FastRegs<T>::NU;
+    const LaneBase<T, TA> lane_a(wm * 64, g, r16);
+    const LaneBase<T, !TB> lane_b(wn * S::WAVE_N, g, r16);
+    // One slab: units 0 .. NU - 2 each request the values of the unit after them and multiply their own; then,
+    // with the values of the last unit in registers, nothing of this stage is needed any more: the wave waits
+    // for its own copies into the other stage, meets the other waves at the barrier (after which that stage is
+    // complete and this one is free), starts the copies of the slab after next into this stage, requests the
+    // first values of the next slab -- and only then issues the MFMAs of its last unit, which cover all of that.
+    // `more`: another slab follows; `copy`: and one after it.
+    auto slab = [&](const T* sa, const T* sb, T* sa_w, T* sb_w, const T* na, const T* nb, SlabInfo cur, SlabInfo nxt, bool more) {
+#pragma unroll
+        for (int u = 0; u + 1 < NU; ++u) {
+            lds_fence();
+            unit_load<T, TA, TB>(R, sa, sb, u + 1, lane_a, lane_b);
+            __builtin_amdgcn_sched_barrier(0);
+            unit_mfma<T, TA, TB, MASK>(acc, R, u, wm, wn, g, r16, cur.mflags, cur.k0, i_base, j_base);
+        }
+        lds_fence();
+        if (more) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's copies into the other stage have landed
+            __syncthreads();
+            if (advance()) {
+                dma_slab<T, TA>(pa, lda, sa_w, wave, alt_a);
+                dma_slab<T, !TB>(pb, ldb, sb_w, wave, alt_b);
+            }
+            unit_load<T, TA, TB>(R, na, nb, 0, lane_a, lane_b);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        unit_mfma<T, TA, TB, MASK>(acc, R, NU - 1, wm, wn, g, r16, cur.mflags, cur.k0, i_base, j_base);
     };
     // Slabs are processed in pairs (stage 0, then stage 1) with no exit in between, so that the
     // accumulators stay in one set of registers (the host only sends chains with an even count:
     // every k is a multiple of two slabs).
-    for (int pair = 0; pair < total / 2; ++pair) {
-        // stage 0 holds the current slab once every wave's copies have landed
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-        __syncthreads();
-        advance();
-        dma_slab<T, TA>(pa, lda, sA1, wave);
-        dma_slab<T, !TB>(pb, ldb, sB1, wave);
-        multiply(sA0, sB0);
+    if (total > 0) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
+        __syncthreads();                          // stage 0 holds the first slab
         if (advance()) {
-            dma_slab<T, TA>(pa, lda, sA0, wave);
-            dma_slab<T, !TB>(pb, ldb, sB0, wave);
+            dma_slab<T, TA>(pa, lda, sA1, wave, alt_a);
+            dma_slab<T, !TB>(pb, ldb, sB1, wave, alt_b);
         }
-        multiply(sA1, sB1);
+        unit_load<T, TA, TB>(R, sA0, sB0, 0, lane_a, lane_b);
+        SlabInfo cur = slab_info();
+        for (int pair = 0; pair < total / 2; ++pair) {
+            SlabInfo nxt = slab_info();
+            slab(sA0, sB0, sA0, sB0, sA1, sB1, cur, nxt, true);
+            cur = nxt;
+            const bool more = pair + 1 < total / 2;
+            if (more) nxt = slab_info();
+            slab(sA1, sB1, sA1, sB1, sA0, sB0, cur, nxt, more);
+            cur = nxt;
+        }
     }
 
     T* __restrict__ C = static_cast<T*>(st.C);
@@ -638,7 +722,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     // Output-triangle mask (diagonal tiles of SYRK): +1 keeps i >= j, -1 keeps i <= j, 0 keeps all.
     const int tri = (st.flags & TS_C_LOWER) ? 1 : ((st.flags & TS_C_UPPER) ? -1 : 0);
 #pragma unroll
-    for (int bj = 0; bj < 2; ++bj)
+    for (int bj = 0; bj < S::NBJ; ++bj)
 #pragma unroll
         for (int rh = 0; rh < 4; rh += 2) {
             // half a 16-column block at a time: 8 values of C and 8 of the addend D in flight per lane
@@ -648,7 +732,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
 #pragma unroll
                 for (int bi = 0; bi < 4; ++bi) {
                     const int i = i_base + wm * 64 + bi * 16 + r16;
-                    const int j = j_base + wn * 32 + bj * 16 + Mfma<T>::drow(rh + r, g);
+                    const int j = j_base + wn * S::WAVE_N + bj * 16 + Mfma<T>::drow(rh + r, g);
                     const bool keep = tri * (i - j) >= 0;
                     cv[r][bi] = (use_c && keep) ? C[(size_t)i + (size_t)j * ldc] : T(0);
                     dv[r][bi] = (D && keep) ? D[(size_t)i + (size_t)j * ldc] : T(0);
@@ -658,7 +742,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
 #pragma unroll
                 for (int bi = 0; bi < 4; ++bi) {
                     const int i = i_base + wm * 64 + bi * 16 + r16;
-                    const int j = j_base + wn * 32 + bj * 16 + Mfma<T>::drow(rh + r, g);
+                    const int j = j_base + wn * S::WAVE_N + bj * 16 + Mfma<T>::drow(rh + r, g);
                     T v = alpha * acc[bi][bj][rh + r] + dv[r][bi];
                     if (use_c) v += beta * cv[r][bi];
                     if (tri * (i - j) >= 0) C[(size_t)i + (size_t)j * ldc] = v;
@@ -673,11 +757,14 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
 // MODE 2: general path, everything else with predication.
 enum { MODE_FAST = 0, MODE_FAST_MASKED = 1, MODE_GENERAL = 2 };
 
-template <int MODE>
-constexpr int kernel_threads() { return MODE == MODE_GENERAL ? NTHREADS : FAST_THREADS; }
+template <typename T, int MODE>
+constexpr int kernel_threads() { return MODE == MODE_GENERAL ? NTHREADS : FastShape<T>::THREADS; }
+// waves per SIMD the register budget is cut for: two workgroups per CU in every case
+template <typename T, int MODE>
+constexpr int kernel_waves_per_simd() { return MODE == MODE_GENERAL ? 2 : 2 * FastShape<T>::WAVES / 4; }
 
 template <typename T, bool TA, bool TB, int MODE>
-__global__ __launch_bounds__((kernel_threads<MODE>()), (MODE == MODE_GENERAL ? 2 : 4))
+__global__ __launch_bounds__((kernel_threads<T, MODE>()), (kernel_waves_per_simd<T, MODE>()))
 void tile_steps_kernel(const LaunchPack pack) {
     // XCD-aware virtual workgroup index: XCD x gets the contiguous range [x*per, (x+1)*per).
     const uint32_t per = gridDim.x / NXCD;
@@ -711,7 +798,7 @@ hipError_t launch_tile_steps(int dtype, bool ta, bool tb, int mode, const Launch
     if (pack.nsteps <= 0 || pack.total_wg == 0) return hipSuccess;
     const uint32_t grid = NXCD * ((pack.total_wg + NXCD - 1) / NXCD);
 #define BLASX_LAUNCH_MODE(T, TA, TB, MODE) \
-    hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, MODE>), dim3(grid), dim3(kernel_threads<MODE>()), 0, stream, pack)
+    hipLaunchKernelGGL((tile_steps_kernel<T, TA, TB, MODE>), dim3(grid), dim3(kernel_threads<T, MODE>()), 0, stream, pack)
 #define BLASX_LAUNCH(T, TA, TB)                                             \
     do {                                                                    \
         if (mode == MODE_FAST) BLASX_LAUNCH_MODE(T, TA, TB, MODE_FAST);     \

@@ -528,17 +528,23 @@ def check_gemm_whole_tiles(ta, tb, M, N, K, alpha, A, B, beta, c_seed, C, T, cou
     worst = 0.0
     for (ti, tj) in whole_tiles(ntm, ntn, count, seed):
         r0, r1, c0, c1 = ti * T, min(M, ti * T + T), tj * T, min(N, tj * T + T)
-        # views of the host matrices as they are stored: the oracle takes the transposition flags itself
-        a = A[r0:r1, :] if ta == blasx.NoTrans else A[:, r0:r1]
+        # views of the host matrices as they are stored: the oracle takes the transposition flags itself.  (A transposed
+        # A is handed over as a transposed copy instead: the oracle's inner loop runs over the rows of op(A), which in the
+        # stored transpose are a whole leading dimension apart.)
+        ta_ref = ta
+        if ta == blasx.NoTrans:
+            a = A[r0:r1, :]
+        else:
+            a, ta_ref = np.asfortranarray(A[:, r0:r1].T), blasx.NoTrans
         b = B[:, c0:c1] if tb == blasx.NoTrans else B[c0:c1, :]
         if c_seed is None:
             before = np.zeros((r1 - r0, c1 - c0), dtype=dtype, order="F")
         else:
             before = synth.block(c_seed[0], c_seed[1], M, r0, c0, r1 - r0, c1 - c0, dtype=dtype)
         want = np.array(before, order="F")
-        ref.gemm(ref.ColMajor, ta, tb, alpha, a, b, beta, want)
+        ref.gemm(ref.ColMajor, ta_ref, tb, alpha, a, b, beta, want)
         got = np.asarray(C)[r0:r1, c0:c1]
-        bound = elem_bound(norms(a, 1 if ta == blasx.NoTrans else 0), norms(b, 0 if tb == blasx.NoTrans else 1), alpha,
+        bound = elem_bound(norms(a, 1 if ta_ref == blasx.NoTrans else 0), norms(b, 0 if tb == blasx.NoTrans else 1), alpha,
                            beta * before.astype(np.float64), single=single, want=want)
         worst = max(worst, assert_close(got, want, bound, tol, "whole tile (%d, %d)" % (ti, tj)))
     return worst
