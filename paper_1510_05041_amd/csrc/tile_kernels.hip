@@ -295,6 +295,9 @@ template <typename T> struct FastShape {
     static constexpr int WAVES = 2 * WAVES_N;
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int DMA_PER_WAVE = 16 / WAVES;      // wave-wide copies per operand slab and wave
+    // When a slab's copies are issued: copy i of each operand goes out at position i / COPY_PP - 1, where -1 is
+    // right after the barrier that frees the stage and u >= 0 is together with unit u of the next slab.
+    static constexpr int COPY_PP = sizeof(T) == 8 ? 1 : DMA_PER_WAVE;
 };
 
 // Source of this lane for the first of its wave's copies of an operand slab, as an element offset from
@@ -314,11 +317,6 @@ __device__ __forceinline__ size_t dma_offset(int ld, int mn_base, int wave, int 
     const int m = lane >> 3, q = (lane & 7) ^ m;
     return (size_t)(S::EPC * q) + (size_t)(mn_base + wave * S::DMA_PER_WAVE * 8 + m) * ld;
 }
-template <typename T, bool KCONTIG>
-__device__ __forceinline__ const T* dma_origin(const T* p, int ld, int mn_base, int wave, int lane) {
-    return p + dma_offset<T, KCONTIG>(ld, mn_base, wave, lane);
-}
-
 // What to add (in elements) to this lane's source address for a copy whose rows lie in the other kind
 // of 4-row group than the wave's first copy (mn-contiguous fp32 sources only, else 0): chunk ^ 4.
 template <typename T, bool KCONTIG>
@@ -330,18 +328,45 @@ __device__ __forceinline__ int dma_alt(int wave, int lane) {
     return (chunk & 4) ? -4 * S::EPC : 4 * S::EPC;
 }
 
-// This wave's copies of one operand slab into the operand's 16 KB LDS window `stage`.
-template <typename T, bool KCONTIG>
-__device__ __forceinline__ void dma_slab(const T* origin, int ld, T* stage, int wave, int alt) {
-    typedef FastShape<T> S;
-    const int row0 = wave * S::DMA_PER_WAVE * S::ROWS_PER_COPY;      // first row of the wave's first copy
-#pragma unroll
-    for (int i = 0; i < S::DMA_PER_WAVE; ++i) {
-        const T* src = origin + (size_t)(KCONTIG ? 8 * i : S::ROWS_PER_COPY * i) * ld;
-        if (!KCONTIG && sizeof(T) == 4 && ((((row0 + S::ROWS_PER_COPY * i) >> 2) ^ (row0 >> 2)) & 1)) src += alt;
-        T* dst = stage + (wave * S::DMA_PER_WAVE + i) * (1024 / (int)sizeof(T));
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
+// The lane-dependent part of a copy's source address, as a byte offset from the first element of the tile's
+// current slab; worked out once per macro-tile.  The rest of the address (tile, slab, copy number) is the same
+// for the whole wave and stays in scalar registers (a buffer descriptor for the tile and a scalar byte offset):
+// a copy then reads one 32-bit address register per lane instead of a 64-bit pair, and neither a copy nor the
+// move to the next slab costs a vector instruction.
+// off[1]: for the copies whose rows lie in the other kind of 4-row group (see dma_alt).
+template <typename T, bool KCONTIG> struct CopyLane {
+    uint32_t off[2];
+    __device__ __forceinline__ CopyLane(int ld, int mn_base, int wave, int lane) {
+        off[0] = (uint32_t)(dma_offset<T, KCONTIG>(ld, mn_base, wave, lane) * sizeof(T));
+        off[1] = off[0] + (uint32_t)(dma_alt<T, KCONTIG>(wave, lane) * (int)sizeof(T));
     }
+};
+
+// Raw buffer descriptor over a tile (no stride, no swizzle, 32-bit data format); the range is left at its
+// maximum: the host has checked the steps of a fast-path pack against the tile extents.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* tile) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(tile), 0, 0x7fffffff, 0x27000);
+}
+
+// Copy number i (0 .. DMA_PER_WAVE - 1) of this wave's share of one operand slab, from the slab that starts
+// `slab_off` bytes into the tile, into the operand's 16 KB LDS window `stage`: lane l's 16 bytes land at byte
+// 16 l of the copy's 1 KB part of it.
+template <typename T, bool KCONTIG>
+__device__ __forceinline__ void dma_piece(__amdgpu_buffer_rsrc_t tile, uint32_t slab_off, int ld, const CopyLane<T, KCONTIG>& cl,
+                                          T* stage, int wave, int i) {
+    typedef FastShape<T> S;
+    // a wave's copies start at a multiple of 8 rows, so which 4-row group copy i falls in depends on i alone
+    static_assert(sizeof(T) != 4 || (S::DMA_PER_WAVE * S::ROWS_PER_COPY) % 8 == 0, "copy rows per wave");
+    const bool other = !KCONTIG && sizeof(T) == 4 && (((S::ROWS_PER_COPY * i) >> 2) & 1);
+    const uint32_t rows = slab_off + (uint32_t)((KCONTIG ? 8 * i : S::ROWS_PER_COPY * i) * ld * (int)sizeof(T));
+    T* dst = stage + (wave * S::DMA_PER_WAVE + i) * (1024 / (int)sizeof(T));
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(tile, (lds_ptr_t)dst, 16, (int)cl.off[other], (int)rows, 0, 0);
+}
+// All of them at once.
+template <typename T, bool KCONTIG>
+__device__ __forceinline__ void dma_slab(__amdgpu_buffer_rsrc_t tile, uint32_t slab_off, int ld, const CopyLane<T, KCONTIG>& cl, T* stage, int wave) {
+#pragma unroll
+    for (int i = 0; i < FastShape<T>::DMA_PER_WAVE; ++i) dma_piece<T, KCONTIG>(tile, slab_off, ld, cl, stage, wave, i);
 }
 
 // Where a lane finds its operand values in an operand's LDS stage: the lane-dependent part of the element
@@ -424,11 +449,16 @@ __device__ __forceinline__ void unit_load(FastRegs<T>& R, const T* sa, const T* 
     typedef FastShape<T> S;
     constexpr int NBJ = S::NBJ;
     if constexpr (sizeof(T) == 8) {
+        // mn-contiguous operands only: a k-contiguous one comes a whole 16-byte chunk (both h) at a time, see unit_load_late
         const int c = u / S::EPC, h = u % S::EPC;
+        if (!TA) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) R.a[u & 1][b] = sa[la.at(b, c, h)];
+            for (int b = 0; b < 4; ++b) R.a[u & 1][b] = sa[la.at(b, c, h)];
+        }
+        if (TB) {
 #pragma unroll
-        for (int b = 0; b < NBJ; ++b) R.b[u & 1][b] = sb[lb.at(b, c, h)];
+            for (int b = 0; b < NBJ; ++b) R.b[u & 1][b] = sb[lb.at(b, c, h)];
+        }
     } else {
         const int c = u >> 2, bi = u & 3;
         if (TA) {
@@ -450,6 +480,35 @@ __device__ __forceinline__ void unit_load(FastRegs<T>& R, const T* sa, const T* 
 #pragma unroll
                     for (int h = 0; h < 4; ++h) R.b[cb][b][h] = sb[lb.at(b, cb, h)];
                 }
+            }
+        }
+    }
+}
+
+// Double precision, k-contiguous operands: the two values h = 0, 1 that a lane needs from half slab c are the two
+// halves of one 16-byte chunk, and only a 16-byte read of that layout is free of bank conflicts (eight lanes per
+// cycle, eight bank groups; 8-byte reads serve sixteen lanes per cycle and collide in pairs).  So the chunk is read
+// whole, into the registers of both units (c, 0) and (c, 1) -- which is only possible once the MFMAs of the unit
+// before, (c - 1, 1), have been issued: these requests follow them instead of preceding them.
+template <typename T, bool TA, bool TB>
+__device__ __forceinline__ void unit_load_late(FastRegs<T>& R, const T* sa, const T* sb, int c, const LaneBase<T, TA>& la,
+                                               const LaneBase<T, !TB>& lb) {
+    if constexpr (sizeof(T) == 8) {
+        typedef typename Mfma<T>::vec2_t V2;
+        if (TA) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const V2 x = *reinterpret_cast<const V2*>(sa + la.at(b, c, 0));
+                R.a[0][b] = x.x;
+                R.a[1][b] = x.y;
+            }
+        }
+        if (!TB) {
+#pragma unroll
+            for (int b = 0; b < FastShape<T>::NBJ; ++b) {
+                const V2 x = *reinterpret_cast<const V2*>(sb + lb.at(b, c, 0));
+                R.b[0][b] = x.x;
+                R.b[1][b] = x.y;
             }
         }
     }
@@ -593,15 +652,18 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
         for (int bj = 0; bj < S::NBJ; ++bj) acc[bi][bj] = acc_t{0, 0, 0, 0};
-    const int alt_a = dma_alt<T, TA>(wave, lane), alt_b = dma_alt<T, !TB>(wave, lane);
+    const CopyLane<T, TA> copy_a(lda, i_base, wave, lane);
+    const CopyLane<T, !TB> copy_b(ldb, j_base, wave, lane);
 
-    const size_t step_a = TA ? (size_t)S::SLAB_K : (size_t)S::SLAB_K * lda;
-    const size_t step_b = !TB ? (size_t)S::SLAB_K : (size_t)S::SLAB_K * ldb;
+    // bytes from one slab of a tile to the next
+    const uint32_t step_a = (uint32_t)((TA ? S::SLAB_K : S::SLAB_K * lda) * (int)sizeof(T));
+    const uint32_t step_b = (uint32_t)((!TB ? S::SLAB_K : S::SLAB_K * ldb) * (int)sizeof(T));
 
-    // Copy cursor: slab `pslab` of the k range [pkb, pke) of pair `pseg` is the next one to fetch.
+    // Copy cursor: slab `pslab` of the k range [pkb, pke) of pair `pseg` is the next one to fetch; it starts
+    // pa, pb bytes into the pair's tiles ta, tb (all of this is the same for every lane).
     int pseg = -1, pslab = 0, pkb = 0, pke = 0;
-    const T* pa = nullptr;
-    const T* pb = nullptr;
+    __amdgpu_buffer_rsrc_t ta = tile_rsrc(st.seg[0].A), tb = tile_rsrc(st.seg[0].B);
+    uint32_t pa = 0, pb = 0;
     // first slab of the next pair that has any (a masked pair may have none for this macro-tile)
     auto next_pair = [&]() -> bool {
         if constexpr (MASK) {
@@ -610,14 +672,15 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
                 if (pke > pkb) break;
             }
             if (pseg >= nseg) return false;
-            pa = dma_origin<T, TA>(static_cast<const T*>(st.seg[pseg].A), lda, i_base, wave, lane) + (size_t)(pkb / S::SLAB_K) * step_a;
-            pb = dma_origin<T, !TB>(static_cast<const T*>(st.seg[pseg].B), ldb, j_base, wave, lane) + (size_t)(pkb / S::SLAB_K) * step_b;
+            pa = (uint32_t)(pkb / S::SLAB_K) * step_a;
+            pb = (uint32_t)(pkb / S::SLAB_K) * step_b;
         } else {
             if (++pseg >= nseg) return false;
             pke = st.seg[pseg].k;
-            pa = dma_origin<T, TA>(static_cast<const T*>(st.seg[pseg].A), lda, i_base, wave, lane);
-            pb = dma_origin<T, !TB>(static_cast<const T*>(st.seg[pseg].B), ldb, j_base, wave, lane);
+            pa = pb = 0;
         }
+        ta = tile_rsrc(st.seg[pseg].A);
+        tb = tile_rsrc(st.seg[pseg].B);
         pslab = 0;
         return true;
     };
@@ -636,8 +699,8 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
         total += (ke - kb) / S::SLAB_K;
     }
     if (next_pair()) {
-        dma_slab<T, TA>(pa, lda, sA0, wave, alt_a);
-        dma_slab<T, !TB>(pb, ldb, sB0, wave, alt_b);
+        dma_slab<T, TA>(ta, pa, lda, copy_a, sA0, wave);
+        dma_slab<T, !TB>(tb, pb, ldb, copy_b, sB0, wave);
     }
     // Compute cursor: where in its pair the slab being multiplied lies and whether it needs masking (only
     // the masks need to know); `cur` describes the slab whose units are being issued, `nxt` the one after.
@@ -667,29 +730,50 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     // One slab: units 0 .. NU - 2 each request the values of the unit after them and multiply their own; then,
     // with the values of the last unit in registers, nothing of this stage is needed any more: the wave waits
     // for its own copies into the other stage, meets the other waves at the barrier (after which that stage is
-    // complete and this one is free), starts the copies of the slab after next into this stage, requests the
-    // first values of the next slab -- and only then issues the MFMAs of its last unit, which cover all of that.
-    // `more`: another slab follows; `copy`: and one after it.
-    auto slab = [&](const T* sa, const T* sb, T* sa_w, T* sb_w, const T* na, const T* nb, SlabInfo cur, SlabInfo nxt, bool more) {
+    // complete and this one is free), moves the copy cursor on to the slab after next, requests the first values
+    // of the next slab -- and only then issues the MFMAs of its last unit, which cover all of that.
+    // The copies of the slab the cursor is on go into the stage that is not being read: the first ones right
+    // after the barrier (into the stage just freed), the rest, if the shape says so, with the first units of the
+    // next slab (see FastShape::COPY_PP).
+    // `more`: another slab follows.
+    bool pend = false;                            // the cursor is on a slab that has copies still to be issued
+    constexpr int LAST_POS = (S::DMA_PER_WAVE - 1) / S::COPY_PP - 1;
+    static_assert(LAST_POS < NU / 2, "the copies must be out by the middle of the slab");
+    auto copies_at = [&](int pos, T* wa, T* wb) {
+#pragma unroll
+        for (int i = 0; i < S::DMA_PER_WAVE; ++i)
+            if (i / S::COPY_PP - 1 == pos) {
+                dma_piece<T, TA>(ta, pa, lda, copy_a, wa, wave, i);
+                dma_piece<T, !TB>(tb, pb, ldb, copy_b, wb, wave, i);
+            }
+    };
+    auto slab = [&](T* sa, T* sb, T* na, T* nb, SlabInfo cur, SlabInfo nxt, bool more) {
 #pragma unroll
         for (int u = 0; u + 1 < NU; ++u) {
             lds_fence();
             unit_load<T, TA, TB>(R, sa, sb, u + 1, lane_a, lane_b);
+            if (u <= LAST_POS && pend) copies_at(u, na, nb);
             __builtin_amdgcn_sched_barrier(0);
             unit_mfma<T, TA, TB, MASK>(acc, R, u, wm, wn, g, r16, cur.mflags, cur.k0, i_base, j_base);
+            if (sizeof(T) == 8 && (TA || !TB) && (u & 1)) {
+                __builtin_amdgcn_sched_barrier(0);
+                unit_load_late<T, TA, TB>(R, sa, sb, (u + 1) / 2, lane_a, lane_b);
+            }
         }
         lds_fence();
         if (more) {
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's copies into the other stage have landed
             __syncthreads();
-            if (advance()) {
-                dma_slab<T, TA>(pa, lda, sa_w, wave, alt_a);
-                dma_slab<T, !TB>(pb, ldb, sb_w, wave, alt_b);
-            }
+            pend = advance();
+            if (pend) copies_at(-1, sa, sb);
             unit_load<T, TA, TB>(R, na, nb, 0, lane_a, lane_b);
             __builtin_amdgcn_sched_barrier(0);
         }
         unit_mfma<T, TA, TB, MASK>(acc, R, NU - 1, wm, wn, g, r16, cur.mflags, cur.k0, i_base, j_base);
+        if (sizeof(T) == 8 && (TA || !TB) && more) {
+            __builtin_amdgcn_sched_barrier(0);
+            unit_load_late<T, TA, TB>(R, na, nb, 0, lane_a, lane_b);
+        }
     };
     // Slabs are processed in pairs (stage 0, then stage 1) with no exit in between, so that the
     // accumulators stay in one set of registers (the host only sends chains with an even count:
@@ -697,19 +781,18 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     if (total > 0) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();                          // stage 0 holds the first slab
-        if (advance()) {
-            dma_slab<T, TA>(pa, lda, sA1, wave, alt_a);
-            dma_slab<T, !TB>(pb, ldb, sB1, wave, alt_b);
-        }
+        pend = advance();
+        if (pend) copies_at(-1, sA1, sB1);
         unit_load<T, TA, TB>(R, sA0, sB0, 0, lane_a, lane_b);
+        unit_load_late<T, TA, TB>(R, sA0, sB0, 0, lane_a, lane_b);
         SlabInfo cur = slab_info();
         for (int pair = 0; pair < total / 2; ++pair) {
             SlabInfo nxt = slab_info();
-            slab(sA0, sB0, sA0, sB0, sA1, sB1, cur, nxt, true);
+            slab(sA0, sB0, sA1, sB1, cur, nxt, true);
             cur = nxt;
             const bool more = pair + 1 < total / 2;
             if (more) nxt = slab_info();
-            slab(sA1, sB1, sA1, sB1, sA0, sB0, cur, nxt, more);
+            slab(sA1, sB1, sA0, sB0, cur, nxt, more);
             cur = nxt;
         }
     }
