@@ -50,14 +50,17 @@ Library& lib() {
 //     small beside its transfer time: 1024 (8 MB) in double precision from 2048 rows or columns up, one tile
 //     per matrix below; larger tiles only shorten the k loop that the wide schedule pipelines;
 //   - single precision: 2048 (the same 16 MB) from 6656 up, but 1024 where the wide schedule applies or nearly
-//     (output and inner dimension from 11264), below 6656, and for the triangular product throughout;
+//     (output and inner dimension from 11264), below 6656, and for the triangular product throughout; 2048 again
+//     where every tile of C is a task (GEMM, SYMM) and all three extents reach 28672: such a call is bound by
+//     the kernel, and launches of four times the work each have less fixed cost to pay;
 //   - `solve_order` (order of the triangular matrix of a TRSM, else 0): the wide solve advances one k-tile per
 //     round, so its update launches are one tile deep, and from 20 tiles of 1024 on the twice as deep launches
 //     of 2048-tiles win (double precision from 20480; single precision above 12288, 1024 from 4097);
 //   - small triangular calls take the tile that gives them the five block rows from which the wide schedule
 //     runs: 512 for orders 2560 .. 4096 (TRSM in both precisions, DTRMM);
 //   - halved until 64 tiles fit the cache (running set + operands), else eviction thrashes.
-int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solve_order = 0, bool tri_product = false) {
+int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solve_order = 0, bool tri_product = false,
+              bool full_output = false) {
     Library& L = lib();
     if (L.T > 0) return L.T;
     const int64_t n = std::max<int64_t>(1, std::max(rows, cols));
@@ -73,6 +76,7 @@ int pick_tile(int dtype, int64_t rows, int64_t cols, int64_t inner, int64_t solv
         if (solve_order > 12288) T = 2048;
         else if (five_rows_of_512) T = 512;
         else if (solve_order > 4096) T = 1024;
+        else if (full_output && std::min(rows, cols) >= 28672 && inner >= 28672) T = 2048;
         else if (n >= 11264 && inner >= 11264) T = 1024;
         else if (n >= 6656 && !tri_product) T = 2048;
         else T = n > 2048 ? 1024 : (int)std::min<int64_t>(2048, one_tile);
@@ -223,7 +227,7 @@ int gemm_impl(int dtype, int Order, int TransA, int TransB, int M, int N, int K,
             return BLASX_ERR_TOO_LARGE;
         }
     } else {
-        T_call = pick_tile(dtype, M, N, K);
+        T_call = pick_tile(dtype, M, N, K, 0, false, true);
     }
     Problem p;
     if (col)
@@ -323,7 +327,7 @@ int symm_impl(int dtype, int Order, int Side, int Uplo, int M, int N, double alp
     // row-major: C^T = alpha (A B)^T = alpha B^T A: side and triangle flip, M and N swap
     const bool left = col ? (Side == BLASX_LEFT) : (Side == BLASX_RIGHT);
     const bool lower = col ? (Uplo == BLASX_LOWER) : (Uplo == BLASX_UPPER);
-    build_symm(p, dtype, pick_tile(dtype, M, N, Side == BLASX_LEFT ? M : N), left, lower, col ? M : N, col ? N : M, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
+    build_symm(p, dtype, pick_tile(dtype, M, N, Side == BLASX_LEFT ? M : N, 0, false, true), left, lower, col ? M : N, col ? N : M, alpha, A, lda, B, ldb, beta, C, ldc, lib().order);
     return run_problem(p);
 }
 
