@@ -27,7 +27,7 @@ class Stats(ctypes.Structure):
         "copies_h2d", "copies_d2h", "bytes_h2d", "bytes_d2h", "slot_waits", "peak_slots",
         "profiled_launches")] + [(n, ctypes.c_double) for n in ("flops", "t_total_s", "t_issue_s", "t_kernel_s")] + [
         ("invalidations", ctypes.c_uint64)] + [(n, ctypes.c_double) for n in (
-            "t_wait_s", "t_kernel_busy_s", "t_copy_unoverlapped_s", "t_device_span_s")]
+            "t_wait_s", "t_kernel_busy_s", "t_copy_unoverlapped_s", "t_device_span_s")] + [("steps_general", ctypes.c_uint64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -145,6 +145,13 @@ class Library:
         arr = (ctypes.c_void_p * nstreams)(*stream_ptrs)
         self._check("blasx_init", self._lib.blasx_init(arena_ptr, int(arena_bytes), arr, nstreams))
         self._keep = keep
+
+    def arena_tensor(self):
+        """The torch tensor that init() made for the tile arena (None when the caller supplied the memory)."""
+        for k in self._keep or []:
+            if hasattr(k, "data_ptr"):
+                return k
+        return None
 
     def init_raw(self, arena_bytes, nstreams=4):
         """blasx_init with NULL arena and streams: the library allocates its own."""

@@ -30,6 +30,9 @@ public:
                          size_t width, size_t height, int stream) = 0;
     virtual int copy_d2h(void* host_dst, size_t dpitch, const void* dev_src, size_t spitch,
                          size_t width, size_t height, int stream) = 0;
+    // Zeroes `height` runs of `width` bytes, `pitch` bytes apart, in device memory (width and the address
+    // are multiples of 4): the padding of a ragged tile in its slot.
+    virtual int fill_zero(void* dev, size_t pitch, size_t width, size_t height, int stream) = 0;
     virtual int launch(int dtype, bool ta, bool tb, int mode, const LaunchPack& pack, int stream) = 0;   // mode: step_mode()
     // Invert the nb x nb diagonal blocks of an n x n triangular tile (device pointers, column-
     // major); flags: TS_TRI_LOWER / TS_TRI_UNIT of the source.  Used by the TRSM diagonal step.

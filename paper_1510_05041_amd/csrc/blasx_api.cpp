@@ -582,6 +582,7 @@ int blasx_get_stats(blasx_stats* out) {
     out->flops = s.flops; out->t_total_s = s.t_total_s; out->t_issue_s = s.t_issue_s; out->t_kernel_s = s.t_kernel_s;
     out->t_wait_s = s.t_wait_s; out->t_kernel_busy_s = s.t_kernel_busy_s; out->t_copy_unoverlapped_s = s.t_copy_unoverlapped_s;
     out->t_device_span_s = s.t_device_span_s;
+    out->steps_general = s.steps_general;
     return 0;
 }
 

@@ -2,6 +2,7 @@
 // (hipMemcpy2DAsync on page-locked memory), grouped tile-step launches, events.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <map>
 #include <string>
 #include <vector>
@@ -111,6 +112,13 @@ __global__ void transpose_kernel(const T* __restrict__ src, int ld_src, int rows
         const int r = threadIdx.x;                             // dst row = src column bc + r, dst column = src row br + c
         if (bc + r < cols && br + c < rows) dst[(size_t)(bc + r) + (size_t)(br + c) * ld_dst] = blk[r][c];
     }
+}
+
+// Zeroes `height` runs of `width` 4-byte words, `pitch` words apart.
+__global__ void fill_zero_kernel(uint32_t* __restrict__ p, size_t pitch, size_t width, size_t height) {
+    const size_t total = width * height;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (size_t)gridDim.x * blockDim.x)
+        p[(q / width) * pitch + q % width] = 0u;
 }
 
 #define HB_CHECK(call)                                   \
@@ -246,6 +254,15 @@ public:
     }
     int copy_d2h(void* dst, size_t dpitch, const void* src, size_t spitch, size_t width, size_t height, int s) override {
         HB_CHECK(hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, hipMemcpyDeviceToHost, stream(s)));
+        return 0;
+    }
+    int fill_zero(void* dev, size_t pitch, size_t width, size_t height, int s) override {
+        if (width == 0 || height == 0) return 0;
+        const size_t words = width / 4 * height;
+        const unsigned grid = (unsigned)std::min<size_t>((words + 255) / 256, 1024);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, stream(s), static_cast<uint32_t*>(dev), pitch / 4, width / 4,
+                           height);
+        HB_CHECK(hipGetLastError());
         return 0;
     }
     int launch(int dtype, bool ta, bool tb, int mode, const LaunchPack& pack, int s) override {

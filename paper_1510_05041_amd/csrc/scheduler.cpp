@@ -236,6 +236,23 @@ void Scheduler::dissect_time() {
     base_ev_ = -1;
 }
 
+// Clears what lies between a tile's true extent and the next multiples of the macro-tile edge in its slot
+// (the columns beyond `cols` as whole columns of the slot, then the rows beyond `rows` of the true columns),
+// on `stream`, so that the unpredicated kernel can read the tile on its padded extent.
+int Scheduler::zero_padding(int slot, int rows, int cols, int stream) {
+    if (!pad_ok_) return 0;
+    const size_t es = p_->esize;
+    const int rows_pad = round_up_to(rows, kBM), cols_pad = round_up_to(cols, kBN);
+    char* base = slot_ptr(slot);
+    if (cols_pad > cols &&
+        be_.fill_zero(base + (size_t)cols * T_ * es, (size_t)T_ * es, (size_t)(cols_pad - cols) * T_ * es, 1, stream))
+        return BLASX_ERR_DEVICE;
+    if (rows_pad > rows && cols > 0 &&
+        be_.fill_zero(base + (size_t)rows * es, (size_t)T_ * es, (size_t)(rows_pad - rows) * es, (size_t)cols, stream))
+        return BLASX_ERR_DEVICE;
+    return 0;
+}
+
 int Scheduler::issue_h2d(const TileRef& t, int slot) {
     int stream = STREAM_H2D;
     if (be_.num_streams() >= 4) {
@@ -251,6 +268,7 @@ int Scheduler::issue_h2d(const TileRef& t, int slot) {
     if (be_.copy_h2d(slot_ptr(slot), (size_t)T_ * es, t.host, (size_t)t.ld * es, (size_t)t.rows * es, (size_t)t.cols, stream))
         return BLASX_ERR_DEVICE;
     BX_TRY(profiled_copy_end(stream));
+    BX_TRY(zero_padding(slot, (int)t.rows, (int)t.cols, stream));     // before the fill event: consumers see the padded tile
     if (fill_ev_[slot] < 0) fill_ev_[slot] = be_.event_create();
     if (be_.event_record(fill_ev_[slot], stream)) return BLASX_ERR_DEVICE;
     fill_seq_[slot] = ++h2d_issued_[stream];
@@ -427,8 +445,8 @@ int Scheduler::flush(OpenPack& op) {
     f.free_slots.swap(op.free_slots);
     ++stats_.launches;
     stats_.tile_steps += op.steps;
+    if (op.mode == 2) stats_.steps_general += op.steps;
     stats_.flops += op.flops;
-    flushed_pack_id_ = std::max(flushed_pack_id_, op.id);
     const int done_ev = f.done_ev;
     inflight_.push_back(std::move(f));
     std::vector<int> finishing;
@@ -455,6 +473,18 @@ int Scheduler::flush(OpenPack& op) {
     // bound the host's run-ahead: at most `depth` launches in flight
     while ((int)inflight_.size() > cfg_.depth) retire(true);
     return 0;
+}
+
+// Whether the launch pack with this id is still being filled (its steps have not been launched).  Packs of
+// different kernel instantiations are open side by side and are launched in no particular order of their
+// ids -- a full one goes out while an older one of another kind is still open -- so "launched" cannot be
+// told from the largest id launched so far.
+bool Scheduler::pack_is_open(uint64_t id) const {
+    for (int q = 0; q < 3; ++q)
+        for (int a = 0; a < 2; ++a)
+            for (int b = 0; b < 2; ++b)
+                if (packs_[q][a][b].pack.nsteps > 0 && packs_[q][a][b].id == id) return true;
+    return false;
 }
 
 int Scheduler::flush_all() {
@@ -504,6 +534,9 @@ int Scheduler::finish_task(int ri) {
         w.key = key_of(c);
         w.block = cache_.adopt(w.key, r.c_slot);
         if (!w.block) return BLASX_ERR_DEVICE;
+        // a result that later calls may find in the cache as an operand: pad it like a fetched tile (after
+        // the launch that wrote it, which is already on the compute stream)
+        BX_TRY(zero_padding(r.c_slot, t.m, t.n, STREAM_COMPUTE));
         cache_.acquire(w.block);
     }
     writebacks_.push_back(w);
@@ -742,7 +775,7 @@ int Scheduler::build_chain(int ri) {
         const StepSpec& s = t.steps[r.next_step + nseg];
         if (s.dep >= 0) {
             if (task_final_pack_[s.dep] == 0) break;          // producer's last launch not built yet
-            if (task_final_pack_[s.dep] > flushed_pack_id_) BX_TRY(flush_all());
+            if (pack_is_open(task_final_pack_[s.dep])) BX_TRY(flush_all());
         }
         Block *ba = nullptr, *bb = nullptr;
         const int sym_kind = s.sym_lower ? kDerivedSymLower : kDerivedSymUpper;
@@ -803,6 +836,9 @@ int Scheduler::build_chain(int ri) {
     st.m = (uint16_t)t.m;
     st.n = (uint16_t)t.n;
     st.flags = (ta ? TS_TRANS_A : 0u) | (tb ? TS_TRANS_B : 0u) | t.c_flags;
+    // Every operand tile is zero-padded in its slot: those that came from the host when they were copied, those
+    // derived from them by the kernels that made them, the results of a solve when they were adopted as operands.
+    if (pad_ok_ && step_is_ragged(st, p_->dtype)) st.flags |= TS_PADDED;
     st.alpha = t.alpha_step;
     OpenPack& op = pack_for(step_mode(st, p_->dtype), ta, tb);
     BX_TRY(add_step(op, ta, tb, st, flops, (uint64_t)nseg));
@@ -960,7 +996,6 @@ int Scheduler::make_inverses(const Task* const* tasks, size_t count) {
         f.blocks.push_back(job.inv);
         f.free_slots.push_back(job.tmp);
     }
-    flushed_pack_id_ = std::max(flushed_pack_id_, f.id);
     inflight_.push_back(std::move(f));
     return 0;
 }
@@ -993,10 +1028,13 @@ int Scheduler::fetch_derived(const TileRef& t, int kind, Block** out) {
             compute_waited_[fill_stream_[slot]] = fill_seq_[slot];
         }
     }
+    // on padded extents where tiles are kept padded: the source's padding is zero, so the new tile's is too
+    const int d_rows = pad_ok_ ? round_up_to((int)t.rows, kBM) : (int)t.rows;
+    const int d_cols = pad_ok_ ? round_up_to((int)t.cols, kBN) : (int)t.cols;
     const int lrc = kind == kDerivedTranspose
-                        ? be_.launch_transpose(p_->dtype, slot_ptr(src->slot), T_, (int)t.rows, (int)t.cols, slot_ptr(sym->slot), T_,
+                        ? be_.launch_transpose(p_->dtype, slot_ptr(src->slot), T_, d_rows, d_cols, slot_ptr(sym->slot), T_,
                                                STREAM_COMPUTE)
-                        : be_.launch_symmetrize(p_->dtype, slot_ptr(src->slot), T_, slot_ptr(sym->slot), T_, (int)t.rows,
+                        : be_.launch_symmetrize(p_->dtype, slot_ptr(src->slot), T_, slot_ptr(sym->slot), T_, d_rows,
                                                 kind == kDerivedSymLower, STREAM_COMPUTE);
     if (lrc) return BLASX_ERR_DEVICE;
     // Both tiles keep a reader until the kernel has run: the stored one because it is read, the
@@ -1018,7 +1056,7 @@ int Scheduler::fetch_derived(const TileRef& t, int kind, Block** out) {
 int Scheduler::build_solve(int ri) {
     Running& r = running_[ri];
     const Task& t = p_->tasks[r.task];
-    if (r.last_pack > flushed_pack_id_) BX_TRY(flush_all());
+    if (pack_is_open(r.last_pack)) BX_TRY(flush_all());
     if (wide_ && r.first) BX_TRY(load_c_direct(r, t));   // no update step came before: the right-hand-side tile has not been fetched yet
     Block* inv = nullptr;
     BX_TRY(get_inverse(t, &inv));
@@ -1072,6 +1110,7 @@ int Scheduler::run(Problem& p) {
     t_wait_ = 0;
     p_ = &p;
     T_ = p.T;
+    pad_ok_ = T_ % kBM == 0 && T_ % kBN == 0;
     const size_t ntasks = p.tasks.size();
     next_task_ = 0;
     rs_.clear();

@@ -65,6 +65,7 @@ struct Stats {
     double t_kernel_busy_s = 0;        // profile 2: time during which at least one kernel ran (COMPT)
     double t_copy_unoverlapped_s = 0;  // profile 2: time during which a tile copy ran and no kernel did (COMM)
     double t_device_span_s = 0;        // profile 2: first device operation of a call to its last
+    uint64_t steps_general = 0;        // tile steps launched in the general (bounds-checked) kernel
 };
 
 class Scheduler {
@@ -138,6 +139,7 @@ private:
 
     int  fetch(const TileRef& t, Block** out);               // translate + inbound copy on a miss
     int  issue_h2d(const TileRef& t, int slot);
+    int  zero_padding(int slot, int rows, int cols, int stream);
     int  take_slot_blocking(int* slot);
     int  start_task(int task_index, Running* r);
     int  ensure_panel(int panel);
@@ -158,6 +160,7 @@ private:
     std::vector<const Task*> diag_tasks(const Problem& p) const;
     int  fetch_derived(const TileRef& t, int kind, Block** out);
     OpenPack& pack_for(int mode, bool ta, bool tb) { return packs_[mode][ta ? 1 : 0][tb ? 1 : 0]; }
+    bool pack_is_open(uint64_t id) const;
     int  add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, double flops, uint64_t nsteps);
     int  flush(OpenPack& op);
     int  flush_all();
@@ -182,6 +185,9 @@ private:
     Stats& stats_;
     Problem* p_ = nullptr;
     int T_ = 0;
+    // Tiles are kept zero-padded to whole macro-tiles in their slots (possible when the slot edge is a multiple
+    // of the macro-tile edge): ragged tile steps can then run in the unpredicated kernel (TS_PADDED).
+    bool pad_ok_ = false;
     int kchain_ = 4;                    // this run: k-steps fused per launch
     bool wide_ = false;                 // this run: all tasks advance together, C tiles arrive late
     size_t round_ = 0;                  // wide mode: index of the round being built
@@ -213,7 +219,7 @@ private:
     std::vector<uint64_t> task_final_pack_;          // pack id of the launch that finishes it
     std::vector<PanelState> panels_;
     OpenPack packs_[3][2][2];           // open launch packs, one per kernel instantiation (mode, transA, transB)
-    uint64_t next_pack_id_ = 1, flushed_pack_id_ = 0;
+    uint64_t next_pack_id_ = 1;
     std::deque<InFlight> inflight_;
     std::deque<WriteBack> writebacks_;
     std::unordered_map<TileKey, int, TileKeyHash> pending_wb_;   // host tile -> event of its outbound copy

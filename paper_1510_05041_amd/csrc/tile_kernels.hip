@@ -629,6 +629,14 @@ __device__ __forceinline__ MaskedOrder masked_order(const TileStep& st) {
     return MaskedOrder{false, false};
 }
 
+// The inner dimension of a pair as the fast kernel walks it: whole slab pairs.  Only a step of zero-padded
+// tiles (TS_PADDED) has a k that this rounds up; the products with the padding are zero.
+template <typename T>
+__device__ __forceinline__ int whole_slab_pairs(int k) {
+    constexpr int Q = 2 * FastShape<T>::SLAB_K;
+    return (k + Q - 1) / Q * Q;
+}
+
 // MASK: the pack holds steps with triangular operands (separate kernel instantiation, so that
 // the plain one carries no trace of the masking code).
 template <typename T, bool TA, bool TB, bool MASK>
@@ -676,7 +684,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
             pb = (uint32_t)(pkb / S::SLAB_K) * step_b;
         } else {
             if (++pseg >= nseg) return false;
-            pke = st.seg[pseg].k;
+            pke = whole_slab_pairs<T>(st.seg[pseg].k);
             pa = pb = 0;
         }
         ta = tile_rsrc(st.seg[pseg].A);
@@ -694,7 +702,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     };
     int total = 0;
     for (int q = 0; q < nseg; ++q) {
-        int kb = 0, ke = st.seg[q].k;
+        int kb = 0, ke = whole_slab_pairs<T>(st.seg[q].k);
         if (MASK) masked_k_range<TA, TB>(st.seg[q].flags, st.seg[q].k, i_base, j_base, kb, ke);
         total += (ke - kb) / S::SLAB_K;
     }
@@ -804,6 +812,8 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     const int ldc = st.ldc;
     // Output-triangle mask (diagonal tiles of SYRK): +1 keeps i >= j, -1 keeps i <= j, 0 keeps all.
     const int tri = (st.flags & TS_C_LOWER) ? 1 : ((st.flags & TS_C_UPPER) ? -1 : 0);
+    // C is m x n; a step of zero-padded tiles computes whole macro-tiles and stores what lies inside
+    const int m_end = st.m, n_end = st.n;
 #pragma unroll
     for (int bj = 0; bj < S::NBJ; ++bj)
 #pragma unroll
@@ -816,7 +826,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
                 for (int bi = 0; bi < 4; ++bi) {
                     const int i = i_base + wm * 64 + bi * 16 + r16;
                     const int j = j_base + wn * S::WAVE_N + bj * 16 + Mfma<T>::drow(rh + r, g);
-                    const bool keep = tri * (i - j) >= 0;
+                    const bool keep = tri * (i - j) >= 0 && i < m_end && j < n_end;
                     cv[r][bi] = (use_c && keep) ? C[(size_t)i + (size_t)j * ldc] : T(0);
                     dv[r][bi] = (D && keep) ? D[(size_t)i + (size_t)j * ldc] : T(0);
                 }
@@ -828,7 +838,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
                     const int j = j_base + wn * S::WAVE_N + bj * 16 + Mfma<T>::drow(rh + r, g);
                     T v = alpha * acc[bi][bj][rh + r] + dv[r][bi];
                     if (use_c) v += beta * cv[r][bi];
-                    if (tri * (i - j) >= 0) C[(size_t)i + (size_t)j * ldc] = v;
+                    if (tri * (i - j) >= 0 && i < m_end && j < n_end) C[(size_t)i + (size_t)j * ldc] = v;
                 }
             __builtin_amdgcn_sched_barrier(0);
         }

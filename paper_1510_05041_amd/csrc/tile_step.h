@@ -24,6 +24,11 @@ enum : uint32_t {
     // Output triangle (diagonal tiles of SYRK, Eq. 1b): only this triangle of C is read/written.
     TS_C_LOWER   = 1u << 6,
     TS_C_UPPER   = 1u << 7,
+    // Every operand tile of the step is stored with zeros between its true extent and the next
+    // multiple of the macro-tile edge, in both directions, and that much storage exists: the
+    // unpredicated kernel may then run on the padded extents (products with the padding are zero;
+    // rows and columns of C beyond m and n are computed and not stored).
+    TS_PADDED    = 1u << 8,
 };
 
 // One k-deep pair of operand tiles.  Several of them chained in one TileStep are
@@ -76,24 +81,40 @@ inline uint32_t macro_tiles(int m, int n) {
 // True when a step can run in the unpredicated kernel: whole macro-tiles, every k a multiple of
 // two slabs (a slab is 8 sixteen-byte chunks deep: 16 k in fp64, 32 k in fp32; the kernel works on
 // slab pairs), operands 16-byte aligned with leading dimensions that keep columns aligned.  Masks are
-// fine: operand masks are applied to fragments, the output-triangle mask in the epilogue.
+// fine: operand masks are applied to fragments, the output-triangle mask in the epilogue.  A step of
+// zero-padded tiles (TS_PADDED) may have any extents that, rounded up, still lie inside the tiles'
+// storage (a square of the leading dimension).
+inline int round_up_to(int x, int q) { return (x + q - 1) / q * q; }
+inline bool step_is_ragged(const TileStep& st, int dtype) {
+    const int epc = dtype == 0 ? 2 : 4;
+    if (st.m % kBM || st.n % kBN) return true;
+    for (int s = 0; s < st.nseg; ++s)
+        if (st.seg[s].k % (16 * epc)) return true;
+    return false;
+}
 inline bool step_is_fast(const TileStep& st, int dtype) {
     const int epc = dtype == 0 ? 2 : 4;          // elements per 16-byte chunk
-    if (st.m <= 0 || st.n <= 0 || st.m % kBM || st.n % kBN || st.lda % epc || st.ldb % epc) return false;
-    if (st.flags & ~(TS_TRANS_A | TS_TRANS_B | TS_C_LOWER | TS_C_UPPER)) return false;
+    const bool padded = st.flags & TS_PADDED;
+    if (st.m <= 0 || st.n <= 0 || st.lda % epc || st.ldb % epc) return false;
+    if (!padded && (st.m % kBM || st.n % kBN)) return false;
+    if (st.flags & ~(TS_TRANS_A | TS_TRANS_B | TS_C_LOWER | TS_C_UPPER | TS_PADDED)) return false;
+    if (padded && (round_up_to(st.m, kBM) > st.lda || round_up_to(st.n, kBN) > st.ldb)) return false;
     for (int s = 0; s < st.nseg; ++s) {
         const TileSeg& sg = st.seg[s];
-        if (sg.k <= 0 || sg.k % (16 * epc)) return false;
+        if (sg.k <= 0) return false;
+        if (!padded && sg.k % (16 * epc)) return false;
+        if (padded && (round_up_to(sg.k, 16 * epc) > st.lda || round_up_to(sg.k, 16 * epc) > st.ldb)) return false;
         if ((reinterpret_cast<uintptr_t>(sg.A) | reinterpret_cast<uintptr_t>(sg.B)) % 16) return false;
     }
     return true;
 }
 
 // Which kernel instantiation a step needs: 0 = fast, 1 = fast with operand masks, 2 = general.
+// The masked fast kernel works out its k ranges from whole macro-tiles: ragged masked steps are general.
 inline int step_mode(const TileStep& st, int dtype) {
     if (!step_is_fast(st, dtype)) return 2;
     for (int s = 0; s < st.nseg; ++s)
-        if (st.seg[s].flags) return 1;
+        if (st.seg[s].flags) return step_is_ragged(st, dtype) ? 2 : 1;
     return 0;
 }
 

@@ -22,7 +22,7 @@ namespace blasx {
 namespace {
 
 struct Op {
-    enum Kind { COPY, LAUNCH, TRTRI, SYMMETRIZE, TRANSPOSE, RECORD, WAIT } kind = COPY;
+    enum Kind { COPY, FILL, LAUNCH, TRTRI, SYMMETRIZE, TRANSPOSE, RECORD, WAIT } kind = COPY;
     // COPY (both directions are plain strided memcpy on the host)
     char* dst = nullptr;
     const char* src = nullptr;
@@ -58,8 +58,11 @@ double tri_value(const T* p, int ld, int r, int c, uint32_t f) {
     return inside ? (double)p[(size_t)r + (size_t)c * ld] : 0.0;
 }
 
+// k_quantum: what the unpredicated device kernel rounds the inner dimension of a zero-padded step up to.  The
+// double reads that padding too, so that a tile whose padding was not cleared gives a wrong result here as well
+// (the arena starts as NaN).
 template <typename T>
-void run_step(const TileStep& st) {
+void run_step(const TileStep& st, int k_quantum) {
     T* C = static_cast<T*>(st.C);
     const bool ta = st.flags & TS_TRANS_A, tb = st.flags & TS_TRANS_B;
     std::vector<double> acc((size_t)st.m * st.n, 0.0);
@@ -67,8 +70,9 @@ void run_step(const TileStep& st) {
         const TileSeg& sg = st.seg[s];
         const T* A = static_cast<const T*>(sg.A);
         const T* B = static_cast<const T*>(sg.B);
+        const int k_read = (st.flags & TS_PADDED) ? round_up_to(sg.k, k_quantum) : sg.k;
         for (int j = 0; j < st.n; ++j)
-            for (int l = 0; l < sg.k; ++l) {
+            for (int l = 0; l < k_read; ++l) {
                 double b;
                 if (sg.flags & TS_TRI_B) b = tb ? tri_value(B, st.ldb, j, l, sg.flags) : tri_value(B, st.ldb, l, j, sg.flags);
                 else b = tb ? (double)B[(size_t)j + (size_t)l * st.ldb] : (double)B[(size_t)l + (size_t)j * st.ldb];
@@ -145,7 +149,7 @@ void run_transpose(const Op& op) {
 
 class SimBackend : public Backend {
 public:
-    SimBackend(size_t bytes, int nstreams) : mem_(bytes, (char)0xA5), queues_(nstreams), rng_(g_seed) {}
+    SimBackend(size_t bytes, int nstreams) : mem_(bytes, (char)0xFF), queues_(nstreams), rng_(g_seed) {}
     ~SimBackend() override { drain(); }
 
     char* arena() override { return mem_.data(); }
@@ -163,6 +167,16 @@ public:
     }
     int copy_d2h(void* dst, size_t dp, const void* src, size_t sp, size_t w, size_t h, int s) override {
         return copy(dst, dp, src, sp, w, h, s);
+    }
+    int fill_zero(void* dev, size_t pitch, size_t width, size_t height, int s) override {
+        Op op;
+        op.kind = Op::FILL;
+        op.dst = static_cast<char*>(dev);
+        op.dpitch = pitch;
+        op.width = width;
+        op.height = height;
+        push(s, op);
+        return 0;
     }
     int launch(int dtype, bool ta, bool tb, int mode, const LaunchPack& pack, int s) override {
         // what each kernel instantiation assumes must hold for every step of its pack
@@ -342,10 +356,13 @@ private:
             case Op::COPY:
                 for (size_t r = 0; r < op.height; ++r) std::memcpy(op.dst + r * op.dpitch, op.src + r * op.spitch, op.width);
                 break;
+            case Op::FILL:
+                for (size_t r = 0; r < op.height; ++r) std::memset(op.dst + r * op.dpitch, 0, op.width);
+                break;
             case Op::LAUNCH:
                 for (int q = 0; q < op.pack.nsteps; ++q) {
-                    if (op.dtype == 0) run_step<double>(op.pack.step[q]);
-                    else run_step<float>(op.pack.step[q]);
+                    if (op.dtype == 0) run_step<double>(op.pack.step[q], 32);
+                    else run_step<float>(op.pack.step[q], 64);
                 }
                 break;
             case Op::TRTRI:

@@ -626,6 +626,92 @@ def test_wide_schedule_dgemm_ragged_full_compare(lib, ta, tb):
     assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N) and st["copies_d2h"] == 6 * 5
 
 
+def poison_arena(lib):
+    """Every byte of the tile arena 0xFF: NaN in both precisions wherever the library reads what it has not written."""
+    import torch
+    lib.arena_tensor().fill_(0xFF)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("T", [128, 1024])
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_ragged_sizes_run_in_the_fast_kernels_on_zero_padded_tiles(lib, T, dtype):
+    """Sizes that are no multiple of anything: tiles are zero-padded in their slots to whole macro-tiles and every
+    tile step but the ragged diagonal ones of the triangular product runs in the unpredicated kernels (the arena starts
+    as NaN, so a tile whose padding was not cleared, after its copy or after it was derived on the device, shows)."""
+    f64 = dtype == np.float64
+    tol, single = (TOL64, False) if f64 else (TOL32, True)
+    gemm, syrk, syr2k, symm, trmm = ((lib.dgemm, lib.dsyrk, lib.dsyr2k, lib.dsymm, lib.dtrmm) if f64 else
+                                     (lib.sgemm, lib.ssyrk, lib.ssyr2k, lib.ssymm, lib.strmm))
+    M, N, K = (1500, 1300, 2300) if T == 1024 else (650, 530, 1490)
+    for wide in (0, 1):
+        configure(lib, T=T, arena_gb=1.0, **(dict(group=0, kchain=0, wide=2) if wide else {}))
+        poison_arena(lib)
+        for ta, tb in itertools.product(TRANS, TRANS):
+            A, ka = pinned(*((M, K) if ta == blasx.NoTrans else (K, M)), 70, 0, dtype=dtype)
+            B, kb = pinned(*((K, N) if tb == blasx.NoTrans else (N, K)), 70, 1, dtype=dtype)
+            C, kc = pinned(M, N, 70, 2, dtype=dtype)
+            want, C0 = np.array(C, order="F"), np.array(C, order="F")
+            gemm(blasx.ColMajor, ta, tb, M, N, K, -1.25, A, A.shape[0], B, B.shape[0], 0.75, C, M)
+            ref.gemm(ref.ColMajor, ta, tb, -1.25, np.asarray(A), np.asarray(B), 0.75, want)
+            assert_close(C, want, elem_bound(norms(op(A, ta), 1), norms(op(B, tb), 0), -1.25, 0.75 * C0, single=single, want=want), tol)
+        A, ka = pinned(M, K, 71, 0, dtype=dtype)
+        B, kb = pinned(M, K, 71, 1, dtype=dtype)
+        C, kc = pinned(M, M, 71, 2, dtype=dtype)
+        other = np.triu_indices(M, 1)
+        C[other] = 1234.5
+        want, C0 = np.array(C, order="F"), np.array(C, order="F")
+        syrk(blasx.ColMajor, blasx.Lower, blasx.NoTrans, M, K, 1.0, A, M, 0.5, C, M)
+        ref.syrk(ref.ColMajor, ref.Lower, ref.NoTrans, 1.0, np.asarray(A), 0.5, want)
+        ra, rb = norms(A, 1), norms(B, 1)
+        assert np.all(np.asarray(C)[other] == 1234.5)
+        assert_close(C, want, elem_bound(ra, ra, 1.0, 0.5 * C0, single=single, want=want) + square_sums(ra, K, single=single), tol)
+        C1 = np.array(C, order="F")
+        want = np.array(C, order="F")
+        syr2k(blasx.ColMajor, blasx.Lower, blasx.NoTrans, M, K, 0.5, A, M, B, M, 1.0, C, M)
+        ref.syr2k(ref.ColMajor, ref.Lower, ref.NoTrans, 0.5, np.asarray(A), np.asarray(B), 1.0, want)
+        assert np.all(np.asarray(C)[other] == 1234.5)
+        assert_close(C, want, elem_bound(ra, rb, 0.5, C1, single=single, want=want) + elem_bound(rb, ra, 0.5, single=single), tol)
+        for side, uplo in ((blasx.Left, blasx.Lower), (blasx.Right, blasx.Upper)):
+            na = M if side == blasx.Left else N
+            S, ks = pinned(na, na, 72, 0, dtype=dtype)
+            S[np.triu_indices(na, 1) if uplo == blasx.Lower else np.tril_indices(na, -1)] = np.nan
+            B, kb = pinned(M, N, 72, 1, dtype=dtype)
+            C, kc = pinned(M, N, 72, 2, dtype=dtype)
+            want, C0 = np.array(C, order="F"), np.array(C, order="F")
+            symm(blasx.ColMajor, side, uplo, M, N, -1.5, S, na, B, M, 0.25, C, M)
+            ref.symm(ref.ColMajor, side, uplo, -1.5, np.asarray(S), np.asarray(B), 0.25, want)
+            full = sym_matrix(S, uplo)
+            bound = (elem_bound(norms(full, 1), norms(B, 0), -1.5, 0.25 * C0, single=single, want=want) if side == blasx.Left
+                     else elem_bound(norms(B, 1), norms(full, 0), -1.5, 0.25 * C0, single=single, want=want))
+            assert_close(C, want, bound, tol)
+        st = lib.get_stats()
+        assert st["steps_general"] == 0 and st["tile_steps"] > 0
+        P, kp = pinned(M, M, 73, 0, dtype=dtype)
+        synth.dominant_diag(P, 73, 0)
+        P[np.triu_indices(M, 1)] = np.nan
+        B, kb = pinned(M, N, 73, 1, dtype=dtype)
+        want, B0 = np.array(B, order="F"), np.array(B, order="F")
+        trmm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, M, N, -0.8, P, M, B, M)
+        ref.trmm(ref.ColMajor, ref.Left, ref.Lower, ref.NoTrans, ref.NonUnit, -0.8, np.asarray(P), want)
+        assert_close(B, want, trmm_bound(blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, P, B0, -0.8, single=single, want=want), tol)
+        st2 = lib.get_stats()
+        assert 0 < st2["steps_general"] < st2["tile_steps"] - st["tile_steps"]
+        # the solve: its results become operands of later steps and are padded when they are adopted
+        for side, uplo in ((blasx.Left, blasx.Upper), (blasx.Right, blasx.Lower)):
+            na = M if side == blasx.Left else N
+            P, kp = pinned(na, na, 74, 0, dtype=dtype)
+            synth.dominant_diag(P, 74, 0)
+            P[np.tril_indices(na, -1) if uplo == blasx.Upper else np.triu_indices(na, 1)] = np.nan
+            B, kb = pinned(M, N, 74, 1, dtype=dtype)
+            B0 = np.array(B, order="F")
+            trsm = lib.dtrsm if f64 else lib.strsm
+            trsm(blasx.ColMajor, side, uplo, blasx.NoTrans, blasx.NonUnit, M, N, 1.5, P, na, B, M)
+            assert_trsm_residual(side, uplo, blasx.NoTrans, blasx.NonUnit, P, B, B0, 1.5, tol, single=not f64)
+        st3 = lib.get_stats()
+        assert st3["steps_general"] - st2["steps_general"] < st3["tile_steps"] - st2["tile_steps"]
+
+
 def test_wide_schedule_symmetric_routines_full_compare(lib):
     N, K = 650, 1700
     configure(lib, T=128, arena_gb=0.5, **AUTO)

@@ -1153,3 +1153,101 @@ def test_seeded_random_problems_every_routine_schedule_and_cache_size(sim, seed)
         assert np.all(np.isfinite(np.asarray(Bs))), tag
         assert relerr(Bs, np.asarray(Br)) < 1e-12, tag
     sim.set_option("persist", 0)
+
+
+# ------------------------------------------------ ragged tiles in the fast kernel ----------
+
+@pytest.mark.parametrize("seed", range(3))
+def test_ragged_tiles_are_kept_zero_padded_and_run_in_the_fast_kernel(sim, seed):
+    """With a tile edge that is a multiple of the macro-tile edge, ragged tile steps are flagged as zero-padded and go
+    to the unpredicated kernel; the device double then reads the k padding too (its memory starts as NaN bytes), so a
+    tile whose padding had not been cleared after its copy, or after it was derived on the device, shows here."""
+    rng = np.random.default_rng(seed)
+    T = 128
+    for wide in (0, 2):
+        setup(sim, T=T, seed=seed, arena_tiles=96, group=3, kchain=2, wide=wide)
+        M, N, K = 300, 200, 170
+        for ta, tb in itertools.product(TRANS, TRANS):
+            A = rng.uniform(-1, 1, (K, M) if ta == blasx.Trans else (M, K))
+            B = rng.uniform(-1, 1, (N, K) if tb == blasx.Trans else (K, N))
+            C = rng.uniform(-1, 1, (M, N))
+            As, Bs, Cs, Cr = store(A, blasx.ColMajor, 3), store(B, blasx.ColMajor, 1), store(C, blasx.ColMajor, 2), store(C, blasx.ColMajor, 2)
+            sim.dgemm(blasx.ColMajor, ta, tb, M, N, K, 0.7, As, ld_of(As, blasx.ColMajor), Bs, ld_of(Bs, blasx.ColMajor), -0.3, Cs, ld_of(Cs, blasx.ColMajor))
+            ref.gemm(blasx.ColMajor, ta, tb, 0.7, As, Bs, -0.3, Cr)
+            assert relerr(Cs, np.asarray(Cr)) < 1e-14
+        # SYRK / SYR2K (output-triangle mask on ragged diagonal tiles), SYMM (tiles derived on the device), TRMM
+        n, k = 300, 170
+        A, B, C = rng.uniform(-1, 1, (n, k)), rng.uniform(-1, 1, (n, k)), rng.uniform(-1, 1, (n, n))
+        Cs, Cr = store(C, blasx.ColMajor, 1), store(C, blasx.ColMajor, 1)
+        sim.dsyrk(blasx.ColMajor, blasx.Lower, blasx.NoTrans, n, k, 1.1, A.copy(order="F"), n, 0.5, Cs, ld_of(Cs, blasx.ColMajor))
+        ref.syrk(blasx.ColMajor, blasx.Lower, blasx.NoTrans, 1.1, A.copy(order="F"), 0.5, Cr)
+        assert relerr(Cs, np.asarray(Cr)) < 1e-14
+        Cs, Cr = store(C, blasx.ColMajor, 1), store(C, blasx.ColMajor, 1)
+        sim.dsyr2k(blasx.ColMajor, blasx.Upper, blasx.NoTrans, n, k, 1.1, A.copy(order="F"), n, B.copy(order="F"), n, 0.5, Cs, ld_of(Cs, blasx.ColMajor))
+        ref.syr2k(blasx.ColMajor, blasx.Upper, blasx.NoTrans, 1.1, A.copy(order="F"), B.copy(order="F"), 0.5, Cr)
+        assert relerr(Cs, np.asarray(Cr)) < 1e-14
+        general_before = sim.get_stats()["steps_general"]
+        assert general_before == 0
+        for side, uplo in ((blasx.Left, blasx.Lower), (blasx.Right, blasx.Upper)):
+            m2, n2 = 300, 200
+            na = m2 if side == blasx.Left else n2
+            S = rng.uniform(-1, 1, (na, na))
+            S[np.triu_indices(na, 1) if uplo == blasx.Lower else np.tril_indices(na, -1)] = np.nan
+            B2, C2 = rng.uniform(-1, 1, (m2, n2)), rng.uniform(-1, 1, (m2, n2))
+            Ss, Bs, Cs, Cr = store(S, blasx.ColMajor, 2), store(B2, blasx.ColMajor), store(C2, blasx.ColMajor), store(C2, blasx.ColMajor)
+            sim.dsymm(blasx.ColMajor, side, uplo, m2, n2, -1.5, Ss, ld_of(Ss, blasx.ColMajor), Bs, m2, 0.25, Cs, m2)
+            ref.symm(blasx.ColMajor, side, uplo, -1.5, Ss, Bs, 0.25, Cr)
+            assert np.all(np.isfinite(np.asarray(Cs)))
+            assert relerr(Cs, np.asarray(Cr)) < 1e-14
+        assert sim.get_stats()["steps_general"] == 0
+        steps_before = sim.get_stats()["tile_steps"]
+        P = poisoned(rng, 300, blasx.Lower, blasx.NonUnit)
+        B3 = rng.uniform(-1, 1, (300, 200))
+        Ps, Bs, Br = store(P, blasx.ColMajor, 2), store(B3, blasx.ColMajor), store(B3, blasx.ColMajor)
+        sim.dtrmm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, 300, 200, -0.8, Ps, ld_of(Ps, blasx.ColMajor), Bs, 300)
+        ref.trmm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, -0.8, Ps, Br)
+        assert relerr(Bs, np.asarray(Br)) < 1e-14
+        st = sim.get_stats()
+        # only chains that hold a ragged diagonal step of the triangular product (last block row, last block column)
+        # are general: the others of the 12 steps stay fast
+        assert st["tile_steps"] - steps_before == 12 and 0 < st["steps_general"] <= 6
+        # the solve: results become operands (padded when they are adopted); all four side / triangle cases
+        for side, uplo in itertools.product((blasx.Left, blasx.Right), (blasx.Lower, blasx.Upper)):
+            m3, n3 = 300, 200
+            na = m3 if side == blasx.Left else n3
+            P = poisoned(rng, na, uplo, blasx.NonUnit, dominant=True)
+            B4 = rng.uniform(-1, 1, (m3, n3))
+            Ps, Bs, Br = store(P, blasx.ColMajor, 2), store(B4, blasx.ColMajor), store(B4, blasx.ColMajor)
+            before = sim.get_stats()
+            sim.dtrsm(blasx.ColMajor, side, uplo, blasx.NoTrans, blasx.NonUnit, m3, n3, 1.3, Ps, ld_of(Ps, blasx.ColMajor), Bs, m3)
+            ref.trsm(blasx.ColMajor, side, uplo, blasx.NoTrans, blasx.NonUnit, 1.3, Ps, Br)
+            assert np.all(np.isfinite(np.asarray(Bs)))
+            assert relerr(Bs, np.asarray(Br)) < 1e-13
+            after = sim.get_stats()
+            assert after["steps_general"] - before["steps_general"] < after["tile_steps"] - before["tile_steps"]
+    # single precision: k is rounded up to 64
+    setup(sim, T=128, seed=seed, arena_tiles=96, esize=4, group=3, kchain=2)
+    A, B, C = (rng.uniform(-1, 1, s).astype(np.float32) for s in ((200, 170), (170, 150), (200, 150)))
+    Cs, Cr = np.asfortranarray(C), np.asfortranarray(C)
+    sim.sgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 200, 150, 170, 1.0, np.asfortranarray(A), 200, np.asfortranarray(B), 170, 1.0, Cs, 200)
+    ref.gemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 1.0, np.asfortranarray(A), np.asfortranarray(B), 1.0, Cr)
+    assert relerr(Cs, np.asarray(Cr)) < 1e-6
+    assert sim.get_stats()["steps_general"] == 0
+
+
+@pytest.mark.parametrize("wide", [0, 2])
+def test_solve_results_are_never_read_before_their_launch_when_packs_of_two_kernels_are_open(sim, wide):
+    """A dependency level of more tasks than one launch holds, with a ragged last block column: the solves of the
+    whole tiles and the ragged one go to different kernel instantiations, whose launch packs are open side by side
+    and go out in no order of their ids.  A step that reads a solve's result must wait for that very pack."""
+    T, M, N = 128, 300, 2300
+    rng = np.random.default_rng(5)
+    for seed in range(3):
+        setup(sim, T=T, seed=seed, arena_tiles=200, group=16, kchain=0, rs=32, wide=wide)
+        A = np.tril(rng.uniform(-1, 1, (M, M))) + M * np.eye(M)
+        B = rng.uniform(-1, 1, (M, N))
+        Bs = np.asfortranarray(B)
+        sim.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, M, N, 1.0, np.asfortranarray(A), M, Bs, M)
+        X = np.linalg.solve(A, B)
+        assert relerr(Bs, X) < 1e-13
+        assert sim.get_option("last_wide") == (1 if wide else 0)
