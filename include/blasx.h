@@ -150,7 +150,10 @@ int blasx_shutdown(void);
  * call from the extent of the output matrix, the element type and the room in the tile cache (1024 for
  * most double-precision calls, 1024 or 2048 in single precision, 512 or 2048 for some triangular
  * orders; halved until 64 tiles fit in the cache).  The choice of the latest call is
- * blasx_get_option("last_tile").  The default is 1024. */
+ * blasx_get_option("last_tile").  The default is 1024.  With T a multiple of 128 matrices of any order
+ * run in the fast kernels (ragged edge tiles are kept zero-padded in the tile cache); with another T, tile
+ * steps on ragged tiles, and all steps when T itself is no multiple of 128, take the slower bounds-checked
+ * kernel (blasx_stats.steps_general counts them). */
 int blasx_set_tile(int T);
 /* Number of streams the scheduler uses (paper Section IV.D: tasks progress on concurrent
  * streams; its experiments use 4).  n = 2..4 with the roles listed at blasx_init, or 0 for the
