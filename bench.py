@@ -98,6 +98,13 @@ def run_secondary(np, torch, lib, blasx, synth, A, B, C, owners, n, want_cfg3):
             continue
         dt = timed(lambda: lib.dgemm(CM, NT, NT, m, m, m, 1.0, A, n, B, n, 1.0, C, n))
         out.append(secondary_entry("DGEMM NN N=%d T=1024 alpha=beta=1" % m, 2.0 * m ** 3, 3 * 8.0 * m * m, dt, FP64_MFMA_PEAK_TFLOPS))
+    if n >= 30000:
+        # an order that is no multiple of the tile (or of anything): ragged edge tiles, zero-padded in the tile cache
+        m = 30000
+        dt = timed(lambda: lib.dgemm(CM, NT, NT, m, m, m, 1.0, A, n, B, n, 1.0, C, n))
+        e = secondary_entry("DGEMM NN N=30000 T=1024 alpha=beta=1 (ragged edge tiles)", 2.0 * m ** 3, 3 * 8.0 * m * m, dt, FP64_MFMA_PEAK_TFLOPS)
+        e["steps_general"] = lib.get_stats()["steps_general"]
+        out.append(e)
     if n >= 16384:
         N, K = 16384, 8192
         dt = timed(lambda: lib.dsyrk(CM, blasx.Lower, NT, N, K, 1.0, A, n, 1.0, C, n))

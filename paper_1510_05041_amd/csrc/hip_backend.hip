@@ -430,6 +430,10 @@ bool backend_host_is_pinned(const void* p) {
 int backend_warm_kernels(Backend& be, int dtype) {
     HipBackend& hb = static_cast<HipBackend&>(be);
     if (launch_tile_steps_empty(dtype, hb.compute_stream()) != hipSuccess) return 1;
+    // the padding fill as well (no words to clear: every thread finds nothing to do)
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, hb.compute_stream(), static_cast<uint32_t*>(nullptr), (size_t)0,
+                       (size_t)0, (size_t)0);
+    if (hipGetLastError() != hipSuccess) return 1;
     return hipStreamSynchronize(hb.compute_stream()) == hipSuccess ? 0 : 1;
 }
 
