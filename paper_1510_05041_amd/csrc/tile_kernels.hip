@@ -297,7 +297,9 @@ template <typename T> struct FastShape {
     static constexpr int DMA_PER_WAVE = 16 / WAVES;      // wave-wide copies per operand slab and wave
     // When a slab's copies are issued: copy i of each operand goes out at position i / COPY_PP - 1, where -1 is
     // right after the barrier that frees the stage and u >= 0 is together with unit u of the next slab.
-    static constexpr int COPY_PP = sizeof(T) == 8 ? 1 : DMA_PER_WAVE;
+    // Measured: one copy per operand and position in fp64 (2 positions), two in fp32 (2 positions); all of a slab's
+    // copies in one burst after the barrier is 0.5 % slower in both, one per unit in fp32 1 % slower.
+    static constexpr int COPY_PP = sizeof(T) == 8 ? 1 : DMA_PER_WAVE / 2;
 };
 
 // Source of this lane for the first of its wave's copies of an operand slab, as an element offset from
