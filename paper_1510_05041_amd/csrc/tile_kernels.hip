@@ -694,13 +694,15 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
         pslab = 0;
         return true;
     };
-    // advance the copy cursor to the next slab of the chain; false when the chain is exhausted
-    auto advance = [&]() -> bool {
+    // `pend`: the cursor is on a slab (whose copies are still to be issued); false once the chain is exhausted.
+    // advance() moves it to the next slab of the chain.  Only the step into another pair, once in a whole tile's
+    // worth of slabs, takes a branch; the common case is three scalar additions and a compare.
+    bool pend = false;
+    auto advance = [&]() {
         ++pslab;
-        if ((MASK ? pkb : 0) + pslab * S::SLAB_K >= pke) return next_pair();
         pa += step_a;
         pb += step_b;
-        return true;
+        if (__builtin_expect((MASK ? pkb : 0) + pslab * S::SLAB_K >= pke, 0)) pend = next_pair();
     };
     int total = 0;
     for (int q = 0; q < nseg; ++q) {
@@ -708,7 +710,8 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
         if (MASK) masked_k_range<TA, TB>(st.seg[q].flags, st.seg[q].k, i_base, j_base, kb, ke);
         total += (ke - kb) / S::SLAB_K;
     }
-    if (next_pair()) {
+    pend = next_pair();
+    if (pend) {
         dma_slab<T, TA>(ta, pa, lda, copy_a, sA0, wave);
         dma_slab<T, !TB>(tb, pb, ldb, copy_b, sB0, wave);
     }
@@ -746,7 +749,6 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     // after the barrier (into the stage just freed), the rest, if the shape says so, with the first units of the
     // next slab (see FastShape::COPY_PP).
     // `more`: another slab follows.
-    bool pend = false;                            // the cursor is on a slab that has copies still to be issued
     constexpr int LAST_POS = (S::DMA_PER_WAVE - 1) / S::COPY_PP - 1;
     static_assert(LAST_POS < NU / 2, "the copies must be out by the middle of the slab");
     auto copies_at = [&](int pos, T* wa, T* wb) {
@@ -774,7 +776,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
         if (more) {
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's copies into the other stage have landed
             __syncthreads();
-            pend = advance();
+            advance();
             if (pend) copies_at(-1, sa, sb);
             unit_load<T, TA, TB>(R, na, nb, 0, lane_a, lane_b);
             __builtin_amdgcn_sched_barrier(0);
@@ -791,7 +793,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     if (total > 0) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();                          // stage 0 holds the first slab
-        pend = advance();
+        advance();
         if (pend) copies_at(-1, sA1, sB1);
         unit_load<T, TA, TB>(R, sA0, sB0, 0, lane_a, lane_b);
         unit_load_late<T, TA, TB>(R, sA0, sB0, 0, lane_a, lane_b);
