@@ -678,7 +678,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     auto next_pair = [&]() -> bool {
         if constexpr (MASK) {
             for (++pseg; pseg < nseg; ++pseg) {
-                masked_k_range<TA, TB>(st.seg[pseg].flags, st.seg[pseg].k, i_base, j_base, pkb, pke);
+                masked_k_range<TA, TB>(st.seg[pseg].flags, whole_slab_pairs<T>(st.seg[pseg].k), i_base, j_base, pkb, pke);
                 if (pke > pkb) break;
             }
             if (pseg >= nseg) return false;
@@ -707,7 +707,7 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
     int total = 0;
     for (int q = 0; q < nseg; ++q) {
         int kb = 0, ke = whole_slab_pairs<T>(st.seg[q].k);
-        if (MASK) masked_k_range<TA, TB>(st.seg[q].flags, st.seg[q].k, i_base, j_base, kb, ke);
+        if (MASK) masked_k_range<TA, TB>(st.seg[q].flags, whole_slab_pairs<T>(st.seg[q].k), i_base, j_base, kb, ke);
         total += (ke - kb) / S::SLAB_K;
     }
     pend = next_pair();
@@ -728,8 +728,8 @@ __device__ __forceinline__ void macro_tile_fast(const TileStep& st, int i_base, 
         if (ckb + cslab * S::SLAB_K >= cke) {
             for (++cseg; cseg < nseg; ++cseg) {
                 ckb = 0;
-                cke = st.seg[cseg].k;
-                masked_k_range<TA, TB>(st.seg[cseg].flags, st.seg[cseg].k, i_base, j_base, ckb, cke);
+                cke = whole_slab_pairs<T>(st.seg[cseg].k);
+                masked_k_range<TA, TB>(st.seg[cseg].flags, whole_slab_pairs<T>(st.seg[cseg].k), i_base, j_base, ckb, cke);
                 if (cke > ckb) break;
             }
             cslab = 0;

@@ -110,11 +110,10 @@ inline bool step_is_fast(const TileStep& st, int dtype) {
 }
 
 // Which kernel instantiation a step needs: 0 = fast, 1 = fast with operand masks, 2 = general.
-// The masked fast kernel works out its k ranges from whole macro-tiles: ragged masked steps are general.
 inline int step_mode(const TileStep& st, int dtype) {
     if (!step_is_fast(st, dtype)) return 2;
     for (int s = 0; s < st.nseg; ++s)
-        if (st.seg[s].flags) return step_is_ragged(st, dtype) ? 2 : 1;
+        if (st.seg[s].flags) return 1;
     return 0;
 }
 

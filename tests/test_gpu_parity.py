@@ -637,7 +637,7 @@ def poison_arena(lib):
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_ragged_sizes_run_in_the_fast_kernels_on_zero_padded_tiles(lib, T, dtype):
     """Sizes that are no multiple of anything: tiles are zero-padded in their slots to whole macro-tiles and every
-    tile step but the ragged diagonal ones of the triangular product runs in the unpredicated kernels (the arena starts
+    tile step of the products runs in the unpredicated kernels (the arena starts
     as NaN, so a tile whose padding was not cleared, after its copy or after it was derived on the device, shows)."""
     f64 = dtype == np.float64
     tol, single = (TOL64, False) if f64 else (TOL32, True)
@@ -696,7 +696,7 @@ def test_ragged_sizes_run_in_the_fast_kernels_on_zero_padded_tiles(lib, T, dtype
         ref.trmm(ref.ColMajor, ref.Left, ref.Lower, ref.NoTrans, ref.NonUnit, -0.8, np.asarray(P), want)
         assert_close(B, want, trmm_bound(blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, P, B0, -0.8, single=single, want=want), tol)
         st2 = lib.get_stats()
-        assert 0 < st2["steps_general"] < st2["tile_steps"] - st["tile_steps"]
+        assert st2["steps_general"] == 0 and st2["tile_steps"] > st["tile_steps"]
         # the solve: its results become operands of later steps and are padded when they are adopted
         for side, uplo in ((blasx.Left, blasx.Upper), (blasx.Right, blasx.Lower)):
             na = M if side == blasx.Left else N
