@@ -268,8 +268,7 @@ typedef struct blasx_stats {
     double   t_device_span_s;        /* first device operation of each call to its last; the rest of it
                                         is OTHER = span - COMPT - COMM */
     uint64_t steps_general;  /* of tile_steps: run by the bounds-checked general kernel instead of a fast one
-                                (tile edge not a multiple of 128, ragged tiles of a solve or with a triangular
-                                operand, unaligned leading dimensions) */
+                                (tile edge not a multiple of 128; the ragged diagonal steps of a solve) */
 } blasx_stats;
 
 int blasx_get_stats(blasx_stats* out);
