@@ -1250,3 +1250,31 @@ def test_solve_results_are_never_read_before_their_launch_when_packs_of_two_kern
         X = np.linalg.solve(A, B)
         assert relerr(Bs, X) < 1e-13
         assert sim.get_option("last_wide") == (1 if wide else 0)
+
+
+def test_adopted_solve_results_are_padded_for_later_calls(sim):
+    """Persistent cache, tile edge 128, ragged sizes: the solution tiles of a solve stay cached under B's address; a
+    later product that reads them as a k-ragged operand runs in the fast kernel on the padded extent, so their padding
+    must have been cleared when they were adopted (the double's memory starts as NaN and it reads the padding)."""
+    setup(sim, T=128, arena_tiles=96, persist=1, group=4)
+    rng = np.random.default_rng(24)
+    n, m = 300, 200
+    for uplo in (blasx.Lower, blasx.Upper):
+        tri = np.tril if uplo == blasx.Lower else np.triu
+        L = np.asfortranarray(tri(rng.uniform(-1, 1, (n, n))) + n * np.eye(n))
+        X = rng.uniform(-1, 1, (n, m))
+        B = np.asfortranarray(L @ X)
+        sim.dtrsm(CM, blasx.Left, uplo, NT, blasx.NonUnit, n, m, 1.0, L, n, B, n)
+        assert relerr(B, X) < 1e-13
+        sim.reset_stats()
+        # B (n x m) as the left operand: k = m = 200 is ragged; as the transposed right operand: k = n = 300 is
+        W, E = fmat(rng, m, 70), np.zeros((n, 70), order="F")
+        sim.dgemm(CM, NT, NT, n, 70, m, 1.0, B, n, W, m, 0.0, E, n)
+        assert np.all(np.isfinite(E)) and relerr(E, X @ W) < 1e-13
+        st = sim.get_stats()
+        assert st["steps_general"] == 0 and st["misses"] == 2          # only W's two tiles were copied
+        V, F = fmat(rng, 90, n), np.zeros((90, m), order="F")
+        sim.dgemm(CM, NT, NT, 90, m, n, 1.0, V, 90, B, n, 0.0, F, 90)
+        assert np.all(np.isfinite(F)) and relerr(F, V @ X) < 1e-13
+        assert sim.get_stats()["steps_general"] == 0
+        sim.invalidate_all()
