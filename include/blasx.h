@@ -151,9 +151,8 @@ int blasx_shutdown(void);
  * most double-precision calls, 1024 or 2048 in single precision, 512 or 2048 for some triangular
  * orders; halved until 64 tiles fit in the cache).  The choice of the latest call is
  * blasx_get_option("last_tile").  The default is 1024.  With T a multiple of 128 matrices of any order
- * run in the fast kernels (ragged edge tiles are kept zero-padded in the tile cache); with another T, tile
- * steps on ragged tiles, and all steps when T itself is no multiple of 128, take the slower bounds-checked
- * kernel (blasx_stats.steps_general counts them). */
+ * run in the fast kernels (ragged edge tiles are kept zero-padded in the tile cache); with another T every
+ * tile step takes the slower bounds-checked kernel (blasx_stats.steps_general counts them). */
 int blasx_set_tile(int T);
 /* Number of streams the scheduler uses (paper Section IV.D: tasks progress on concurrent
  * streams; its experiments use 4).  n = 2..4 with the roles listed at blasx_init, or 0 for the
@@ -268,7 +267,7 @@ typedef struct blasx_stats {
     double   t_device_span_s;        /* first device operation of each call to its last; the rest of it
                                         is OTHER = span - COMPT - COMM */
     uint64_t steps_general;  /* of tile_steps: run by the bounds-checked general kernel instead of a fast one
-                                (tile edge not a multiple of 128; the ragged diagonal steps of a solve) */
+                                (only with a tile edge that is not a multiple of 128) */
 } blasx_stats;
 
 int blasx_get_stats(blasx_stats* out);

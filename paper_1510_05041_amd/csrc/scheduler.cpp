@@ -937,6 +937,9 @@ int Scheduler::make_inverses(const Task* const* tasks, size_t count) {
                 compute_waited_[fill_stream_[slot]] = fill_seq_[slot];
             }
         }
+        // the inverse is an operand of the solve steps: padded like every operand tile (the kernels below write
+        // inside its true extent only)
+        BX_TRY(zero_padding(job.inv->slot, job.n, job.n, STREAM_COMPUTE));
         if (be_.launch_trtri_blocks(p_->dtype, slot_ptr(job.src->slot), T_, slot_ptr(job.inv->slot), T_, job.n, kTrtriBlock,
                                     job.flags, STREAM_COMPUTE))
             return BLASX_ERR_DEVICE;
@@ -1086,6 +1089,9 @@ int Scheduler::build_solve(int ri) {
     }
     st.alpha = r.first ? t.beta_first : 1.0;   // a task without update steps still owes the alpha
     st.beta = 0.0;
+    // both operands are padded: the inverse when it was made, the right-hand side because its slot was filled by the
+    // inbound copy of the task's tile of B (every later launch wrote inside the true extent only)
+    if (pad_ok_ && step_is_ragged(st, p_->dtype)) st.flags |= TS_PADDED;
     OpenPack& op = pack_for(step_mode(st, p_->dtype), p_->ta, p_->tb);
     BX_TRY(add_step(op, p_->ta, p_->tb, st, 1.0 * t.m * t.n * st.seg[0].k, 1));
     op.blocks.push_back(inv);

@@ -709,7 +709,7 @@ def test_ragged_sizes_run_in_the_fast_kernels_on_zero_padded_tiles(lib, T, dtype
             trsm(blasx.ColMajor, side, uplo, blasx.NoTrans, blasx.NonUnit, M, N, 1.5, P, na, B, M)
             assert_trsm_residual(side, uplo, blasx.NoTrans, blasx.NonUnit, P, B, B0, 1.5, tol, single=not f64)
         st3 = lib.get_stats()
-        assert st3["steps_general"] - st2["steps_general"] < st3["tile_steps"] - st2["tile_steps"]
+        assert st3["steps_general"] == 0 and st3["tile_steps"] > st2["tile_steps"]
 
 
 def test_wide_schedule_symmetric_routines_full_compare(lib):

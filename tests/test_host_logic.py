@@ -1223,7 +1223,7 @@ def test_ragged_tiles_are_kept_zero_padded_and_run_in_the_fast_kernel(sim, seed)
             assert np.all(np.isfinite(np.asarray(Bs)))
             assert relerr(Bs, np.asarray(Br)) < 1e-13
             after = sim.get_stats()
-            assert after["steps_general"] - before["steps_general"] < after["tile_steps"] - before["tile_steps"]
+            assert after["steps_general"] == before["steps_general"] and after["tile_steps"] > before["tile_steps"]
     # single precision: k is rounded up to 64
     setup(sim, T=128, seed=seed, arena_tiles=96, esize=4, group=3, kchain=2)
     A, B, C = (rng.uniform(-1, 1, s).astype(np.float32) for s in ((200, 170), (170, 150), (200, 150)))
