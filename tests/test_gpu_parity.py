@@ -633,13 +633,15 @@ def poison_arena(lib):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("T", [128, 1024])
+@pytest.mark.parametrize("T", [128, 1024, 208])
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_ragged_sizes_run_in_the_fast_kernels_on_zero_padded_tiles(lib, T, dtype):
     """Sizes that are no multiple of anything: tiles are zero-padded in their slots to whole macro-tiles and every
     tile step of the products runs in the unpredicated kernels (the arena starts
-    as NaN, so a tile whose padding was not cleared, after its copy or after it was derived on the device, shows)."""
+    as NaN, so a tile whose padding was not cleared, after its copy or after it was derived on the device, shows).
+    With a tile edge that is no multiple of the macro-tile edge (208) the same calls run in the bounds-checked kernel."""
     f64 = dtype == np.float64
+    fast = T % 128 == 0
     tol, single = (TOL64, False) if f64 else (TOL32, True)
     gemm, syrk, syr2k, symm, trmm = ((lib.dgemm, lib.dsyrk, lib.dsyr2k, lib.dsymm, lib.dtrmm) if f64 else
                                      (lib.sgemm, lib.ssyrk, lib.ssyr2k, lib.ssymm, lib.strmm))
@@ -686,7 +688,7 @@ def test_ragged_sizes_run_in_the_fast_kernels_on_zero_padded_tiles(lib, T, dtype
                      else elem_bound(norms(B, 1), norms(full, 0), -1.5, 0.25 * C0, single=single, want=want))
             assert_close(C, want, bound, tol)
         st = lib.get_stats()
-        assert st["steps_general"] == 0 and st["tile_steps"] > 0
+        assert st["tile_steps"] > 0 and st["steps_general"] == (0 if fast else st["tile_steps"])
         P, kp = pinned(M, M, 73, 0, dtype=dtype)
         synth.dominant_diag(P, 73, 0)
         P[np.triu_indices(M, 1)] = np.nan
@@ -696,7 +698,7 @@ def test_ragged_sizes_run_in_the_fast_kernels_on_zero_padded_tiles(lib, T, dtype
         ref.trmm(ref.ColMajor, ref.Left, ref.Lower, ref.NoTrans, ref.NonUnit, -0.8, np.asarray(P), want)
         assert_close(B, want, trmm_bound(blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, P, B0, -0.8, single=single, want=want), tol)
         st2 = lib.get_stats()
-        assert st2["steps_general"] == 0 and st2["tile_steps"] > st["tile_steps"]
+        assert st2["tile_steps"] > st["tile_steps"] and st2["steps_general"] == (0 if fast else st2["tile_steps"])
         # the solve: its results become operands of later steps and are padded when they are adopted
         for side, uplo in ((blasx.Left, blasx.Upper), (blasx.Right, blasx.Lower)):
             na = M if side == blasx.Left else N
@@ -709,7 +711,7 @@ def test_ragged_sizes_run_in_the_fast_kernels_on_zero_padded_tiles(lib, T, dtype
             trsm(blasx.ColMajor, side, uplo, blasx.NoTrans, blasx.NonUnit, M, N, 1.5, P, na, B, M)
             assert_trsm_residual(side, uplo, blasx.NoTrans, blasx.NonUnit, P, B, B0, 1.5, tol, single=not f64)
         st3 = lib.get_stats()
-        assert st3["steps_general"] == 0 and st3["tile_steps"] > st2["tile_steps"]
+        assert st3["tile_steps"] > st2["tile_steps"] and st3["steps_general"] == (0 if fast else st3["tile_steps"])
 
 
 def test_wide_schedule_symmetric_routines_full_compare(lib):
@@ -1319,7 +1321,7 @@ def test_seeded_random_problems_every_routine_and_schedule(lib, seed):
     shape (left-over steps first, a split first round, two rounds only)."""
     rng = np.random.default_rng(1000 + seed)
     routine = ("gemm", "syrk", "syr2k", "symm", "trmm", "trsm")[seed % 6]
-    T = int(rng.choice([128, 256]))
+    T = int(rng.choice([128, 256, 208]))      # 208: no multiple of the macro-tile edge, the bounds-checked kernel
     opts = dict(group=int(rng.choice([0, 4, 16])), kchain=int(rng.choice([0, 0, 3, 8])), wide=int(rng.choice([0, 2, 12])),
                 ramp=int(rng.choice([0, 0, 1, 8])))
     configure(lib, T=T, arena_gb=1.5, **opts)
@@ -1396,7 +1398,7 @@ def test_seeded_random_problems_single_precision(lib, seed):
     """The same in single precision (tile-aligned and ragged extents, so both the fast and the general kernel run)."""
     rng = np.random.default_rng(2000 + seed)
     routine = ("gemm", "syrk", "syr2k", "symm", "trmm", "trsm")[seed % 6]
-    T = int(rng.choice([256, 512]))
+    T = int(rng.choice([256, 512, 336]))      # 336: the bounds-checked kernel
     opts = dict(group=int(rng.choice([0, 4, 16])), kchain=int(rng.choice([0, 0, 3])), wide=int(rng.choice([0, 2, 12])))
     configure(lib, T=T, arena_gb=1.5, **opts)
     uplo = int(rng.choice([blasx.Lower, blasx.Upper]))
