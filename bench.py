@@ -19,10 +19,11 @@ if ROOT not in sys.path:
 
 FP64_MFMA_PEAK_TFLOPS = 78.6     # MI355X dense FP64 matrix peak (published)
 FP32_MFMA_PEAK_TFLOPS = 157.3    # MI355X dense FP32 matrix peak (published)
-# Sustained inbound rate of the host link for a long run of strided tile copies (one 8 MiB tile per 163 us on the
-# copy engine, measured with a memory-copy trace; 57 GB/s for one contiguous copy).  A call cannot take less than
-# its inbound bytes at this rate: both directions run at once and a call sends out less than it takes in.
-LINK_SUSTAINED_GBPS = 51.4
+# Inbound rate of the host link for ONE long contiguous copy from page-locked memory, the most this link has been
+# seen to carry (a run of single 8 MiB tile copies sustains 51.4 GB/s, one tile per 163 us; neighbouring tiles merged
+# four to a strided copy 55.9 GB/s).  A call cannot take less than its inbound bytes at this rate: both directions
+# run at once and a call sends out less than it takes in.
+LINK_PEAK_GBPS = 57.6
 
 
 def cpu_baseline(np, oracle, A, B, n, rows=2048, cols=8192):
@@ -61,9 +62,9 @@ def traffic_from_profile():
 
 def secondary_entry(name, flop, bytes_in, seconds, peak_tflops, extra=None):
     """One line of the secondary list: time and rate of a single call after a warm-up call, against the smaller of
-    the two bounds of a host-resident call -- its inbound bytes at the link's sustained rate, or its flop at the
-    MFMA peak."""
-    t_link = bytes_in / (LINK_SUSTAINED_GBPS * 1e9)
+    the two bounds of a host-resident call -- its inbound bytes at the rate of one long contiguous copy over the
+    link, or its flop at the MFMA peak."""
+    t_link = bytes_in / (LINK_PEAK_GBPS * 1e9)
     t_mfma = flop / (peak_tflops * 1e12)
     bound = "link" if t_link > t_mfma else "mfma"
     t_bound = max(t_link, t_mfma)
@@ -185,6 +186,7 @@ def main():
     ap.add_argument("--shells", type=int, default=None)
     ap.add_argument("--rs", type=int, default=None)
     ap.add_argument("--prefetch", type=int, default=None)
+    ap.add_argument("--merge", type=int, default=None, help="most neighbouring tiles per inbound copy (default 4; 1: one copy per tile)")
     ap.add_argument("--wide", type=int, default=None, help="least k-steps per task for which all tasks advance together when the cache has room (default 11); 0: grouped")
     ap.add_argument("--arena-gb", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -235,7 +237,7 @@ def main():
     lib.set_tile(T)
     lib.set_cache_bytes(0)
     for name, val in (("group", args.group), ("kchain", args.kchain), ("depth", args.depth), ("shells", args.shells),
-                      ("rs", args.rs), ("wide", args.wide), ("prefetch", args.prefetch)):
+                      ("rs", args.rs), ("wide", args.wide), ("prefetch", args.prefetch), ("merge", args.merge)):
         if val is not None:
             lib.set_option(name, val)
     if args.sb:
@@ -319,6 +321,8 @@ def main():
         "link": {
             "h2d_GBps": round(st["bytes_h2d"] / dt / 1e9, 2), "d2h_GBps": round(st["bytes_d2h"] / dt / 1e9, 2),
             "bytes_h2d_per_step": st["bytes_h2d"] // args.steps, "bytes_d2h_per_step": st["bytes_d2h"] // args.steps,
+            "tiles_in_per_step": st["copies_h2d"] // args.steps, "inbound_copies_per_step": st["transfers_h2d"] // args.steps,
+            "merge": lib.get_option("merge"),
         },
         "cache": {k: st[k] for k in ("hits", "misses", "evictions", "refetches", "peak_slots", "slot_waits")},
         "host": {"pin_seconds": round(t_pin, 2), "fill_seconds": round(t_fill, 2),

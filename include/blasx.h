@@ -187,6 +187,16 @@ int blasx_set_cache_bytes(size_t cap);
  *              first rather than last, and when nothing is left over the first full round is split
  *              into 2 steps and the rest.  The choice of the latest call is "last_ramp"
  *   "prefetch" wide schedule: inbound copies are started this many launches ahead (default 24)
+ *   "merge"    most whole tiles that one inbound copy may carry (1..8, default 4).  Tiles that lie side
+ *              by side in a block row of a column-major host matrix and go to neighbouring slots of the
+ *              tile cache are one strided copy: the copy engine pauses between copies, not inside one.
+ *              1: one copy per tile (the paper's scheme)
+ *   "late_c"   1 (default): a call in the grouped schedule whose tiles all fit the cache beside two slots per
+ *              running task fetches the host tile of C for a task's last launch only (as the wide schedule
+ *              always does) and cuts the k loop into launches of two k-tiles; 0: C comes in with the task's
+ *              first launch (the paper's order), launches of four k-tiles
+ *   "row_order" 1 (default): the same calls take their tasks block row by block row of C, whatever
+ *              "sb_rows" / "sb_cols" / "shells" say; 0: always in the queue order those give
  *   "depth"    launches the host may run ahead of the device (>= 1)
  *   "rs"       reservation-station size: queued tasks whose priorities are compared (>= group)
  *   "priority" 1 (default): the next task to start is the one of the reservation station with the
@@ -268,6 +278,7 @@ typedef struct blasx_stats {
                                         is OTHER = span - COMPT - COMM */
     uint64_t steps_general;  /* of tile_steps: run by the bounds-checked general kernel instead of a fast one
                                 (only with a tile edge that is not a multiple of 128) */
+    uint64_t transfers_h2d;  /* inbound copies handed to the copy engine; copies_h2d counts the tiles they carried */
 } blasx_stats;
 
 int blasx_get_stats(blasx_stats* out);

@@ -27,7 +27,7 @@ class Stats(ctypes.Structure):
         "copies_h2d", "copies_d2h", "bytes_h2d", "bytes_d2h", "slot_waits", "peak_slots",
         "profiled_launches")] + [(n, ctypes.c_double) for n in ("flops", "t_total_s", "t_issue_s", "t_kernel_s")] + [
         ("invalidations", ctypes.c_uint64)] + [(n, ctypes.c_double) for n in (
-            "t_wait_s", "t_kernel_busy_s", "t_copy_unoverlapped_s", "t_device_span_s")] + [("steps_general", ctypes.c_uint64)]
+            "t_wait_s", "t_kernel_busy_s", "t_copy_unoverlapped_s", "t_device_span_s")] + [("steps_general", ctypes.c_uint64), ("transfers_h2d", ctypes.c_uint64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -1,5 +1,8 @@
 #include "alru.h"
 
+#include <algorithm>
+#include <functional>
+
 namespace blasx {
 
 bool TileKey::overlaps(const void* base, int64_t ld_r, int64_t rows_r, int64_t cols_r, int esize_r) const {
@@ -29,8 +32,10 @@ bool TileKey::overlaps(const void* base, int64_t ld_r, int64_t rows_r, int64_t c
 }
 
 Alru::Alru(int nslots) : nslots_(nslots) {
+    // A min-heap: the lowest free slot is handed out first, so slots taken one after the other are neighbours in
+    // the arena whenever a run of them is free (tiles copied in together can then share a strided copy).
     free_.reserve(nslots);
-    for (int s = nslots - 1; s >= 0; --s) free_.push_back(s);   // slot 0 is handed out first
+    for (int s = 0; s < nslots; ++s) free_.push_back(s);        // ascending order is a valid min-heap
 }
 
 Alru::~Alru() {
@@ -81,6 +86,7 @@ int Alru::evict_one() {
 int Alru::take_slot() {
     int slot;
     if (!free_.empty()) {
+        std::pop_heap(free_.begin(), free_.end(), std::greater<int>());
         slot = free_.back();
         free_.pop_back();
     } else {
@@ -95,7 +101,10 @@ int Alru::take_slot() {
     return slot;
 }
 
-void Alru::give_slot(int slot) { free_.push_back(slot); }
+void Alru::give_slot(int slot) {
+    free_.push_back(slot);
+    std::push_heap(free_.begin(), free_.end(), std::greater<int>());
+}
 
 // Alg. 2 Translate (+ Enqueue on a miss).
 Block* Alru::translate(const TileKey& key, bool* hit) {

@@ -506,6 +506,9 @@ int blasx_set_option(const char* name, long value) {
     else if (n == "wide") { if (value < 0 || value > 65536) return BLASX_ERR_CONFIG; L.cfg.wide = (int)value; }
     else if (n == "ramp") { if (value < 0 || value > kMaxChain) return BLASX_ERR_CONFIG; L.cfg.ramp = (int)value; }
     else if (n == "prefetch") { if (value < 0 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.prefetch = (int)value; }
+    else if (n == "late_c") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.late_c = value != 0; }
+    else if (n == "row_order") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.row_order = value != 0; }
+    else if (n == "merge") { if (value < 1 || value > 8) return BLASX_ERR_CONFIG; L.cfg.merge = (int)value; }
     else if (n == "profile") { if (value < 0 || value > 2) return BLASX_ERR_CONFIG; L.cfg.profile = (int)value; }
     else if (n == "persist") {
         if (value < 0 || value > 1) return BLASX_ERR_CONFIG;
@@ -531,6 +534,9 @@ long blasx_get_option(const char* name) {
     if (n == "wide") return L.cfg.wide;
     if (n == "prefetch") return L.cfg.prefetch;
     if (n == "ramp") return L.cfg.ramp;
+    if (n == "merge") return L.cfg.merge;
+    if (n == "row_order") return L.cfg.row_order ? 1 : 0;
+    if (n == "late_c") return L.cfg.late_c ? 1 : 0;
     if (n == "profile") return L.cfg.profile;
     if (n == "streams") return L.be ? L.be->num_streams() : 0;
     if (n == "persist") return L.persist ? 1 : 0;
@@ -583,6 +589,7 @@ int blasx_get_stats(blasx_stats* out) {
     out->t_wait_s = s.t_wait_s; out->t_kernel_busy_s = s.t_kernel_busy_s; out->t_copy_unoverlapped_s = s.t_copy_unoverlapped_s;
     out->t_device_span_s = s.t_device_span_s;
     out->steps_general = s.steps_general;
+    out->transfers_h2d = s.transfers_h2d;
     return 0;
 }
 

@@ -66,7 +66,12 @@ Scheduler::~Scheduler() {
 // copy gets an event of its own (re-recorded when the slot is filled again): measured on the
 // copy engines an event record costs under 1 us next to a 150 us tile copy, while an event shared
 // by several copies would make a launch wait for copies that were only prefetched for later ones.
-int Scheduler::fill_event(int slot) const { return fill_ev_[slot]; }
+// A copy that is still being gathered goes out first, so that the event of every slot that has been
+// given a copy has been recorded when somebody orders work after it.
+int Scheduler::fill_event(int slot) {
+    if (held_.stream >= 0 && release_held()) err_ = BLASX_ERR_DEVICE;
+    return fill_ev_[slot];
+}
 
 TileKey Scheduler::key_of(const TileRef& t, int tag) const {
     TileKey k;
@@ -94,6 +99,7 @@ int Scheduler::new_event() {
 // paper does this after a full StreamsSynch; here one event per launch tells the same thing
 // without draining the streams.
 void Scheduler::wait_event(int ev) {
+    if (held_.stream >= 0 && release_held()) err_ = BLASX_ERR_DEVICE;    // the host is about to sleep: nothing is held back
     const double t = now_s();
     be_.event_sync(ev);
     t_wait_ += now_s() - t;
@@ -253,28 +259,106 @@ int Scheduler::zero_padding(int slot, int rows, int cols, int stream) {
     return 0;
 }
 
+// Hands the copy that issue_h2d() has been gathering to the copy engine, and records the event of every slot it fills.
+int Scheduler::release_held() {
+    if (held_.stream < 0) return 0;
+    const int stream = held_.stream;
+    held_.stream = -1;
+    const size_t es = p_->esize;
+    BX_TRY(profiled_copy_begin(stream));
+    if (be_.copy_h2d(held_.dst, (size_t)T_ * es, held_.src, held_.spitch, (size_t)T_ * es, (size_t)T_ * held_.ntiles, stream))
+        return BLASX_ERR_DEVICE;
+    BX_TRY(profiled_copy_end(stream));
+    for (int q = 0; q < held_.ntiles; ++q) {
+        const int slot = held_.slots[q];
+        if (fill_ev_[slot] < 0) fill_ev_[slot] = be_.event_create();
+        if (be_.event_record(fill_ev_[slot], stream)) return BLASX_ERR_DEVICE;
+    }
+    ++stats_.transfers_h2d;
+    return 0;
+}
+
+// Starts the inbound copy of a host tile into `slot`.  A whole tile is not handed to the copy engine at once: if the
+// next tile asked for is its right-hand neighbour in the host matrix and goes to the next slot of the arena, the two
+// (up to `merge` of them) are one strided copy -- the columns of the second tile follow those of the first at the same
+// pitch on both sides.  The copy goes out when a tile that does not continue it is asked for, when anybody needs the
+// event of one of its slots, when a launch is issued and before the host blocks.
 int Scheduler::issue_h2d(const TileRef& t, int slot) {
+    const size_t es = p_->esize;
+    const size_t spitch = (size_t)t.ld * es;
+    const bool whole = cfg_.merge > 1 && t.rows == T_ && t.cols == T_;
+    if (held_.stream >= 0) {
+        // (a slot whose previous copy went through the other stream needs an ordering wait first: not merged)
+        if (whole && held_.ntiles < std::min(cfg_.merge, (int)kMaxMerge) && spitch == held_.spitch &&
+            t.host == held_.src + (size_t)held_.ntiles * T_ * spitch &&
+            slot_ptr(slot) == held_.dst + (size_t)held_.ntiles * T_ * T_ * es &&
+            (fill_seq_[slot] == 0 || fill_stream_[slot] == held_.stream)) {
+            held_.slots[held_.ntiles++] = slot;
+            fill_seq_[slot] = ++h2d_issued_[held_.stream];
+            fill_stream_[slot] = held_.stream;
+            ++stats_.copies_h2d;
+            stats_.bytes_h2d += (uint64_t)t.rows * t.cols * es;
+            return 0;
+        }
+        BX_TRY(release_held());
+    }
     int stream = STREAM_H2D;
     if (be_.num_streams() >= 4) {
         stream = (h2d_rr_++ & 1) ? STREAM_H2D_B : STREAM_H2D;
     }
-    const size_t es = p_->esize;
     // A slot can change owner while a copy for its previous owner is still queued on the other
     // inbound stream (a block that was evicted before any launch read it): order the two copies.
     if (fill_seq_[slot] != 0 && fill_stream_[slot] != stream) {
         if (be_.stream_wait_event(stream, fill_event(slot))) return BLASX_ERR_DEVICE;
     }
-    BX_TRY(profiled_copy_begin(stream));
-    if (be_.copy_h2d(slot_ptr(slot), (size_t)T_ * es, t.host, (size_t)t.ld * es, (size_t)t.rows * es, (size_t)t.cols, stream))
-        return BLASX_ERR_DEVICE;
-    BX_TRY(profiled_copy_end(stream));
-    BX_TRY(zero_padding(slot, (int)t.rows, (int)t.cols, stream));     // before the fill event: consumers see the padded tile
-    if (fill_ev_[slot] < 0) fill_ev_[slot] = be_.event_create();
-    if (be_.event_record(fill_ev_[slot], stream)) return BLASX_ERR_DEVICE;
+    if (whole) {
+        held_.stream = stream;
+        held_.dst = slot_ptr(slot);
+        held_.src = t.host;
+        held_.spitch = spitch;
+        held_.ntiles = 1;
+        held_.slots[0] = slot;
+    } else {
+        BX_TRY(profiled_copy_begin(stream));
+        if (be_.copy_h2d(slot_ptr(slot), (size_t)T_ * es, t.host, spitch, (size_t)t.rows * es, (size_t)t.cols, stream))
+            return BLASX_ERR_DEVICE;
+        BX_TRY(profiled_copy_end(stream));
+        BX_TRY(zero_padding(slot, (int)t.rows, (int)t.cols, stream));     // before the fill event: consumers see the padded tile
+        if (fill_ev_[slot] < 0) fill_ev_[slot] = be_.event_create();
+        if (be_.event_record(fill_ev_[slot], stream)) return BLASX_ERR_DEVICE;
+        ++stats_.transfers_h2d;
+    }
     fill_seq_[slot] = ++h2d_issued_[stream];
     fill_stream_[slot] = stream;
     ++stats_.copies_h2d;
     stats_.bytes_h2d += (uint64_t)t.rows * t.cols * es;
+    return 0;
+}
+
+// Inbound copies that are wanted soon, started in an order in which tiles that lie side by side in a host matrix
+// follow each other (so that issue_h2d() can carry them in one copy): by leading dimension, then by the position of
+// the tile's block row within a column, then by address.  Tiles already cached are skipped.  Without may_evict only
+// free slots are used.  Returns what fetch() returns for the first tile that could not be started (-1: no slot).
+int Scheduler::fetch_sorted(std::vector<const TileRef*>& refs, bool may_evict) {
+    const size_t es = p_->esize;
+    auto row_of = [es](const TileRef* r) { return (uintptr_t)r->host % ((uintptr_t)r->ld * es); };
+    std::sort(refs.begin(), refs.end(), [&](const TileRef* x, const TileRef* y) {
+        if (x->ld != y->ld) return x->ld < y->ld;
+        const uintptr_t rx = row_of(x), ry = row_of(y);
+        if (rx != ry) return rx < ry;
+        return x->host < y->host;
+    });
+    const TileRef* prev = nullptr;
+    for (const TileRef* ref : refs) {
+        if (prev && prev->host == ref->host && prev->ld == ref->ld && prev->rows == ref->rows && prev->cols == ref->cols) continue;
+        prev = ref;
+        const Block* have = cache_.find(key_of(*ref));
+        if (have && !have->pending) continue;
+        if (!may_evict && !have && cache_.used_slots() >= cache_.nslots()) return -1;
+        Block* b = nullptr;
+        const int rc = fetch(*ref, &b);
+        if (rc) return rc;
+    }
     return 0;
 }
 
@@ -419,6 +503,7 @@ int Scheduler::add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, doub
 
 int Scheduler::flush(OpenPack& op) {
     if (op.pack.nsteps == 0) return 0;
+    BX_TRY(release_held());
     // Make the compute stream wait for the inbound copies this launch reads: one wait per
     // copy stream is enough, on the youngest copy (streams are in order).
     for (int stream : {(int)STREAM_H2D, (int)STREAM_H2D_B}) {
@@ -488,6 +573,7 @@ bool Scheduler::pack_is_open(uint64_t id) const {
 }
 
 int Scheduler::flush_all() {
+    BX_TRY(release_held());
     for (int q = 0; q < 3; ++q)
         for (int a = 0; a < 2; ++a)
             for (int b = 0; b < 2; ++b) BX_TRY(flush(packs_[q][a][b]));
@@ -561,7 +647,7 @@ int Scheduler::start_task(int task_index, Running* r) {
     *r = Running();
     r->task = task_index;
     r->c_slot = slot;
-    if (t.load_c && !wide_) {
+    if (t.load_c && !late_c_) {
         TileRef c;
         c.host = t.c_host;
         c.ld = p_->ldc;
@@ -647,43 +733,60 @@ const std::vector<uint32_t>& Scheduler::round_order(size_t round) {
 void Scheduler::prefetch_ahead(size_t build_pos) {
     const size_t ntasks = p_->tasks.size();
     const size_t target = build_pos + (size_t)cfg_.prefetch * kMaxStepsPerLaunch;
+    // The cursor moves by the tasks of one launch at a time: their tiles are asked for together, sorted so that
+    // neighbours in a host matrix follow each other and can share a copy (a launch waits for all of them anyway).
+    auto batch_end = [&](size_t pos) {
+        const size_t round = pos / ntasks, in_round = pos % ntasks;
+        return round * ntasks + std::min(ntasks, (in_round / kMaxStepsPerLaunch + 1) * kMaxStepsPerLaunch);
+    };
+    struct WantC { Running* r; const Task* t; bool direct; };
+    auto c_before = [&](const WantC& x, const WantC& y) {
+        const uintptr_t col = (uintptr_t)p_->ldc * p_->esize;
+        const uintptr_t rx = (uintptr_t)x.t->c_host % col, ry = (uintptr_t)y.t->c_host % col;
+        return rx != ry ? rx < ry : x.t->c_host < y.t->c_host;
+    };
+    std::vector<const TileRef*> refs;
+    std::vector<WantC> want_c;
     if (pf_pos_ <= build_pos) pf_pos_ = build_pos + 1;
     while (pf_pos_ <= target) {
         const size_t round = pf_pos_ / ntasks;
         if (round > pf_last_round_) break;                                // nothing left in any task
-        const size_t ri = round_order(round)[pf_pos_ % ntasks];
-        if (ri >= running_.size()) break;
-        Running& r = running_[ri];
-        if (r.task < 0 || r.done) {
-            ++pf_pos_;
-            continue;
-        }
-        const Task& t = p_->tasks[r.task];
-        const size_t nsteps = t.steps.size();
-        const size_t s0 = std::min(nsteps, round_begin(round)), s1 = std::min(nsteps, round_begin(round + 1));
-        bool stalled = false;
-        for (size_t q = s0; q < s1 && !stalled; ++q) {
-            for (const TileRef* ref : {&t.steps[q].a, &t.steps[q].b}) {
-                // an operand that another task produces is not on the host yet
-                if ((ref == &t.steps[q].a && t.steps[q].a_is_dep) || (ref == &t.steps[q].b && t.steps[q].b_is_dep)) continue;
-                const Block* have = cache_.find(key_of(*ref));
-                if (have && !have->pending) continue;
-                Block* b = nullptr;
-                if (fetch(*ref, &b) != 0) {       // no slot right now: try again after the next launch
-                    stalled = true;
-                    break;
-                }
-            }
-        }
-        if (stalled) break;
-        if (s0 < nsteps && s1 >= nsteps && t.load_c) {
-            if (s0 == 0) {
-                if (r.first && load_c_direct(r, t) != 0) break;
-            } else if (prefetch_c(r, t, false) != 0 || r.h_slot < 0) {
+        const std::vector<uint32_t>& order = round_order(round);
+        const size_t end = batch_end(pf_pos_);
+        refs.clear();
+        want_c.clear();
+        bool beyond = false;
+        for (size_t pos = pf_pos_; pos < end; ++pos) {
+            const size_t ri = order[pos % ntasks];
+            if (ri >= running_.size()) {
+                beyond = true;
                 break;
             }
+            Running& r = running_[ri];
+            if (r.task < 0 || r.done) continue;
+            const Task& t = p_->tasks[r.task];
+            const size_t nsteps = t.steps.size();
+            const size_t s0 = std::min(nsteps, round_begin(round)), s1 = std::min(nsteps, round_begin(round + 1));
+            for (size_t q = s0; q < s1; ++q) {
+                // an operand that another task produces is not on the host yet
+                if (!t.steps[q].a_is_dep) refs.push_back(&t.steps[q].a);
+                if (!t.steps[q].b_is_dep) refs.push_back(&t.steps[q].b);
+            }
+            if (s0 < nsteps && s1 >= nsteps && t.load_c) want_c.push_back(WantC{&r, &t, s0 == 0});
         }
-        ++pf_pos_;
+        if (fetch_sorted(refs, true) != 0) break;       // no slot right now: try again after the next launch
+        std::sort(want_c.begin(), want_c.end(), c_before);
+        bool stalled = false;
+        for (const WantC& w : want_c) {
+            if (w.direct) {
+                if (w.r->first && load_c_direct(*w.r, *w.t) != 0) stalled = true;
+            } else if (prefetch_c(*w.r, *w.t, false) != 0 || w.r->h_slot < 0) {
+                stalled = true;
+            }
+            if (stalled) break;
+        }
+        if (stalled || beyond) break;
+        pf_pos_ = end;
     }
     // Host C tiles are wanted by the last launch of each task only, and the last round is the one
     // in which the link is busiest (its operand tiles in, every result tile out).  They are
@@ -694,19 +797,73 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
     while (pfc_pos_ <= c_target) {
         const size_t round = pfc_pos_ / ntasks;
         if (round > pf_last_round_) break;
-        const size_t ri = round_order(round)[pfc_pos_ % ntasks];
-        if (ri >= running_.size()) break;
-        Running& r = running_[ri];
-        if (r.task >= 0 && !r.done && r.h_slot < 0) {
+        const std::vector<uint32_t>& order = round_order(round);
+        const size_t end = batch_end(pfc_pos_);
+        want_c.clear();
+        bool beyond = false;
+        for (size_t pos = pfc_pos_; pos < end; ++pos) {
+            const size_t ri = order[pos % ntasks];
+            if (ri >= running_.size()) {
+                beyond = true;
+                break;
+            }
+            Running& r = running_[ri];
+            if (r.task < 0 || r.done || r.h_slot >= 0) continue;
             const Task& t = p_->tasks[r.task];
             const size_t nsteps = t.steps.size();
             const size_t s0 = std::min(nsteps, round_begin(round)), s1 = std::min(nsteps, round_begin(round + 1));
-            if (s0 < nsteps && s1 >= nsteps && s0 > 0 && t.load_c) {
-                if ((size_t)(cache_.nslots() - cache_.used_slots()) <= pf_reserve_) break;
-                if (prefetch_c(r, t, false) != 0 || r.h_slot < 0) break;
+            if (s0 < nsteps && s1 >= nsteps && s0 > 0 && t.load_c) want_c.push_back(WantC{&r, &t, false});
+        }
+        std::sort(want_c.begin(), want_c.end(), c_before);
+        bool stalled = false;
+        for (const WantC& w : want_c) {
+            if ((size_t)(cache_.nslots() - cache_.used_slots()) <= pf_reserve_ || prefetch_c(*w.r, *w.t, false) != 0 ||
+                w.r->h_slot < 0) {
+                stalled = true;
+                break;
             }
         }
-        ++pfc_pos_;
+        if (stalled || beyond) break;
+        pfc_pos_ = end;
+    }
+}
+
+// Grouped schedule: the operand tiles of the chains that the coming round builds, for all running tasks together and
+// in fetch_sorted()'s order, into free slots only (a hint: build_chain() fetches whatever is missing).
+void Scheduler::prefetch_grouped_round() {
+    if (cfg_.merge <= 1) return;
+    std::vector<const TileRef*> refs;
+    for (const Running& r : running_) {
+        if (r.done || r.task < 0) continue;
+        const Task& t = p_->tasks[r.task];
+        const int nsteps = (int)t.steps.size();
+        for (int q = r.next_step; q < std::min(nsteps, r.next_step + kchain_); ++q) {
+            const StepSpec& s = t.steps[q];
+            if (s.dep >= 0) break;                           // the chain may end at a step that waits for a producer
+            if (!s.a_sym && !s.a_mirror) refs.push_back(&s.a);
+            if (!s.b_sym && !s.b_mirror) refs.push_back(&s.b);
+        }
+    }
+    // not when slots are scarce: a tile fetched here holds no reader yet, and a later tile of the batch must not push
+    // an earlier one out again
+    if ((size_t)(cache_.nslots() - cache_.used_slots()) < refs.size() + 2 * running_.size()) return;
+    if (fetch_sorted(refs, false) != 0 || !late_c_) return;
+    // then the host tiles of C that the coming launches need, block row by block row
+    std::vector<Running*> want_c;
+    for (Running& r : running_) {
+        if (r.done || r.task < 0 || r.h_slot >= 0 || r.c_direct) continue;
+        const Task& t = p_->tasks[r.task];
+        if (t.load_c && r.next_step + kchain_ >= (int)t.steps.size()) want_c.push_back(&r);
+    }
+    const uintptr_t col = (uintptr_t)p_->ldc * p_->esize;
+    std::sort(want_c.begin(), want_c.end(), [&](const Running* x, const Running* y) {
+        const char *cx = p_->tasks[x->task].c_host, *cy = p_->tasks[y->task].c_host;
+        const uintptr_t rx = (uintptr_t)cx % col, ry = (uintptr_t)cy % col;
+        return rx != ry ? rx < ry : cx < cy;
+    });
+    for (Running* r : want_c) {
+        const Task& t = p_->tasks[r->task];
+        if (r->first ? load_c_direct(*r, t) != 0 : (prefetch_c(*r, t, false) != 0 || r->h_slot < 0)) return;
     }
 }
 
@@ -813,7 +970,7 @@ int Scheduler::build_chain(int ri) {
     int acc_slot = -1;          // wide mode: accumulator that the last launch only reads
     st.C = slot_ptr(r.c_slot);
     st.beta = r.first ? t.beta_first : 1.0;
-    if (wide_) {
+    if (late_c_) {
         // The host C tile is not needed before the task's last launch: earlier launches build
         // alpha * sum(A B) in the accumulator slot, the last one computes
         // alpha * (its products) + beta * C_host + accumulator  into the slot holding C_host.
@@ -1060,7 +1217,7 @@ int Scheduler::build_solve(int ri) {
     Running& r = running_[ri];
     const Task& t = p_->tasks[r.task];
     if (pack_is_open(r.last_pack)) BX_TRY(flush_all());
-    if (wide_ && r.first) BX_TRY(load_c_direct(r, t));   // no update step came before: the right-hand-side tile has not been fetched yet
+    if (late_c_ && r.first) BX_TRY(load_c_direct(r, t));   // no update step came before: the right-hand-side tile has not been fetched yet
     Block* inv = nullptr;
     BX_TRY(get_inverse(t, &inv));
     cache_.acquire(inv);
@@ -1129,6 +1286,8 @@ int Scheduler::run(Problem& p) {
     panels_.assign(p.panels.size(), PanelState());
     for (size_t q = 0; q < p.panels.size(); ++q) panels_[q].remaining = p.panels[q].ntasks;
     int rc = 0;
+    err_ = 0;
+    held_.stream = -1;
     if (cfg_.profile >= 2) {
         base_ev_ = new_event();
         if (base_ev_ < 0 || be_.event_record(base_ev_, STREAM_COMPUTE)) rc = BLASX_ERR_DEVICE;
@@ -1164,6 +1323,28 @@ int Scheduler::run(Problem& p) {
     }
     kchain_ = p.results_are_operands ? 1 : cfg_.kchain ? cfg_.kchain : wide_chain;
     wide_ = cfg_.wide > 0 && (int)ntasks > cfg_.group && wide_fits(p);
+    // Grouped schedule with room for every tile of the call and a second slot per running task (the link-bound sizes):
+    // the host tile of C is fetched for a task's last launch only, as in the wide schedule, and launches are two
+    // k-tiles long.  What is left to do when the last inbound tile has landed is then one short launch and its results
+    // going out, instead of the whole k loop of the last group.
+    late_c_ = wide_;
+    if (!wide_ && cfg_.late_c && !p.results_are_operands && p.panels.empty()) {
+        std::unordered_set<TileKey, TileKeyHash> uniq;
+        for (const Task& t : p.tasks)
+            for (const StepSpec& s : t.steps) {
+                uniq.insert(key_of(s.a));
+                uniq.insert(key_of(s.b));
+            }
+        late_c_ = (size_t)cache_.nslots() >= uniq.size() + 2 * (size_t)cfg_.group * (cfg_.depth + 2) + kMaxStepsPerLaunch;
+        if (late_c_) grouped_chain = std::min(grouped_chain, 2);
+        // Such a call is bound by the link, and the queue order decides what is left to do when the last tile has
+        // landed.  Block row by block row, every row after the first asks for the same few new tiles (its tiles of
+        // the left operand and of C) per unit of work, so copies and launches stay in step to the end; super-block
+        // shells end in a corner whose operands are all cached, and its products queue up behind the link.
+        if (late_c_ && cfg_.row_order)
+            std::stable_sort(p.tasks.begin(), p.tasks.end(),
+                             [](const Task& a, const Task& b) { return a.ti != b.ti ? a.ti < b.ti : a.tj < b.tj; });
+    }
     if (!wide_) kchain_ = cfg_.kchain ? cfg_.kchain : grouped_chain;
     // Length of the first round.  The last round is the one in which every result tile leaves and
     // every late C tile arrives: a short one cannot hide that traffic.  So the left-over steps are
@@ -1273,6 +1454,7 @@ int Scheduler::run(Problem& p) {
                 else if (brc != 1) rc = brc;
             }
         } else {
+            prefetch_grouped_round();
             for (size_t ri = 0; ri < running_.size() && !rc; ++ri) {
                 if (running_[ri].done) continue;
                 const int brc = build_chain((int)ri);
@@ -1296,6 +1478,8 @@ int Scheduler::run(Problem& p) {
     // drain: wait for everything that was issued, even after an error
     {
         if (rc == 0) rc = flush_all();
+        if (rc == 0 && err_) rc = err_;
+        held_.stream = -1;
         while (!inflight_.empty()) retire(true);
         poll_writebacks(true);
         const double tw = now_s();

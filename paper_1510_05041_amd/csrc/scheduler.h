@@ -51,6 +51,11 @@ struct SchedConfig {
     int prefetch = 24;  // wide mode: inbound copies are started this many launches ahead of the launch being built
     int ramp = 0;       // wide mode: k-steps per task in the first round (1..kMaxChain, cut to the chain length of
                         // the run, i.e. kMaxChain = no shorter first round; 0: chosen per run, see run())
+    int merge = 4;      // most whole tiles that lie side by side in a host matrix (and land in neighbouring slots) carried
+                        // by one inbound copy; 1: every tile is a copy of its own
+    bool late_c = true; // grouped schedule: fetch the host tile of C for a task's last launch only, when the cache has room
+                        // for every tile of the call (see run()); false: with the task's first launch, always
+    bool row_order = true;  // the same calls take their tasks block row by block row of C instead of in the queue's order
     int profile = 0;    // 1: time every launch with events; 2: also every tile copy, and dissect the call's time on the
                         // device into kernels / copies not hidden under a kernel / neither (Section V.A, time profile)
 };
@@ -66,6 +71,7 @@ struct Stats {
     double t_copy_unoverlapped_s = 0;  // profile 2: time during which a tile copy ran and no kernel did (COMM)
     double t_device_span_s = 0;        // profile 2: first device operation of a call to its last
     uint64_t steps_general = 0;        // tile steps launched in the general (bounds-checked) kernel
+    uint64_t transfers_h2d = 0;        // inbound copies handed to the copy engine (one may carry several tiles)
 };
 
 class Scheduler {
@@ -139,6 +145,9 @@ private:
 
     int  fetch(const TileRef& t, Block** out);               // translate + inbound copy on a miss
     int  issue_h2d(const TileRef& t, int slot);
+    int  release_held();                                     // hands the inbound copy that is being gathered to the engine
+    int  fetch_sorted(std::vector<const TileRef*>& refs, bool may_evict);
+    void prefetch_grouped_round();
     int  zero_padding(int slot, int rows, int cols, int stream);
     int  take_slot_blocking(int* slot);
     int  start_task(int task_index, Running* r);
@@ -165,7 +174,7 @@ private:
     int  flush(OpenPack& op);
     int  flush_all();
     int  finish_task(int ri);
-    int  fill_event(int slot) const;
+    int  fill_event(int slot);
     bool retire(bool block_on_oldest);
     void poll_writebacks(bool block);
     void wait_event(int ev);            // blocks the host; the time counts as waiting, not issuing
@@ -190,6 +199,7 @@ private:
     bool pad_ok_ = false;
     int kchain_ = 4;                    // this run: k-steps fused per launch
     bool wide_ = false;                 // this run: all tasks advance together, C tiles arrive late
+    bool late_c_ = false;               // this run: a task's host C tile is fetched for its last launch (wide, or grouped with room)
     size_t round_ = 0;                  // wide mode: index of the round being built
     size_t pf_last_round_ = 0;          // wide mode: last round in which any task still has steps
     size_t pfc_pos_ = 0;                // wide mode: same for the host C tiles, which run further ahead
@@ -209,6 +219,18 @@ private:
     uint64_t h2d_issued_[4] = {0, 0, 0, 0};      // per stream role
     uint64_t compute_waited_[4] = {0, 0, 0, 0};
     int h2d_rr_ = 0;
+    // An inbound copy that has not been handed to the copy engine yet: whole tiles that follow each other along a
+    // block row of a host matrix and whose slots follow each other in the arena travel as one strided copy
+    // (the engine leaves about 10 us between two copies, whatever their size).
+    static constexpr int kMaxMerge = 8;
+    struct HeldCopy {
+        int stream = -1;                // -1: nothing held
+        char* dst = nullptr;
+        const char* src = nullptr;
+        size_t spitch = 0;              // bytes between columns in the host matrix
+        int ntiles = 0;
+        int slots[kMaxMerge];
+    } held_;
 
     size_t next_task_ = 0;
     std::vector<int> rs_;               // task indices waiting in the reservation station

@@ -76,7 +76,7 @@ def _problem(lib, routine, n, k):
     raise ValueError(routine)
 
 
-def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=11, kchain=0, ramp=0, warmup_s=2.0):
+def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=11, kchain=0, ramp=0, warmup_s=2.0, merge=4, order=(4, 4, 1), late_c=1):
     lib = blasx.default()
     results = []
     warm = False
@@ -100,10 +100,12 @@ def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None
                     lib.init(int(arena_gb * 2 ** 30), nstreams=ns)
                     lib.set_tile(T)
                     lib.set_cache_bytes(0)
-                    for name, v in dict(group=g, rs=max(32, 2 * g), kchain=kchain, depth=6, sb_rows=4, sb_cols=4, shells=1,
+                    for name, v in dict(group=g, rs=max(32, 2 * g), kchain=kchain, depth=6, sb_rows=order[0], sb_cols=order[1], shells=order[2],
                                         profile=0, persist=0, wide=wide).items():
                         lib.set_option(name, v)
                     lib.set_option("ramp", ramp)
+                    lib.set_option("merge", merge)
+                    lib.set_option("late_c", late_c)
                     times = []
                     for rep in range(reps + 1):
                         if refresh:
@@ -159,13 +161,16 @@ def main(argv=None):
     ap.add_argument("--wide", type=int, default=11, help="option \"wide\": least k-steps per task for which all tasks advance together; 0: never")
     ap.add_argument("--kchain", type=int, default=0, help="option \"kchain\": k-tiles per launch and task; 0: the library's choice")
     ap.add_argument("--ramp", type=int, default=0, help="option \"ramp\": k-steps per task in the first round of the wide schedule (8: as in the others); 0: the library's choice")
+    ap.add_argument("--merge", type=int, default=4, help="option \"merge\": most neighbouring tiles per inbound copy (1: one copy per tile)")
+    ap.add_argument("--late-c", type=int, default=1, help="option \"late_c\": grouped schedule with room for every tile fetches C for a task's last launch only")
+    ap.add_argument("--order", default="4,4,1", help="options sb_rows,sb_cols,shells: super-block shape of the task queue and whether super-blocks are visited in growing shells (1) or block row by block row (0)")
     ap.add_argument("--warmup-s", type=float, default=2.0, help="seconds of untimed calls of the first problem before anything is timed")
     ap.add_argument("--out", default="", help="also append the JSON records to this file")
     a = ap.parse_args(argv)
     ints = lambda s: [int(x) for x in s.split(",") if x]
     sizes, tiles, streams, groups = ints(a.sizes), ints(a.tiles), ints(a.streams), ints(a.groups)
     out = open(a.out, "a") if a.out else None
-    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out, a.wide, a.kchain, a.ramp, a.warmup_s)
+    res = sweep(a.routine, sizes, tiles, streams, groups, a.k, a.reps, a.arena_gb, out, a.wide, a.kchain, a.ramp, a.warmup_s, a.merge, tuple(ints(a.order)), a.late_c)
     print()
     print(tables(res, tiles, streams))
 

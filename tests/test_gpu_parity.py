@@ -51,7 +51,8 @@ def configure(L, T, nstreams=4, arena_gb=2.0, cap_bytes=0, **opts):
     L.init(int(arena_gb * 2 ** 30), nstreams=nstreams)
     L.set_tile(T)
     L.set_cache_bytes(cap_bytes)
-    defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, shells=1, priority=1, profile=0, persist=0, wide=0, ramp=0)
+    defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, shells=1, priority=1, profile=0, persist=0, wide=0, ramp=0,
+                    merge=4, late_c=1, row_order=1)
     defaults.update(opts)
     for k, v in defaults.items():
         L.set_option(k, v)
@@ -1141,6 +1142,40 @@ def test_symmetric_and_triangular_routines_integer_exact(lib, schedule):
         assert np.array_equal(np.asarray(Bs), want), ("trmm", side, uplo, trans, diag)
 
 
+@pytest.mark.parametrize("schedule", ["grouped", "wide"])
+@pytest.mark.parametrize("ta,tb", [(blasx.NoTrans, blasx.NoTrans), (blasx.Trans, blasx.NoTrans), (blasx.NoTrans, blasx.Trans)])
+def test_neighbouring_tiles_share_an_inbound_copy_integer_exact(lib, schedule, ta, tb):
+    """Whole tiles that lie side by side in a block row of a host matrix travel in one strided copy ("merge" tiles at
+    most) when they go to neighbouring slots.  The copy engine then sees fewer copies than tiles; bytes, tile counts
+    and results (integer inputs: bit for bit) are those of one copy per tile.  Both schedules; in the grouped one
+    also with C fetched for the first launch and in queue order."""
+    T = 256
+    M, N, K = 8 * T, 8 * T, 12 * T
+    A, ka = int_pinned(M if ta == blasx.NoTrans else K, K if ta == blasx.NoTrans else M, 61, 0)
+    B, kb = int_pinned(K if tb == blasx.NoTrans else N, N if tb == blasx.NoTrans else K, 61, 1)
+    C0, kc = int_pinned(M, N, 61, 2)
+    want = np.array(C0, order="F")
+    ref.gemm(ref.ColMajor, ta, tb, 2.0, np.asarray(A), np.asarray(B), -1.0, want)
+    variants = [dict(merge=1), dict(merge=4), dict(merge=8)]
+    if schedule == "grouped":
+        variants += [dict(merge=4, late_c=0), dict(merge=4, row_order=0), dict(merge=8, late_c=0, row_order=0, kchain=3)]
+    transfers = []
+    for v in variants:
+        configure(lib, T=T, arena_gb=1.0, **dict(AUTO if schedule == "wide" else dict(group=4, kchain=0), **v))
+        C, kcc = blasx.pinned_matrix(M, N)
+        C[...] = np.asarray(C0)
+        lib.dgemm(blasx.ColMajor, ta, tb, M, N, K, 2.0, A, A.shape[0], B, B.shape[0], -1.0, C, M)
+        assert lib.get_option("last_wide") == (1 if schedule == "wide" else 0)
+        assert np.array_equal(np.asarray(C), want), (schedule, v)
+        st = lib.get_stats()
+        assert st["copies_h2d"] == 64 + 2 * 96 and st["bytes_h2d"] == 8 * (M * K + K * N + M * N), (v, st)
+        assert st["steps_general"] == 0
+        transfers.append(st["transfers_h2d"])
+    print("inbound copies for 256 tiles:", list(zip([str(v) for v in variants], transfers)), flush=True)
+    assert transfers[0] == 256
+    assert all(t <= 0.7 * 256 for t in transfers[1:]), transfers
+
+
 @pytest.mark.parametrize("ta,tb,T", [(blasx.NoTrans, blasx.Trans, 1024), (blasx.Trans, blasx.NoTrans, 512), (blasx.NoTrans, blasx.NoTrans, 2048)])
 def test_sgemm_integer_exact(lib, ta, tb, T):
     """Single precision: entries in {-2..2} and K <= 22528 keep every partial sum below 2^24, so float32 is exact too."""
@@ -1324,6 +1359,9 @@ def test_seeded_random_problems_every_routine_and_schedule(lib, seed):
     T = int(rng.choice([128, 256, 208]))      # 208: no multiple of the macro-tile edge, the bounds-checked kernel
     opts = dict(group=int(rng.choice([0, 4, 16])), kchain=int(rng.choice([0, 0, 3, 8])), wide=int(rng.choice([0, 2, 12])),
                 ramp=int(rng.choice([0, 0, 1, 8])))
+    # how tiles travel and when C is fetched (a generator of their own: the problems above stay what they were)
+    rng2 = np.random.default_rng(5000 + seed)
+    opts.update(merge=int(rng2.choice([1, 4, 4, 8])), late_c=int(rng2.choice([0, 1, 1])), row_order=int(rng2.choice([0, 1, 1])))
     configure(lib, T=T, arena_gb=1.5, **opts)
     uplo = int(rng.choice([blasx.Lower, blasx.Upper]))
     trans = int(rng.choice(TRANS))

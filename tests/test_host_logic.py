@@ -30,7 +30,8 @@ def setup(sim, T, nstreams=4, arena_tiles=64, cap_tiles=0, seed=1, esize=8, **op
     sim.init_raw(arena_tiles * T * T * esize, nstreams)
     sim.set_tile(T)
     sim.set_cache_bytes(cap_tiles * T * T * esize)
-    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, shells=1, priority=1, profile=0, persist=0, wide=0, ramp=0)
+    defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, shells=1, priority=1, profile=0, persist=0, wide=0, ramp=0,
+                    merge=4, late_c=1, row_order=1)
     defaults.update(opts)
     for k, v in defaults.items():
         sim.set_option(k, v)
@@ -1278,3 +1279,124 @@ def test_adopted_solve_results_are_padded_for_later_calls(sim):
         assert np.all(np.isfinite(F)) and relerr(F, V @ X) < 1e-13
         assert sim.get_stats()["steps_general"] == 0
         sim.invalidate_all()
+
+
+# ------------------------------------------------------------------ merged inbound copies ----------
+
+@pytest.mark.parametrize("wide", [0, 3])
+def test_neighbouring_tiles_share_an_inbound_copy(sim, wide):
+    """Whole tiles that lie side by side in a block row of a host matrix and go to neighbouring slots are one
+    strided copy: with "merge" = 4 the copy engine sees fewer copies than tiles, the bytes moved stay what the
+    method fixes, and the result is bit-identical to the one-copy-per-tile run."""
+    M = N = K = 128
+    A = synth.matrix(M, K, 11, 0, integers=True)
+    B = synth.matrix(K, N, 11, 1, integers=True)
+    C = synth.matrix(M, N, 11, 2, integers=True)
+    want = 2.0 * (np.asarray(A) @ np.asarray(B)) - np.asarray(C)
+    seen = {}
+    for merge in (1, 4, 8):
+        setup(sim, T=16, arena_tiles=400, group=4, kchain=4, wide=wide, sb_rows=4, sb_cols=4, merge=merge, seed=merge)
+        Cs = C.copy(order="F")
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 2.0, A, M, B, K, -1.0, Cs, M)
+        assert np.array_equal(Cs, want), merge
+        st = sim.get_stats()
+        assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N) and st["copies_h2d"] == 3 * 64
+        seen[merge] = st["transfers_h2d"]
+    assert seen[1] == 3 * 64
+    assert seen[4] <= 0.6 * seen[1], seen        # most tiles travel in company
+    assert seen[8] <= 0.6 * seen[1], seen
+    sim.set_option("merge", 4)
+
+
+@pytest.mark.parametrize("late_c", [0, 1])
+def test_grouped_schedule_with_room_fetches_c_for_the_last_launch(sim, late_c):
+    """With room for every tile of the call the grouped schedule fetches a task's host C tile for its last launch only
+    (option "late_c", default 1) and cuts the k loop into launches of two k-tiles; results and link bytes are the same
+    either way, for every routine that reads C."""
+    rng = np.random.default_rng(5 + late_c)
+    M, N, K = 83, 70, 101
+    setup(sim, T=16, arena_tiles=600, group=3, kchain=0, depth=3, late_c=late_c, seed=3)
+    A = np.asfortranarray(rng.uniform(-1, 1, (M, K)))
+    B = np.asfortranarray(rng.uniform(-1, 1, (K, N)))
+    C = np.asfortranarray(rng.uniform(-1, 1, (M, N)))
+    Cs, Cr = C.copy(order="F"), C.copy(order="F")
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 1.5, A, M, B, K, -0.5, Cs, M)
+    ref.gemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 1.5, A, B, -0.5, Cr)
+    assert relerr(Cs, np.asarray(Cr)) < 1e-14
+    st = sim.get_stats()
+    assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N) and st["bytes_d2h"] == 8 * M * N
+    assert sim.get_option("last_kchain") == (2 if late_c else 4) and sim.get_option("last_wide") == 0
+    # integer inputs: bit-exact whichever launch adds the host tile
+    Ai = synth.matrix(M, K, 21, 0, integers=True)
+    Ci = synth.matrix(M, M, 21, 2, integers=True)
+    want = np.asarray(Ci).copy()
+    full = 2.0 * (np.asarray(Ai) @ np.asarray(Ai).T) + 3.0 * np.asarray(Ci)
+    low = np.tril_indices(M)
+    want[low] = full[low]
+    Cs = Ci.copy(order="F")
+    sim.dsyrk(blasx.ColMajor, blasx.Lower, blasx.NoTrans, M, K, 2.0, Ai, M, 3.0, Cs, M)
+    assert np.array_equal(Cs, want)
+    S = np.asfortranarray(rng.uniform(-1, 1, (M, M)))
+    Cs, Cr = C.copy(order="F"), C.copy(order="F")
+    sim.dsymm(blasx.ColMajor, blasx.Left, blasx.Upper, M, N, 0.75, S, M, B[:M, :] if K >= M else B, K, 1.25, Cs, M)
+    ref.symm(blasx.ColMajor, blasx.Left, blasx.Upper, 0.75, S, B[:M, :], 1.25, Cr)
+    assert relerr(Cs, np.asarray(Cr)) < 1e-14
+    sim.set_option("late_c", 1)
+
+
+def test_grouped_schedule_with_room_takes_tasks_block_row_by_block_row(sim):
+    """A grouped call whose tiles all fit is bound by the link; its tasks are then taken block row by block row of C
+    (option "row_order", default 1), whatever the super-block options say.  Seen in the order in which the host tiles
+    of C are asked for, one task running at a time."""
+    T, nt = 16, 4
+    n = nt * T
+    A = synth.matrix(n, n, 31, 0, integers=True)
+    B = synth.matrix(n, n, 31, 1, integers=True)
+    C0 = synth.matrix(n, n, 31, 2, integers=True)
+    seen = {}
+    for row_order in (0, 1):
+        setup(sim, T=T, arena_tiles=200, group=1, rs=1, kchain=0, sb_rows=2, sb_cols=2, shells=1, row_order=row_order, priority=0)
+        C = C0.copy(order="F")
+        sim._lib.blasx_sim_trace_reset()
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 1.0, C, n)
+        assert np.array_equal(C, np.asarray(A) @ np.asarray(B) + np.asarray(C0))
+        seen[row_order] = start_order(sim, C, T)
+    rows = [(i, j) for i in range(nt) for j in range(nt)]
+    assert seen[1] == rows
+    assert sorted(seen[0]) == rows and seen[0] != rows and seen[0][:4] == [(0, 0), (0, 1), (1, 0), (1, 1)]
+    # a cache too small for that keeps the queue's order
+    setup(sim, T=T, arena_tiles=24, group=1, rs=1, kchain=0, sb_rows=2, sb_cols=2, shells=1, row_order=1, priority=0)
+    C = C0.copy(order="F")
+    sim._lib.blasx_sim_trace_reset()
+    sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, n, B, n, 1.0, C, n)
+    assert np.array_equal(C, np.asarray(A) @ np.asarray(B) + np.asarray(C0))
+    assert start_order(sim, C, T) == seen[0]
+
+
+def test_merged_copies_under_a_tight_cache_random_problems(sim):
+    """Slots change owner all the time under a tight cache: a copy that is still being gathered must go out before
+    anything is ordered after one of its slots.  Every routine, random shapes, merge 1..8, against the oracle."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        T = 16
+        M, N, K = (int(x) for x in rng.integers(33, 130, 3))
+        merge = int(rng.integers(1, 9))
+        wide = int(rng.choice([0, 2]))
+        arena = int(rng.integers(14, 60)) if case % 3 else int(rng.integers(200, 500))
+        setup(sim, T=T, arena_tiles=arena, group=int(rng.integers(1, 5)), kchain=int(rng.integers(1, 5)), wide=wide,
+              merge=merge, nstreams=int(rng.integers(2, 5)), seed=case)
+        A = np.asfortranarray(rng.uniform(-1, 1, (M, K)))
+        B = np.asfortranarray(rng.uniform(-1, 1, (K, N)))
+        C = np.asfortranarray(rng.uniform(-1, 1, (M, N)))
+        Cs, Cr = C.copy(order="F"), C.copy(order="F")
+        sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 1.5, A, M, B, K, 0.5, Cs, M)
+        ref.gemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, 1.5, A, B, 0.5, Cr)
+        assert relerr(Cs, np.asarray(Cr)) < 1e-14, (case, M, N, K, merge, wide, arena)
+        # triangular solve on the same cache: results become operands, slots are recycled at once
+        L = np.asfortranarray(np.tril(rng.uniform(-1, 1, (M, M))) + M * np.eye(M))
+        X = np.asfortranarray(rng.uniform(-1, 1, (M, N)))
+        Xs, Xr = X.copy(order="F"), X.copy(order="F")
+        sim.dtrsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, M, N, 1.0, L, M, Xs, M)
+        ref.trsm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, 1.0, L, Xr)
+        assert relerr(Xs, np.asarray(Xr)) < 1e-12, (case, M, N, merge, wide, arena)
+    sim.set_option("merge", 4)
