@@ -485,7 +485,7 @@ int Scheduler::add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, doub
     if (op.pack.nsteps > 0 && (op.ta != ta || op.tb != tb)) BX_TRY(flush(op));
     // A launch is cut at a multiple of 8 steps: 8 whole-tile steps of 64 macro-tiles fill the 512
     // workgroup slots of the chip once, so multiples of 8 leave no partial wave of workgroups.
-    if (op.pack.nsteps == (kMaxStepsPerLaunch / 8) * 8) BX_TRY(flush(op));
+    if (op.pack.nsteps >= pack_cut_) BX_TRY(flush(op));
     if (op.pack.nsteps == 0) {
         op.ta = ta;
         op.tb = tb;
@@ -713,8 +713,10 @@ const std::vector<uint32_t>& Scheduler::round_order(size_t round) {
         for (size_t i = 0; i < n; ++i) o.push_back((uint32_t)i);
     } else {
         auto cls = [&](size_t i) {
-            const size_t ns = p_->tasks[i].steps.size();
-            return ns == round ? 0 : ns > round + 1 ? 1 : ns == round + 1 ? 2 : 3;
+            const long lr = local_round(i, round);      // a trailing column panel is `lag` rounds behind
+            if (lr < 0) return 3;
+            const size_t ns = p_->tasks[i].steps.size(), r = (size_t)lr;
+            return ns == r ? 0 : ns > r + 1 ? 1 : ns == r + 1 ? 2 : 3;
         };
         for (int c = 0; c < 4; ++c)
             for (size_t i = 0; i < n; ++i)
@@ -747,7 +749,7 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
     };
     std::vector<const TileRef*> refs;
     std::vector<WantC> want_c;
-    if (pf_pos_ <= build_pos) pf_pos_ = build_pos + 1;
+    if (pf_pos_ < build_pos) pf_pos_ = build_pos;      // the chain about to be built included: its tiles are asked for in sorted order too
     while (pf_pos_ <= target) {
         const size_t round = pf_pos_ / ntasks;
         if (round > pf_last_round_) break;                                // nothing left in any task
@@ -766,13 +768,17 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
             if (r.task < 0 || r.done) continue;
             const Task& t = p_->tasks[r.task];
             const size_t nsteps = t.steps.size();
-            const size_t s0 = std::min(nsteps, round_begin(round)), s1 = std::min(nsteps, round_begin(round + 1));
+            const long lr = local_round((size_t)r.task, round);
+            if (lr < 0) continue;
+            const size_t s0 = std::min(nsteps, round_begin((size_t)lr)), s1 = std::min(nsteps, round_begin((size_t)lr + 1));
             for (size_t q = s0; q < s1; ++q) {
                 // an operand that another task produces is not on the host yet
                 if (!t.steps[q].a_is_dep) refs.push_back(&t.steps[q].a);
                 if (!t.steps[q].b_is_dep) refs.push_back(&t.steps[q].b);
             }
-            if (s0 < nsteps && s1 >= nsteps && t.load_c) want_c.push_back(WantC{&r, &t, s0 == 0});
+            // the host tile of C (of B, for a solve) is wanted by the task's last launch of updates; a solve task
+            // without updates wants it for its solve, in its first round
+            if (t.load_c && ((s0 < nsteps && s1 >= nsteps) || (t.solve && nsteps == 0 && lr == 0))) want_c.push_back(WantC{&r, &t, s0 == 0});
         }
         if (fetch_sorted(refs, true) != 0) break;       // no slot right now: try again after the next launch
         std::sort(want_c.begin(), want_c.end(), c_before);
@@ -793,7 +799,7 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
     // therefore fetched up to a whole round early, into slots that are free anyway: never at
     // the price of evicting an operand tile.
     const size_t c_target = build_pos + ntasks;
-    if (pfc_pos_ <= build_pos) pfc_pos_ = build_pos + 1;
+    if (pfc_pos_ < build_pos) pfc_pos_ = build_pos;
     while (pfc_pos_ <= c_target) {
         const size_t round = pfc_pos_ / ntasks;
         if (round > pf_last_round_) break;
@@ -811,7 +817,9 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
             if (r.task < 0 || r.done || r.h_slot >= 0) continue;
             const Task& t = p_->tasks[r.task];
             const size_t nsteps = t.steps.size();
-            const size_t s0 = std::min(nsteps, round_begin(round)), s1 = std::min(nsteps, round_begin(round + 1));
+            const long lr = local_round((size_t)r.task, round);
+            if (lr < 0) continue;
+            const size_t s0 = std::min(nsteps, round_begin((size_t)lr)), s1 = std::min(nsteps, round_begin((size_t)lr + 1));
             if (s0 < nsteps && s1 >= nsteps && s0 > 0 && t.load_c) want_c.push_back(WantC{&r, &t, false});
         }
         std::sort(want_c.begin(), want_c.end(), c_before);
@@ -915,6 +923,9 @@ int Scheduler::build_chain(int ri) {
     Running& r = running_[ri];
     const Task& t = p_->tasks[r.task];
     const int nsteps = (int)t.steps.size();
+    if (wide_) prefetch_ahead(build_pos_);
+    const long lr = wide_ ? local_round((size_t)r.task, round_) : 0;
+    if (lr < 0) return 1;                   // a trailing column panel of the solve: not its turn yet
     if (r.next_step >= nsteps && !(r.first && !t.solve)) {
         if (t.solve && !r.solved) return build_solve(ri);
         return 1;
@@ -927,7 +938,7 @@ int Scheduler::build_chain(int ri) {
     const bool ta = p_->ta, tb = p_->tb;
     // wide mode: up to the end of the current round (the first round may be a short one)
     int chain_limit = kchain_;
-    if (wide_) chain_limit = std::max(1, std::min(kchain_, (int)round_begin(round_ + 1) - r.next_step));
+    if (wide_) chain_limit = std::max(1, std::min(kchain_, (int)round_begin((size_t)lr + 1) - r.next_step));
     while (nseg < chain_limit && r.next_step + nseg < nsteps) {
         const StepSpec& s = t.steps[r.next_step + nseg];
         if (s.dep >= 0) {
@@ -1018,7 +1029,6 @@ int Scheduler::build_chain(int ri) {
         op.finishing.push_back(ri);
         task_final_pack_[r.task] = op.id;
     }
-    if (wide_) prefetch_ahead(build_pos_);
     return 0;
 }
 
@@ -1043,7 +1053,7 @@ int Scheduler::get_inverse(const Task& t, Block** out) {
 // one 1024 x 1024 tile is a few small products, far too few to fill the device, and the ten
 // levels of a tile run one after the other; the levels of many tiles fill it better and cost
 // little more than those of one.
-int Scheduler::make_inverses(const Task* const* tasks, size_t count) {
+int Scheduler::make_inverses(const Task* const* tasks, size_t count, bool prefetch_after_fetch) {
     struct Job {
         Block *src, *inv;
         int tmp, n;
@@ -1081,6 +1091,10 @@ int Scheduler::make_inverses(const Task* const* tasks, size_t count) {
         jobs.push_back(job);
     }
     if (jobs.empty()) return 0;
+    if (prefetch_after_fetch && wide_ && !running_.empty()) {
+        build_pos_ = 0;
+        prefetch_ahead(0);
+    }
     BX_TRY(flush_all());
     const size_t es = p_->esize;
     auto at = [&](int slot, int r, int c) { return slot_ptr(slot) + ((size_t)r + (size_t)c * T_) * es; };
@@ -1287,6 +1301,7 @@ int Scheduler::run(Problem& p) {
     for (size_t q = 0; q < p.panels.size(); ++q) panels_[q].remaining = p.panels[q].ntasks;
     int rc = 0;
     err_ = 0;
+    pack_cut_ = (kMaxStepsPerLaunch / 8) * 8;
     held_.stream = -1;
     if (cfg_.profile >= 2) {
         base_ev_ = new_event();
@@ -1380,10 +1395,50 @@ int Scheduler::run(Problem& p) {
     for (size_t& key : order_round_) key = SIZE_MAX;
     pf_pos_ = pfc_pos_ = 0;
     pf_last_round_ = 0;
+    lag_.clear();
     if (wide_) {
         size_t max_steps = 0;
         for (const Task& t : p.tasks) max_steps = std::max(max_steps, t.steps.size());
         while (round_begin(pf_last_round_ + 1) < max_steps) ++pf_last_round_;
+        // Wide triangular solve: the right-hand sides are cut into `solve_panels` panels of block columns (block rows
+        // when the triangular matrix is on the right), which do not depend on each other, and panel q runs
+        // q * solve_lag rounds behind panel 0.  All panels in step would finish their last block rows, where a round
+        // is a few launches long, in one burst that the outbound link needs several times as long to carry, and
+        // would start with nothing to compute while the first block row of every panel comes in; staggered, the
+        // burst of one panel leaves under the product-rich early rounds of the next.
+        // It pays when the device, not the link, bounds the call (measured: double precision from order 16384 with
+        // tiles of 1024, 24576 with tiles of 2048; below, the link is busy to the end and the smaller launches of
+        // two panels only cost): unless a lag is given, the panels are staggered by 3/8 of the rounds when the
+        // call's flop at 70 (single precision: 140) TFLOP/s take longer than its inbound bytes at 55 GB/s.
+        if (p.results_are_operands && cfg_.solve_panels > 1 && cfg_.solve_lag >= 0 && max_steps >= 4) {
+            int nb = 0;
+            for (const Task& t : p.tasks) nb = std::max(nb, (t.solve_on_right ? t.ti : t.tj) + 1);
+            const int panels = std::min(cfg_.solve_panels, nb);
+            size_t lag = std::min<size_t>((size_t)cfg_.solve_lag, max_steps);
+            if (cfg_.solve_lag == 0) {
+                std::unordered_set<TileKey, TileKeyHash> uniq;
+                double bytes_in = 0;
+                for (const Task& t : p.tasks) {
+                    bytes_in += (double)t.m * t.n * p.esize;
+                    for (const StepSpec& st : t.steps)
+                        if (!st.a_is_dep && uniq.insert(key_of(st.a)).second) bytes_in += (double)st.a.rows * st.a.cols * p.esize;
+                    for (const StepSpec& st : t.steps)
+                        if (!st.b_is_dep && uniq.insert(key_of(st.b)).second) bytes_in += (double)st.b.rows * st.b.cols * p.esize;
+                }
+                const bool device_bound = p.flops / (p.dtype == 0 ? 70e12 : 140e12) > bytes_in / 55e9;
+                lag = device_bound ? (3 * max_steps + 4) / 8 : 0;
+            }
+            if (panels > 1 && lag > 0) {
+                lag_.resize(ntasks);
+                size_t lag_max = 0;
+                for (size_t i = 0; i < ntasks; ++i) {
+                    const Task& t = p.tasks[i];
+                    lag_[i] = (uint32_t)((size_t)((t.solve_on_right ? t.ti : t.tj) * panels / nb) * lag);
+                    lag_max = std::max<size_t>(lag_max, lag_[i]);
+                }
+                pf_last_round_ += lag_max;
+            }
+        }
     }
     // Tiles kept from earlier calls: whatever overlaps the matrix this call writes is stale from
     // now on (and must not collide with result tiles adopted under the same host address).
@@ -1394,10 +1449,7 @@ int Scheduler::run(Problem& p) {
     // Made on demand, the inverse of block row k stands between rounds k - 1 and k: its diagonal
     // tile would be requested behind all the copies already queued, and its ten merge levels keep
     // the device nearly idle for half a millisecond per round.
-    if (rc == 0 && wide_ && p.results_are_operands) {
-        const std::vector<const Task*> diag = diag_tasks(p);
-        rc = make_inverses(diag.data(), diag.size());
-    }
+    bool inverses_first = wide_ && p.results_are_operands;
 
     for (; rc == 0;) {
         retire(false);
@@ -1436,6 +1488,14 @@ int Scheduler::run(Problem& p) {
             if (!wide_) refill_rs();
         }
         if (rc) break;
+        if (inverses_first) {
+            // (once every task has its slot: the copies of the first rounds are queued behind the diagonal tiles
+            // before the host turns to the many small launches that make the inverses)
+            inverses_first = false;
+            const std::vector<const Task*> diag = diag_tasks(p);
+            rc = make_inverses(diag.data(), diag.size(), true);
+            if (rc) break;
+        }
         if (active == 0) {
             if (rs_.empty() && next_task_ >= ntasks) break;
             rc = BLASX_ERR_DEVICE;   // tasks remain but none can start: broken dependency order
@@ -1449,6 +1509,11 @@ int Scheduler::run(Problem& p) {
                 const size_t ri = order[pos];
                 if (ri >= running_.size() || running_[ri].done) continue;
                 build_pos_ = round_ * ntasks + pos;
+                // The results of the very last launch leave with nothing left to hide them: the last sixteen tasks of
+                // the last round go out as four launches of four, so that twelve of their tiles leave under a kernel.
+                pack_cut_ = cfg_.tail_cut > 0 && round_ == pf_last_round_ && order.size() - pos <= (size_t)kMaxStepsPerLaunch
+                                ? std::min(cfg_.tail_cut, (kMaxStepsPerLaunch / 8) * 8)
+                                : (kMaxStepsPerLaunch / 8) * 8;
                 const int brc = build_chain((int)ri);
                 if (brc == 0) progressed = true;
                 else if (brc != 1) rc = brc;

@@ -56,6 +56,10 @@ struct SchedConfig {
     bool late_c = true; // grouped schedule: fetch the host tile of C for a task's last launch only, when the cache has room
                         // for every tile of the call (see run()); false: with the task's first launch, always
     bool row_order = true;  // the same calls take their tasks block row by block row of C instead of in the queue's order
+    int tail_cut = 4;   // wide mode: tile steps per launch for the last sixteen tasks of the last round (0: sixteen, as everywhere)
+    int solve_panels = 2;   // wide triangular solve: independent panels of right-hand sides that run staggered,
+    int solve_lag = 0;      // each this many rounds behind the one before; 0: chosen per call (none when the link
+                            // bounds it); -1 or one panel: all right-hand sides in step
     int profile = 0;    // 1: time every launch with events; 2: also every tile copy, and dissect the call's time on the
                         // device into kernels / copies not hidden under a kernel / neither (Section V.A, time profile)
 };
@@ -165,7 +169,9 @@ private:
     }
     int  build_solve(int ri);
     int  get_inverse(const Task& t, Block** out);
-    int  make_inverses(const Task* const* tasks, size_t count);
+    int  make_inverses(const Task* const* tasks, size_t count, bool prefetch_after_fetch = false);
+    // wide solve: the round of a task's own schedule that global round R is (negative: its panel has not started)
+    long local_round(size_t task, size_t R) const { return lag_.empty() ? (long)R : (long)R - (long)lag_[task]; }
     std::vector<const Task*> diag_tasks(const Problem& p) const;
     int  fetch_derived(const TileRef& t, int kind, Block** out);
     OpenPack& pack_for(int mode, bool ta, bool tb) { return packs_[mode][ta ? 1 : 0][tb ? 1 : 0]; }
@@ -199,8 +205,10 @@ private:
     bool pad_ok_ = false;
     int kchain_ = 4;                    // this run: k-steps fused per launch
     bool wide_ = false;                 // this run: all tasks advance together, C tiles arrive late
+    int pack_cut_ = 16;                 // a launch pack is launched when it holds this many tile steps
     bool late_c_ = false;               // this run: a task's host C tile is fetched for its last launch (wide, or grouped with room)
     size_t round_ = 0;                  // wide mode: index of the round being built
+    std::vector<uint32_t> lag_;         // wide solve: rounds by which each task's panel trails the first one (empty: none)
     size_t pf_last_round_ = 0;          // wide mode: last round in which any task still has steps
     size_t pfc_pos_ = 0;                // wide mode: same for the host C tiles, which run further ahead
     size_t pf_reserve_ = 0;             // free slots that early C tiles must leave for operand tiles

@@ -31,7 +31,7 @@ def setup(sim, T, nstreams=4, arena_tiles=64, cap_tiles=0, seed=1, esize=8, **op
     sim.set_tile(T)
     sim.set_cache_bytes(cap_tiles * T * T * esize)
     defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, shells=1, priority=1, profile=0, persist=0, wide=0, ramp=0,
-                    merge=4, late_c=1, row_order=1)
+                    merge=4, late_c=1, row_order=1, tail_cut=0, solve_panels=2, solve_lag=3)
     defaults.update(opts)
     for k, v in defaults.items():
         sim.set_option(k, v)
@@ -640,6 +640,60 @@ def test_wide_mode_first_round_takes_the_odd_steps(sim, ktiles, ramp, expect):
     # request: the first full round is split into 2 + 6, the same number of rounds as 2 + 8 + ... + 6)
     rounds = 1 + -(-(ktiles - expect) // kc) if expect < kc else -(-ktiles // kc)
     assert st["tasks"] == 9 and st["launches"] == rounds
+
+
+def test_wide_mode_last_launches_are_cut_short(sim):
+    """Wide schedule: the last sixteen tasks of the last round go out as launches of "tail_cut" tasks, so that most of
+    their results leave under a kernel.  Same results, same bytes, more launches."""
+    M, N, K = 16 * 6, 16 * 8, 16 * 9                   # 48 tasks, 9 k-tiles: rounds of 1 + 4 + 4 with chains of 4
+    A = synth.matrix(M, K, 41, 0, integers=True)
+    B = synth.matrix(K, N, 41, 1, integers=True)
+    C0 = synth.matrix(M, N, 41, 2, integers=True)
+    want = np.asarray(A) @ np.asarray(B) - 2.0 * np.asarray(C0)
+    launches = {}
+    for tail in (0, 4, 2, 16):
+        setup(sim, T=16, arena_tiles=800, seed=tail, wide=2, group=2, kchain=4, tail_cut=tail)
+        C = C0.copy(order="F")
+        sim.dgemm(CM, NT, NT, M, N, K, 1.0, A, M, B, K, -2.0, C, M)
+        assert sim.get_option("last_wide") == 1 and np.array_equal(C, want), tail
+        st = sim.get_stats()
+        assert st["bytes_h2d"] == 8 * (M * K + K * N + M * N) and st["tasks"] == 48
+        launches[tail] = st["launches"]
+    assert launches[0] == launches[16] == 3 * 3         # three rounds of three launches of sixteen
+    assert launches[4] == 9 + 3 and launches[2] == 9 + 7
+
+
+@pytest.mark.parametrize("side", [blasx.Left, blasx.Right])
+@pytest.mark.parametrize("uplo", [blasx.Lower, blasx.Upper])
+@pytest.mark.parametrize("trans", TRANS)
+def test_wide_solve_with_staggered_panels_of_right_hand_sides(sim, side, uplo, trans):
+    """Wide triangular solve: the right-hand sides are cut into "solve_panels" independent panels, each "solve_lag"
+    rounds behind the one before.  Any number of panels and any lag give the solution of the oracle (residual and
+    elementwise), also when the cache is tight and when the lag exceeds the number of rounds."""
+    rng = np.random.default_rng(uplo + 2 * trans + 5 * side)
+    T = 16
+    n, m = 16 * 7 - 3, 16 * 6 + 5                     # triangular order n, other extent m
+    A = np.asfortranarray(rng.uniform(-1, 1, (n, n)) + n * np.eye(n))
+    M, N = (n, m) if side == blasx.Left else (m, n)
+    B0 = np.asfortranarray(rng.uniform(-1, 1, (M, N)))
+    want = B0.copy(order="F")
+    ref.trsm(blasx.ColMajor, side, uplo, trans, blasx.NonUnit, 0.5, A, want)
+    for case, (panels, lag, arena) in enumerate([(1, 3, 300), (2, -1, 300), (2, 3, 300), (2, 6, 300), (3, 2, 300), (4, 1, 300), (7, 1, 300),
+                                                 (2, 50, 300), (2, 3, 120), (3, 2, 100)]):
+        setup(sim, T=T, arena_tiles=arena, seed=case, wide=1, group=2, kchain=0, solve_panels=panels, solve_lag=lag)
+        B = B0.copy(order="F")
+        sim.dtrsm(blasx.ColMajor, side, uplo, trans, blasx.NonUnit, M, N, 0.5, A, n, B, M)
+        assert relerr(B, np.asarray(want)) < 1e-13, (panels, lag, arena)
+        st = sim.get_stats()
+        assert st["bytes_d2h"] == 8 * M * N
+        if arena == 300:
+            assert sim.get_option("last_wide") == 1, (panels, lag)
+            assert st["refetches"] == 0 and st["evictions"] == 0        # every tile crosses the link once
+    # no lag given: chosen per call (this one is far too small to be device-bound: none)
+    setup(sim, T=T, arena_tiles=300, wide=1, group=2, kchain=0, solve_panels=2, solve_lag=0)
+    B = B0.copy(order="F")
+    sim.dtrsm(blasx.ColMajor, side, uplo, trans, blasx.NonUnit, M, N, 0.5, A, n, B, M)
+    assert relerr(B, np.asarray(want)) < 1e-13
 
 
 def test_wide_mode_special_cases(sim):
