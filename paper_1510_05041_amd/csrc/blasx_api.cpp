@@ -509,8 +509,8 @@ int blasx_set_option(const char* name, long value) {
     else if (n == "late_c") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.late_c = value != 0; }
     else if (n == "row_order") { if (value < 0 || value > 1) return BLASX_ERR_CONFIG; L.cfg.row_order = value != 0; }
     else if (n == "tail_cut") { if (value < 0 || value > 16) return BLASX_ERR_CONFIG; L.cfg.tail_cut = (int)value; }
-    else if (n == "solve_panels") { if (value < 1 || value > 64) return BLASX_ERR_CONFIG; L.cfg.solve_panels = (int)value; }
-    else if (n == "solve_lag") { if (value < -1 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.solve_lag = (int)value; }
+    else if (n == "stagger_panels") { if (value < 1 || value > 64) return BLASX_ERR_CONFIG; L.cfg.stagger_panels = (int)value; }
+    else if (n == "stagger_lag") { if (value < -1 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.stagger_lag = (int)value; }
     else if (n == "merge") { if (value < 1 || value > 8) return BLASX_ERR_CONFIG; L.cfg.merge = (int)value; }
     else if (n == "profile") { if (value < 0 || value > 2) return BLASX_ERR_CONFIG; L.cfg.profile = (int)value; }
     else if (n == "persist") {
@@ -538,8 +538,8 @@ long blasx_get_option(const char* name) {
     if (n == "prefetch") return L.cfg.prefetch;
     if (n == "ramp") return L.cfg.ramp;
     if (n == "merge") return L.cfg.merge;
-    if (n == "solve_panels") return L.cfg.solve_panels;
-    if (n == "solve_lag") return L.cfg.solve_lag;
+    if (n == "stagger_panels") return L.cfg.stagger_panels;
+    if (n == "stagger_lag") return L.cfg.stagger_lag;
     if (n == "tail_cut") return L.cfg.tail_cut;
     if (n == "row_order") return L.cfg.row_order ? 1 : 0;
     if (n == "late_c") return L.cfg.late_c ? 1 : 0;

@@ -1400,40 +1400,44 @@ int Scheduler::run(Problem& p) {
         size_t max_steps = 0;
         for (const Task& t : p.tasks) max_steps = std::max(max_steps, t.steps.size());
         while (round_begin(pf_last_round_ + 1) < max_steps) ++pf_last_round_;
-        // Wide triangular solve: the right-hand sides are cut into `solve_panels` panels of block columns (block rows
-        // when the triangular matrix is on the right), which do not depend on each other, and panel q runs
-        // q * solve_lag rounds behind panel 0.  All panels in step would finish their last block rows, where a round
-        // is a few launches long, in one burst that the outbound link needs several times as long to carry, and
-        // would start with nothing to compute while the first block row of every panel comes in; staggered, the
-        // burst of one panel leaves under the product-rich early rounds of the next.
-        // It pays when the device, not the link, bounds the call (measured: double precision from order 16384 with
-        // tiles of 1024, 24576 with tiles of 2048; below, the link is busy to the end and the smaller launches of
-        // two panels only cost): unless a lag is given, the panels are staggered by 3/8 of the rounds when the
-        // call's flop at 70 (single precision: 140) TFLOP/s take longer than its inbound bytes at 55 GB/s.
-        if (p.results_are_operands && cfg_.solve_panels > 1 && cfg_.solve_lag >= 0 && max_steps >= 4) {
+        // Wide triangular solve: the right-hand sides are cut into `stagger_panels` panels of
+        // block columns (block rows when the triangular matrix is on the right), which do not depend on each other,
+        // and panel q runs q * stagger_lag rounds behind panel 0.  All panels in step would finish their last block
+        // rows, where a round is a few launches long, in one burst that the outbound link needs several times as long
+        // to carry, and would start with nothing to compute while the first block row of every panel comes in;
+        // staggered, the burst of one panel leaves under the product-rich early rounds of the next.
+        // It pays when the device, not the link, bounds the call (measured for the solve: double precision from order
+        // 16384 with tiles of 1024, 24576 with tiles of 2048; below, the link is busy to the end and the smaller
+        // launches of two panels only cost): unless a lag is given, the panels are staggered by 3/8 of the rounds when
+        // the call's flop at 70 (single precision: 140) TFLOP/s take longer than its inbound bytes at 55 GB/s.
+        // (The triangular product gains nothing from it: 16384: 78 -> 82 .. 88 ms with two to four panels; its launches
+        // hold chains of one length only as long as all panels are in step.)
+        const size_t nrounds = pf_last_round_ + 1;
+        if (p.results_are_operands && cfg_.stagger_panels > 1 && cfg_.stagger_lag >= 0 && nrounds >= 4) {
+            auto panel_of = [](const Task& t) { return t.solve_on_right ? t.ti : t.tj; };
             int nb = 0;
-            for (const Task& t : p.tasks) nb = std::max(nb, (t.solve_on_right ? t.ti : t.tj) + 1);
-            const int panels = std::min(cfg_.solve_panels, nb);
-            size_t lag = std::min<size_t>((size_t)cfg_.solve_lag, max_steps);
-            if (cfg_.solve_lag == 0) {
+            for (const Task& t : p.tasks) nb = std::max(nb, panel_of(t) + 1);
+            const int panels = std::min(cfg_.stagger_panels, nb);
+            size_t lag = std::min<size_t>((size_t)cfg_.stagger_lag, nrounds);
+            if (cfg_.stagger_lag == 0) {
                 std::unordered_set<TileKey, TileKeyHash> uniq;
                 double bytes_in = 0;
                 for (const Task& t : p.tasks) {
-                    bytes_in += (double)t.m * t.n * p.esize;
+                    if (t.load_c) bytes_in += (double)t.m * t.n * p.esize;
                     for (const StepSpec& st : t.steps)
                         if (!st.a_is_dep && uniq.insert(key_of(st.a)).second) bytes_in += (double)st.a.rows * st.a.cols * p.esize;
                     for (const StepSpec& st : t.steps)
                         if (!st.b_is_dep && uniq.insert(key_of(st.b)).second) bytes_in += (double)st.b.rows * st.b.cols * p.esize;
                 }
                 const bool device_bound = p.flops / (p.dtype == 0 ? 70e12 : 140e12) > bytes_in / 55e9;
-                lag = device_bound ? (3 * max_steps + 4) / 8 : 0;
+                lag = device_bound ? std::max<size_t>(1, (3 * nrounds + 4) / 8) : 0;
             }
             if (panels > 1 && lag > 0) {
                 lag_.resize(ntasks);
                 size_t lag_max = 0;
                 for (size_t i = 0; i < ntasks; ++i) {
                     const Task& t = p.tasks[i];
-                    lag_[i] = (uint32_t)((size_t)((t.solve_on_right ? t.ti : t.tj) * panels / nb) * lag);
+                    lag_[i] = (uint32_t)((size_t)(panel_of(t) * panels / nb) * lag);
                     lag_max = std::max<size_t>(lag_max, lag_[i]);
                 }
                 pf_last_round_ += lag_max;

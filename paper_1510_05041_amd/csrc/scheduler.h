@@ -57,8 +57,8 @@ struct SchedConfig {
                         // for every tile of the call (see run()); false: with the task's first launch, always
     bool row_order = true;  // the same calls take their tasks block row by block row of C instead of in the queue's order
     int tail_cut = 4;   // wide mode: tile steps per launch for the last sixteen tasks of the last round (0: sixteen, as everywhere)
-    int solve_panels = 2;   // wide triangular solve: independent panels of right-hand sides that run staggered,
-    int solve_lag = 0;      // each this many rounds behind the one before; 0: chosen per call (none when the link
+    int stagger_panels = 2;   // wide triangular solve: independent panels of right-hand sides that run staggered,
+    int stagger_lag = 0;      // each this many rounds behind the one before; 0: chosen per call (none when the link
                             // bounds it); -1 or one panel: all right-hand sides in step
     int profile = 0;    // 1: time every launch with events; 2: also every tile copy, and dissect the call's time on the
                         // device into kernels / copies not hidden under a kernel / neither (Section V.A, time profile)

@@ -52,7 +52,7 @@ def configure(L, T, nstreams=4, arena_gb=2.0, cap_bytes=0, **opts):
     L.set_tile(T)
     L.set_cache_bytes(cap_bytes)
     defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, shells=1, priority=1, profile=0, persist=0, wide=0, ramp=0,
-                    merge=4, late_c=1, row_order=1, tail_cut=4, solve_panels=2, solve_lag=0)
+                    merge=4, late_c=1, row_order=1, tail_cut=4, stagger_panels=2, stagger_lag=0)
     defaults.update(opts)
     for k, v in defaults.items():
         L.set_option(k, v)
@@ -1028,7 +1028,7 @@ def test_wide_schedule_dtrsm_full_compare_and_residual(lib, side, uplo, trans, d
     """The triangular solve in the wide schedule (14 x 11 ragged tiles), compared element by element and by residual.
     Half of the cases with the right-hand sides in three staggered panels, two rounds apart (what large solves do)."""
     M, N = 1700, 1330
-    stagger = dict(solve_panels=3, solve_lag=2) if (side + uplo + trans + diag) % 2 else dict(solve_lag=-1)
+    stagger = dict(stagger_panels=3, stagger_lag=2) if (side + uplo + trans + diag) % 2 else dict(stagger_lag=-1)
     configure(lib, T=128, arena_gb=0.5, **dict(AUTO, **stagger))
     n = M if side == blasx.Left else N
     A, ka = triangular(n, 33, uplo, diag)
@@ -1364,7 +1364,7 @@ def test_seeded_random_problems_every_routine_and_schedule(lib, seed):
     # how tiles travel and when C is fetched (a generator of their own: the problems above stay what they were)
     rng2 = np.random.default_rng(5000 + seed)
     opts.update(merge=int(rng2.choice([1, 4, 4, 8])), late_c=int(rng2.choice([0, 1, 1])), row_order=int(rng2.choice([0, 1, 1])),
-                solve_panels=int(rng2.choice([1, 2, 3])), solve_lag=int(rng2.choice([0, 1, 2, 4])), tail_cut=int(rng2.choice([0, 4, 4, 2])))
+                stagger_panels=int(rng2.choice([1, 2, 3])), stagger_lag=int(rng2.choice([0, 1, 2, 4])), tail_cut=int(rng2.choice([0, 4, 4, 2])))
     configure(lib, T=T, arena_gb=1.5, **opts)
     uplo = int(rng.choice([blasx.Lower, blasx.Upper]))
     trans = int(rng.choice(TRANS))

@@ -31,7 +31,7 @@ def setup(sim, T, nstreams=4, arena_tiles=64, cap_tiles=0, seed=1, esize=8, **op
     sim.set_tile(T)
     sim.set_cache_bytes(cap_tiles * T * T * esize)
     defaults = dict(group=4, kchain=2, depth=3, rs=8, sb_rows=2, sb_cols=2, shells=1, priority=1, profile=0, persist=0, wide=0, ramp=0,
-                    merge=4, late_c=1, row_order=1, tail_cut=0, solve_panels=2, solve_lag=3)
+                    merge=4, late_c=1, row_order=1, tail_cut=0, stagger_panels=2, stagger_lag=3)
     defaults.update(opts)
     for k, v in defaults.items():
         sim.set_option(k, v)
@@ -667,7 +667,7 @@ def test_wide_mode_last_launches_are_cut_short(sim):
 @pytest.mark.parametrize("uplo", [blasx.Lower, blasx.Upper])
 @pytest.mark.parametrize("trans", TRANS)
 def test_wide_solve_with_staggered_panels_of_right_hand_sides(sim, side, uplo, trans):
-    """Wide triangular solve: the right-hand sides are cut into "solve_panels" independent panels, each "solve_lag"
+    """Wide triangular solve: the right-hand sides are cut into "stagger_panels" independent panels, each "stagger_lag"
     rounds behind the one before.  Any number of panels and any lag give the solution of the oracle (residual and
     elementwise), also when the cache is tight and when the lag exceeds the number of rounds."""
     rng = np.random.default_rng(uplo + 2 * trans + 5 * side)
@@ -680,7 +680,7 @@ def test_wide_solve_with_staggered_panels_of_right_hand_sides(sim, side, uplo, t
     ref.trsm(blasx.ColMajor, side, uplo, trans, blasx.NonUnit, 0.5, A, want)
     for case, (panels, lag, arena) in enumerate([(1, 3, 300), (2, -1, 300), (2, 3, 300), (2, 6, 300), (3, 2, 300), (4, 1, 300), (7, 1, 300),
                                                  (2, 50, 300), (2, 3, 120), (3, 2, 100)]):
-        setup(sim, T=T, arena_tiles=arena, seed=case, wide=1, group=2, kchain=0, solve_panels=panels, solve_lag=lag)
+        setup(sim, T=T, arena_tiles=arena, seed=case, wide=1, group=2, kchain=0, stagger_panels=panels, stagger_lag=lag)
         B = B0.copy(order="F")
         sim.dtrsm(blasx.ColMajor, side, uplo, trans, blasx.NonUnit, M, N, 0.5, A, n, B, M)
         assert relerr(B, np.asarray(want)) < 1e-13, (panels, lag, arena)
@@ -690,7 +690,7 @@ def test_wide_solve_with_staggered_panels_of_right_hand_sides(sim, side, uplo, t
             assert sim.get_option("last_wide") == 1, (panels, lag)
             assert st["refetches"] == 0 and st["evictions"] == 0        # every tile crosses the link once
     # no lag given: chosen per call (this one is far too small to be device-bound: none)
-    setup(sim, T=T, arena_tiles=300, wide=1, group=2, kchain=0, solve_panels=2, solve_lag=0)
+    setup(sim, T=T, arena_tiles=300, wide=1, group=2, kchain=0, stagger_panels=2, stagger_lag=0)
     B = B0.copy(order="F")
     sim.dtrsm(blasx.ColMajor, side, uplo, trans, blasx.NonUnit, M, N, 0.5, A, n, B, M)
     assert relerr(B, np.asarray(want)) < 1e-13
