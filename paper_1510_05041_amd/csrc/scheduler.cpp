@@ -14,6 +14,9 @@ double now_s() {
     return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
 constexpr int kTrtriBlock = 32;   // order of the diagonal blocks inverted directly
+// grouped schedule with room: operand tiles are asked for this many launches per task ahead, so that a task's tiles
+// of a block row come in as few copies (DGEMM 8192: 30.9 -> 30.7 ms against 2; 1: 31.0)
+constexpr int kHintChains = 4;
 // cache-key tags of tiles derived on the device (1..4 are the inverses of triangular diagonal tiles)
 constexpr int kDerivedSymUpper = 5, kDerivedSymLower = 6, kDerivedTranspose = 7;
 }  // namespace
@@ -845,7 +848,7 @@ void Scheduler::prefetch_grouped_round() {
         if (r.done || r.task < 0) continue;
         const Task& t = p_->tasks[r.task];
         const int nsteps = (int)t.steps.size();
-        for (int q = r.next_step; q < std::min(nsteps, r.next_step + kchain_); ++q) {
+        for (int q = r.next_step; q < std::min(nsteps, r.next_step + kHintChains * kchain_); ++q) {
             const StepSpec& s = t.steps[q];
             if (s.dep >= 0) break;                           // the chain may end at a step that waits for a producer
             if (!s.a_sym && !s.a_mirror) refs.push_back(&s.a);
