@@ -197,13 +197,14 @@ int blasx_set_cache_bytes(size_t cap);
  *              first launch (the paper's order), launches of four k-tiles
  *   "row_order" 1 (default): the same calls take their tasks block row by block row of C, whatever
  *              "sb_rows" / "sb_cols" / "shells" say; 0: always in the queue order those give
- *   "stagger_panels", "stagger_lag"  wide triangular solve: the right-hand sides are cut into
- *              stagger_panels (default 2) independent panels of block columns (block rows for Side =
- *              Right), each running stagger_lag rounds (one round = one block row of the triangle)
- *              behind the one before, so that the short last rounds of one panel, whose results leave in
- *              a burst, run under the product-rich first rounds of the next.  stagger_lag 0 (default):
- *              3/8 of the rounds when the device rather than the link bounds the call, else none;
- *              -1: none
+ *   "stagger_panels", "stagger_lag"  wide triangular solve and triangular product: the right-hand sides
+ *              are cut into stagger_panels (default 2) independent panels of block columns (block rows
+ *              for Side = Right), each running stagger_lag rounds (solve: one round = one block row of
+ *              the triangle; product: one launch per task) behind the one before, so that the short last
+ *              rounds of one panel, whose results leave in a burst, run under the product-rich first
+ *              rounds of the next.  stagger_lag 0 (default): 3/8 of the rounds (product: half, one round
+ *              when it has fewer than five) when the device rather than the link bounds the call, else
+ *              none; -1: none
  *   "tail_cut" wide schedule: the last sixteen tasks of the last round are launched this many at a time
  *              (default 4; 0 or 16: sixteen, like every other launch), so that most of their result tiles
  *              leave while a kernel still runs

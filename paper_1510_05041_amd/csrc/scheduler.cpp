@@ -703,7 +703,7 @@ int Scheduler::load_c_direct(Running& r, const Task& t) {
 // copies are prefetched in the same order, so the first update launches of a round wait for a
 // handful of tiles instead of a whole block row of B (which is first used a round later).
 const std::vector<uint32_t>& Scheduler::round_order(size_t round) {
-    const size_t key = p_->results_are_operands ? round : 0;
+    const size_t key = p_->results_are_operands || !lag_.empty() ? round : 0;
     int q = 0;                           // an unused entry, else the earliest round
     for (int i = 0; i < kOrders; ++i) {
         if (order_round_[i] == key) return order_[i];
@@ -712,8 +712,19 @@ const std::vector<uint32_t>& Scheduler::round_order(size_t round) {
     std::vector<uint32_t>& o = order_[q];
     o.clear();
     const size_t n = p_->tasks.size();
-    if (!p_->results_are_operands) {
+    if (!p_->results_are_operands && lag_.empty()) {
         for (size_t i = 0; i < n; ++i) o.push_back((uint32_t)i);
+    } else if (!p_->results_are_operands) {
+        // staggered panels of tasks of unequal length: chains of one length next to each other, as without the stagger
+        auto len = [&](size_t i) -> size_t {
+            const long lr = local_round(i, round);
+            if (lr < 0) return SIZE_MAX;
+            const size_t ns = p_->tasks[i].steps.size();
+            const size_t l = std::min(ns, round_begin((size_t)lr + 1)) - std::min(ns, round_begin((size_t)lr));
+            return l ? l : SIZE_MAX;
+        };
+        for (size_t i = 0; i < n; ++i) o.push_back((uint32_t)i);
+        std::stable_sort(o.begin(), o.end(), [&](uint32_t x, uint32_t y) { return len(x) < len(y); });
     } else {
         auto cls = [&](size_t i) {
             const long lr = local_round(i, round);      // a trailing column panel is `lag` rounds behind
@@ -1403,7 +1414,7 @@ int Scheduler::run(Problem& p) {
         size_t max_steps = 0;
         for (const Task& t : p.tasks) max_steps = std::max(max_steps, t.steps.size());
         while (round_begin(pf_last_round_ + 1) < max_steps) ++pf_last_round_;
-        // Wide triangular solve: the right-hand sides are cut into `stagger_panels` panels of
+        // Wide triangular solve and triangular product: the right-hand sides are cut into `stagger_panels` panels of
         // block columns (block rows when the triangular matrix is on the right), which do not depend on each other,
         // and panel q runs q * stagger_lag rounds behind panel 0.  All panels in step would finish their last block
         // rows, where a round is a few launches long, in one burst that the outbound link needs several times as long
@@ -1411,13 +1422,15 @@ int Scheduler::run(Problem& p) {
         // staggered, the burst of one panel leaves under the product-rich early rounds of the next.
         // It pays when the device, not the link, bounds the call (measured for the solve: double precision from order
         // 16384 with tiles of 1024, 24576 with tiles of 2048; below, the link is busy to the end and the smaller
-        // launches of two panels only cost): unless a lag is given, the panels are staggered by 3/8 of the rounds when
-        // the call's flop at 70 (single precision: 140) TFLOP/s take longer than its inbound bytes at 55 GB/s.
-        // (The triangular product gains nothing from it: 16384: 78 -> 82 .. 88 ms with two to four panels; its launches
-        // hold chains of one length only as long as all panels are in step.)
+        // launches of two panels only cost): unless a lag is given, the panels are staggered when the call's flop at
+        // 70 (single precision: 140) TFLOP/s take longer than its inbound bytes at 55 GB/s -- the solve by 3/8 of its
+        // rounds (16384: lag 4 / 6 / 8 / 10 of 15: 76.5 / 75.5 / 74.1 / 75.1 ms against 77.5), the product by half of
+        // them (DTRMM 16384, 6 rounds, lag 1 .. 5: 76.8 / 77.4 / 75.7 / 78.7 / 79.9 ms against 78.6; the chains of a
+        // round are then sorted by length across the panels, see round_order(); with the 3 or 4 rounds of chains of
+        // eight one round: 32768 507.5 ms against 512.0 with two and 518.3 in step).
         const size_t nrounds = pf_last_round_ + 1;
-        if (p.results_are_operands && cfg_.stagger_panels > 1 && cfg_.stagger_lag >= 0 && nrounds >= 4) {
-            auto panel_of = [](const Task& t) { return t.solve_on_right ? t.ti : t.tj; };
+        if ((p.results_are_operands || !p.panels.empty()) && cfg_.stagger_panels > 1 && cfg_.stagger_lag >= 0 && nrounds >= 3) {
+            auto panel_of = [](const Task& t) { return t.panel >= 0 ? t.panel : t.solve_on_right ? t.ti : t.tj; };
             int nb = 0;
             for (const Task& t : p.tasks) nb = std::max(nb, panel_of(t) + 1);
             const int panels = std::min(cfg_.stagger_panels, nb);
@@ -1433,7 +1446,7 @@ int Scheduler::run(Problem& p) {
                         if (!st.b_is_dep && uniq.insert(key_of(st.b)).second) bytes_in += (double)st.b.rows * st.b.cols * p.esize;
                 }
                 const bool device_bound = p.flops / (p.dtype == 0 ? 70e12 : 140e12) > bytes_in / 55e9;
-                lag = device_bound ? std::max<size_t>(1, (3 * nrounds + 4) / 8) : 0;
+                lag = !device_bound ? 0 : p.results_are_operands ? std::max<size_t>(1, (3 * nrounds + 4) / 8) : nrounds >= 5 ? nrounds / 2 : 1;
             }
             if (panels > 1 && lag > 0) {
                 lag_.resize(ntasks);

@@ -1048,7 +1048,8 @@ def test_wide_schedule_dtrsm_full_compare_and_residual(lib, side, uplo, trans, d
 def test_wide_schedule_dtrmm_full_compare(lib, side, uplo, trans, diag):
     """The in-place triangular product in the wide schedule (14 x 13 ragged tiles): all panels pinned at once."""
     M, N = 1700, 1600
-    configure(lib, T=128, arena_gb=0.5, **AUTO)
+    stagger = dict(stagger_panels=3, stagger_lag=2) if (side + uplo + trans + diag) % 2 else dict(stagger_lag=-1)
+    configure(lib, T=128, arena_gb=0.5, **dict(AUTO, **stagger))
     A, ka = triangular(M if side == blasx.Left else N, 34, uplo, diag)
     B, kb = pinned(M, N, 34, 1)
     want = np.array(B, order="F")

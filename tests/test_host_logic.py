@@ -812,6 +812,29 @@ def test_wide_mode_trmm_all_flags(sim, order, side, uplo, trans, diag):
     assert st["bytes_h2d"] >= 8 * M * N           # every tile of B once (its original), plus the triangle of A
 
 
+@pytest.mark.parametrize("side,uplo,trans", [(blasx.Left, blasx.Lower, blasx.NoTrans), (blasx.Left, blasx.Upper, blasx.Trans),
+                                             (blasx.Right, blasx.Lower, blasx.NoTrans), (blasx.Right, blasx.Upper, blasx.NoTrans)])
+def test_wide_product_with_staggered_panels(sim, side, uplo, trans):
+    """Wide triangular product with its right-hand sides in panels that run some rounds apart: small integers, so any
+    order of the sums gives the same bits; every panel count, lag and chain length, roomy and tight caches."""
+    rng = np.random.default_rng(uplo + 3 * side + trans)
+    n, m = 16 * 7 - 5, 16 * 6 + 3
+    A = rng.integers(-2, 3, (n, n)).astype(np.float64)
+    Tm = np.tril(A) if uplo == blasx.Lower else np.triu(A)
+    Top = Tm if trans == blasx.NoTrans else Tm.T
+    M, N = (n, m) if side == blasx.Left else (m, n)
+    B = rng.integers(-2, 3, (M, N)).astype(np.float64)
+    want = 2.0 * (Top @ B if side == blasx.Left else B @ Top)
+    for case, (panels, lag, kchain, arena) in enumerate([(2, -1, 1, 300), (2, 1, 1, 300), (2, 3, 2, 300), (3, 2, 1, 300), (4, 1, 3, 300),
+                                                         (7, 1, 1, 300), (2, 40, 1, 300), (2, 2, 1, 170), (3, 1, 2, 160)]):
+        setup(sim, T=16, arena_tiles=arena, seed=case, wide=2, group=2, kchain=kchain, stagger_panels=panels, stagger_lag=lag)
+        As, Bs = store(A, blasx.ColMajor), store(B, blasx.ColMajor)
+        sim.dtrmm(blasx.ColMajor, side, uplo, trans, blasx.NonUnit, M, N, 2.0, As, n, Bs, M)
+        assert sim.get_option("last_wide") == 1, (panels, lag, kchain, arena)
+        assert np.array_equal(np.asarray(Bs), want), (panels, lag, kchain, arena)
+        assert sim.get_stats()["bytes_d2h"] == 8 * M * N
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_wide_mode_trmm_tight_cache_many_interleavings(sim, seed):
     rng = np.random.default_rng(80 + seed)
