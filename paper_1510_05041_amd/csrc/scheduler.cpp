@@ -344,7 +344,7 @@ int Scheduler::issue_h2d(const TileRef& t, int slot) {
 // free slots are used.  Returns what fetch() returns for the first tile that could not be started (-1: no slot).
 int Scheduler::fetch_sorted(std::vector<const TileRef*>& refs, bool may_evict) {
     const size_t es = p_->esize;
-    auto row_of = [es](const TileRef* r) { return (uintptr_t)r->host % ((uintptr_t)r->ld * es); };
+    auto row_of = [es](const TileRef* r) { return r->ld > 0 ? (uintptr_t)r->host % ((uintptr_t)r->ld * es) : (uintptr_t)0; };
     std::sort(refs.begin(), refs.end(), [&](const TileRef* x, const TileRef* y) {
         if (x->ld != y->ld) return x->ld < y->ld;
         const uintptr_t rx = row_of(x), ry = row_of(y);
