@@ -422,6 +422,34 @@ int Scheduler::ensure_panel(int panel) {
     return 0;
 }
 
+// Wide TRMM: every panel is entered at once, so all their tiles get their slots here in one pass, block row by block
+// row of the matrix across the panels: tiles that are neighbours in the host matrix then sit in neighbouring slots and
+// can share an inbound copy (panel by panel, the neighbours of a tile would be a whole panel of slots away).
+int Scheduler::reserve_all_panels() {
+    struct Want { const TileRef* ref; int panel; };
+    std::vector<Want> all;
+    for (size_t q = 0; q < p_->panels.size(); ++q) {
+        if (panels_[q].loaded) continue;
+        for (const TileRef& t : p_->panels[q].tiles) all.push_back(Want{&t, (int)q});
+    }
+    const size_t es = p_->esize;
+    auto row_of = [es](const TileRef* r) { return r->ld > 0 ? (uintptr_t)r->host % ((uintptr_t)r->ld * es) : (uintptr_t)0; };
+    std::stable_sort(all.begin(), all.end(), [&](const Want& x, const Want& y) {
+        const uintptr_t rx = row_of(x.ref), ry = row_of(y.ref);
+        return rx != ry ? rx < ry : x.ref->host < y.ref->host;
+    });
+    for (const Want& w : all) {
+        bool hit = false;
+        Block* b = cache_.translate(key_of(*w.ref), &hit);
+        if (!b) return BLASX_ERR_ARENA_TOO_SMALL;        // wide_fits() has counted them
+        if (!hit) b->pending = true;
+        cache_.acquire(b);
+        panels_[w.panel].blocks.push_back(b);
+    }
+    for (size_t q = 0; q < p_->panels.size(); ++q) panels_[q].loaded = true;
+    return 0;
+}
+
 // ---------------------------------------------------------------- reservation station ----
 
 void Scheduler::refill_rs() {
@@ -1470,6 +1498,7 @@ int Scheduler::run(Problem& p) {
     // tile would be requested behind all the copies already queued, and its ten merge levels keep
     // the device nearly idle for half a millisecond per round.
     bool inverses_first = wide_ && p.results_are_operands;
+    if (rc == 0 && wide_ && !p.panels.empty()) rc = reserve_all_panels();
 
     for (; rc == 0;) {
         retire(false);

@@ -156,6 +156,7 @@ private:
     int  take_slot_blocking(int* slot);
     int  start_task(int task_index, Running* r);
     int  ensure_panel(int panel);
+    int  reserve_all_panels();
     int  build_chain(int ri);
     const std::vector<uint32_t>& round_order(size_t round);
     int  prefetch_c(Running& r, const Task& t, bool may_wait);
