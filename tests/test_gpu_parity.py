@@ -866,6 +866,35 @@ def test_config4_dtrsm_left_lower_notrans_nonunit_residual(lib, schedule):
     check_trsm_columns(A, B, M, cols, 5, TOL64)
 
 
+def test_dtrmm_left_lower_16384_sampled_columns(lib):
+    """DTRMM Left/Lower/NoTrans/NonUnit M=N=16384 in place, the library's own choices: wide schedule, tasks sorted by
+    length, right-hand sides in two staggered panels (the call is bound by the device).  Whole columns of the result
+    against the oracle: both panels, both ends of each, columns across tile boundaries and single ones."""
+    M = N = 16384
+    T = 1024
+    configure(lib, T=0, nstreams=4, arena_gb=12.0, **AUTO)
+    A, ka = pinned(M, M, 8, synth.MAT_A)
+    iu = np.triu_indices(T, 1)
+    for c in range(0, M, T):                             # the strictly upper triangle is never read
+        A[:c, c:c + T] = np.nan
+        A[c:c + T, c:c + T][iu] = np.nan
+    B, kb = pinned(M, N, 8, synth.MAT_B)
+    rng = np.random.default_rng(8)
+    cols = np.unique(np.concatenate([np.arange(0, 24), np.arange(N // 2 - 12, N // 2 + 12), np.arange(N - 24, N),
+                                     np.arange(5 * T - 8, 5 * T + 8), np.arange(11 * T - 8, 11 * T + 8), rng.choice(N, 24, replace=False)]))
+    B0 = np.array(np.asarray(B)[:, cols], order="F")
+    dt = timed(lambda: lib.dtrmm(blasx.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, M, N, -0.75, A, M, B, M))
+    report("DTRMM L/L/N/N M=N=16384 auto", lib, 1.0 * M * M * N, dt)
+    assert lib.get_option("last_tile") == T and lib.get_option("last_wide") == 1
+    st = lib.get_stats()
+    assert st["tasks"] == 256 and st["bytes_d2h"] == 8 * M * N and st["steps_general"] == 0
+    assert st["bytes_h2d"] == 8 * (M * N + T * T * 136)      # every tile of B and of the stored triangle once
+    want = B0.copy(order="F")
+    ref.trmm(ref.ColMajor, blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, -0.75, np.asarray(A), want)
+    got = np.asarray(B)[:, cols]
+    assert_close(got, want, trmm_bound(blasx.Left, blasx.Lower, blasx.NoTrans, blasx.NonUnit, A, B0, -0.75), TOL64, "dtrmm 16384 columns")
+
+
 def test_dtrsm_order_20480_takes_2048_tiles_residual(lib):
     """A triangular matrix of order 20480: the automatic tile is 2048 (10 x 2 tiles, wide right-looking solve);
     residual on sampled columns."""
