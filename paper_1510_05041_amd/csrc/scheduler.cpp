@@ -526,7 +526,7 @@ int Scheduler::add_step(OpenPack& op, bool ta, bool tb, const TileStep& st, doub
     TileStep& dst = op.pack.step[op.pack.nsteps++];
     dst = st;
     dst.wg_begin = op.pack.total_wg;
-    op.pack.total_wg += macro_tiles(st.m, st.n);
+    op.pack.total_wg += macro_tiles(st.m, st.n, st.flags);
     op.flops += flops;
     op.steps += nsteps;
     return 0;

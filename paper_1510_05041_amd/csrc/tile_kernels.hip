@@ -901,6 +901,22 @@ void tile_steps_kernel(const LaunchPack pack) {
         i_base = (int)(order.rows_slow ? local / tiles_n : local % tiles_m) * BM;
         j_base = (int)(order.rows_slow ? local % tiles_n : local / tiles_m) * BN;
     }
+    // Diagonal tile of SYRK / SYR2K (Eq. 1b): only the macro-tiles that touch the triangle of C that the step reads and
+    // writes have workgroups (36 of the 64 of a 1024 x 1024 tile), numbered column by column as macro_tiles() counts them.
+    if (st.flags & (TS_C_LOWER | TS_C_UPPER)) {
+        const uint32_t tiles_n = (uint32_t)(st.n + BN - 1) / BN;
+        uint32_t rest = v - st.wg_begin, i = 0, j = 0;
+        for (; j < tiles_n; ++j) {
+            const uint32_t count = (st.flags & TS_C_LOWER) ? (tiles_m > j ? tiles_m - j : 0) : (j + 1 < tiles_m ? j + 1 : tiles_m);
+            if (rest < count) {
+                i = (st.flags & TS_C_LOWER) ? j + rest : rest;
+                break;
+            }
+            rest -= count;
+        }
+        i_base = (int)i * BM;
+        j_base = (int)j * BN;
+    }
     if (MODE == MODE_GENERAL)
         macro_tile<T, TA, TB>(st, i_base, j_base);
     else

@@ -65,7 +65,7 @@ constexpr int kMaxStepsPerLaunch = 16;
 
 struct LaunchPack {
     int32_t  nsteps;
-    uint32_t total_wg;       // sum over steps of ceil(m/BM)*ceil(n/BN)
+    uint32_t total_wg;       // sum over steps of macro_tiles()
     TileStep step[kMaxStepsPerLaunch];
 };
 static_assert(sizeof(LaunchPack) <= 4096, "launch pack must fit the kernel-argument segment");
@@ -74,8 +74,15 @@ constexpr int kBM = 128;     // macro-tile rows of C per workgroup
 constexpr int kBN = 128;     // macro-tile columns of C per workgroup
 constexpr int kBK = 16;      // depth of one LDS slab
 
-inline uint32_t macro_tiles(int m, int n) {
-    return (uint32_t)((m + kBM - 1) / kBM) * (uint32_t)((n + kBN - 1) / kBN);
+// Workgroups of a step: one per macro-tile of C; with an output triangle (TS_C_LOWER / TS_C_UPPER, the diagonal tiles
+// of SYRK and SYR2K) only the macro-tiles that touch the triangle, column by column (tile_steps_kernel maps its
+// workgroup index the same way).
+inline uint32_t macro_tiles(int m, int n, uint32_t flags = 0) {
+    const uint32_t tm = (uint32_t)((m + kBM - 1) / kBM), tn = (uint32_t)((n + kBN - 1) / kBN);
+    if (!(flags & (TS_C_LOWER | TS_C_UPPER))) return tm * tn;
+    uint32_t count = 0;
+    for (uint32_t j = 0; j < tn; ++j) count += (flags & TS_C_LOWER) ? (tm > j ? tm - j : 0) : (j + 1 < tm ? j + 1 : tm);
+    return count;
 }
 
 // True when a step can run in the unpredicated kernel: whole macro-tiles, every k a multiple of
