@@ -202,7 +202,7 @@ int blasx_set_cache_bytes(size_t cap);
  *              for Side = Right), each running stagger_lag rounds (solve: one round = one block row of
  *              the triangle; product: one launch per task) behind the one before, so that the short last
  *              rounds of one panel, whose results leave in a burst, run under the product-rich first
- *              rounds of the next.  stagger_lag 0 (default): 3/8 of the rounds (product: half, one round
+ *              rounds of the next.  stagger_lag 0 (default): half of the rounds (product: one round
  *              when it has fewer than five) when the device rather than the link bounds the call, else
  *              none; -1: none
  *   "tail_cut" wide schedule: the last sixteen tasks of the last round are launched this many at a time

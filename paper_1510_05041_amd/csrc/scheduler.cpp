@@ -1451,11 +1451,11 @@ int Scheduler::run(Problem& p) {
         // It pays when the device, not the link, bounds the call (measured for the solve: double precision from order
         // 16384 with tiles of 1024, 24576 with tiles of 2048; below, the link is busy to the end and the smaller
         // launches of two panels only cost): unless a lag is given, the panels are staggered when the call's flop at
-        // 70 (single precision: 140) TFLOP/s take longer than its inbound bytes at 55 GB/s -- the solve by 3/8 of its
-        // rounds (16384: lag 4 / 6 / 8 / 10 of 15: 76.5 / 75.5 / 74.1 / 75.1 ms against 77.5), the product by half of
-        // them (DTRMM 16384, 6 rounds, lag 1 .. 5: 76.8 / 77.4 / 75.7 / 78.7 / 79.9 ms against 78.6; the chains of a
-        // round are then sorted by length across the panels, see round_order(); with the 3 or 4 rounds of chains of
-        // eight one round: 32768 507.5 ms against 512.0 with two and 518.3 in step).
+        // 70 (single precision: 140) TFLOP/s take longer than its inbound bytes at 55 GB/s -- by half of the rounds
+        // (DTRSM 16384, 15 rounds, lag 4 / 6 / 8 / 10: 76.5 / 75.5 / 74.1 / 75.1 ms against 77.5 in step; DTRMM 16384,
+        // 6 rounds, lag 1 .. 5: 76.8 / 77.4 / 75.7 / 78.7 / 79.9 ms against 78.6, its chains of a round sorted by length
+        // across the panels, see round_order(); with the 3 or 4 rounds of chains of eight the product takes one round:
+        // 32768 507.5 ms against 512.0 with two and 518.3 in step).
         const size_t nrounds = pf_last_round_ + 1;
         if ((p.results_are_operands || !p.panels.empty()) && cfg_.stagger_panels > 1 && cfg_.stagger_lag >= 0 && nrounds >= 3) {
             auto panel_of = [](const Task& t) { return t.panel >= 0 ? t.panel : t.solve_on_right ? t.ti : t.tj; };
@@ -1474,7 +1474,7 @@ int Scheduler::run(Problem& p) {
                         if (!st.b_is_dep && uniq.insert(key_of(st.b)).second) bytes_in += (double)st.b.rows * st.b.cols * p.esize;
                 }
                 const bool device_bound = p.flops / (p.dtype == 0 ? 70e12 : 140e12) > bytes_in / 55e9;
-                lag = !device_bound ? 0 : p.results_are_operands ? std::max<size_t>(1, (3 * nrounds + 4) / 8) : nrounds >= 5 ? nrounds / 2 : 1;
+                lag = !device_bound ? 0 : p.results_are_operands ? (nrounds + 1) / 2 : nrounds >= 5 ? nrounds / 2 : 1;
             }
             if (panels > 1 && lag > 0) {
                 lag_.resize(ntasks);
