@@ -119,6 +119,10 @@ def run_secondary(np, torch, lib, blasx, synth, A, B, C, owners, n, want_cfg3):
         nt = M // 1024
         out.append(secondary_entry("DTRSM Left/Lower/NoTrans/NonUnit M=N=16384", 1.0 * M * M * M,
                                    8.0 * (1024 * 1024 * nt * (nt + 1) // 2 + M * M), dt, FP64_MFMA_PEAK_TFLOPS))
+        # triangular product in place on the same matrices (two calls: the values stay far inside the double range)
+        dt = timed(lambda: lib.dtrmm(CM, blasx.Left, blasx.Lower, NT, blasx.NonUnit, M, M, 1.0, A, n, B, n))
+        out.append(secondary_entry("DTRMM Left/Lower/NoTrans/NonUnit M=N=16384", 1.0 * M * M * M,
+                                   8.0 * (1024 * 1024 * nt * (nt + 1) // 2 + M * M), dt, FP64_MFMA_PEAK_TFLOPS))
         synth.fill(A, 0, synth.MAT_A)
         synth.fill(B, 0, synth.MAT_B)
     if n >= 32768:
