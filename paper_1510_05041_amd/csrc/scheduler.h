@@ -25,7 +25,16 @@
 //     result tile out and must be a full one); tasks of unequal length (triangular product)
 //     are sorted by length, because a launch lasts as long as its longest chain.  The
 //     triangular solve runs the same way one k-tile per round (right-looking), with every
-//     diagonal tile inverted before the first round.
+//     diagonal tile inverted before the first round; when the device bounds the call, the
+//     right-hand sides of the solve and of the triangular product run as two panels some
+//     rounds apart, so that the results of one leave under the kernels of the other;
+//   - inbound copies carry up to `merge` tiles: whole tiles that are neighbours in a block row
+//     of the host matrix and in the arena are one strided copy (the copy engine pauses between
+//     copies, not inside one); the free list hands out the lowest slot and the lists of tiles
+//     to fetch are sorted so that neighbours follow each other;
+//   - a grouped call whose tiles all fit the cache (the link-bound sizes) fetches C for a
+//     task's last launch only, like the wide schedule, and takes its tasks block row by block
+//     row, so that little is left to do when the last inbound tile has landed.
 #pragma once
 #include <stdint.h>
 
