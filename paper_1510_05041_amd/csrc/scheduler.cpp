@@ -15,7 +15,7 @@ double now_s() {
 }
 constexpr int kTrtriBlock = 32;   // order of the diagonal blocks inverted directly
 // grouped schedule with room: operand tiles are asked for this many launches per task ahead, so that a task's tiles
-// of a block row come in as few copies (DGEMM 8192: 30.9 -> 30.7 ms against 2; 1: 31.0)
+// of a block row come in as few copies
 constexpr int kHintChains = 4;
 // cache-key tags of tiles derived on the device (1..4 are the inverses of triangular diagonal tiles)
 constexpr int kDerivedSymUpper = 5, kDerivedSymLower = 6, kDerivedTranspose = 7;
@@ -1447,15 +1447,11 @@ int Scheduler::run(Problem& p) {
         // and panel q runs q * stagger_lag rounds behind panel 0.  All panels in step would finish their last block
         // rows, where a round is a few launches long, in one burst that the outbound link needs several times as long
         // to carry, and would start with nothing to compute while the first block row of every panel comes in;
-        // staggered, the burst of one panel leaves under the product-rich early rounds of the next.
-        // It pays when the device, not the link, bounds the call (measured for the solve: double precision from order
-        // 16384 with tiles of 1024, 24576 with tiles of 2048; below, the link is busy to the end and the smaller
-        // launches of two panels only cost): unless a lag is given, the panels are staggered when the call's flop at
-        // 70 (single precision: 140) TFLOP/s take longer than its inbound bytes at 55 GB/s -- by half of the rounds
-        // (DTRSM 16384, 15 rounds, lag 4 / 6 / 8 / 10: 76.5 / 75.5 / 74.1 / 75.1 ms against 77.5 in step; DTRMM 16384,
-        // 6 rounds, lag 1 .. 5: 76.8 / 77.4 / 75.7 / 78.7 / 79.9 ms against 78.6, its chains of a round sorted by length
-        // across the panels, see round_order(); with the 3 or 4 rounds of chains of eight the product takes one round:
-        // 32768 507.5 ms against 512.0 with two and 518.3 in step).
+        // staggered, the burst of one panel leaves under the product-rich early rounds of the next.  It pays when
+        // the device, not the link, bounds the call (else the smaller launches of two panels only cost): unless a
+        // lag is given, the panels are staggered by half of the rounds (the product with fewer than five rounds: by
+        // one) when the call's flop at 70 (single precision: 140) TFLOP/s take longer than its inbound bytes at
+        // 55 GB/s.  The product's chains of a round are then sorted by length across the panels (round_order()).
         const size_t nrounds = pf_last_round_ + 1;
         if ((p.results_are_operands || !p.panels.empty()) && cfg_.stagger_panels > 1 && cfg_.stagger_lag >= 0 && nrounds >= 3) {
             auto panel_of = [](const Task& t) { return t.panel >= 0 ? t.panel : t.solve_on_right ? t.ti : t.tj; };
