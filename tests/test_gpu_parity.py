@@ -607,6 +607,10 @@ def test_config2_dgemm_large_sampled(lib, n, schedule):
     check_gemm_whole_tiles(blasx.NoTrans, blasx.NoTrans, n, n, n, 1.0, A, B, 1.0, (0, synth.MAT_C), C, 1024, 4, n, TOL64)
     assert st["bytes_h2d"] == 3 * 8 * n * n and st["bytes_d2h"] == 8 * n * n and st["refetches"] == 0
     assert lib.get_option("last_wide") == (1 if schedule == "auto" else 0)
+    # one inbound copy per tile counted, and (in the configuration bench.py times) most tiles travelled in company
+    assert st["copies_h2d"] == 3 * (n // 1024) ** 2 and st["transfers_h2d"] <= st["copies_h2d"]
+    if schedule == "auto":
+        assert st["transfers_h2d"] <= 0.4 * st["copies_h2d"], (st["transfers_h2d"], st["copies_h2d"])
 
 
 @pytest.mark.parametrize("ta,tb", list(itertools.product(TRANS, TRANS)))
