@@ -190,7 +190,7 @@ def main():
     ap.add_argument("--shells", type=int, default=None)
     ap.add_argument("--rs", type=int, default=None)
     ap.add_argument("--prefetch", type=int, default=None)
-    ap.add_argument("--merge", type=int, default=None, help="most neighbouring tiles per inbound copy (default 4; 1: one copy per tile)")
+    ap.add_argument("--merge", type=int, default=None, help="most neighbouring tiles per inbound copy (default: as many as make 32 MiB; 1: one copy per tile)")
     ap.add_argument("--wide", type=int, default=None, help="least k-steps per task for which all tasks advance together when the cache has room (default 11); 0: grouped")
     ap.add_argument("--arena-gb", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")

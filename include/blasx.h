@@ -187,7 +187,8 @@ int blasx_set_cache_bytes(size_t cap);
  *              first rather than last, and when nothing is left over the first full round is split
  *              into 2 steps and the rest.  The choice of the latest call is "last_ramp"
  *   "prefetch" wide schedule: inbound copies are started this many launches ahead (default 24)
- *   "merge"    most whole tiles that one inbound copy may carry (1..8, default 4).  Tiles that lie side
+ *   "merge"    most whole tiles that one inbound copy may carry (1..8; 0, the default: as many as make
+ *              32 MiB, between 2 and 8: 4 tiles of 1024 x 1024 doubles).  Tiles that lie side
  *              by side in a block row of a column-major host matrix and go to neighbouring slots of the
  *              tile cache are one strided copy: the copy engine pauses between copies, not inside one.
  *              1: one copy per tile (the paper's scheme)

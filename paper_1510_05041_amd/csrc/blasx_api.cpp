@@ -511,7 +511,7 @@ int blasx_set_option(const char* name, long value) {
     else if (n == "tail_cut") { if (value < 0 || value > 16) return BLASX_ERR_CONFIG; L.cfg.tail_cut = (int)value; }
     else if (n == "stagger_panels") { if (value < 1 || value > 64) return BLASX_ERR_CONFIG; L.cfg.stagger_panels = (int)value; }
     else if (n == "stagger_lag") { if (value < -1 || value > 4096) return BLASX_ERR_CONFIG; L.cfg.stagger_lag = (int)value; }
-    else if (n == "merge") { if (value < 1 || value > 8) return BLASX_ERR_CONFIG; L.cfg.merge = (int)value; }
+    else if (n == "merge") { if (value < 0 || value > 8) return BLASX_ERR_CONFIG; L.cfg.merge = (int)value; }
     else if (n == "profile") { if (value < 0 || value > 2) return BLASX_ERR_CONFIG; L.cfg.profile = (int)value; }
     else if (n == "persist") {
         if (value < 0 || value > 1) return BLASX_ERR_CONFIG;

@@ -289,10 +289,10 @@ int Scheduler::release_held() {
 int Scheduler::issue_h2d(const TileRef& t, int slot) {
     const size_t es = p_->esize;
     const size_t spitch = (size_t)t.ld * es;
-    const bool whole = cfg_.merge > 1 && t.rows == T_ && t.cols == T_;
+    const bool whole = merge_ > 1 && t.rows == T_ && t.cols == T_;
     if (held_.stream >= 0) {
         // (a slot whose previous copy went through the other stream needs an ordering wait first: not merged)
-        if (whole && held_.ntiles < std::min(cfg_.merge, (int)kMaxMerge) && spitch == held_.spitch &&
+        if (whole && held_.ntiles < merge_ && spitch == held_.spitch &&
             t.host == held_.src + (size_t)held_.ntiles * T_ * spitch &&
             slot_ptr(slot) == held_.dst + (size_t)held_.ntiles * T_ * T_ * es &&
             (fill_seq_[slot] == 0 || fill_stream_[slot] == held_.stream)) {
@@ -881,7 +881,7 @@ void Scheduler::prefetch_ahead(size_t build_pos) {
 // Grouped schedule: the operand tiles of the chains that the coming round builds, for all running tasks together and
 // in fetch_sorted()'s order, into free slots only (a hint: build_chain() fetches whatever is missing).
 void Scheduler::prefetch_grouped_round() {
-    if (cfg_.merge <= 1) return;
+    if (merge_ <= 1) return;
     std::vector<const TileRef*> refs;
     for (const Running& r : running_) {
         if (r.done || r.task < 0) continue;
@@ -1330,6 +1330,10 @@ int Scheduler::run(Problem& p) {
     p_ = &p;
     T_ = p.T;
     pad_ok_ = T_ % kBM == 0 && T_ % kBN == 0;
+    // tiles per inbound copy: as configured, else as many as make 32 MiB (2 .. 8): beyond that a copy gains nothing
+    // more from the pause it saves and only delays its first tile
+    merge_ = cfg_.merge > 0 ? std::min(cfg_.merge, (int)kMaxMerge)
+                            : (int)std::max<size_t>(2, std::min<size_t>(kMaxMerge, ((size_t)32 << 20) / ((size_t)T_ * T_ * p.esize)));
     const size_t ntasks = p.tasks.size();
     next_task_ = 0;
     rs_.clear();

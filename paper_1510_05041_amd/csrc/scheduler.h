@@ -60,8 +60,8 @@ struct SchedConfig {
     int prefetch = 24;  // wide mode: inbound copies are started this many launches ahead of the launch being built
     int ramp = 0;       // wide mode: k-steps per task in the first round (1..kMaxChain, cut to the chain length of
                         // the run, i.e. kMaxChain = no shorter first round; 0: chosen per run, see run())
-    int merge = 4;      // most whole tiles that lie side by side in a host matrix (and land in neighbouring slots) carried
-                        // by one inbound copy; 1: every tile is a copy of its own
+    int merge = 0;      // most whole tiles that lie side by side in a host matrix (and land in neighbouring slots) carried
+                        // by one inbound copy; 1: every tile is a copy of its own; 0: as many as make 32 MiB (2 .. 8)
     bool late_c = true; // grouped schedule: fetch the host tile of C for a task's last launch only, when the cache has room
                         // for every tile of the call (see run()); false: with the task's first launch, always
     bool row_order = true;  // the same calls take their tasks block row by block row of C instead of in the queue's order
@@ -215,6 +215,7 @@ private:
     bool pad_ok_ = false;
     int kchain_ = 4;                    // this run: k-steps fused per launch
     bool wide_ = false;                 // this run: all tasks advance together, C tiles arrive late
+    int merge_ = 1;                     // this run: most tiles per inbound copy
     int pack_cut_ = 16;                 // a launch pack is launched when it holds this many tile steps
     bool late_c_ = false;               // this run: a task's host C tile is fetched for its last launch (wide, or grouped with room)
     size_t round_ = 0;                  // wide mode: index of the round being built

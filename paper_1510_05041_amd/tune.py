@@ -76,7 +76,7 @@ def _problem(lib, routine, n, k):
     raise ValueError(routine)
 
 
-def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=11, kchain=0, ramp=0, warmup_s=2.0, merge=4, order=(4, 4, 1), late_c=1):
+def sweep(routine, sizes, tiles, streams, groups, kdim, reps, arena_gb, out=None, wide=11, kchain=0, ramp=0, warmup_s=2.0, merge=0, order=(4, 4, 1), late_c=1):
     lib = blasx.default()
     results = []
     warm = False
@@ -161,7 +161,7 @@ def main(argv=None):
     ap.add_argument("--wide", type=int, default=11, help="option \"wide\": least k-steps per task for which all tasks advance together; 0: never")
     ap.add_argument("--kchain", type=int, default=0, help="option \"kchain\": k-tiles per launch and task; 0: the library's choice")
     ap.add_argument("--ramp", type=int, default=0, help="option \"ramp\": k-steps per task in the first round of the wide schedule (8: as in the others); 0: the library's choice")
-    ap.add_argument("--merge", type=int, default=4, help="option \"merge\": most neighbouring tiles per inbound copy (1: one copy per tile)")
+    ap.add_argument("--merge", type=int, default=0, help="option \"merge\": most neighbouring tiles per inbound copy (1: one copy per tile; 0: the library's choice)")
     ap.add_argument("--late-c", type=int, default=1, help="option \"late_c\": grouped schedule with room for every tile fetches C for a task's last launch only")
     ap.add_argument("--order", default="4,4,1", help="options sb_rows,sb_cols,shells: super-block shape of the task queue and whether super-blocks are visited in growing shells (1) or block row by block row (0)")
     ap.add_argument("--warmup-s", type=float, default=2.0, help="seconds of untimed calls of the first problem before anything is timed")

@@ -52,7 +52,7 @@ def configure(L, T, nstreams=4, arena_gb=2.0, cap_bytes=0, **opts):
     L.set_tile(T)
     L.set_cache_bytes(cap_bytes)
     defaults = dict(group=16, kchain=4, depth=6, rs=32, sb_rows=4, sb_cols=4, shells=1, priority=1, profile=0, persist=0, wide=0, ramp=0,
-                    merge=4, late_c=1, row_order=1, tail_cut=4, stagger_panels=2, stagger_lag=0)
+                    merge=0, late_c=1, row_order=1, tail_cut=4, stagger_panels=2, stagger_lag=0)
     defaults.update(opts)
     for k, v in defaults.items():
         L.set_option(k, v)
@@ -1192,7 +1192,7 @@ def test_neighbouring_tiles_share_an_inbound_copy_integer_exact(lib, schedule, t
     C0, kc = int_pinned(M, N, 61, 2)
     want = np.array(C0, order="F")
     ref.gemm(ref.ColMajor, ta, tb, 2.0, np.asarray(A), np.asarray(B), -1.0, want)
-    variants = [dict(merge=1), dict(merge=4), dict(merge=8)]
+    variants = [dict(merge=1), dict(merge=4), dict(merge=8), dict(merge=0)]
     if schedule == "grouped":
         variants += [dict(merge=4, late_c=0), dict(merge=4, row_order=0), dict(merge=8, late_c=0, row_order=0, kchain=3)]
     transfers = []
@@ -1397,7 +1397,7 @@ def test_seeded_random_problems_every_routine_and_schedule(lib, seed):
                 ramp=int(rng.choice([0, 0, 1, 8])))
     # how tiles travel and when C is fetched (a generator of their own: the problems above stay what they were)
     rng2 = np.random.default_rng(5000 + seed)
-    opts.update(merge=int(rng2.choice([1, 4, 4, 8])), late_c=int(rng2.choice([0, 1, 1])), row_order=int(rng2.choice([0, 1, 1])),
+    opts.update(merge=int(rng2.choice([1, 0, 4, 8])), late_c=int(rng2.choice([0, 1, 1])), row_order=int(rng2.choice([0, 1, 1])),
                 stagger_panels=int(rng2.choice([1, 2, 3])), stagger_lag=int(rng2.choice([0, 1, 2, 4])), tail_cut=int(rng2.choice([0, 4, 4, 2])))
     configure(lib, T=T, arena_gb=1.5, **opts)
     uplo = int(rng.choice([blasx.Lower, blasx.Upper]))

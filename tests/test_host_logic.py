@@ -1371,7 +1371,7 @@ def test_neighbouring_tiles_share_an_inbound_copy(sim, wide):
     C = synth.matrix(M, N, 11, 2, integers=True)
     want = 2.0 * (np.asarray(A) @ np.asarray(B)) - np.asarray(C)
     seen = {}
-    for merge in (1, 4, 8):
+    for merge in (1, 4, 8, 0):          # 0: the library's choice, as many tiles as make 32 MiB, at most 8
         setup(sim, T=16, arena_tiles=400, group=4, kchain=4, wide=wide, sb_rows=4, sb_cols=4, merge=merge, seed=merge)
         Cs = C.copy(order="F")
         sim.dgemm(blasx.ColMajor, blasx.NoTrans, blasx.NoTrans, M, N, K, 2.0, A, M, B, K, -1.0, Cs, M)
@@ -1381,7 +1381,7 @@ def test_neighbouring_tiles_share_an_inbound_copy(sim, wide):
         seen[merge] = st["transfers_h2d"]
     assert seen[1] == 3 * 64
     assert seen[4] <= 0.6 * seen[1], seen        # most tiles travel in company
-    assert seen[8] <= 0.6 * seen[1], seen
+    assert seen[8] <= 0.6 * seen[1] and seen[0] <= 0.6 * seen[1], seen
     sim.set_option("merge", 4)
 
 
